@@ -1,0 +1,557 @@
+/*
+ * CPU oracle for label-filtered top-k search over a dual-structured
+ * label-centric inverted index (arXiv 2506.00812, "VecFlow").
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, obviously-correct
+ * statement of what the GPU library must return.  It shares no code, header,
+ * table or helper with the HIP path; only tests, the smoke check and the
+ * benchmark's CPU-baseline leg may call it.
+ *
+ * What follows the paper directly:
+ *   - posting lists C_l, the HS/LS split at threshold T, the metadata
+ *     S (sizes), O (offsets), M (local->global map)      Section 4.1.1-4.1.2,
+ *                                                         Section 4.2.1, Alg. 1
+ *   - routing of a query by |C_l| against T               Section 4.1.2 (routing eq.)
+ *   - IVF-BFS = exact scan of the label's list            Section 4.2.2, Alg. 2
+ *   - IVF-Graph = top-M list / candidate expansion loop   Section 4.2.1, Alg. 2
+ *   - predicate function on sorted per-point label arrays Section 4.3.2
+ *   - AND: smallest list + predicate (greedy policy)      Section 4.3.2
+ *   - interleaved list layout (groups of 32, 16-byte chunks) Section 4.2.2
+ *
+ * Readings where the paper is silent (each one is listed in the design notes):
+ *   - distance = squared Euclidean, no square root;
+ *   - C_l is kept in ascending global id, so local order == global order;
+ *   - the per-list graph is the exact R-nearest-neighbour graph, rows ordered by
+ *     (distance, local id);  CAGRA's NN-descent + reordering is not specified by
+ *     the paper and is not reproduced;
+ *   - seeds are ns = min(n_seeds, n) stratified local ids floor(j*n/ns), the same
+ *     for every query of a label (the paper: random sampling confined to the
+ *     label's size);
+ *   - the loop runs a fixed number of iterations and stops early when the top-M
+ *     list holds no unexpanded entry; ties are broken by lower id everywhere;
+ *   - under AND, a scored point that fails the predicate never enters the top-M
+ *     list and is never expanded.
+ *
+ * PARITY STATUS.  Scan path, posting lists, routing, predicate: pinned by the
+ * definitions (exact filtered brute force in numpy, the paper's worked
+ * examples).  Beam search: PARITY UNPINNED BY THE PAPER (it prints no worked
+ * trajectory); it is pinned by special cases that reduce to exact filtered kNN,
+ * by invariants, by a hand-worked example and by visited-capacity independence
+ * (see tests).
+ *
+ * Floating point.  The scan path is the plain definition and is evaluated in
+ * fp64.  Beam search and graph construction take data-dependent decisions
+ * (which vertex to expand next), so they are evaluated in the precision the GPU
+ * kernel uses: fp32 with a written-down summation order (dist_f32_ordered).
+ * Compile with -ffp-contract=off and without -ffast-math.
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#if defined(__FAST_MATH__) || (defined(FLT_EVAL_METHOD) && FLT_EVAL_METHOD != 0)
+#error "the oracle needs strict IEEE fp32 evaluation (no -ffast-math, no x87 excess precision)"
+#endif
+
+#define VFO_U8 0
+#define VFO_F32 1
+
+typedef struct vfo_index {
+    int dtype;
+    int64_t n;
+    int32_t dim;
+    const void *X; /* borrowed: the single global vector table (Section 4.2.1) */
+    int32_t n_labels, T, R;
+    /* predicate function's arrays (Section 4.3.2): sorted, duplicate-free labels per point */
+    int64_t *pl_off; /* [n+1] */
+    int32_t *pl_ids;
+    /* per label */
+    int64_t *S;    /* |C_l| */
+    int64_t *O_HS; /* start of l in the compacted HS arrays, -1 if l is not a graph label */
+    int64_t *O_LS; /* start of l in the compacted LS arrays, -1 if l is not a scan label  */
+    int64_t n_HS, n_LS;
+    int32_t *M_HS; /* [n_HS] local -> global */
+    int32_t *M_LS; /* [n_LS] */
+    int32_t *G_HS; /* [n_HS][R] local ids */
+    uint8_t *G_built; /* [n_HS] row-built flags (lazy mode fills rows on demand) */
+    int lazy;
+} vfo_index;
+
+/* ------------------------------------------------------------------ distances */
+
+/* fp32 squared L2 in the order the GPU kernel uses: eight partial sums a_t,
+ * a_t taking elements e = 32*s + 4*t + c (s ascending, then c = 0..3), each term
+ * rounded as d = q-x, p = d*d, a_t = a_t + p; then the fixed tree
+ * ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7)). */
+float vfo_dist_f32_ordered(const float *q, const float *x, int32_t dim)
+{
+    float a[8];
+    for (int t = 0; t < 8; ++t) a[t] = 0.0f;
+    for (int s = 0; s * 32 < dim; ++s)
+        for (int t = 0; t < 8; ++t)
+            for (int c = 0; c < 4; ++c) {
+                int e = s * 32 + t * 4 + c;
+                if (e < dim) {
+                    float d = q[e] - x[e];
+                    float p = d * d;
+                    a[t] = a[t] + p;
+                }
+            }
+    float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];
+    float c0 = b0 + b1, c1 = b2 + b3;
+    return c0 + c1;
+}
+
+int32_t vfo_dist_u8(const uint8_t *q, const uint8_t *x, int32_t dim)
+{
+    int32_t acc = 0;
+    for (int e = 0; e < dim; ++e) {
+        int32_t d = (int32_t)q[e] - (int32_t)x[e];
+        acc += d * d;
+    }
+    return acc;
+}
+
+double vfo_dist_f64(const float *q, const float *x, int32_t dim)
+{
+    double acc = 0.0;
+    for (int e = 0; e < dim; ++e) {
+        double d = (double)q[e] - (double)x[e];
+        acc += d * d;
+    }
+    return acc;
+}
+
+/* distance used where decisions are taken (graph rows, beam search) */
+static inline float decision_dist(const vfo_index *ix, const void *q, int64_t g)
+{
+    if (ix->dtype == VFO_U8)
+        return (float)vfo_dist_u8((const uint8_t *)q, (const uint8_t *)ix->X + g * ix->dim, ix->dim);
+    return vfo_dist_f32_ordered((const float *)q, (const float *)ix->X + g * ix->dim, ix->dim);
+}
+
+/* ------------------------------------------------------------------ predicate (Section 4.3.2) */
+
+static int bsearch_range(const int32_t *a, int64_t lo, int64_t hi, int32_t key, int64_t *pos)
+{ /* inclusive range [lo, hi] */
+    while (lo <= hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (a[mid] == key) { *pos = mid; return 1; }
+        if (a[mid] < key) lo = mid + 1; else hi = mid - 1;
+    }
+    return 0;
+}
+
+/* Does the sorted label array `pl[0..np)` hold every label of the sorted query
+ * label array `ql[0..nql)`?  Smallest and largest query labels are located
+ * first; the rest are searched strictly between those two positions.
+ * pos_out (optional, nql entries) receives the index each label was found at. */
+int vfo_predicate(const int32_t *pl, int64_t np, const int32_t *ql, int32_t nql, int64_t *pos_out)
+{
+    if (nql == 0) return 1;
+    if (np == 0) return 0;
+    int64_t plo, phi;
+    if (!bsearch_range(pl, 0, np - 1, ql[0], &plo)) return 0;
+    if (pos_out) pos_out[0] = plo;
+    if (nql == 1) return 1;
+    if (!bsearch_range(pl, plo, np - 1, ql[nql - 1], &phi)) return 0;
+    if (pos_out) pos_out[nql - 1] = phi;
+    for (int32_t i = 1; i + 1 < nql; ++i) {
+        int64_t p;
+        if (!bsearch_range(pl, plo + 1, phi - 1, ql[i], &p)) return 0;
+        if (pos_out) pos_out[i] = p;
+    }
+    return 1;
+}
+
+static int point_has_all(const vfo_index *ix, int64_t g, const int32_t *others, int32_t n_others)
+{
+    return vfo_predicate(ix->pl_ids + ix->pl_off[g], ix->pl_off[g + 1] - ix->pl_off[g], others, n_others, NULL);
+}
+
+/* ------------------------------------------------------------------ interleaved layout (Section 4.2.2) */
+
+/* Groups of 32 vectors; inside a group the components are stored in chunks of
+ * veclen = 16/elem_size elements: chunk 0 of v0..v31, then chunk 1 of v0..v31, ...
+ * Missing vectors of the last group and missing elements of the last chunk are zero.
+ * dst must hold ceil(n/32) * 32 * ceil(dim/veclen)*veclen elements. */
+void vfo_store_interleaved(const void *src, int64_t n, int32_t dim, int32_t elem_size, void *dst)
+{
+    int32_t veclen = 16 / elem_size;
+    int32_t n_chunks = (dim + veclen - 1) / veclen;
+    int64_t n_groups = (n + 31) / 32;
+    memset(dst, 0, (size_t)n_groups * 32 * n_chunks * 16);
+    for (int64_t v = 0; v < n; ++v)
+        for (int32_t e = 0; e < dim; ++e) {
+            int64_t grp = v / 32, lane = v % 32;
+            int32_t chunk = e / veclen, within = e % veclen;
+            int64_t pos = ((grp * n_chunks + chunk) * 32 + lane) * veclen + within;
+            memcpy((char *)dst + pos * elem_size, (const char *)src + (v * dim + e) * elem_size, elem_size);
+        }
+}
+
+/* ------------------------------------------------------------------ index construction (Alg. 1) */
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+typedef struct { float d; int32_t id; } dist_id;
+
+static inline int less_di(float d1, int32_t i1, float d2, int32_t i2)
+{
+    return d1 < d2 || (d1 == d2 && i1 < i2);
+}
+
+/* Row j of label l's graph: the R nearest other members of X_l as local ids,
+ * ordered by (distance, local id). */
+static void build_row(const vfo_index *ix, int64_t base, int64_t n, int64_t j, int32_t *row)
+{
+    int32_t R = ix->R, cnt = 0;
+    dist_id *best = (dist_id *)malloc(sizeof(dist_id) * (R + 1));
+    size_t es = ix->dtype == VFO_U8 ? 1 : 4;
+    const void *xj = (const char *)ix->X + (int64_t)ix->M_HS[base + j] * ix->dim * es;
+    for (int64_t c = 0; c < n; ++c) {
+        if (c == j) continue;
+        float d = decision_dist(ix, xj, ix->M_HS[base + c]);
+        if (cnt == R && !less_di(d, (int32_t)c, best[R - 1].d, best[R - 1].id)) continue;
+        int32_t p = cnt < R ? cnt : R - 1;
+        while (p > 0 && less_di(d, (int32_t)c, best[p - 1].d, best[p - 1].id)) { best[p] = best[p - 1]; --p; }
+        best[p].d = d; best[p].id = (int32_t)c;
+        if (cnt < R) ++cnt;
+    }
+    for (int32_t e = 0; e < R; ++e) row[e] = e < cnt ? best[e].id : -1;
+    free(best);
+}
+
+static const int32_t *graph_row(vfo_index *ix, int64_t base, int64_t n, int64_t j)
+{
+    int64_t r = base + j;
+    if (!__atomic_load_n(&ix->G_built[r], __ATOMIC_ACQUIRE)) {
+        int32_t *tmp = (int32_t *)malloc(sizeof(int32_t) * ix->R);
+        build_row(ix, base, n, j, tmp);
+#pragma omp critical(vfo_row_publish)
+        {
+            if (!ix->G_built[r]) {
+                memcpy(ix->G_HS + r * ix->R, tmp, sizeof(int32_t) * ix->R);
+                __atomic_store_n(&ix->G_built[r], 1, __ATOMIC_RELEASE);
+            }
+        }
+        free(tmp);
+    }
+    return ix->G_HS + r * ix->R;
+}
+
+void vfo_free(vfo_index *ix)
+{
+    if (!ix) return;
+    free(ix->pl_off); free(ix->pl_ids); free(ix->S); free(ix->O_HS); free(ix->O_LS);
+    free(ix->M_HS); free(ix->M_LS); free(ix->G_HS); free(ix->G_built);
+    free(ix);
+}
+
+/* label_offsets/label_ids: CSR of each point's labels, any order, duplicates allowed.
+ * lazy_graph != 0: graph rows are computed on first use instead of up front.
+ * Returns NULL on invalid arguments. */
+vfo_index *vfo_build(const void *X, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                     const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t R, int lazy_graph,
+                     int n_threads)
+{
+    if (!X || n <= 0 || dim <= 0 || n_labels <= 0 || R <= 0 || T < R + 1) return NULL;
+    if (dtype != VFO_U8 && dtype != VFO_F32) return NULL;
+    for (int64_t i = 0; i < label_offsets[n]; ++i)
+        if (label_ids[i] < 0 || label_ids[i] >= n_labels) return NULL;
+    vfo_index *ix = (vfo_index *)calloc(1, sizeof(vfo_index));
+    ix->dtype = dtype; ix->n = n; ix->dim = dim; ix->X = X;
+    ix->n_labels = n_labels; ix->T = T; ix->R = R; ix->lazy = lazy_graph;
+
+    /* sorted, duplicate-free labels per point */
+    ix->pl_off = (int64_t *)calloc(n + 1, sizeof(int64_t));
+    ix->pl_ids = (int32_t *)malloc(sizeof(int32_t) * (label_offsets[n] > 0 ? label_offsets[n] : 1));
+    int64_t w = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t b = label_offsets[i], e = label_offsets[i + 1], start = w;
+        for (int64_t p = b; p < e; ++p) ix->pl_ids[w++] = label_ids[p];
+        qsort(ix->pl_ids + start, w - start, sizeof(int32_t), cmp_i32);
+        int64_t u = start;
+        for (int64_t p = start; p < w; ++p)
+            if (p == start || ix->pl_ids[p] != ix->pl_ids[p - 1]) ix->pl_ids[u++] = ix->pl_ids[p];
+        w = u;
+        ix->pl_off[i + 1] = w;
+    }
+
+    /* pass 1: C_l = { i : l in L_{X_i} }, ascending i */
+    ix->S = (int64_t *)calloc(n_labels, sizeof(int64_t));
+    for (int64_t p = 0; p < w; ++p) ix->S[ix->pl_ids[p]]++;
+
+    /* pass 2: split by T; compacted arrays ordered by label */
+    ix->O_HS = (int64_t *)malloc(sizeof(int64_t) * n_labels);
+    ix->O_LS = (int64_t *)malloc(sizeof(int64_t) * n_labels);
+    for (int32_t l = 0; l < n_labels; ++l) {
+        ix->O_HS[l] = ix->O_LS[l] = -1;
+        if (ix->S[l] >= T) { ix->O_HS[l] = ix->n_HS; ix->n_HS += ix->S[l]; }
+        else if (ix->S[l] > 0) { ix->O_LS[l] = ix->n_LS; ix->n_LS += ix->S[l]; }
+    }
+    ix->M_HS = (int32_t *)malloc(sizeof(int32_t) * (ix->n_HS > 0 ? ix->n_HS : 1));
+    ix->M_LS = (int32_t *)malloc(sizeof(int32_t) * (ix->n_LS > 0 ? ix->n_LS : 1));
+    int64_t *fill = (int64_t *)calloc(n_labels, sizeof(int64_t));
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t p = ix->pl_off[i]; p < ix->pl_off[i + 1]; ++p) {
+            int32_t l = ix->pl_ids[p];
+            if (ix->O_HS[l] >= 0) ix->M_HS[ix->O_HS[l] + fill[l]++] = (int32_t)i;
+            else ix->M_LS[ix->O_LS[l] + fill[l]++] = (int32_t)i;
+        }
+    free(fill);
+
+    ix->G_HS = (int32_t *)malloc(sizeof(int32_t) * (ix->n_HS > 0 ? ix->n_HS : 1) * R);
+    ix->G_built = (uint8_t *)calloc(ix->n_HS > 0 ? ix->n_HS : 1, 1);
+    if (!lazy_graph) {
+        for (int32_t l = 0; l < n_labels; ++l) {
+            if (ix->O_HS[l] < 0) continue;
+            int64_t base = ix->O_HS[l], nl = ix->S[l];
+#pragma omp parallel for schedule(dynamic, 8) num_threads(n_threads > 0 ? n_threads : 1)
+            for (int64_t j = 0; j < nl; ++j) {
+                build_row(ix, base, nl, j, ix->G_HS + (base + j) * R);
+                ix->G_built[base + j] = 1;
+            }
+        }
+    }
+    return ix;
+}
+
+/* ------------------------------------------------------------------ export */
+
+int64_t vfo_n_HS(const vfo_index *ix) { return ix->n_HS; }
+int64_t vfo_n_LS(const vfo_index *ix) { return ix->n_LS; }
+const int64_t *vfo_S(const vfo_index *ix) { return ix->S; }
+const int64_t *vfo_O_HS(const vfo_index *ix) { return ix->O_HS; }
+const int64_t *vfo_O_LS(const vfo_index *ix) { return ix->O_LS; }
+const int32_t *vfo_M_HS(const vfo_index *ix) { return ix->M_HS; }
+const int32_t *vfo_M_LS(const vfo_index *ix) { return ix->M_LS; }
+const int32_t *vfo_G_HS(const vfo_index *ix) { return ix->G_HS; }
+
+/* one graph row by (label, local id); builds it if the index is lazy. Returns 0 on success. */
+int vfo_graph_row(vfo_index *ix, int32_t label, int64_t j, int32_t *row_out)
+{
+    if (label < 0 || label >= ix->n_labels || ix->O_HS[label] < 0 || j < 0 || j >= ix->S[label]) return -1;
+    memcpy(row_out, graph_row(ix, ix->O_HS[label], ix->S[label], j), sizeof(int32_t) * ix->R);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ search (Alg. 2) */
+
+typedef struct { float d; int32_t id; int32_t expanded; } top_entry;
+
+typedef struct {
+    int32_t *stamp; /* exact visited set: stamp[c] == tick  <=>  visited in this query */
+    int64_t stamp_len;
+    int32_t tick;
+    int32_t *ftab; /* optional bounded, forgetful visited table (direct mapped) */
+    int64_t fcap;
+} visit_state;
+
+static int visited_test_and_set(visit_state *vs, int32_t c)
+{
+    if (vs->fcap > 0) {
+        int64_t slot = (int64_t)(((uint64_t)(uint32_t)c * 2654435761u) % (uint64_t)vs->fcap);
+        if (vs->ftab[slot] == c) return 1;
+        vs->ftab[slot] = c; /* overwrites, i.e. forgets, whatever was there */
+        return 0;
+    }
+    if (vs->stamp[c] == vs->tick) return 1;
+    vs->stamp[c] = vs->tick;
+    return 0;
+}
+
+/* insert (d, id) into the sorted top-M list of capacity itopk */
+static void topm_insert(top_entry *list, int32_t *len, int32_t itopk, float d, int32_t id)
+{
+    int32_t p = *len;
+    if (p == itopk) {
+        if (!less_di(d, id, list[p - 1].d, list[p - 1].id)) return;
+        p = itopk - 1;
+    } else {
+        (*len)++;
+    }
+    while (p > 0 && less_di(d, id, list[p - 1].d, list[p - 1].id)) { list[p] = list[p - 1]; --p; }
+    list[p].d = d; list[p].id = id; list[p].expanded = 0;
+}
+
+static int topm_contains(const top_entry *list, int32_t len, int32_t id)
+{
+    for (int32_t i = 0; i < len; ++i) if (list[i].id == id) return 1;
+    return 0;
+}
+
+/* IVF-Graph search of one query inside label l's virtual graph. */
+static void graph_search(vfo_index *ix, const void *q, int32_t l, const int32_t *others, int32_t n_others,
+                         int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
+                         visit_state *vs, int64_t *out_ids, float *out_dists, int64_t *counters)
+{
+    int64_t base = ix->O_HS[l], n = ix->S[l];
+    int32_t R = ix->R, len = 0;
+    top_entry *list = (top_entry *)malloc(sizeof(top_entry) * itopk);
+    int32_t *parents = (int32_t *)malloc(sizeof(int32_t) * width);
+    int64_t n_scored = 0, n_expanded = 0, n_tested = 0;
+
+#define SCORE(c)                                                                         \
+    do {                                                                                 \
+        int64_t g_ = ix->M_HS[base + (c)];                                               \
+        int ok_ = 1;                                                                     \
+        if (n_others > 0) { ++n_tested; ok_ = point_has_all(ix, g_, others, n_others); } \
+        if (ok_) {                                                                       \
+            /* a forgetful visited table may hand back an id the list still holds */     \
+            if (vs->fcap > 0 && topm_contains(list, len, (c))) break;                    \
+            ++n_scored;                                                                  \
+            topm_insert(list, &len, itopk, decision_dist(ix, q, g_), (c));               \
+        }                                                                                \
+    } while (0)
+
+    /* InitializeSearch: stratified sample of local ids confined to [0, S[l]) */
+    int64_t ns = n_seeds < n ? n_seeds : n;
+    for (int64_t j = 0; j < ns; ++j) {
+        int32_t c = (int32_t)((j * n) / ns);
+        if (visited_test_and_set(vs, c)) continue;
+        SCORE(c);
+    }
+    for (int32_t it = 0; it < iters; ++it) {
+        /* the (at most) `width` best unexpanded entries of the top-M list become parents */
+        int32_t np = 0;
+        for (int32_t i = 0; i < len && np < width; ++i)
+            if (!list[i].expanded) { list[i].expanded = 1; parents[np++] = list[i].id; }
+        if (np == 0) break; /* top-M list can no longer change */
+        for (int32_t p = 0; p < np; ++p) {
+            const int32_t *row = graph_row(ix, base, n, parents[p]);
+            ++n_expanded;
+            for (int32_t e = 0; e < R; ++e) {
+                int32_t c = row[e];
+                if (c < 0) continue;
+                if (visited_test_and_set(vs, c)) continue;
+                SCORE(c);
+            }
+        }
+    }
+#undef SCORE
+    for (int32_t i = 0; i < k; ++i) {
+        if (i < len) { out_ids[i] = ix->M_HS[base + list[i].id]; out_dists[i] = list[i].d; }
+        else { out_ids[i] = -1; out_dists[i] = INFINITY; }
+    }
+    if (counters) { counters[0] = n_scored; counters[1] = n_expanded; counters[2] = n_tested; }
+    free(list); free(parents);
+}
+
+typedef struct { double d; int64_t id; } scan_entry;
+
+/* IVF-BFS: exact filtered top-k over label l's posting list (the plain definition). */
+static void scan_search(const vfo_index *ix, const void *q, int32_t l, const int32_t *others, int32_t n_others,
+                        int32_t k, int64_t *out_ids, float *out_dists, int64_t *counters)
+{
+    const int32_t *C;
+    int64_t n = ix->S[l];
+    C = ix->O_HS[l] >= 0 ? ix->M_HS + ix->O_HS[l] : ix->M_LS + ix->O_LS[l];
+    scan_entry *best = (scan_entry *)malloc(sizeof(scan_entry) * (k + 1));
+    int32_t cnt = 0;
+    int64_t n_scored = 0, n_tested = 0;
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t g = C[j];
+        if (n_others > 0) { ++n_tested; if (!point_has_all(ix, g, others, n_others)) continue; }
+        double d;
+        if (ix->dtype == VFO_U8)
+            d = (double)vfo_dist_u8((const uint8_t *)q, (const uint8_t *)ix->X + g * ix->dim, ix->dim);
+        else
+            d = vfo_dist_f64((const float *)q, (const float *)ix->X + g * ix->dim, ix->dim);
+        ++n_scored;
+        if (cnt == k && !(d < best[k - 1].d || (d == best[k - 1].d && g < best[k - 1].id))) continue;
+        int32_t p = cnt < k ? cnt : k - 1;
+        while (p > 0 && (d < best[p - 1].d || (d == best[p - 1].d && g < best[p - 1].id))) { best[p] = best[p - 1]; --p; }
+        best[p].d = d; best[p].id = g;
+        if (cnt < k) ++cnt;
+    }
+    for (int32_t i = 0; i < k; ++i) {
+        if (i < cnt) { out_ids[i] = best[i].id; out_dists[i] = (float)best[i].d; }
+        else { out_ids[i] = -1; out_dists[i] = INFINITY; }
+    }
+    if (counters) { counters[0] = n_scored; counters[1] = 0; counters[2] = n_tested; }
+    free(best);
+}
+
+/* Batched search.  method_out (optional, [nq]): 0 = empty result, 1 = scan, 2 = graph.
+ * route_label_out (optional, [nq]): the label whose list was searched, -1 if none.
+ * counters (optional, [nq][3]): distances computed, rows expanded, predicate tests.
+ * force_scan != 0 answers every query by exact scan (ground truth).
+ * visited_cap > 0 replaces the exact visited set by a forgetful table of that many slots.
+ * Returns 0, or -1 on invalid arguments. */
+int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
+               int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, int64_t visited_cap, int force_scan,
+               int64_t *out_ids, float *out_dists, int32_t *method_out, int32_t *route_label_out,
+               int64_t *counters, int n_threads)
+{
+    if (!ix || nq < 0 || k <= 0) return -1;
+    if (!force_scan && (itopk < k || width <= 0 || iters < 0)) return -1;
+    if (n_seeds <= 0) n_seeds = itopk;
+    for (int64_t j = 0; j < nq; ++j) {
+        if (qoff[j + 1] <= qoff[j]) return -1; /* a query needs at least one label */
+        for (int64_t p = qoff[j]; p < qoff[j + 1]; ++p)
+            if (qids[p] < 0 || qids[p] >= ix->n_labels) return -1;
+    }
+    int64_t max_list = 1;
+    for (int32_t l = 0; l < ix->n_labels; ++l) if (ix->S[l] > max_list) max_list = ix->S[l];
+    size_t es = ix->dtype == VFO_U8 ? 1 : 4;
+
+#pragma omp parallel num_threads(n_threads > 0 ? n_threads : 1)
+    {
+        visit_state vs;
+        vs.stamp_len = max_list; vs.tick = 0;
+        vs.stamp = (int32_t *)calloc(max_list, sizeof(int32_t));
+        vs.fcap = visited_cap;
+        vs.ftab = visited_cap > 0 ? (int32_t *)malloc(sizeof(int32_t) * visited_cap) : NULL;
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t j = 0; j < nq; ++j) {
+            int32_t nl = (int32_t)(qoff[j + 1] - qoff[j]);
+            int32_t *ql = (int32_t *)malloc(sizeof(int32_t) * nl);
+            memcpy(ql, qids + qoff[j], sizeof(int32_t) * nl);
+            qsort(ql, nl, sizeof(int32_t), cmp_i32);
+            int32_t u = 0;
+            for (int32_t p = 0; p < nl; ++p) if (p == 0 || ql[p] != ql[p - 1]) ql[u++] = ql[p];
+            nl = u;
+            /* the query label with the smallest posting list (ties: lower label id) */
+            int32_t best = ql[0], empty = 0;
+            for (int32_t p = 0; p < nl; ++p) {
+                if (ix->S[ql[p]] == 0) empty = 1;
+                if (ix->S[ql[p]] < ix->S[best]) best = ql[p];
+            }
+            int32_t n_others = 0;
+            for (int32_t p = 0; p < nl; ++p) if (ql[p] != best) ql[n_others++] = ql[p]; /* stays sorted */
+            int64_t *oi = out_ids + j * k;
+            float *od = out_dists + j * k;
+            int64_t *cn = counters ? counters + j * 3 : NULL;
+            const void *q = (const char *)Q + j * ix->dim * es;
+            int32_t method;
+            if (empty) {
+                for (int32_t i = 0; i < k; ++i) { oi[i] = -1; od[i] = INFINITY; }
+                if (cn) cn[0] = cn[1] = cn[2] = 0;
+                method = 0; best = -1;
+            } else if (force_scan || ix->S[best] < ix->T) {
+                scan_search(ix, q, best, ql, n_others, k, oi, od, cn);
+                method = 1;
+            } else {
+                vs.tick++;
+                if (vs.fcap > 0) for (int64_t s = 0; s < vs.fcap; ++s) vs.ftab[s] = -1;
+                graph_search(ix, q, best, ql, n_others, k, itopk, width, iters, n_seeds, &vs, oi, od, cn);
+                method = 2;
+            }
+            if (method_out) method_out[j] = method;
+            if (route_label_out) route_label_out[j] = best;
+            free(ql);
+        }
+        free(vs.stamp); free(vs.ftab);
+    }
+    return 0;
+}

@@ -1,0 +1,407 @@
+"""Pins for the CPU oracle: each test checks the oracle against something other
+than itself -- the definitions in the paper, its worked examples, exact filtered
+brute force written separately in numpy, special cases and invariants."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleIndex
+from paper_2506_00812_amd.workloads import make_workload
+from tests.bruteforce import filtered_knn, membership, recall_at_k
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return json.load(f)
+
+
+# ------------------------------------------------------------------ index (Alg. 1, Section 4.1.2 / 4.2.1)
+
+def test_posting_lists_match_definition(tiny, tiny_oracle):
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    S = tiny_oracle.S
+    assert np.array_equal(S, mem.sum(axis=0))
+    O_HS, O_LS, M_HS, M_LS = tiny_oracle.O_HS, tiny_oracle.O_LS, tiny_oracle.M_HS, tiny_oracle.M_LS
+    run_hs = run_ls = 0
+    for l in range(s.n_labels):
+        C_l = np.flatnonzero(mem[:, l])          # C_l = { i : l in L_{X_i} }, ascending
+        if S[l] >= s.T:                          # |C_l| == T is a graph list
+            assert O_HS[l] == run_hs and O_LS[l] == -1
+            assert np.array_equal(M_HS[run_hs:run_hs + S[l]], C_l)
+            run_hs += S[l]
+        elif S[l] > 0:
+            assert O_LS[l] == run_ls and O_HS[l] == -1
+            assert np.array_equal(M_LS[run_ls:run_ls + S[l]], C_l)
+            run_ls += S[l]
+        else:
+            assert O_HS[l] == -1 and O_LS[l] == -1
+    assert run_hs == tiny_oracle.n_HS and run_ls == tiny_oracle.n_LS
+    # the tiny workload happens to hold a list of exactly T ids: the boundary case is live
+    assert (S == s.T).any()
+
+
+def test_graph_rows_are_exact_knn_uint8(tiny, tiny_oracle):
+    s = tiny.spec
+    S, O, M, G = tiny_oracle.S, tiny_oracle.O_HS, tiny_oracle.M_HS, tiny_oracle.G_HS
+    rng = np.random.default_rng(1)
+    X = tiny.vectors.astype(np.int64)
+    for l in np.flatnonzero(S >= s.T):
+        loc = M[O[l]:O[l] + S[l]]
+        for j in rng.integers(0, S[l], size=12):
+            d = ((X[loc] - X[loc[j]][None, :]) ** 2).sum(axis=1)
+            d[j] = np.iinfo(np.int64).max          # no self edge
+            want = np.lexsort((np.arange(S[l]), d))[:s.graph_degree]
+            assert np.array_equal(G[O[l] + j], want), (l, j)
+    assert G.min() >= 0
+    # every entry is a local id of its own list
+    for l in np.flatnonzero(S >= s.T):
+        assert G[O[l]:O[l] + S[l]].max() < S[l]
+
+
+def test_lazy_graph_rows_equal_eager(tiny, tiny_oracle):
+    s = tiny.spec
+    lazy = OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, s.graph_degree,
+                       lazy_graph=True)
+    S, O, G = tiny_oracle.S, tiny_oracle.O_HS, tiny_oracle.G_HS
+    for l in np.flatnonzero(S >= s.T)[:3]:
+        for j in (0, 7, int(S[l]) - 1):
+            assert np.array_equal(lazy.graph_row(l, j), G[O[l] + j])
+    a = lazy.search(tiny.queries[:200], tiny.qlabel_offsets[:201], tiny.qlabel_ids[:200], 10, 32, 1, 20)
+    b = tiny_oracle.search(tiny.queries[:200], tiny.qlabel_offsets[:201], tiny.qlabel_ids[:200], 10, 32, 1, 20)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_build_rejects_bad_arguments(tiny):
+    s = tiny.spec
+    with pytest.raises(ValueError):   # T must leave room for R neighbours besides the vertex itself
+        OracleIndex(tiny.vectors[:100], tiny.label_offsets[:101], tiny.label_ids[:tiny.label_offsets[100]],
+                    s.n_labels, 16, 16)
+    with pytest.raises(ValueError):   # label id outside the vocabulary
+        OracleIndex(tiny.vectors[:100], tiny.label_offsets[:101], tiny.label_ids[:tiny.label_offsets[100]],
+                    3, 500, 16)
+
+
+# ------------------------------------------------------------------ routing (Section 4.1.2 eq., Section 4.3.2)
+
+def test_routing_threshold_and_boundary(tiny, tiny_oracle):
+    s = tiny.spec
+    S = tiny_oracle.S
+    _, _, info = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, s.k, s.itopk, s.width,
+                                    s.iters, with_info=True)
+    ql = tiny.qlabel_ids
+    want = np.where(S[ql] == 0, 0, np.where(S[ql] < s.T, 1, 2))
+    assert np.array_equal(info["method"], want)
+    assert np.array_equal(info["route_label"], np.where(S[ql] == 0, -1, ql))
+    lab_T = int(np.flatnonzero(S == s.T)[0])
+    _, _, info = tiny_oracle.search(tiny.queries[:1], np.array([0, 1]), np.array([lab_T]), s.k, s.itopk, 1, 5,
+                                    with_info=True)
+    assert info["method"][0] == 2
+
+
+def test_and_searches_smallest_list_paper_example():
+    g = _gold("paper_examples.json")["and_list_choice"]
+    nA, nB, nC = g["label_sizes"]["A"], g["label_sizes"]["B"], g["label_sizes"]["C"]
+    n = nA
+    X = (np.arange(n) % 251).astype(np.uint8).reshape(n, 1)
+    # label ids: A=0, B=1, C=2; B is carried by the first nB points, C by the first nC
+    cnt = 1 + (np.arange(n) < nB) + (np.arange(n) < nC)
+    off = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(cnt, out=off[1:])
+    ids = np.empty(off[-1], dtype=np.int32)
+    for i in range(n):
+        labs = [0] + ([1] if i < nB else []) + ([2] if i < nC else [])
+        ids[off[i]:off[i + 1]] = labs
+    ix = OracleIndex(X, off, ids, 3, 100_000, 2, lazy_graph=True)   # T above every list: scan path
+    assert list(ix.S) == [nA, nB, nC]
+    _, _, info = ix.search(X[:1], np.array([0, 3]), np.array([0, 1, 2]), 5, with_info=True)
+    assert info["route_label"][0] == {"A": 0, "B": 1, "C": 2}[g["searched"]]
+    assert info["counters"][0, 2] == nB          # exactly the smallest list was predicate-tested
+    # ties in list size go to the lower label id
+    ix2 = OracleIndex(X[:10], np.arange(0, 21, 2), np.tile(np.array([1, 0], dtype=np.int32), 10), 2, 1000, 2,
+                      lazy_graph=True)
+    _, _, info = ix2.search(X[:1], np.array([0, 2]), np.array([1, 0]), 5, with_info=True)
+    assert info["route_label"][0] == 0
+
+
+# ------------------------------------------------------------------ predicate (Section 4.3.2)
+
+def test_predicate_paper_example():
+    g = _gold("paper_examples.json")["predicate"]
+    ok, pos = oracle.predicate(g["point_labels"], g["query_labels"])
+    assert ok == g["found"]
+    assert pos[0] == g["position_of_smallest"] and pos[2] == g["position_of_largest"]
+    lo, hi = g["middle_search_range"]
+    assert lo <= pos[1] <= hi and pos[1] == g["position_of_middle"]
+    assert lo == pos[0] + 1 and hi == pos[2] - 1
+
+
+def test_predicate_equals_subset_test():
+    rng = np.random.default_rng(3)
+    for _ in range(3000):
+        pl = np.unique(rng.integers(0, 24, size=rng.integers(0, 12)))
+        ql = np.unique(rng.integers(0, 24, size=rng.integers(1, 5)))
+        ok, pos = oracle.predicate(pl, ql)
+        assert ok == set(ql.tolist()).issubset(set(pl.tolist()))
+        if ok:
+            assert np.array_equal(pl[pos], ql)
+
+
+# ------------------------------------------------------------------ interleaved layout (Section 4.2.2)
+
+def test_interleaved_layout_paper_example():
+    n, dim = 70, 12
+    v = (np.arange(n)[:, None] * 100 + np.arange(dim)[None, :]).astype(np.float32)
+    out = oracle.store_interleaved(v)
+    veclen = 4                                    # 16 / sizeof(float32)
+    g = _gold("paper_examples.json")["interleaved_float32"]["order_prefix"]
+    # (v0[0:3], v1[0:3], ..., v31[0:3], v0[4:7], v1[4:7], ...)
+    where = {"v0": 0, "v1": 1, "v31": 31}
+    for name, lo, hi in g:
+        vec, chunk = where[name], lo // veclen
+        pos = (chunk * 32 + vec) * veclen
+        assert np.array_equal(out[pos:pos + veclen], v[vec, lo:hi + 1])
+    # round trip of the whole table, ragged last group zero-filled
+    n_chunks = dim // veclen
+    blk = out.reshape(-1, n_chunks, 32, veclen)   # [group][chunk][vector][element]
+    back = blk.transpose(0, 2, 1, 3).reshape(-1, dim)
+    assert np.array_equal(back[:n], v)
+    assert not back[n:].any()
+    u = np.arange(40 * 32, dtype=np.uint8).reshape(40, 32)
+    bu = oracle.store_interleaved(u).reshape(-1, 2, 32, 16).transpose(0, 2, 1, 3).reshape(-1, 32)
+    assert np.array_equal(bu[:40], u)
+
+
+# ------------------------------------------------------------------ distances
+
+def test_distance_closed_forms():
+    rng = np.random.default_rng(5)
+    for dim in (1, 4, 31, 32, 96, 128, 200):
+        q = rng.integers(-8, 9, size=dim).astype(np.float32)
+        x = rng.integers(-8, 9, size=dim).astype(np.float32)
+        # small integers: every partial sum is exact, so any summation order gives the integer result
+        assert oracle.dist_f32_ordered(q, x) == float(((q.astype(np.int64) - x.astype(np.int64)) ** 2).sum())
+        qu = rng.integers(0, 256, size=dim).astype(np.uint8)
+        xu = rng.integers(0, 256, size=dim).astype(np.uint8)
+        assert oracle.dist_u8(qu, xu) == int(((qu.astype(np.int64) - xu.astype(np.int64)) ** 2).sum())
+        qf = rng.standard_normal(dim).astype(np.float32)
+        xf = rng.standard_normal(dim).astype(np.float32)
+        exact = ((qf.astype(np.float64) - xf.astype(np.float64)) ** 2).sum()
+        # fp32 accumulation over <= dim terms: relative error well inside (dim+2) * 2^-24
+        assert abs(oracle.dist_f32_ordered(qf, xf) - exact) <= (dim + 2) * 2.0 ** -24 * exact
+    assert oracle.dist_f32_ordered(np.ones(7), np.ones(7)) == 0.0
+    # swapping the operands cannot change a squared difference
+    assert oracle.dist_f32_ordered(qf, xf) == oracle.dist_f32_ordered(xf, qf)
+
+
+# ------------------------------------------------------------------ scan path = exact filtered kNN (Def. 1)
+
+def test_scan_equals_brute_force_uint8(tiny, tiny_oracle):
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    ids, dists, info = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, s.k, s.itopk,
+                                          s.width, s.iters, with_info=True)
+    scan_q = np.flatnonzero(info["method"] == 1)
+    assert len(scan_q) > 100
+    for j in scan_q[:300]:
+        wi, wd = filtered_knn(tiny.vectors, mem, tiny.queries[j], [tiny.qlabel_ids[j]], s.k)
+        assert np.array_equal(ids[j], wi)
+        assert np.array_equal(dists[j].astype(np.float64), wd)    # integer distances: exact
+
+
+def test_force_scan_is_exact_filtered_knn_with_and(tiny, tiny_oracle):
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    rng = np.random.default_rng(7)
+    nq = 150
+    # AND pairs, some with empty intersections, some repeated labels
+    a = rng.integers(0, 12, size=nq).astype(np.int32)
+    b = rng.integers(0, 40, size=nq).astype(np.int32)
+    qoff = np.arange(0, 2 * nq + 1, 2)
+    qids = np.stack([a, b], axis=1).reshape(-1)
+    ids, dists = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, force_scan=True)
+    n_short = 0
+    for j in range(nq):
+        wi, wd = filtered_knn(tiny.vectors, mem, tiny.queries[j], [a[j], b[j]], s.k)
+        assert np.array_equal(ids[j], wi)
+        assert np.array_equal(dists[j].astype(np.float64), wd)
+        n_short += int((wi < 0).any())
+    assert n_short > 0           # padding with (-1, +inf) was exercised
+
+
+def test_scan_float_matches_brute_force():
+    w = make_workload("c2", n=6000, nq=120, n_labels=60, n_clusters=16, T=400)
+    s = w.spec
+    ix = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, 8, lazy_graph=True)
+    mem = membership(w.label_offsets, w.label_ids, s.n_labels)
+    ids, dists = ix.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, force_scan=True)
+    for j in range(s.nq):
+        wi, wd = filtered_knn(w.vectors, mem, w.queries[j], [w.qlabel_ids[j]], 10)
+        assert np.array_equal(ids[j], wi)
+        ok = wi >= 0
+        assert np.allclose(dists[j][ok], wd[ok], rtol=1e-6)
+
+
+# ------------------------------------------------------------------ beam search (Alg. 2 loop) -- pins of this repo's reading
+
+def _hand_index():
+    g = _gold("beam_hand_worked.json")
+    X = np.array(g["values"], dtype=np.uint8).reshape(-1, 1)
+    n = len(X)
+    ix = OracleIndex(X, np.arange(n + 1), np.zeros(n, dtype=np.int32), 1, g["T"], g["R"])
+    return g, X, ix
+
+
+def test_beam_hand_worked_example():
+    g, X, ix = _hand_index()
+    assert np.array_equal(ix.G_HS, np.array(g["graph_rows"]))
+    for c in g["cases"]:
+        q = np.array([[c["query"]]], dtype=np.uint8)
+        ids, dists, info = ix.search(q, np.array([0, 1]), np.array([0]), c["k"], c["itopk"], c["width"], c["iters"],
+                                     c["n_seeds"], with_info=True)
+        assert ids[0].tolist() == c["ids"], c["why"]
+        assert dists[0].tolist() == c["dists"]
+        assert info["counters"][0, 0] == c["n_scored"] and info["counters"][0, 1] == c["n_expanded"]
+
+
+def _small_graph_workload(dtype):
+    base = "tiny" if dtype == "uint8" else "c2"
+    return make_workload(base, n=1500, nq=80, n_labels=12, n_clusters=6, T=17, graph_degree=16)
+
+
+@pytest.mark.parametrize("dtype", ["uint8", "float32"])
+def test_beam_with_every_vertex_seeded_is_exact(dtype):
+    """itopk >= n and n_seeds >= n: every list member is scored, so the result
+    must be the exact filtered top-k, single label and AND alike."""
+    w = _small_graph_workload(dtype)
+    s = w.spec
+    ix = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    mem = membership(w.label_offsets, w.label_ids, s.n_labels)
+    big = int(ix.S.max())
+    rng = np.random.default_rng(11)
+    other = rng.integers(0, s.n_labels, size=s.nq).astype(np.int32)
+    for qoff, qids in ((w.qlabel_offsets, w.qlabel_ids),
+                       (np.arange(0, 2 * s.nq + 1, 2), np.stack([w.qlabel_ids, other], 1).reshape(-1))):
+        ids, dists, info = ix.search(w.queries, qoff, qids, 10, itopk=big, width=1, iters=0, n_seeds=big,
+                                     with_info=True)
+        assert (info["method"][ix.S[info["route_label"]] >= s.T] == 2).all()
+        for j in range(s.nq):
+            labs = qids[qoff[j]:qoff[j + 1]]
+            wi, wd = filtered_knn(w.vectors, mem, w.queries[j], labs, 10)
+            assert np.array_equal(ids[j], wi), j
+            ok = wi >= 0
+            assert np.allclose(dists[j][ok], wd[ok], rtol=1e-5)
+
+
+def test_beam_iters_zero_returns_best_seeds(tiny, tiny_oracle):
+    s = tiny.spec
+    S, O, M = tiny_oracle.S, tiny_oracle.O_HS, tiny_oracle.M_HS
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    ids, dists, info = tiny_oracle.search(tiny.queries[:200], tiny.qlabel_offsets[:201], tiny.qlabel_ids[:200],
+                                          s.k, itopk=32, width=1, iters=0, n_seeds=48, with_info=True)
+    for j in np.flatnonzero(info["method"] == 2):
+        l = tiny.qlabel_ids[j]
+        n = int(S[l])
+        seeds_local = (np.arange(48) * n) // 48
+        seeds_global = M[O[l] + seeds_local]
+        wi, wd = filtered_knn(tiny.vectors, mem, tiny.queries[j], [l], s.k, restrict=seeds_global)
+        assert np.array_equal(ids[j], wi)
+        assert np.array_equal(dists[j].astype(np.float64), wd)
+        assert info["counters"][j, 0] == 48 and info["counters"][j, 1] == 0
+
+
+def test_beam_invariants_and_recall(tiny, tiny_oracle):
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    rng = np.random.default_rng(13)
+    nq = 400
+    # half single-label, half 2-label AND between frequent labels so the graph path is used
+    a = tiny.qlabel_ids[:nq].copy()
+    b = rng.integers(0, 8, size=nq).astype(np.int32)
+    two = rng.random(nq) < 0.5
+    cnt = np.where(two, 2, 1)
+    qoff = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum(cnt, out=qoff[1:])
+    qids = np.empty(qoff[-1], dtype=np.int32)
+    qids[qoff[:-1]] = a
+    qids[qoff[:-1][two] + 1] = b[two]
+    ids, dists, info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, itopk=64, width=2, iters=40,
+                                          n_seeds=256, with_info=True)
+    gt = np.empty_like(ids)
+    X = tiny.vectors.astype(np.int64)
+    for j in range(nq):
+        labs = np.unique(qids[qoff[j]:qoff[j + 1]])
+        got = ids[j][ids[j] >= 0]
+        assert len(np.unique(got)) == len(got)                       # no duplicates
+        assert mem[got][:, labs].all()                               # every id carries all query labels
+        assert (np.diff(dists[j][:len(got)]) >= 0).all()             # non-decreasing
+        assert np.isinf(dists[j][len(got):]).all() and (ids[j][len(got):] == -1).all()
+        d = ((X[got] - tiny.queries[j].astype(np.int64)[None, :]) ** 2).sum(axis=1)
+        assert np.array_equal(d.astype(np.float64), dists[j][:len(got)].astype(np.float64))
+        for i in range(1, len(got)):                                 # ties in ascending id
+            if dists[j][i] == dists[j][i - 1]:
+                assert got[i] > got[i - 1]
+        gt[j], _ = filtered_knn(tiny.vectors, mem, tiny.queries[j], labs, s.k)
+    graph_q = info["method"] == 2
+    assert graph_q.sum() > 100
+    single = graph_q & ~two
+    # with 256 seeds over 32 clusters the graph lists are navigable: recall must be high
+    assert recall_at_k(ids[single], gt[single]) > 0.9
+    assert recall_at_k(ids[info["method"] == 1], gt[info["method"] == 1]) == 1.0
+
+
+def test_beam_result_independent_of_visited_capacity(tiny, tiny_oracle):
+    s = tiny.spec
+    nq = 300
+    args = (tiny.queries[:nq], tiny.qlabel_offsets[:nq + 1], tiny.qlabel_ids[:nq], s.k)
+    ref = tiny_oracle.search(*args, itopk=32, width=2, iters=30, n_seeds=64, with_info=True)
+    for cap in (1, 7, 64, 1021):
+        got = tiny_oracle.search(*args, itopk=32, width=2, iters=30, n_seeds=64, visited_cap=cap, with_info=True)
+        assert np.array_equal(ref[0], got[0]) and np.array_equal(ref[1], got[1])
+    # forgetting costs extra distance evaluations, never fewer
+    tiny_cap = tiny_oracle.search(*args, itopk=32, width=2, iters=30, n_seeds=64, visited_cap=1, with_info=True)
+    assert (tiny_cap[2]["counters"][:, 0] >= ref[2]["counters"][:, 0]).all()
+
+
+def test_search_rejects_bad_arguments(tiny, tiny_oracle):
+    q = tiny.queries[:2]
+    with pytest.raises(ValueError):    # k > itopk
+        tiny_oracle.search(q, np.array([0, 1, 2]), np.array([0, 1]), 40, itopk=32)
+    with pytest.raises(ValueError):    # a query with no label
+        tiny_oracle.search(q, np.array([0, 0, 1]), np.array([0]), 10)
+    with pytest.raises(ValueError):    # label outside the vocabulary
+        tiny_oracle.search(q, np.array([0, 1, 2]), np.array([0, 100]), 10)
+
+
+def test_unknown_or_empty_label_gives_empty_rows():
+    w = make_workload("tiny", n=300, nq=4, n_labels=50, T=40, graph_degree=8)
+    ix = OracleIndex(w.vectors, w.label_offsets, w.label_ids, 60, 40, 8)     # labels 50..59 never occur
+    ids, dists = ix.search(w.queries, np.array([0, 1, 2, 4, 6]), np.array([55, 0, 0, 55, 55, 0]), 5, 32, 1, 5)
+    assert (ids[0] == -1).all() and np.isinf(dists[0]).all()
+    assert (ids[1] >= 0).any()
+    assert (ids[2] == -1).all() and (ids[3] == -1).all()
+
+
+# ------------------------------------------------------------------ recall (Eq. 1) and memory model (Section 4.2.4)
+
+def test_recall_formula():
+    a = np.array([[1, 2, 3, 4], [5, 6, 7, 8]])
+    gt = np.array([[1, 2, 9, 10], [5, 6, 7, 8]])
+    assert recall_at_k(a, gt) == (2 + 4) / 8
+
+
+def test_memory_model_worked_numbers():
+    g = _gold("paper_examples.json")["memory_model"]
+    N, D, R, Rp, b = g["N"], g["D"], g["R"], g["R_prime"], g["b"]
+    GiB = 2.0 ** 30
+    hs = N * (D + g["F_HS"] * Rp) * b / GiB
+    ls = N * D * g["F_LS"] * b / GiB
+    assert round(hs, 2) == g["hs_GiB"] and round(ls, 2) == g["ls_GiB"]
+    assert abs(hs + ls - g["total_GiB"]) < 0.011
+    assert round(N * (D + R) * b / GiB, 2) == g["single_index_GiB"]
+    assert round(N * g["F"] * b / GiB, 2) == g["mapping_GiB"]
