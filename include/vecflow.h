@@ -1,0 +1,145 @@
+/*
+ * vecflow.h -- C ABI of the MI355X (gfx950) label-filtered top-k search library.
+ *
+ * The library implements the query hot path of the dual-structured
+ * label-centric inverted index of arXiv 2506.00812: every label l owns a
+ * posting list C_l of vector ids (Section 4.1.2); lists with |C_l| >= T are
+ * searched by beam search over a per-label proximity graph ("IVF-Graph",
+ * Section 4.2.1, Alg. 2), smaller lists are scanned exhaustively ("IVF-BFS",
+ * Section 4.2.2); multi-label AND queries search the smallest of their lists and
+ * test the remaining labels with a predicate (Section 4.3.2).
+ *
+ * Conventions
+ *   - Every function returns VF_OK (0) or a negative error code and never throws
+ *     or aborts.  vf_last_error() returns a thread-local message for the last
+ *     failing call of the calling thread.
+ *   - "device" pointers are HIP device memory on the current device; "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it passes.
+ *   - Distances are squared Euclidean (no square root).
+ *   - dtype VF_U8: uint8 vectors, integer-exact distances (exactly representable in
+ *     the float output for dim <= 258).  dtype VF_F32: float32 vectors.
+ *   - Supported shapes: VF_U8 needs dim % 16 == 0, VF_F32 needs dim % 4 == 0;
+ *     16 <= dim*sizeof(elem) <= 2048; n < 2^31.
+ */
+#ifndef VECFLOW_H
+#define VECFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VF_OK 0
+#define VF_EINVAL (-1) /* bad shape / dtype / parameter / label id            */
+#define VF_ENOMEM (-2) /* host or device allocation failed                     */
+#define VF_EHIP (-3)   /* a HIP runtime call failed; text in vf_last_error()   */
+
+#define VF_U8 0
+#define VF_F32 1
+
+typedef struct vf_index vf_index; /* opaque; owned by the library */
+
+/*
+ * Index construction (Alg. 1; layout of Section 4.2.1 "redundancy bypassing" and
+ * Section 4.2.2 "interleaved" lists).
+ *
+ *   vectors        device, row-major [n][dim], dtype as given.  NOT copied: the
+ *                  index references this single global table X and the caller must
+ *                  keep it alive and unmodified for the index's lifetime.
+ *   label_offsets  host, [n+1], CSR over label_ids
+ *   label_ids      host, labels of each vector in any order; duplicates allowed
+ *   n_labels       vocabulary size; every id must lie in [0, n_labels)
+ *   T              specificity threshold on the posting-list size: |C_l| >= T ->
+ *                  graph list, 0 < |C_l| < T -> scan list (Section 4.1.1-4.1.2)
+ *   graph_degree   R, out-degree of each per-label graph; needs 1 <= R <= 64 and
+ *                  T >= R + 1
+ *   hip_stream     hipStream_t (NULL = default stream); the call returns after the
+ *                  build has completed on it
+ *   out            receives the index
+ *
+ * Per label the library keeps S (size), O (offset) and M (local -> global id map),
+ * separately for the graph ("HS") and scan ("LS") partitions, both compacted in
+ * ascending label id.  Posting lists are in ascending global id.  A graph list's
+ * rows are the exact R nearest other members of the list, as local ids, ordered by
+ * (distance, local id).
+ */
+int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                   const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                   void *hip_stream, vf_index **out);
+
+/*
+ * Batched label-filtered top-k search (Alg. 2; AND semantics of Section 4.3.2).
+ *
+ *   queries         device, row-major [nq][dim], same dtype as the index
+ *   qlabel_offsets  host, [nq+1]; every query needs at least one label
+ *   qlabel_ids      host; a query with several labels is an AND query.  Duplicates
+ *                   are ignored.  At most 8 distinct labels per query.
+ *   k               results per query, 1 <= k <= itopk
+ *   itopk           capacity of the top-M list of the graph search, <= 256
+ *   width           parents expanded per iteration, width * R <= 128
+ *   iters           number of graph iterations (fixed; the loop also ends when the
+ *                   top-M list holds no unexpanded entry)
+ *   n_seeds         initial candidates per graph query: min(n_seeds, |C_l|) local ids
+ *                   floor(j * |C_l| / n_seeds); 0 means itopk
+ *   out_ids         device [nq][k] global vector ids, ascending by (distance, id);
+ *                   -1 where fewer than k vectors qualify
+ *   out_dists       device [nq][k] squared distances; +inf where out_ids is -1
+ *   hip_stream      the search is enqueued on this stream and the call returns
+ *                   without waiting; outputs are valid once the stream has been
+ *                   synchronised.  The index holds one workspace: calls on the same
+ *                   index must be issued on one stream at a time.
+ *
+ * A query whose label (any of its labels) has an empty posting list, or whose
+ * labels have an empty intersection, yields a row of (-1, +inf); that is not an
+ * error.
+ */
+int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+              const int32_t *qlabel_ids, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
+              int64_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
+ * Exact filtered top-k (Section 3, Def. 1) for every query, graph lists included,
+ * by exhaustive scan of the smallest list with the predicate applied: the ground
+ * truth against which recall (Section 3, Eq. 1) is measured.  Arguments as in
+ * vf_search.  Synchronises the stream before returning.
+ */
+int vf_search_exact(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                    const int32_t *qlabel_ids, int32_t k, int64_t *out_ids, float *out_dists, void *hip_stream);
+
+/* Arrays that vf_index_export can copy to the host (names follow Alg. 1). */
+#define VF_ARR_S 0      /* int64 [n_labels]      |C_l|                                            */
+#define VF_ARR_O_HS 1   /* int64 [n_labels]      start of l in M_HS / G_HS rows, -1 if not a graph label */
+#define VF_ARR_O_LS 2   /* int64 [n_labels]      start of l in M_LS, -1 if not a scan label        */
+#define VF_ARR_M_HS 3   /* int32 [n_HS]          local -> global id, graph partition               */
+#define VF_ARR_M_LS 4   /* int32 [n_LS]          local -> global id, scan partition                */
+#define VF_ARR_G_HS 5   /* int32 [n_HS][R]       compacted label graphs, local ids                 */
+#define VF_ARR_GO_LS 6  /* int64 [n_labels]      first 32-vector group of l in X_LS, -1 if none    */
+#define VF_ARR_X_LS 7   /* bytes                 interleaved scan lists: [group][chunk][32][16 B]  */
+#define VF_ARR_BITSET 8 /* uint32 [n_graph_labels][ceil(n/32)]  membership bitsets, graph labels in label order */
+
+/*
+ * Copy one index array to host memory.  With host_dst == NULL only *bytes is set
+ * (the size needed); otherwise *bytes must be at least that size on entry.
+ */
+int vf_index_export(const vf_index *index, int which, void *host_dst, size_t *bytes);
+
+typedef struct vf_stats {
+    int64_t n, n_HS, n_LS, n_groups_LS;
+    int32_t dim, dtype, n_labels, T, graph_degree, n_graph_labels, n_scan_labels, chunks_per_vector;
+    int64_t bytes_graph, bytes_maps, bytes_x_ls, bytes_bitsets, bytes_meta, bytes_total;
+} vf_stats;
+
+int vf_index_stats(const vf_index *index, vf_stats *out);
+
+/* Releases the index and its workspace.  NULL is allowed. */
+void vf_index_free(vf_index *index);
+
+/* Message of the calling thread's last failing call; valid until its next call. */
+const char *vf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,616 @@
+// Host side of the C ABI declared in include/vecflow.h: index construction
+// (Alg. 1), query routing and grouping (ClassifyQueries of Alg. 2, list choice of
+// Section 4.3.2), kernel launches, export.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "../../include/vecflow.h"
+#include "vf_internal.h"
+
+namespace vf {
+
+static thread_local std::string g_err;
+void set_error(const std::string &msg) { g_err = msg; }
+
+#define VF_HIP(expr)                                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) {                                                                        \
+            set_error(std::string(#expr) + ": " + hipGetErrorString(e_));                              \
+            return e_ == hipErrorOutOfMemory ? VF_ENOMEM : VF_EHIP;                                    \
+        }                                                                                              \
+    } while (0)
+
+#define VF_REQUIRE(cond, msg)                 \
+    do {                                      \
+        if (!(cond)) {                        \
+            set_error(msg);                   \
+            return VF_EINVAL;                 \
+        }                                     \
+    } while (0)
+
+struct DevBuf {
+    void *p = nullptr;
+    size_t cap = 0;
+    int reserve(size_t bytes)
+    {
+        if (bytes <= cap) return VF_OK;
+        if (p) { (void)hipFree(p); p = nullptr; cap = 0; }
+        const size_t want = bytes + bytes / 4 + 256;
+        VF_HIP(hipMalloc(&p, want));
+        cap = want;
+        return VF_OK;
+    }
+    void release()
+    {
+        if (p) (void)hipFree(p);
+        p = nullptr; cap = 0;
+    }
+    template <class T> T *as() const { return (T *)p; }
+};
+
+struct Staging {  // pinned host blob + the event that says its last upload has finished
+    void *p = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+
+}  // namespace vf
+
+using namespace vf;
+
+struct vf_index {
+    int dtype = 0;
+    int64_t n = 0;
+    int32_t dim = 0, n_labels = 0, T = 0, R = 0, ncp = 0;
+    const void *X = nullptr;
+    // host metadata
+    std::vector<int32_t> S, hs_slot;
+    std::vector<int64_t> O_HS, O_LS, GO_LS;
+    std::vector<int32_t> graph_labels;
+    int64_t n_HS = 0, n_LS = 0, n_groups_LS = 0, bitset_words = 0;
+    int32_t n_scan_labels = 0;
+    // device
+    DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
+    // search workspace
+    DevBuf ws_blob, tmp_blk, tmp_norm;
+    Staging stage[2];
+    int stage_next = 0;
+
+    LabelMeta meta() const
+    {
+        LabelMeta m;
+        m.S = d_S.as<int32_t>(); m.O_HS = d_O_HS.as<int64_t>(); m.O_LS = d_O_LS.as<int64_t>();
+        m.hs_slot = d_hs_slot.as<int32_t>(); m.M_HS = d_M_HS.as<int32_t>(); m.M_LS = d_M_LS.as<int32_t>();
+        m.bitsets = d_bitsets.as<uint32_t>(); m.bitset_words = bitset_words;
+        return m;
+    }
+    size_t elem() const { return dtype == VF_U8 ? 1 : 4; }
+    size_t group_bytes() const { return (size_t)2 * ncp * 32 * 16; }
+};
+
+static void free_index(vf_index *ix)
+{
+    if (!ix) return;
+    DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm};
+    for (DevBuf *b : bufs) b->release();
+    for (Staging &s : ix->stage) {
+        if (s.pending) (void)hipEventSynchronize(s.done);
+        if (s.done) (void)hipEventDestroy(s.done);
+        if (s.p) (void)hipHostFree(s.p);
+    }
+    delete ix;
+}
+
+template <class T> static int upload(DevBuf &b, const std::vector<T> &v, hipStream_t s)
+{
+    int rc = b.reserve(std::max<size_t>(v.size() * sizeof(T), 16));
+    if (rc != VF_OK) return rc;
+    if (!v.empty()) VF_HIP(hipMemcpyAsync(b.p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, s));
+    return VF_OK;
+}
+
+// Exact kNN rows of one graph list: interleave the list, contract it against itself,
+// keep K candidates per vertex, order them into rows.
+static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &cand_idx, DevBuf &cand_dist, DevBuf &d_items,
+                                 hipStream_t s)
+{
+    const int64_t base = ix->O_HS[l];
+    const int32_t nl = ix->S[l];
+    const int64_t n_groups = (nl + 31) / 32;
+    const int32_t *map = ix->d_M_HS.as<int32_t>() + base;
+    launch_interleave(ix->dtype, ix->X, ix->dim, map, nullptr, nullptr, nl, n_groups, ix->ncp, ix->tmp_blk.as<uint4>(),
+                      ix->tmp_norm.p, s);
+    std::vector<ScanItem> items((size_t)n_groups);
+    for (int64_t t = 0; t < n_groups; ++t) {
+        ScanItem &it = items[(size_t)t];
+        it.group0 = 0; it.map_off = 0; it.n = nl;
+        it.q_begin = (int32_t)(t * 32);
+        it.q_count = (int32_t)std::min<int64_t>(32, nl - t * 32);
+        it.self_base = it.q_begin;
+    }
+    int rc = upload(d_items, items, s);
+    if (rc != VF_OK) return rc;
+    VF_HIP(hipStreamSynchronize(s));  // `items` is pageable host memory
+    ScanParams p{};
+    p.xblk = ix->tmp_blk.as<uint4>(); p.xnorm = ix->tmp_norm.p; p.map = map;
+    p.qsrc = ix->X; p.qrow = map; p.items = d_items.as<ScanItem>();
+    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.mode = 1;
+    p.res_idx = cand_idx.as<int32_t>(); p.res_dist = cand_dist.as<float>();
+    p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
+    launch_scan(ix->dtype, p, (int)n_groups, s);
+    launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
+                      ix->d_G.as<int32_t>() + base * ix->R, s);
+    VF_HIP(hipGetLastError());
+    return VF_OK;
+}
+
+extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                              const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                              void *hip_stream, vf_index **out)
+{
+    VF_REQUIRE(out != nullptr, "out is NULL");
+    *out = nullptr;
+    VF_REQUIRE(vectors && label_offsets && label_ids, "NULL input pointer");
+    VF_REQUIRE(dtype == VF_U8 || dtype == VF_F32, "dtype must be VF_U8 or VF_F32");
+    VF_REQUIRE(n > 0 && n < ((int64_t)1 << 31), "n must be in [1, 2^31)");
+    const int64_t row_bytes = (int64_t)dim * (dtype == VF_U8 ? 1 : 4);
+    VF_REQUIRE(dim > 0 && row_bytes % 16 == 0 && row_bytes >= 16 && row_bytes <= 2048,
+               "dim: uint8 needs dim % 16 == 0, float32 dim % 4 == 0, 16 <= bytes per vector <= 2048");
+    VF_REQUIRE(((uintptr_t)vectors & 15) == 0, "vectors must be 16-byte aligned");
+    VF_REQUIRE(n_labels > 0, "n_labels must be positive");
+    VF_REQUIRE(graph_degree >= 1 && graph_degree <= 64, "graph_degree must be in [1, 64]");
+    VF_REQUIRE(T >= graph_degree + 1, "T must be at least graph_degree + 1");
+    VF_REQUIRE(label_offsets[0] == 0, "label_offsets[0] must be 0");
+    for (int64_t i = 0; i < n; ++i) VF_REQUIRE(label_offsets[i + 1] >= label_offsets[i], "label_offsets must not decrease");
+    const int64_t n_raw = label_offsets[n];
+    for (int64_t p = 0; p < n_raw; ++p)
+        VF_REQUIRE(label_ids[p] >= 0 && label_ids[p] < n_labels, "label id outside [0, n_labels)");
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    vf_index *ix = new (std::nothrow) vf_index();
+    if (!ix) { set_error("out of host memory"); return VF_ENOMEM; }
+    struct Guard { vf_index *ix; ~Guard() { if (ix) free_index(ix); } } guard{ix};
+    ix->dtype = dtype; ix->n = n; ix->dim = dim; ix->n_labels = n_labels; ix->T = T; ix->R = graph_degree;
+    ix->X = vectors;
+    ix->ncp = (int32_t)((row_bytes / 16 + 1) / 2);
+
+    try {
+        // ---- pass 1 (Alg. 1): posting-list sizes over sorted, duplicate-free label sets
+        std::vector<int32_t> uniq((size_t)n_raw);
+        std::vector<int64_t> uoff((size_t)n + 1, 0);
+        int64_t w = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t b = label_offsets[i], e = label_offsets[i + 1], start = w;
+            for (int64_t p = b; p < e; ++p) uniq[(size_t)w++] = label_ids[p];
+            std::sort(uniq.begin() + start, uniq.begin() + w);
+            w = std::unique(uniq.begin() + start, uniq.begin() + w) - uniq.begin();
+            uoff[(size_t)i + 1] = w;
+        }
+        ix->S.assign((size_t)n_labels, 0);
+        for (int64_t p = 0; p < w; ++p) ix->S[(size_t)uniq[(size_t)p]]++;
+
+        // ---- split by T; S/O/M per partition, compacted in ascending label id
+        ix->O_HS.assign((size_t)n_labels, -1); ix->O_LS.assign((size_t)n_labels, -1);
+        ix->GO_LS.assign((size_t)n_labels, -1); ix->hs_slot.assign((size_t)n_labels, -1);
+        for (int32_t l = 0; l < n_labels; ++l) {
+            const int32_t sz = ix->S[(size_t)l];
+            if (sz >= T) {
+                ix->O_HS[(size_t)l] = ix->n_HS; ix->n_HS += sz;
+                ix->hs_slot[(size_t)l] = (int32_t)ix->graph_labels.size();
+                ix->graph_labels.push_back(l);
+            } else if (sz > 0) {
+                ix->O_LS[(size_t)l] = ix->n_LS; ix->n_LS += sz;
+                ix->GO_LS[(size_t)l] = ix->n_groups_LS; ix->n_groups_LS += (sz + 31) / 32;
+                ix->n_scan_labels++;
+            }
+        }
+        std::vector<int32_t> M_HS((size_t)ix->n_HS), M_LS((size_t)ix->n_LS);
+        {
+            std::vector<int32_t> fill((size_t)n_labels, 0);
+            for (int64_t i = 0; i < n; ++i)
+                for (int64_t p = uoff[(size_t)i]; p < uoff[(size_t)i + 1]; ++p) {
+                    const int32_t l = uniq[(size_t)p];
+                    if (ix->O_HS[(size_t)l] >= 0) M_HS[(size_t)(ix->O_HS[(size_t)l] + fill[(size_t)l]++)] = (int32_t)i;
+                    else M_LS[(size_t)(ix->O_LS[(size_t)l] + fill[(size_t)l]++)] = (int32_t)i;
+                }
+        }
+        std::vector<int32_t>().swap(uniq);
+        std::vector<int64_t>().swap(uoff);
+
+        int rc;
+        if ((rc = upload(ix->d_S, ix->S, s)) != VF_OK) return rc;
+        if ((rc = upload(ix->d_O_HS, ix->O_HS, s)) != VF_OK) return rc;
+        if ((rc = upload(ix->d_O_LS, ix->O_LS, s)) != VF_OK) return rc;
+        if ((rc = upload(ix->d_hs_slot, ix->hs_slot, s)) != VF_OK) return rc;
+        if ((rc = upload(ix->d_M_HS, M_HS, s)) != VF_OK) return rc;
+        if ((rc = upload(ix->d_M_LS, M_LS, s)) != VF_OK) return rc;
+        VF_HIP(hipStreamSynchronize(s));
+
+        // ---- scan partition: StoreInterleaved over every scan list (Section 4.2.2)
+        if (ix->n_groups_LS > 0) {
+            std::vector<int64_t> grp_src((size_t)ix->n_groups_LS);
+            std::vector<int32_t> grp_cnt((size_t)ix->n_groups_LS);
+            for (int32_t l = 0; l < n_labels; ++l) {
+                if (ix->GO_LS[(size_t)l] < 0) continue;
+                const int32_t sz = ix->S[(size_t)l];
+                for (int32_t g = 0; g < (sz + 31) / 32; ++g) {
+                    grp_src[(size_t)(ix->GO_LS[(size_t)l] + g)] = ix->O_LS[(size_t)l] + (int64_t)g * 32;
+                    grp_cnt[(size_t)(ix->GO_LS[(size_t)l] + g)] = std::min(32, sz - g * 32);
+                }
+            }
+            DevBuf d_src, d_cnt;
+            struct R2 { DevBuf &a, &b; ~R2() { a.release(); b.release(); } } r2{d_src, d_cnt};
+            if ((rc = upload(d_src, grp_src, s)) != VF_OK) return rc;
+            if ((rc = upload(d_cnt, grp_cnt, s)) != VF_OK) return rc;
+            if ((rc = ix->d_X_LS.reserve((size_t)ix->n_groups_LS * ix->group_bytes())) != VF_OK) return rc;
+            if ((rc = ix->d_xnorm_LS.reserve((size_t)ix->n_groups_LS * 32 * 4)) != VF_OK) return rc;
+            launch_interleave(dtype, vectors, dim, ix->d_M_LS.as<int32_t>(), d_src.as<int64_t>(), d_cnt.as<int32_t>(),
+                              ix->n_LS, ix->n_groups_LS, ix->ncp, ix->d_X_LS.as<uint4>(), ix->d_xnorm_LS.p, s);
+            VF_HIP(hipGetLastError());
+            VF_HIP(hipStreamSynchronize(s));
+        }
+
+        // ---- graph partition: membership bitsets and one exact kNN graph per list
+        const int32_t n_gl = (int32_t)ix->graph_labels.size();
+        ix->bitset_words = (n + 31) / 32;
+        if (n_gl > 0) {
+            const size_t bs_bytes = (size_t)n_gl * ix->bitset_words * 4;
+            if ((rc = ix->d_bitsets.reserve(bs_bytes)) != VF_OK) return rc;
+            VF_HIP(hipMemsetAsync(ix->d_bitsets.p, 0, bs_bytes, s));
+            if ((rc = ix->d_G.reserve((size_t)ix->n_HS * ix->R * 4)) != VF_OK) return rc;
+            int32_t max_list = 0;
+            for (int32_t l : ix->graph_labels) max_list = std::max(max_list, ix->S[(size_t)l]);
+            const int32_t K = dtype == VF_U8 ? ix->R : std::min(64, ix->R + 16);
+            DevBuf cand_idx, cand_dist, d_items;
+            struct R3 { DevBuf &a, &b, &c; ~R3() { a.release(); b.release(); c.release(); } } r3{cand_idx, cand_dist, d_items};
+            const int64_t max_groups = (max_list + 31) / 32;
+            if ((rc = ix->tmp_blk.reserve((size_t)max_groups * ix->group_bytes())) != VF_OK) return rc;
+            if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
+            if ((rc = cand_idx.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
+            if ((rc = cand_dist.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
+            for (int32_t l : ix->graph_labels) {
+                launch_bitset_fill(ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)l], ix->S[(size_t)l],
+                                   ix->d_bitsets.as<uint32_t>() + (int64_t)ix->hs_slot[(size_t)l] * ix->bitset_words, s);
+                if ((rc = build_graph_for_label(ix, l, K, cand_idx, cand_dist, d_items, s)) != VF_OK) return rc;
+            }
+            VF_HIP(hipStreamSynchronize(s));
+            ix->tmp_blk.release();
+            ix->tmp_norm.release();
+        }
+        VF_HIP(hipGetLastError());
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return VF_ENOMEM;
+    }
+    guard.ix = nullptr;
+    *out = ix;
+    return VF_OK;
+}
+
+// ---------------------------------------------------------------- routing
+
+namespace {
+
+struct Routed {
+    std::vector<int32_t> gq_query, gq_label;          // graph queries
+    std::vector<int32_t> others_off, others;          // [nq+1], AND partner labels per query
+    std::vector<uint64_t> scan_pairs;                 // (label << 32 | query) of scan queries
+    bool any_and = false;
+};
+
+// ClassifyQueries (Alg. 2) + smallest-list choice (Section 4.3.2).
+int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int32_t *qids, bool all_scan, Routed &r)
+{
+    VF_REQUIRE(qoff && qids, "NULL query label arrays");
+    VF_REQUIRE(qoff[0] >= 0, "qlabel_offsets[0] must be >= 0");
+    r.others_off.assign((size_t)nq + 1, 0);
+    r.others.clear();
+    r.gq_query.clear(); r.gq_label.clear(); r.scan_pairs.clear();
+    int32_t labs[kMaxOthers + 1];
+    for (int64_t j = 0; j < nq; ++j) {
+        const int64_t b = qoff[j], e = qoff[j + 1];
+        VF_REQUIRE(e > b, "every query needs at least one label");
+        int32_t nl = 0;
+        for (int64_t p = b; p < e; ++p) {
+            const int32_t l = qids[p];
+            VF_REQUIRE(l >= 0 && l < ix->n_labels, "query label outside [0, n_labels)");
+            bool seen = false;
+            for (int32_t i = 0; i < nl; ++i) seen = seen || labs[i] == l;
+            if (seen) continue;
+            VF_REQUIRE(nl <= kMaxOthers, "more than 8 distinct labels in one query");
+            labs[nl++] = l;
+        }
+        int32_t best = labs[0];
+        bool empty = false;
+        for (int32_t i = 0; i < nl; ++i) {
+            const int32_t l = labs[i];
+            const int32_t sl = ix->S[(size_t)l], sb = ix->S[(size_t)best];
+            if (sl == 0) empty = true;
+            if (sl < sb || (sl == sb && l < best)) best = l;
+        }
+        if (!empty) {
+            for (int32_t i = 0; i < nl; ++i)
+                if (labs[i] != best) r.others.push_back(labs[i]);
+            if (nl > 1) r.any_and = true;
+            if (!all_scan && ix->S[(size_t)best] >= ix->T) {
+                r.gq_query.push_back((int32_t)j);
+                r.gq_label.push_back(best);
+            } else {
+                r.scan_pairs.push_back(((uint64_t)(uint32_t)best << 32) | (uint32_t)j);
+            }
+        }
+        r.others_off[(size_t)j + 1] = (int32_t)r.others.size();
+    }
+    std::sort(r.scan_pairs.begin(), r.scan_pairs.end());
+    return VF_OK;
+}
+
+struct BlobLayout {
+    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, total;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+}  // namespace
+
+static int get_staging(vf_index *ix, size_t bytes, Staging **out)
+{
+    Staging &st = ix->stage[ix->stage_next];
+    ix->stage_next ^= 1;
+    if (st.pending) { VF_HIP(hipEventSynchronize(st.done)); st.pending = false; }
+    if (!st.done) VF_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
+    if (bytes > st.cap) {
+        if (st.p) { (void)hipHostFree(st.p); st.p = nullptr; st.cap = 0; }
+        const size_t want = bytes + bytes / 2 + 4096;
+        VF_HIP(hipHostMalloc(&st.p, want, hipHostMallocDefault));
+        st.cap = want;
+    }
+    *out = &st;
+    return VF_OK;
+}
+
+static int check_search_args(const vf_index *ix, const void *queries, int64_t nq, int32_t k, const int64_t *out_ids,
+                             const float *out_dists)
+{
+    VF_REQUIRE(ix != nullptr, "index is NULL");
+    VF_REQUIRE(nq >= 0 && nq < ((int64_t)1 << 31), "nq out of range");
+    VF_REQUIRE(nq == 0 || (queries && out_ids && out_dists), "NULL query or output pointer");
+    VF_REQUIRE(((uintptr_t)queries & 15) == 0, "queries must be 16-byte aligned");
+    VF_REQUIRE(k >= 1 && k <= 64, "k must be in [1, 64]");
+    return VF_OK;
+}
+
+// Groups the (label, query) pairs of `pairs[lo, hi)` into tiles of <= 32 queries per label.
+// group0/map_off/n of each item are filled by `locate(label, item)`.
+template <class Locate>
+static void make_items(const std::vector<uint64_t> &pairs, size_t lo, size_t hi, std::vector<int32_t> &qrow,
+                       std::vector<ScanItem> &items, Locate locate)
+{
+    size_t i = lo;
+    while (i < hi) {
+        const int32_t l = (int32_t)(pairs[i] >> 32);
+        size_t e = i;
+        while (e < hi && (int32_t)(pairs[e] >> 32) == l) ++e;
+        for (size_t t = i; t < e; t += 32) {
+            ScanItem it{};
+            locate(l, it);
+            it.q_begin = (int32_t)qrow.size();
+            it.q_count = (int32_t)std::min<size_t>(32, e - t);
+            it.self_base = -1;
+            for (size_t u = t; u < t + (size_t)it.q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
+            items.push_back(it);
+        }
+        i = e;
+    }
+}
+
+static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
+                       int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, bool exact, int64_t *out_ids,
+                       float *out_dists, hipStream_t s)
+{
+    int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
+    if (rc != VF_OK) return rc;
+    if (!exact) {
+        VF_REQUIRE(itopk >= k && itopk >= 1 && itopk <= 256, "itopk must be in [k, 256]");
+        VF_REQUIRE(width >= 1 && width <= 8 && width * ix->R <= 128, "width must be >= 1 with width * R <= 128");
+        VF_REQUIRE(iters >= 0, "iters must be >= 0");
+        VF_REQUIRE(n_seeds >= 0, "n_seeds must be >= 0");
+        if (n_seeds == 0) n_seeds = itopk;
+    }
+    if (nq == 0) return VF_OK;
+    try {
+        Routed r;
+        if ((rc = route_queries(ix, nq, qoff, qids, exact, r)) != VF_OK) return rc;
+
+        // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
+        std::vector<int32_t> qrow;
+        std::vector<ScanItem> items;
+        size_t first_hs = r.scan_pairs.size();
+        if (exact) {
+            first_hs = 0;
+            // scan labels first, graph labels after them: sort key (is_graph, label)
+            std::stable_partition(r.scan_pairs.begin(), r.scan_pairs.end(), [&](uint64_t pr) {
+                return ix->O_LS[(size_t)(pr >> 32)] >= 0;
+            });
+            while (first_hs < r.scan_pairs.size() && ix->O_LS[(size_t)(r.scan_pairs[first_hs] >> 32)] >= 0) ++first_hs;
+        }
+        make_items(r.scan_pairs, 0, first_hs, qrow, items, [&](int32_t l, ScanItem &it) {
+            it.group0 = ix->GO_LS[(size_t)l]; it.map_off = ix->O_LS[(size_t)l]; it.n = ix->S[(size_t)l];
+        });
+        const size_t n_ls_items = items.size();
+        // exact mode: one temporary interleaved copy per graph label, used right after it is made
+        struct HsRun { int32_t label; size_t item_lo, item_hi; };
+        std::vector<HsRun> hs_runs;
+        int32_t max_hs_list = 0;
+        for (size_t i = first_hs; i < r.scan_pairs.size();) {
+            const int32_t l = (int32_t)(r.scan_pairs[i] >> 32);
+            size_t e = i;
+            while (e < r.scan_pairs.size() && (int32_t)(r.scan_pairs[e] >> 32) == l) ++e;
+            const size_t lo = items.size();
+            make_items(r.scan_pairs, i, e, qrow, items, [&](int32_t ll, ScanItem &it) {
+                it.group0 = 0; it.map_off = ix->O_HS[(size_t)ll]; it.n = ix->S[(size_t)ll];
+            });
+            hs_runs.push_back({l, lo, items.size()});
+            max_hs_list = std::max(max_hs_list, ix->S[(size_t)l]);
+            i = e;
+        }
+
+        const size_t n_gq = r.gq_query.size();
+        BlobLayout L;
+        size_t o = 0;
+        L.off_gq_query = o; o = align_up(o + n_gq * 4);
+        L.off_gq_label = o; o = align_up(o + n_gq * 4);
+        L.off_others_off = o; o = align_up(o + r.others_off.size() * 4);
+        L.off_others = o; o = align_up(o + std::max<size_t>(r.others.size(), 1) * 4);
+        L.off_qrow = o; o = align_up(o + std::max<size_t>(qrow.size(), 1) * 4);
+        L.off_items = o; o = align_up(o + std::max<size_t>(items.size(), 1) * sizeof(ScanItem));
+        L.total = o;
+
+        Staging *st = nullptr;
+        if ((rc = get_staging(ix, L.total, &st)) != VF_OK) return rc;
+        char *hp = (char *)st->p;
+        if (n_gq) {
+            memcpy(hp + L.off_gq_query, r.gq_query.data(), n_gq * 4);
+            memcpy(hp + L.off_gq_label, r.gq_label.data(), n_gq * 4);
+        }
+        memcpy(hp + L.off_others_off, r.others_off.data(), r.others_off.size() * 4);
+        if (!r.others.empty()) memcpy(hp + L.off_others, r.others.data(), r.others.size() * 4);
+        if (!qrow.empty()) memcpy(hp + L.off_qrow, qrow.data(), qrow.size() * 4);
+        if (!items.empty()) memcpy(hp + L.off_items, items.data(), items.size() * sizeof(ScanItem));
+        if ((rc = ix->ws_blob.reserve(L.total)) != VF_OK) return rc;
+        char *dp = ix->ws_blob.as<char>();
+        VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, s));
+        VF_HIP(hipEventRecord(st->done, s));
+        st->pending = true;
+
+        launch_fill_out(out_ids, out_dists, nq * (int64_t)k, s);
+
+        const int32_t *d_others_off = r.any_and ? (const int32_t *)(dp + L.off_others_off) : nullptr;
+        const int32_t *d_others = (const int32_t *)(dp + L.off_others);
+
+        ScanParams sp{};
+        sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
+        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.mode = 0;
+        sp.out_ids = out_ids; sp.out_dists = out_dists; sp.out_k = k;
+        sp.others_off = d_others_off; sp.others = d_others; sp.meta = ix->meta();
+        if (n_ls_items) {
+            sp.xblk = ix->d_X_LS.as<uint4>(); sp.xnorm = ix->d_xnorm_LS.p; sp.map = ix->d_M_LS.as<int32_t>();
+            sp.items = (const ScanItem *)(dp + L.off_items);
+            launch_scan(ix->dtype, sp, (int)n_ls_items, s);
+        }
+        if (!hs_runs.empty()) {
+            const int64_t max_groups = (max_hs_list + 31) / 32;
+            if ((rc = ix->tmp_blk.reserve((size_t)max_groups * ix->group_bytes())) != VF_OK) return rc;
+            if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
+            for (const HsRun &run : hs_runs) {
+                const int32_t nl = ix->S[(size_t)run.label];
+                launch_interleave(ix->dtype, ix->X, ix->dim, ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)run.label], nullptr,
+                                  nullptr, nl, (nl + 31) / 32, ix->ncp, ix->tmp_blk.as<uint4>(), ix->tmp_norm.p, s);
+                sp.xblk = ix->tmp_blk.as<uint4>(); sp.xnorm = ix->tmp_norm.p; sp.map = ix->d_M_HS.as<int32_t>();
+                sp.items = (const ScanItem *)(dp + L.off_items) + run.item_lo;
+                launch_scan(ix->dtype, sp, (int)(run.item_hi - run.item_lo), s);
+            }
+        }
+        if (n_gq) {
+            BeamParams bp{};
+            bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>();
+            bp.gq_query = (const int32_t *)(dp + L.off_gq_query);
+            bp.gq_label = (const int32_t *)(dp + L.off_gq_label);
+            bp.others_off = d_others_off; bp.others = d_others; bp.meta = ix->meta();
+            bp.dim = ix->dim; bp.R = ix->R; bp.k = k; bp.itopk = itopk; bp.width = width; bp.iters = iters;
+            bp.n_seeds = n_seeds;
+            int32_t LP = 128;
+            while (LP < itopk + std::max(64, width * ix->R)) LP <<= 1;
+            bp.LP = LP;
+            const int64_t visits = (int64_t)itopk + (int64_t)iters * width * ix->R;
+            int32_t hb = 9;
+            while (hb < 13 && ((int64_t)1 << hb) < 2 * visits) ++hb;
+            bp.hash_bits = hb;
+            bp.out_ids = out_ids; bp.out_dists = out_dists;
+            VF_REQUIRE(beam_lds_bytes(bp, ix->dtype) <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
+            launch_beam(ix->dtype, bp, (int)n_gq, s);
+        }
+        VF_HIP(hipGetLastError());
+        if (exact) {
+            VF_HIP(hipStreamSynchronize(s));
+            ix->tmp_blk.release();
+            ix->tmp_norm.release();
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return VF_ENOMEM;
+    }
+    return VF_OK;
+}
+
+extern "C" int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                         const int32_t *qlabel_ids, int32_t k, int32_t itopk, int32_t width, int32_t iters,
+                         int32_t n_seeds, int64_t *out_ids, float *out_dists, void *hip_stream)
+{
+    return search_impl(index, queries, nq, qlabel_offsets, qlabel_ids, k, itopk, width, iters, n_seeds, false, out_ids,
+                       out_dists, (hipStream_t)hip_stream);
+}
+
+extern "C" int vf_search_exact(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                               const int32_t *qlabel_ids, int32_t k, int64_t *out_ids, float *out_dists, void *hip_stream)
+{
+    return search_impl(index, queries, nq, qlabel_offsets, qlabel_ids, k, 0, 0, 0, 0, true, out_ids, out_dists,
+                       (hipStream_t)hip_stream);
+}
+
+// ---------------------------------------------------------------- export / stats
+
+extern "C" int vf_index_export(const vf_index *ix, int which, void *host_dst, size_t *bytes)
+{
+    VF_REQUIRE(ix && bytes, "NULL argument");
+    const void *hsrc = nullptr, *dsrc = nullptr;
+    size_t need = 0;
+    std::vector<int64_t> s64;
+    switch (which) {
+    case VF_ARR_S:
+        s64.assign(ix->S.begin(), ix->S.end()); hsrc = s64.data(); need = s64.size() * 8; break;
+    case VF_ARR_O_HS: hsrc = ix->O_HS.data(); need = ix->O_HS.size() * 8; break;
+    case VF_ARR_O_LS: hsrc = ix->O_LS.data(); need = ix->O_LS.size() * 8; break;
+    case VF_ARR_GO_LS: hsrc = ix->GO_LS.data(); need = ix->GO_LS.size() * 8; break;
+    case VF_ARR_M_HS: dsrc = ix->d_M_HS.p; need = (size_t)ix->n_HS * 4; break;
+    case VF_ARR_M_LS: dsrc = ix->d_M_LS.p; need = (size_t)ix->n_LS * 4; break;
+    case VF_ARR_G_HS: dsrc = ix->d_G.p; need = (size_t)ix->n_HS * ix->R * 4; break;
+    case VF_ARR_X_LS: dsrc = ix->d_X_LS.p; need = (size_t)ix->n_groups_LS * ix->group_bytes(); break;
+    case VF_ARR_BITSET: dsrc = ix->d_bitsets.p; need = ix->graph_labels.size() * (size_t)ix->bitset_words * 4; break;
+    default: VF_REQUIRE(false, "unknown array id");
+    }
+    if (host_dst == nullptr) { *bytes = need; return VF_OK; }
+    VF_REQUIRE(*bytes >= need, "destination buffer too small");
+    *bytes = need;
+    if (need == 0) return VF_OK;
+    if (hsrc) memcpy(host_dst, hsrc, need);
+    else VF_HIP(hipMemcpy(host_dst, dsrc, need, hipMemcpyDeviceToHost));
+    return VF_OK;
+}
+
+extern "C" int vf_index_stats(const vf_index *ix, vf_stats *out)
+{
+    VF_REQUIRE(ix && out, "NULL argument");
+    memset(out, 0, sizeof(*out));
+    out->n = ix->n; out->n_HS = ix->n_HS; out->n_LS = ix->n_LS; out->n_groups_LS = ix->n_groups_LS;
+    out->dim = ix->dim; out->dtype = ix->dtype; out->n_labels = ix->n_labels; out->T = ix->T; out->graph_degree = ix->R;
+    out->n_graph_labels = (int32_t)ix->graph_labels.size(); out->n_scan_labels = ix->n_scan_labels;
+    out->chunks_per_vector = 2 * ix->ncp;
+    out->bytes_graph = ix->n_HS * ix->R * 4;
+    out->bytes_maps = (ix->n_HS + ix->n_LS) * 4;
+    out->bytes_x_ls = ix->n_groups_LS * (int64_t)ix->group_bytes() + ix->n_groups_LS * 32 * 4;
+    out->bytes_bitsets = (int64_t)ix->graph_labels.size() * ix->bitset_words * 4;
+    out->bytes_meta = (int64_t)ix->n_labels * (4 + 8 + 8 + 4);
+    out->bytes_total = out->bytes_graph + out->bytes_maps + out->bytes_x_ls + out->bytes_bitsets + out->bytes_meta;
+    return VF_OK;
+}
+
+extern "C" void vf_index_free(vf_index *ix) { free_index(ix); }
+
+extern "C" const char *vf_last_error(void) { return g_err.c_str(); }

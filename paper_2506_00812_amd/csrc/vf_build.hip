@@ -1,0 +1,166 @@
+// Build-time kernels for Alg. 1: the interleaved list layout of Section 4.2.2
+// (StoreInterleaved), per-label membership bitsets for the AND predicate of
+// Section 4.3.2, and the final ordering of graph rows.
+#include "vf_device.h"
+
+namespace vf {
+
+// One thread per 16-byte chunk slot: xblk[(g * nchunks + c) * 32 + v].
+template <int DT>
+__global__ void interleave_kernel(const char *X, int32_t row_bytes, const int32_t *map, const int64_t *grp_src,
+                                  const int32_t *grp_cnt, int64_t n, int64_t n_groups, int32_t nchunks, uint4 *xblk)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = n_groups * nchunks * 32;
+    if (t >= total) return;
+    const int v = (int)(t & 31);
+    const int64_t gc = t >> 5;
+    const int c = (int)(gc % nchunks);
+    const int64_t g = gc / nchunks;
+    int64_t src;
+    int cnt;
+    if (grp_src != nullptr) { src = grp_src[g]; cnt = grp_cnt[g]; }
+    else { src = g * 32; cnt = (int)(n - src < 32 ? n - src : 32); }
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (v < cnt && c * kChunkBytes < row_bytes)
+        val = *(const uint4 *)(X + (int64_t)map[src + v] * row_bytes + c * kChunkBytes);
+    xblk[t] = val;
+}
+
+// One thread per slot: squared norm of the vector (uint8 after the -128 shift), 0 for padding.
+template <int DT>
+__global__ void norm_kernel(const char *X, int32_t dim, const int32_t *map, const int64_t *grp_src,
+                            const int32_t *grp_cnt, int64_t n, int64_t n_groups, void *xnorm)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_groups * 32) return;
+    const int v = (int)(t & 31);
+    const int64_t g = t >> 5;
+    int64_t src;
+    int cnt;
+    if (grp_src != nullptr) { src = grp_src[g]; cnt = grp_cnt[g]; }
+    else { src = g * 32; cnt = (int)(n - src < 32 ? n - src : 32); }
+    if (DT == 0) {
+        int acc = 0;
+        if (v < cnt) {
+            const uint8_t *x = (const uint8_t *)X + (int64_t)map[src + v] * dim;
+            for (int e = 0; e < dim; ++e) { const int d = (int)x[e] - 128; acc += d * d; }
+        }
+        ((int32_t *)xnorm)[t] = acc;
+    } else {
+        float acc = 0.f;
+        if (v < cnt) {
+            const float *x = (const float *)X + (int64_t)map[src + v] * dim;
+            for (int e = 0; e < dim; ++e) acc += x[e] * x[e];
+        }
+        ((float *)xnorm)[t] = acc;
+    }
+}
+
+void launch_interleave(int dtype, const void *X, int32_t dim, const int32_t *map, const int64_t *grp_src,
+                       const int32_t *grp_cnt, int64_t n, int64_t n_groups, int32_t ncp, uint4 *xblk, void *xnorm,
+                       hipStream_t s)
+{
+    if (n_groups <= 0) return;
+    const int32_t row_bytes = dim * (dtype == 0 ? 1 : 4);
+    const int64_t total = n_groups * 2 * ncp * 32;
+    const unsigned b1 = (unsigned)((total + 255) / 256), b2 = (unsigned)((n_groups * 32 + 255) / 256);
+    if (dtype == 0) {
+        hipLaunchKernelGGL(interleave_kernel<0>, dim3(b1), dim3(256), 0, s, (const char *)X, row_bytes, map, grp_src,
+                           grp_cnt, n, n_groups, 2 * ncp, xblk);
+        hipLaunchKernelGGL(norm_kernel<0>, dim3(b2), dim3(256), 0, s, (const char *)X, dim, map, grp_src, grp_cnt, n,
+                           n_groups, xnorm);
+    } else {
+        hipLaunchKernelGGL(interleave_kernel<1>, dim3(b1), dim3(256), 0, s, (const char *)X, row_bytes, map, grp_src,
+                           grp_cnt, n, n_groups, 2 * ncp, xblk);
+        hipLaunchKernelGGL(norm_kernel<1>, dim3(b2), dim3(256), 0, s, (const char *)X, dim, map, grp_src, grp_cnt, n,
+                           n_groups, xnorm);
+    }
+}
+
+__global__ void bitset_fill_kernel(const int32_t *map, int64_t n, uint32_t *bits)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n) return;
+    const int32_t g = map[t];
+    atomicOr(&bits[g >> 5], 1u << (g & 31));
+}
+
+void launch_bitset_fill(const int32_t *map, int64_t n, uint32_t *bits, hipStream_t s)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(bitset_fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, map, n, bits);
+}
+
+// uint8: candidates come out of the int8 contraction exact and ordered; copy R of them.
+__global__ void graph_rows_copy_kernel(const int32_t *cand_idx, int64_t n, int32_t K, int32_t R, int32_t *G_rows)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * R) return;
+    const int64_t j = t / R;
+    const int e = (int)(t % R);
+    G_rows[t] = cand_idx[j * K + e];
+}
+
+// float32: the contraction's |q|^2+|x|^2-2q.x distances are rounded differently from
+// the ordered fp32 distance the search uses, so the K > R best candidates are scored
+// again with that distance and the R best by (distance, local id) become the row.
+// One wave per vertex.
+__global__ __launch_bounds__(64) void graph_rows_rerank_kernel(const char *X, int32_t row_bytes, const int32_t *map,
+                                                               int64_t n, const int32_t *cand_idx, int32_t K, int32_t R,
+                                                               int32_t *G_rows)
+{
+    extern __shared__ uint4 smem[];
+    const int lane = threadIdx.x, team = lane >> 3, tl = lane & 7;
+    const int64_t j = blockIdx.x;
+    const int nchunks = row_bytes / kChunkBytes;
+    uint4 *qv = smem;
+    uint64_t *keys = (uint64_t *)(smem + nchunks);  // [64]
+    const char *self = X + (int64_t)map[j] * row_bytes;
+    for (int i = lane; i < nchunks; i += 64) qv[i] = *(const uint4 *)(self + i * kChunkBytes);
+    keys[lane] = KEY_MAX;
+    __syncthreads();
+    for (int r0 = 0; r0 < K; r0 += 8) {
+        const int my = r0 + team;
+        const int c = my < K ? cand_idx[j * K + my] : -1;
+        const char *xrow = X + (int64_t)map[c >= 0 ? c : 0] * row_bytes;
+        const uint32_t bits = team_dist_bits_f32(qv, xrow, nchunks, tl);
+        if (tl == 0 && c >= 0) keys[my] = ((uint64_t)bits << 32) | (uint32_t)c;
+    }
+    __syncthreads();
+    wave_bitonic_sort(keys, 64, lane);
+    if (lane < R) {
+        const uint64_t key = keys[lane];
+        G_rows[j * R + lane] = key == KEY_MAX ? -1 : (int32_t)(uint32_t)key;
+    }
+}
+
+void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map, int64_t n, const int32_t *cand_idx,
+                       int32_t K, int32_t R, int32_t *G_rows, hipStream_t s)
+{
+    if (n <= 0) return;
+    if (dtype == 0) {
+        hipLaunchKernelGGL(graph_rows_copy_kernel, dim3((unsigned)((n * R + 255) / 256)), dim3(256), 0, s, cand_idx, n, K,
+                           R, G_rows);
+    } else {
+        const int32_t row_bytes = dim * 4;
+        hipLaunchKernelGGL(graph_rows_rerank_kernel, dim3((unsigned)n), dim3(64), (size_t)row_bytes + 64 * 8, s,
+                           (const char *)X, row_bytes, map, n, cand_idx, K, R, G_rows);
+    }
+}
+
+__global__ void fill_out_kernel(int64_t *ids, float *dists, int64_t count)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    ids[t] = -1;
+    dists[t] = __builtin_inff();
+}
+
+void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s)
+{
+    if (count <= 0) return;
+    hipLaunchKernelGGL(fill_out_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, ids, dists, count);
+}
+
+}  // namespace vf

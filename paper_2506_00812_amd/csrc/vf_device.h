@@ -1,0 +1,131 @@
+// Device-side helpers shared by the gfx950 kernels.
+#pragma once
+
+#include "vf_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace vf {
+
+// Membership test "global id g carries label l" (the predicate of Section 4.3.2).
+// Graph labels answer from their bitset; scan labels by binary search in their
+// ascending posting list.
+__device__ __forceinline__ bool has_label(const LabelMeta &m, int32_t l, int32_t g)
+{
+    const int32_t slot = m.hs_slot[l];
+    if (slot >= 0) return (m.bitsets[(int64_t)slot * m.bitset_words + (g >> 5)] >> (g & 31)) & 1u;
+    const int64_t off = m.O_LS[l];
+    if (off < 0) return false;
+    int32_t lo = 0, hi = m.S[l] - 1;
+    while (lo <= hi) {
+        const int32_t mid = (lo + hi) >> 1;
+        const int32_t v = m.M_LS[off + mid];
+        if (v == g) return true;
+        if (v < g) lo = mid + 1; else hi = mid - 1;
+    }
+    return false;
+}
+
+// ---------------------------------------------------------------- 8-lane teams
+
+// Sum over the 8 lanes of a team in the fixed tree ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7));
+// every lane of the team receives the result.
+__device__ __forceinline__ float team_sum_f(float v)
+{
+    v = v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));  // quad_perm [1,0,3,2]
+    v = v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));  // quad_perm [2,3,0,1]
+    v = v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x141, 0xF, 0xF, true)); // row_half_mirror
+    return v;
+}
+__device__ __forceinline__ int team_sum_i(int v)
+{
+    v = v + __builtin_amdgcn_mov_dpp(v, 0xB1, 0xF, 0xF, true);
+    v = v + __builtin_amdgcn_mov_dpp(v, 0x4E, 0xF, 0xF, true);
+    v = v + __builtin_amdgcn_mov_dpp(v, 0x141, 0xF, 0xF, true);
+    return v;
+}
+
+// Squared L2 distance between the query (16-byte chunks in qv) and the row at xrow,
+// computed by one 8-lane team; tl = lane within the team.  Lane tl handles chunks
+// tl, tl+8, ... .  fp32: lane-sequential sum of rounded (q-x)*(q-x) terms, then
+// team_sum_f -- the order that a CPU evaluation can reproduce bit for bit.
+__device__ __forceinline__ uint32_t team_dist_bits_f32(const uint4 *qv, const char *xrow, int nchunks, int tl)
+{
+    const int steps = (nchunks + 7) >> 3;
+    float acc = 0.0f;
+#pragma unroll 4
+    for (int st = 0; st < steps; ++st) {
+        const int ci = st * 8 + tl;
+        if (ci < nchunks) {
+            const uint4 x = *(const uint4 *)(xrow + ci * kChunkBytes);
+            const uint4 q = qv[ci];
+            float d;
+            d = __uint_as_float(q.x) - __uint_as_float(x.x); acc = acc + d * d;
+            d = __uint_as_float(q.y) - __uint_as_float(x.y); acc = acc + d * d;
+            d = __uint_as_float(q.z) - __uint_as_float(x.z); acc = acc + d * d;
+            d = __uint_as_float(q.w) - __uint_as_float(x.w); acc = acc + d * d;
+        }
+    }
+    return __float_as_uint(team_sum_f(acc));
+}
+
+// uint8: exact integer sum of (q-x)^2 = q.q + x.x - 2 q.x on the packed dot-product unit.
+// qq_lane = sum of q^2 over the bytes this lane handles.
+__device__ __forceinline__ int lane_qq_u8(const uint4 *qv, int nchunks, int tl)
+{
+    uint32_t qq = 0;
+    for (int ci = tl; ci < nchunks; ci += 8) {
+        const uint4 q = qv[ci];
+        qq = __builtin_amdgcn_udot4(q.x, q.x, qq, false);
+        qq = __builtin_amdgcn_udot4(q.y, q.y, qq, false);
+        qq = __builtin_amdgcn_udot4(q.z, q.z, qq, false);
+        qq = __builtin_amdgcn_udot4(q.w, q.w, qq, false);
+    }
+    return (int)qq;
+}
+__device__ __forceinline__ uint32_t team_dist_bits_u8(const uint4 *qv, int qq_lane, const char *xrow, int nchunks, int tl)
+{
+    const int steps = (nchunks + 7) >> 3;
+    uint32_t xx = 0, qx = 0;
+#pragma unroll 2
+    for (int st = 0; st < steps; ++st) {
+        const int ci = st * 8 + tl;
+        if (ci < nchunks) {
+            const uint4 x = *(const uint4 *)(xrow + ci * kChunkBytes);
+            const uint4 q = qv[ci];
+            xx = __builtin_amdgcn_udot4(x.x, x.x, xx, false); qx = __builtin_amdgcn_udot4(q.x, x.x, qx, false);
+            xx = __builtin_amdgcn_udot4(x.y, x.y, xx, false); qx = __builtin_amdgcn_udot4(q.y, x.y, qx, false);
+            xx = __builtin_amdgcn_udot4(x.z, x.z, xx, false); qx = __builtin_amdgcn_udot4(q.z, x.z, qx, false);
+            xx = __builtin_amdgcn_udot4(x.w, x.w, xx, false); qx = __builtin_amdgcn_udot4(q.w, x.w, qx, false);
+        }
+    }
+    return (uint32_t)team_sum_i(qq_lane + (int)xx - 2 * (int)qx);
+}
+
+__device__ __forceinline__ uint64_t shfl64(uint64_t v, int src)
+{
+    const uint32_t lo = __shfl((uint32_t)v, src), hi = __shfl((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t shfl_up64(uint64_t v)
+{
+    const uint32_t lo = __shfl_up((uint32_t)v, 1), hi = __shfl_up((uint32_t)(v >> 32), 1);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Bitonic sort of keys[0..n) ascending in LDS by one wave; n a power of two.
+__device__ __forceinline__ void wave_bitonic_sort(uint64_t *keys, int n, int lane)
+{
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = lane; i < n / 2; i += 64) {
+                const int a = ((i & ~(j - 1)) << 1) | (i & (j - 1)), b = a | j;
+                const bool up = (a & k) == 0;
+                const uint64_t x = keys[a], y = keys[b];
+                if ((x > y) == up) { keys[a] = y; keys[b] = x; }
+            }
+            __syncthreads();
+        }
+}
+
+}  // namespace vf

@@ -1,0 +1,106 @@
+// Internal declarations shared by the host code and the gfx950 kernels.
+// Nothing here is part of the C ABI (see include/vecflow.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+namespace vf {
+
+constexpr uint64_t KEY_MAX = ~0ull;
+constexpr int kGroup = 32;       // vectors per interleaved group (Section 4.2.2)
+constexpr int kChunkBytes = 16;  // bytes per interleaved chunk  (Section 4.2.2)
+constexpr int kMaxOthers = 7;    // AND partners per query besides the searched label
+
+// Per-label metadata on the device, used by the predicate and by the kernels to
+// slice a label's part of the compacted arrays (S, O, M of Alg. 1).
+struct LabelMeta {
+    const int32_t *S;        // [n_labels] |C_l|
+    const int64_t *O_HS;     // [n_labels] start in M_HS / graph rows, -1 if none
+    const int64_t *O_LS;     // [n_labels] start in M_LS, -1 if none
+    const int32_t *hs_slot;  // [n_labels] rank among graph labels (bitset row), -1 if none
+    const int32_t *M_HS;
+    const int32_t *M_LS;
+    const uint32_t *bitsets; // [n_graph_labels][bitset_words]
+    int64_t bitset_words;
+};
+
+// ---------------------------------------------------------------- scan / contraction kernel
+
+struct ScanItem {
+    int64_t group0;    // first 32-vector group of the list in the interleaved buffer
+    int64_t map_off;   // start of the list in `map` (local -> global id)
+    int32_t n;         // list entries
+    int32_t q_begin;   // first tile row in qrow[]
+    int32_t q_count;   // tile rows, 1..32
+    int32_t self_base; // >= 0: entry self_base + r is skipped for tile row r (graph build)
+};
+
+struct ScanParams {
+    const uint4 *xblk;      // [group][2*ncp][32] 16-byte chunks
+    const void *xnorm;      // per slot (group*32 + lane): float (f32) / int32 (u8, after -128 shift)
+    const int32_t *map;
+    const void *qsrc;       // row-major [*][dim] query rows
+    const int32_t *qrow;    // row of qsrc for each tile row
+    const ScanItem *items;
+    int32_t dim, ncp, K, mode; // mode 0: final (ids via map, row = qrow value); 1: local candidates
+    int64_t *out_ids;
+    float *out_dists;
+    int32_t out_k;
+    int32_t *res_idx;
+    float *res_dist;
+    const int32_t *others_off; // [*] per query row value: AND partner labels (mode 0 only), may be null
+    const int32_t *others;
+    LabelMeta meta;
+};
+
+void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s);
+
+// ---------------------------------------------------------------- beam search kernel
+
+struct BeamParams {
+    const void *X;           // global vectors, row-major [n][dim]
+    const void *Q;           // queries, row-major [nq][dim]
+    const int32_t *G;        // [n_HS][R] local ids
+    const int32_t *gq_query; // [n_gq] query index
+    const int32_t *gq_label; // [n_gq] searched label
+    const int32_t *others_off;
+    const int32_t *others;
+    LabelMeta meta;
+    int32_t dim, R, k, itopk, width, iters, n_seeds;
+    int32_t LP;        // list slots (power of two >= itopk + width*R)
+    int32_t hash_bits; // visited table has 1 << hash_bits slots
+    int64_t *out_ids;
+    float *out_dists;
+};
+
+size_t beam_lds_bytes(const BeamParams &p, int dtype);
+void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s);
+
+// ---------------------------------------------------------------- build-time kernels
+
+// Interleave `n_groups` groups of 32 vectors gathered through `map` (Section 4.2.2
+// layout) and compute their norms.  grp_src/grp_cnt give, per group, the first
+// position in `map` and the number of valid vectors; with grp_src == nullptr group
+// g covers map[g*32 .. min(n, g*32+32)).
+void launch_interleave(int dtype, const void *X, int32_t dim, const int32_t *map, const int64_t *grp_src,
+                       const int32_t *grp_cnt, int64_t n, int64_t n_groups, int32_t ncp, uint4 *xblk, void *xnorm,
+                       hipStream_t s);
+
+void launch_bitset_fill(const int32_t *map, int64_t n, uint32_t *bits, hipStream_t s);
+
+// Graph rows from candidate lists: u8 copies the first R candidates (already exact);
+// f32 re-scores K candidates with the ordered fp32 distance and keeps the best R.
+void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map, int64_t n, const int32_t *cand_idx,
+                       int32_t K, int32_t R, int32_t *G_rows, hipStream_t s);
+
+void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s);
+
+// ---------------------------------------------------------------- errors
+
+void set_error(const std::string &msg);
+
+}  // namespace vf

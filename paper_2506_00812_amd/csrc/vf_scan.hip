@@ -1,0 +1,221 @@
+// IVF-BFS (Section 4.2.2, Alg. 2): distances of a tile of up to 32 queries that
+// share a label against every vector of that label's posting list, fused with an
+// exact top-K selection.  The same contraction builds the per-label kNN graphs
+// (queries = the list itself) and the exact ground truth.
+//
+// Mapping to CDNA4.  One wave64 per (query tile, list).  The list is stored in
+// the paper's interleaved layout -- groups of 32 vectors, 16-byte chunks -- which
+// is exactly the B-operand layout of a 32x32 MFMA on a 64-wide wave: lanes 0..31
+// read chunk 2c of vectors 0..31 (512 contiguous bytes), lanes 32..63 chunk 2c+1.
+// So list tiles go HBM -> registers -> MFMA with fully coalesced 1 KiB loads and
+// no LDS round trip; the query tile (A operand) is staged once in LDS in the same
+// chunk-major layout.  uint8 data is shifted by -128 on the fly and contracted on
+// the int8 MFMA (exact int32); float data uses the fp32 MFMA.  Distances are
+// |q|^2 + |x|^2 - 2 q.x.
+//
+// Top-K.  Each lane ends up with the distances of 16 query rows to one list entry
+// (the MFMA accumulator layout).  A per-row threshold (the current K-th best) is
+// kept in registers; survivors are inserted, one at a time, into the row's sorted
+// list in LDS by the whole wave (one slot per lane, K <= 64).  Keys are
+// (distance bits << 32 | entry index): unsigned order == (distance, id) order.
+#include "vf_device.h"
+
+namespace vf {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int DT> struct Acc;
+template <> struct Acc<0> { using type = v16i; };
+template <> struct Acc<1> { using type = v16f; };
+
+template <int DT>
+__global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
+{
+    extern __shared__ uint4 smem[];
+    const ScanItem it = p.items[blockIdx.x];
+    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int nchunks = 2 * p.ncp, K = p.K;
+    const int row_bytes = p.dim * (DT == 0 ? 1 : 4);
+    const int real_chunks = row_bytes / kChunkBytes;
+
+    uint4 *qtile = smem;                                         // [nchunks][32]
+    uint64_t *best = (uint64_t *)(smem + nchunks * 32);          // [32][K]
+    int32_t *qrow_s = (int32_t *)(best + 32 * K);                // [32]
+    uint32_t *qnorm_s = (uint32_t *)(qrow_s + 32);               // [32] float bits / int
+
+    if (lane < 32) qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1;
+    for (int i = lane; i < 32 * K; i += 64) best[i] = KEY_MAX;
+    __syncthreads();
+
+    // ---- stage the query tile, chunk-major, and its norms
+    for (int idx = lane; idx < nchunks * 32; idx += 64) {
+        const int c = idx >> 5, r = idx & 31;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        const int qr = qrow_s[r];
+        if (qr >= 0 && c < real_chunks) {
+            v = *(const uint4 *)((const char *)p.qsrc + (int64_t)qr * row_bytes + c * kChunkBytes);
+            if (DT == 0) { v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u; }
+        }
+        qtile[idx] = v;
+    }
+    __syncthreads();
+    {
+        // row n32, chunks h, h+2, ...
+        if (DT == 0) {
+            int acc = 0;
+            for (int c = h; c < nchunks; c += 2) {
+                const uint4 v = qtile[c * 32 + n32];
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int e = (int)(int8_t)(w[i] >> (8 * b));
+                        acc += e * e;
+                    }
+            }
+            acc += __shfl_xor(acc, 32);
+            if (h == 0) qnorm_s[n32] = (uint32_t)acc;
+        } else {
+            float acc = 0.f;
+            for (int c = h; c < nchunks; c += 2) {
+                const uint4 v = qtile[c * 32 + n32];
+                const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
+            }
+            acc += __shfl_xor(acc, 32);
+            if (h == 0) qnorm_s[n32] = __float_as_uint(acc);
+        }
+    }
+    __syncthreads();
+
+    // per-lane constants for its 16 accumulator rows: row(j) = 8*(j/4) + 4*h + (j%4)
+    uint32_t qn[16], thr[16];
+    uint32_t and_rows = 0;  // bit j: row(j) is an AND query
+    uint32_t live_rows = 0; // bit j: row(j) holds a query
+    int32_t o_begin[16], o_cnt[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int row = 8 * (j >> 2) + 4 * h + (j & 3);
+        qn[j] = qnorm_s[row];
+        thr[j] = 0xFFFFFFFFu;
+        if (row < it.q_count) live_rows |= 1u << j;
+        o_begin[j] = 0; o_cnt[j] = 0;
+        if (p.others_off != nullptr && row < it.q_count) {
+            const int qr = qrow_s[row];
+            o_begin[j] = p.others_off[qr];
+            o_cnt[j] = p.others_off[qr + 1] - o_begin[j];
+            if (o_cnt[j] > 0) and_rows |= 1u << j;
+        }
+    }
+    const bool any_and = __any(and_rows != 0);
+
+    const int n_groups = (it.n + kGroup - 1) / kGroup;
+    for (int grp = 0; grp < n_groups; ++grp) {
+        const uint4 *blk = p.xblk + (it.group0 + grp) * (int64_t)(nchunks * 32);
+        typename Acc<DT>::type acc;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0;
+#pragma unroll 4
+        for (int cp = 0; cp < p.ncp; ++cp) {
+            uint4 b = blk[(2 * cp + h) * 32 + n32];
+            const uint4 a = qtile[(2 * cp + h) * 32 + n32];
+            if constexpr (DT == 0) {
+                b.x ^= 0x80808080u; b.y ^= 0x80808080u; b.z ^= 0x80808080u; b.w ^= 0x80808080u;
+                const v4i av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+                const v4i bv = {(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, acc, 0, 0, 0);
+            } else {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+            }
+        }
+        const int entry = grp * kGroup + n32;
+        const bool col_ok = entry < it.n;
+        const int64_t slot = (it.group0 + grp) * kGroup + n32;
+        uint32_t xn;
+        if (DT == 0) xn = (uint32_t)((const int32_t *)p.xnorm)[slot];
+        else xn = __float_as_uint(((const float *)p.xnorm)[slot]);
+        int32_t gid = -1;
+        if (any_and && col_ok) gid = p.map[it.map_off + entry];
+
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int rowbase = 8 * (j >> 2) + (j & 3);
+            uint32_t bits;
+            if constexpr (DT == 0) {
+                bits = (uint32_t)((int)qn[j] + (int)xn - 2 * acc[j]);
+            } else {
+                float d = (__uint_as_float(qn[j]) + __uint_as_float(xn)) - 2.0f * acc[j];
+                bits = __float_as_uint(fmaxf(d, 0.0f));
+            }
+            bool pass = col_ok && ((live_rows >> j) & 1u) && bits <= thr[j];
+            if (it.self_base >= 0) pass = pass && (entry != it.self_base + rowbase + 4 * h);
+            if (any_and) {
+                if (pass && ((and_rows >> j) & 1u)) {
+                    for (int o = 0; o < o_cnt[j] && pass; ++o) pass = has_label(p.meta, p.others[o_begin[j] + o], gid);
+                }
+            }
+            uint64_t mask = __ballot(pass);
+            while (mask) {
+                const int b = __builtin_ctzll(mask);
+                mask &= mask - 1;
+                const int hh = b >> 5, row = rowbase + 4 * hh;
+                const uint32_t kd = __shfl(bits, b);
+                const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(grp * kGroup + (b & 31));
+                const uint64_t cur = lane < K ? best[row * K + lane] : KEY_MAX;
+                const uint64_t worst = shfl64(cur, K - 1);
+                if (key >= worst) continue;
+                const int pos = __popcll(__ballot(cur < key));
+                const uint64_t up = shfl_up64(cur);
+                const uint64_t nw = lane < pos ? cur : (lane == pos ? key : up);
+                if (lane < K) best[row * K + lane] = nw;
+                const uint32_t t = (uint32_t)(shfl64(nw, K - 1) >> 32);
+                if (h == hh) thr[j] = t;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- results
+    for (int r = 0; r < it.q_count; ++r) {
+        if (lane >= K) continue;
+        const uint64_t key = best[r * K + lane];
+        const bool none = key == KEY_MAX;
+        const uint32_t hi = (uint32_t)(key >> 32), idx = (uint32_t)key;
+        float d;
+        if (none) d = __builtin_inff();
+        else d = DT == 0 ? (float)(int)hi : __uint_as_float(hi);
+        if (p.mode == 0) {
+            if (lane < p.out_k) {
+                const int64_t o = (int64_t)qrow_s[r] * p.out_k + lane;
+                p.out_ids[o] = none ? -1 : (int64_t)p.map[it.map_off + idx];
+                p.out_dists[o] = d;
+            }
+        } else {
+            const int64_t o = (int64_t)(it.q_begin + r) * K + lane;
+            p.res_idx[o] = none ? -1 : (int32_t)idx;
+            p.res_dist[o] = d;
+        }
+    }
+}
+
+static size_t scan_lds_bytes(const ScanParams &p)
+{
+    return (size_t)2 * p.ncp * 32 * 16 + (size_t)32 * p.K * 8 + 32 * 4 + 32 * 4;
+}
+
+void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s)
+{
+    if (n_items <= 0) return;
+    const size_t lds = scan_lds_bytes(p);
+    if (dtype == 0) hipLaunchKernelGGL(scan_topk_kernel<0>, dim3(n_items), dim3(64), lds, s, p);
+    else hipLaunchKernelGGL(scan_topk_kernel<1>, dim3(n_items), dim3(64), lds, s, p);
+}
+
+}  // namespace vf

@@ -1,0 +1,67 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2506_00812_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2506_00812_amd.build import build
+        build(verbose=False)
+    return binding.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "vecflow.h")).read()
+    declared = sorted(set(re.findall(r"\b(vf_[a-z_]+)\s*\(", hdr)))
+    assert declared == sorted(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_stats_struct_matches_header():
+    hdr = open(os.path.join(ROOT, "include", "vecflow.h")).read()
+    body = re.search(r"typedef struct vf_stats \{(.*?)\} vf_stats;", hdr, re.S).group(1)
+    names = [n.strip() for line in body.split(";") for n in line.replace("int64_t", "").replace("int32_t", "").split(",")
+             if n.strip()]
+    assert names == [n for n, _ in binding.VfStats._fields_]
+
+
+def test_build_rejects_bad_arguments_without_gpu(lib):
+    h = C.c_void_p()
+    off = np.array([0, 1, 2], dtype=np.int64)
+    ids = np.array([0, 5], dtype=np.int32)
+    fake = C.c_void_p(4096)    # never dereferenced: validation fails first
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    cases = [
+        dict(dtype=7, dim=16, n_labels=8, T=40, R=8),        # dtype
+        dict(dtype=0, dim=17, n_labels=8, T=40, R=8),        # dim not a multiple of 16
+        dict(dtype=1, dim=6, n_labels=8, T=40, R=8),         # float dim not a multiple of 4
+        dict(dtype=0, dim=16, n_labels=8, T=8, R=8),         # T < R + 1
+        dict(dtype=0, dim=16, n_labels=8, T=400, R=65),      # R too large
+        dict(dtype=0, dim=16, n_labels=4, T=40, R=8),        # label id 5 outside the vocabulary
+    ]
+    for c in cases:
+        rc = lib.vf_build_index(fake, c["dtype"], 2, c["dim"], p(off), p(ids), c["n_labels"], c["T"], c["R"], None,
+                                C.byref(h))
+        assert rc == -1, c
+        assert lib.vf_last_error()
+        assert not h.value
+    assert lib.vf_build_index(None, 0, 2, 16, p(off), p(ids), 8, 40, 8, None, C.byref(h)) == -1
+    lib.vf_index_free(None)    # allowed
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(binding.VecflowError):
+        binding.load_library()

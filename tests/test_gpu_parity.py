@@ -1,0 +1,243 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer (uint8) results and every graph-path result must be
+bit-exact; float scan-path results must agree within 1e-4 relative with id sets
+equal up to ties inside that tolerance."""
+import numpy as np
+import pytest
+
+from oracle import OracleIndex, store_interleaved
+from paper_2506_00812_amd.workloads import make_workload
+from tests.bruteforce import membership, recall_at_k
+from tests.gpu_util import assert_close_with_ties, assert_exact, to_np
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-4   # float distance tolerance stated for this path
+
+
+@pytest.fixture(scope="module")
+def vf():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2506_00812_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _gpu_index(vf, w, **kw):
+    import torch
+    s = w.spec
+    X = torch.from_numpy(w.vectors).cuda()
+    return vf.build_index(X, w.label_offsets, w.label_ids, kw.get("n_labels", s.n_labels), kw.get("T", s.T),
+                          kw.get("R", s.graph_degree))
+
+
+def _search(vf, ix, Q, qoff, qids, k, **kw):
+    import torch
+    ids, d = vf.search(ix, Q, qoff, qids, k, **kw)
+    torch.cuda.synchronize()
+    return to_np(ids), to_np(d)
+
+
+@pytest.fixture(scope="module")
+def tiny_gpu(vf, tiny):
+    import torch
+    ix = _gpu_index(vf, tiny)
+    Q = torch.from_numpy(tiny.queries).cuda()
+    return ix, Q
+
+
+def test_tiny_index_arrays_match_oracle(vf, tiny, tiny_oracle, tiny_gpu):
+    ix, _ = tiny_gpu
+    for name in ("S", "O_HS", "O_LS", "M_HS", "M_LS"):
+        assert np.array_equal(ix.export(name), getattr(tiny_oracle, name)), name
+    G = ix.export("G_HS").reshape(-1, tiny.spec.graph_degree)
+    Go = tiny_oracle.G_HS
+    bad = np.flatnonzero((G != Go).any(axis=1))
+    assert len(bad) == 0, f"{len(bad)} graph rows differ, first {bad[:3]}: {G[bad[0]]} vs {Go[bad[0]]}"
+    st = ix.stats()
+    assert st["n_HS"] == tiny_oracle.n_HS and st["n_LS"] == tiny_oracle.n_LS
+    assert st["n_graph_labels"] == int((tiny_oracle.S >= tiny.spec.T).sum())
+
+
+def test_tiny_interleaved_lists_and_bitsets(vf, tiny, tiny_oracle, tiny_gpu):
+    ix, _ = tiny_gpu
+    s = tiny.spec
+    S, O_LS, M_LS, GO = tiny_oracle.S, tiny_oracle.O_LS, tiny_oracle.M_LS, ix.export("GO_LS")
+    X_LS = ix.export("X_LS")
+    gbytes = 32 * s.dim
+    for l in np.flatnonzero((S > 0) & (S < s.T)):
+        want = store_interleaved(tiny.vectors[M_LS[O_LS[l]:O_LS[l] + S[l]]])     # Section 4.2.2 layout
+        got = X_LS[GO[l] * gbytes: GO[l] * gbytes + len(want)]
+        assert np.array_equal(got, want), l
+    bits = ix.export("BITSET").reshape(-1, (s.n + 31) // 32)
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    for slot, l in enumerate(np.flatnonzero(S >= s.T)):
+        unpacked = np.unpackbits(bits[slot].view(np.uint8), bitorder="little")[:s.n].astype(bool)
+        assert np.array_equal(unpacked, mem[:, l]), l
+
+
+@pytest.mark.parametrize("params", [
+    dict(itopk=32, width=1, iters=20, n_seeds=0),          # the configuration's own parameters
+    dict(itopk=64, width=2, iters=30, n_seeds=256),
+    dict(itopk=32, width=4, iters=10, n_seeds=100),
+    dict(itopk=128, width=1, iters=64, n_seeds=3000),
+    dict(itopk=256, width=8, iters=3, n_seeds=64),
+    dict(itopk=32, width=1, iters=0, n_seeds=48),
+])
+def test_tiny_search_bit_exact(vf, tiny, tiny_oracle, tiny_gpu, params):
+    ix, Q = tiny_gpu
+    k = tiny.spec.k
+    ig, dg = _search(vf, ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k, **params)
+    io, do = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, k, **params)
+    assert_exact(ig, dg, io, do, f"tiny {params}")
+
+
+def _and_queries(nq, n_labels, seed, hi_a=12, hi_b=40):
+    rng = np.random.default_rng(seed)
+    a = rng.integers(0, hi_a, size=nq).astype(np.int32)
+    b = rng.integers(0, min(hi_b, n_labels), size=nq).astype(np.int32)
+    c = rng.integers(0, 6, size=nq).astype(np.int32)
+    three = rng.random(nq) < 0.2
+    cnt = np.where(three, 3, 2)
+    qoff = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum(cnt, out=qoff[1:])
+    qids = np.empty(qoff[-1], dtype=np.int32)
+    qids[qoff[:-1]] = a
+    qids[qoff[:-1] + 1] = b
+    qids[qoff[:-1][three] + 2] = c[three]
+    return qoff, qids
+
+
+def test_tiny_and_queries_bit_exact(vf, tiny, tiny_oracle, tiny_gpu):
+    ix, Q = tiny_gpu
+    nq, k = 600, 10
+    qoff, qids = _and_queries(nq, tiny.spec.n_labels, 21)
+    for params in (dict(itopk=64, width=1, iters=40, n_seeds=256), dict(itopk=32, width=2, iters=10, n_seeds=0)):
+        ig, dg = _search(vf, ix, Q[:nq], qoff, qids, k, **params)
+        io, do, info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, k, with_info=True, **params)
+        assert (info["method"] == 2).sum() > 50 and (info["method"] == 1).sum() > 50
+        assert (io[:, -1] == -1).any()         # short and empty rows are exercised
+        assert_exact(ig, dg, io, do, f"tiny AND {params}")
+
+
+def test_tiny_exact_search_matches_oracle_scan(vf, tiny, tiny_oracle, tiny_gpu):
+    import torch
+    ix, Q = tiny_gpu
+    k = 10
+    ig, dg = vf.search_exact(ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k)
+    io, do = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, k, force_scan=True)
+    assert_exact(to_np(ig), to_np(dg), io, do, "tiny exact")
+    qoff, qids = _and_queries(400, tiny.spec.n_labels, 22)
+    ig, dg = vf.search_exact(ix, Q[:400], qoff, qids, k)
+    io, do = tiny_oracle.search(tiny.queries[:400], qoff, qids, k, force_scan=True)
+    assert_exact(to_np(ig), to_np(dg), io, do, "tiny exact AND")
+    # recall of the configuration's own parameters against this ground truth (reported, Eq. 1)
+    ia, _ = _search(vf, ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k, itopk=32, width=1, iters=20, n_seeds=256)
+    assert recall_at_k(ia, to_np(vf.search_exact(ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k)[0])) > 0.97
+
+
+def test_edge_cases(vf, tiny, tiny_oracle, tiny_gpu):
+    import torch
+    ix, Q = tiny_gpu
+    # nq = 0
+    ids, d = vf.search(ix, Q[:0], np.array([0]), np.array([], dtype=np.int32), 10)
+    assert ids.shape == (0, 10)
+    # labels never seen (vocabulary 110 > the 100 used), duplicates inside a query, k = 1 and k = itopk
+    w = make_workload("tiny", n=3000, nq=64, T=100)
+    ixg = _gpu_index(vf, w, n_labels=110)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, 110, 100, w.spec.graph_degree)
+    Qs = torch.from_numpy(w.queries).cuda()
+    qoff = np.arange(0, 129, 2)
+    qids = np.stack([w.qlabel_ids, w.qlabel_ids], axis=1).reshape(-1).astype(np.int32)
+    qids[0:2] = (105, 0)       # AND with a label nobody carries
+    qids[2:4] = (109, 109)     # single unknown label
+    for k, itopk in ((1, 32), (32, 32), (10, 64)):
+        ig, dg = _search(vf, ixg, Qs, qoff, qids, k, itopk=itopk, width=1, iters=12, n_seeds=64)
+        io, do = ixo.search(w.queries, qoff, qids, k, itopk=itopk, width=1, iters=12, n_seeds=64)
+        assert_exact(ig, dg, io, do, f"edge k={k}")
+        assert (ig[0] == -1).all() and (ig[1] == -1).all() and np.isinf(dg[0]).all()
+    # argument errors surface as exceptions, not crashes
+    with pytest.raises(vf.VecflowError):
+        vf.search(ixg, Qs, qoff, qids, 40, itopk=32)
+    with pytest.raises(vf.VecflowError):
+        vf.search(ixg, Qs, qoff, qids, 10, itopk=512)
+    with pytest.raises(vf.VecflowError):
+        vf.search(ixg, Qs, np.zeros(65, dtype=np.int64), qids, 10)
+    bad = qids.copy(); bad[5] = 110
+    with pytest.raises(vf.VecflowError):
+        vf.search(ixg, Qs, qoff, bad, 10)
+    # results are reproducible run to run
+    a = _search(vf, ixg, Qs, qoff, qids, 10, itopk=64, width=2, iters=12, n_seeds=64)
+    b = _search(vf, ixg, Qs, qoff, qids, 10, itopk=64, width=2, iters=12, n_seeds=64)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def _float_small():
+    return make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32)
+
+
+def test_float_graph_rows_and_search(vf):
+    """float32: graph rows and the graph path are decided by the ordered fp32 distance on
+    both sides, so they must be bit-exact; the scan path uses the fp32 MFMA and is
+    compared within tolerance."""
+    import torch
+    w = _float_small()
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    for name in ("S", "O_HS", "O_LS", "M_HS", "M_LS"):
+        assert np.array_equal(ix.export(name), getattr(ixo, name)), name
+    G = ix.export("G_HS").reshape(-1, s.graph_degree)
+    bad = np.flatnonzero((G != ixo.G_HS).any(axis=1))
+    assert len(bad) == 0, f"{len(bad)} of {len(G)} float graph rows differ, first {bad[:3]}"
+    Q = torch.from_numpy(w.queries).cuda()
+    for params in (dict(itopk=64, width=1, iters=32, n_seeds=0), dict(itopk=32, width=2, iters=16, n_seeds=512),
+                   dict(itopk=128, width=4, iters=20, n_seeds=2048)):
+        ig, dg = _search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+        io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+        g = info["method"] == 2
+        assert g.sum() > 300 and (~g).sum() > 100
+        assert_exact(ig[g], dg[g], io[g], do[g], f"float graph {params}")
+        assert_close_with_ties(ig[~g], dg[~g], io[~g], do[~g], RTOL, f"float scan {params}")
+    ie, de = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10)
+    io, do = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, force_scan=True)
+    assert_close_with_ties(to_np(ie), to_np(de), io, do, RTOL, "float exact")
+
+
+def test_float_and_dim96(vf):
+    import torch
+    w = make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    G = ix.export("G_HS").reshape(-1, s.graph_degree)
+    assert np.array_equal(G, ixo.G_HS)
+    Q = torch.from_numpy(w.queries).cuda()
+    params = dict(itopk=64, width=2, iters=24, n_seeds=512)
+    ig, dg = _search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+    io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+    g = info["method"] == 2
+    assert g.sum() > 100 and (info["method"] == 1).sum() > 100
+    assert_exact(ig[g], dg[g], io[g], do[g], "dim96 AND graph")
+    assert_close_with_ties(ig[~g], dg[~g], io[~g], do[~g], RTOL, "dim96 AND scan")
+
+
+def test_uint8_dim192_mixed_queries(vf):
+    import torch
+    w = make_workload("c3", n=25_000, nq=2000, n_labels=3000, n_clusters=64, T=300, graph_degree=32)
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    for name in ("S", "O_HS", "O_LS", "M_HS", "M_LS"):
+        assert np.array_equal(ix.export(name), getattr(ixo, name)), name
+    assert np.array_equal(ix.export("G_HS").reshape(-1, s.graph_degree), ixo.G_HS)
+    Q = torch.from_numpy(w.queries).cuda()
+    params = dict(itopk=64, width=1, iters=32, n_seeds=512)
+    ig, dg = _search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+    io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+    assert (info["method"] == 2).sum() > 200 and (info["method"] == 1).sum() > 200
+    assert_exact(ig, dg, io, do, "dim192 mixed")
+    ie, de = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10)
+    io, do = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, force_scan=True)
+    assert_exact(to_np(ie), to_np(de), io, do, "dim192 exact")
