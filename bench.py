@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the label-filtered search hot path on one MI355X.
+
+One "step" = one vf_search call over the whole query batch of the workload
+(route + IVF-BFS scan + IVF-Graph beam search + AND predicate + finalise), with the
+index, the queries and the outputs already resident in HBM.  The workload is the
+SIFT-1M-like configuration the metric is quoted on: N = 1e6 float32 vectors of
+dim 128, 1,000 Zipf labels, T = 10,000, graph degree 32, 10,000 single-label
+queries, k = 10 (seeded synthetic stand-in).
+
+Prints ONE JSON line.  `value` is queries/s at the cheapest parameter setting of a
+small candidate list whose recall@10, measured in this run against exact filtered
+ground truth, is >= 0.90; the >= 0.99 operating point is reported beside it.
+`roofline` prices the dominant kernel (beam search) against HBM peak using the
+algorithmic bytes its own work counters imply; `cpu_baseline` times the CPU oracle
+on a bounded sample of the same queries.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+# (itopk, width, iters, n_seeds), roughly by increasing cost
+CANDIDATES = [
+    (32, 1, 8, 1024), (32, 1, 8, 2048), (32, 1, 12, 2048), (32, 1, 12, 3072), (32, 1, 16, 4096),
+    (64, 1, 16, 4096), (64, 1, 24, 6144), (64, 1, 32, 8192), (64, 2, 24, 8192), (128, 2, 32, 12288),
+    (128, 2, 48, 16384), (256, 4, 48, 16384),
+]
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def recall_at_k(found, truth):
+    """Eq. (1) of the paper with |GT| in the denominator when fewer than K vectors match."""
+    num = den = 0
+    for f, t in zip(found, truth):
+        t = t[t >= 0]
+        if len(t) == 0:
+            continue
+        num += np.isin(f[f >= 0], t).sum()
+        den += len(t)
+    return float(num) / max(den, 1)
+
+
+def time_search(vf, ix, Q, qoff, qids, k, params, steps, warmup, out_ids, out_dists):
+    import torch
+    itopk, width, iters, n_seeds = params
+    for _ in range(warmup):
+        vf.search(ix, Q, qoff, qids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        vf.search(ix, Q, qoff, qids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--n", type=int, default=None, help="override the number of vectors (testing only)")
+    ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--T", type=int, default=None)
+    ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-sample", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_00812_amd import binding as vf
+    from paper_2506_00812_amd.workloads import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    vf.load_library()
+
+    t0 = time.time()
+    w = make_workload(args.workload, n=args.n, nq=args.nq, T=args.T)
+    s = w.spec
+    log(f"[bench] workload {s.name}: n={s.n} dim={s.dim} {s.dtype} labels={s.n_labels} T={s.T} R={s.graph_degree} "
+        f"nq={s.nq} generated in {time.time() - t0:.1f}s")
+    X = torch.from_numpy(w.vectors).cuda()
+    Q = torch.from_numpy(w.queries).cuda()
+    t0 = time.time()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    st = ix.stats()
+    log(f"[bench] index built in {build_s:.1f}s: {st['n_graph_labels']} graph labels ({st['n_HS']} postings), "
+        f"{st['n_scan_labels']} scan labels ({st['n_LS']} postings), {st['bytes_total'] / 2**20:.0f} MiB")
+
+    k = s.k
+    t0 = time.time()
+    gt_ids, _ = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, k)
+    gt = gt_ids.cpu().numpy()
+    log(f"[bench] exact filtered ground truth in {time.time() - t0:.1f}s")
+
+    out_ids = torch.empty((s.nq, k), dtype=torch.int64, device="cuda")
+    out_dists = torch.empty((s.nq, k), dtype=torch.float32, device="cuda")
+
+    # ---- pick the operating points: cheapest candidates reaching recall 0.90 and 0.99
+    table = []
+    for params in CANDIDATES:
+        if params[1] * s.graph_degree > 128:
+            continue
+        ms = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, params, 3, 1, out_ids, out_dists)
+        rec = recall_at_k(out_ids.cpu().numpy(), gt)
+        table.append((params, rec, s.nq / ms * 1e3))
+        if args.sweep:
+            log(f"[sweep] itopk={params[0]:3d} width={params[1]} iters={params[2]:2d} n_seeds={params[3]:5d} "
+                f"recall@{k}={rec:.4f} qps={s.nq / ms * 1e3:,.0f}")
+        have90 = any(r >= 0.90 for _, r, _ in table)
+        have99 = any(r >= 0.99 for _, r, _ in table)
+        if have90 and have99 and not args.sweep:
+            break
+
+    def best(th):
+        ok = [t for t in table if t[1] >= th]
+        return max(ok, key=lambda t: t[2]) if ok else None
+
+    p90, p99 = best(0.90), best(0.99)
+    headline = p90 or max(table, key=lambda t: t[1])
+
+    # ---- timed region: exactly K steps at the recall >= 0.90 operating point, profiling events on
+    ix.profile_enable(True)
+    itopk, width, iters, n_seeds = headline[0]
+    for _ in range(args.warmup):
+        vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
+    torch.cuda.synchronize()
+    ix.profile_enable(True)      # resets the duration sums: warm-up steps are not counted
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    pf = ix.profile_read()
+    assert pf["calls"] == args.steps
+    beam_avg_ms = pf["beam_ms_sum"] / pf["calls"]
+    scan_avg_ms = pf["scan_ms_sum"] / pf["calls"]
+    ix.profile_enable(False)
+    recall_head = recall_at_k(out_ids.cpu().numpy(), gt)
+
+    eb = 1 if s.dtype == "uint8" else 4
+    vec_bytes = s.dim * eb
+    beam_bytes = (pf["beam_scored"] * (vec_bytes + 4) + pf["beam_expanded"] * s.graph_degree * 4
+                  + pf["beam_tested"] * 4 + pf["n_graph_queries"] * (vec_bytes + k * 12))
+    scan_bytes = pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12)
+    achieved = beam_bytes / (beam_avg_ms * 1e-3) / 1e9 if beam_avg_ms > 0 else 0.0
+    roofline = {
+        "kernel": "beam_kernel (IVF-Graph search)", "bound": "hbm", "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "algorithmic_bytes_per_launch": int(beam_bytes), "avg_launch_ms": round(beam_avg_ms, 4),
+        "graph_queries_per_launch": int(pf["n_graph_queries"]),
+        "distances_per_graph_query": round(pf["beam_scored"] / max(pf["n_graph_queries"], 1), 1),
+        "scan_kernel": {"avg_launch_ms": round(scan_avg_ms, 4), "algorithmic_bytes_per_launch": int(scan_bytes),
+                        "achieved_GBs": round(scan_bytes / (max(scan_avg_ms, 1e-6) * 1e-3) / 1e9, 1),
+                        "flops_per_launch": int(2 * pf["scan_pairs"] * s.dim)},
+    }
+
+    # second operating point, timed the plain way
+    extra = {}
+    if p99 is not None:
+        ms99 = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, p99[0], args.steps, args.warmup, out_ids,
+                           out_dists)
+        extra = {"qps_at_recall_0.99": round(s.nq / ms99 * 1e3, 1), "recall_0.99_measured": round(p99[1], 4),
+                 "params_0.99": dict(zip(("itopk", "width", "iters", "n_seeds"), p99[0]))}
+    else:
+        extra = {"qps_at_recall_0.99": None, "recall_ceiling": round(max(t[1] for t in table), 4)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same queries
+    cpu = None
+    if not args.no_cpu:
+        from oracle import OracleIndex
+        rng = np.random.default_rng(12345)
+        sample = np.sort(rng.choice(s.nq, size=min(args.cpu_sample, s.nq), replace=False))
+        cores = os.cpu_count() or 1
+        cores = min(cores, 16)
+        qs = np.ascontiguousarray(w.queries[sample])
+        qo = np.arange(len(sample) + 1, dtype=np.int64)
+        ql = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[sample]])
+        t0 = time.time()
+        ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True,
+                          n_threads=cores)
+        ids_o, d_o = ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds)       # untimed: builds the graph rows it touches
+        log(f"[bench] oracle index (lazy graph rows) + first pass over {len(sample)} queries: {time.time() - t0:.1f}s")
+        reps, spent = 0, 0.0
+        t0 = time.perf_counter()
+        while spent < 3.0 and reps < 200:
+            ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds)
+            reps += 1
+            spent = time.perf_counter() - t0
+        cpu_qps = reps * len(sample) / spent
+        gpu_rows = out_ids.cpu().numpy()[sample]     # same parameters as the timed region
+        agree = float(np.mean([np.array_equal(a, b) for a, b in zip(gpu_rows, ids_o)]))
+        cpu = {"value": round(cpu_qps, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": f"{len(sample)} of the {s.nq} queries (seeded random sample), same parameters as the timed "
+                         f"region, {reps} timed passes after one untimed pass that builds the graph rows touched",
+               "rows_identical_to_gpu": round(agree, 4)}
+
+    line = {
+        "metric": "filtered QPS at recall@10 >= 0.90", "value": round(s.nq / ms_per_step * 1e3, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if s.dtype == "float32" else "u8", "data": "synthetic",
+        "config": {"workload": f"{s.name}: N={s.n} dim={s.dim} {s.dtype}, {s.n_clusters} Gaussian clusters, "
+                               f"{s.n_labels} Zipf({s.zipf_alpha}) labels, T={s.T}, R={s.graph_degree}, "
+                               f"{s.nq} queries ({s.query_mode}), k={k}, seed {s.seed}",
+                   "params": dict(zip(("itopk", "width", "iters", "n_seeds"), headline[0])),
+                   "recall_at_10": round(recall_head, 4), "reached_0.90": p90 is not None,
+                   "index_build_s": round(build_s, 2), **extra},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,31 @@ typedef struct vf_stats {
 
 int vf_index_stats(const vf_index *index, vf_stats *out);
 
+/*
+ * Measurement support (not part of the paper's method).  While profiling is on,
+ * every vf_search call brackets its IVF-BFS launch and its IVF-Graph launch with HIP
+ * events on the caller's stream and has the graph kernel record, per query, how
+ * many distances it computed, rows it expanded and predicate tests it made.
+ * vf_profile_read waits for the last profiled call and reports it, together with
+ * the duration sums over all calls since vf_profile_enable(index, 1).  (A profiled
+ * call waits for the previous profiled call's kernels before it launches its own.)
+ *   per_query   optional host buffer [nq][4] int32 of the last call:
+ *               distances computed, rows expanded, predicate tests, 2 if the query
+ *               took the graph path (0 otherwise; the first three are then 0)
+ */
+typedef struct vf_profile {
+    float scan_ms, beam_ms;            /* kernel durations of the last call            */
+    double scan_ms_sum, beam_ms_sum;   /* sums over all calls since profiling was enabled */
+    int64_t calls;                     /* number of calls in those sums                */
+    int64_t nq, n_scan_queries, n_graph_queries, n_scan_items;
+    int64_t scan_list_entries;         /* sum over scan items of the list length       */
+    int64_t scan_pairs;                /* sum over scan items of queries x list length */
+    int64_t beam_scored, beam_expanded, beam_tested;
+} vf_profile;
+
+int vf_profile_enable(vf_index *index, int on);
+int vf_profile_read(vf_index *index, vf_profile *out, int32_t *per_query);
+
 /* Releases the index and its workspace.  NULL is allowed. */
 void vf_index_free(vf_index *index);
 

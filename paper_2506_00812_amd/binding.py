@@ -20,7 +20,7 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
                   GO_LS=np.int64, X_LS=np.uint8, BITSET=np.uint32)
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
-                    "vf_index_free", "vf_last_error")
+                    "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read")
 
 
 class VfStats(C.Structure):
@@ -29,6 +29,14 @@ class VfStats(C.Structure):
                                          "n_scan_labels", "chunks_per_vector")] + \
                [(n, C.c_int64) for n in ("bytes_graph", "bytes_maps", "bytes_x_ls", "bytes_bitsets", "bytes_meta",
                                          "bytes_total")]
+
+
+class VfProfile(C.Structure):
+    _fields_ = [("scan_ms", C.c_float), ("beam_ms", C.c_float), ("scan_ms_sum", C.c_double),
+                ("beam_ms_sum", C.c_double), ("calls", C.c_int64)] + \
+               [(n, C.c_int64) for n in ("nq", "n_scan_queries", "n_graph_queries", "n_scan_items",
+                                         "scan_list_entries", "scan_pairs", "beam_scored", "beam_expanded",
+                                         "beam_tested")]
 
 
 class VecflowError(RuntimeError):
@@ -57,6 +65,10 @@ def load_library():
         L.vf_index_export.argtypes = [p, C.c_int, p, C.POINTER(C.c_size_t)]
         L.vf_index_stats.restype = C.c_int
         L.vf_index_stats.argtypes = [p, C.POINTER(VfStats)]
+        L.vf_profile_enable.restype = C.c_int
+        L.vf_profile_enable.argtypes = [p, C.c_int]
+        L.vf_profile_read.restype = C.c_int
+        L.vf_profile_read.argtypes = [p, C.POINTER(VfProfile), p]
         L.vf_index_free.restype = None
         L.vf_index_free.argtypes = [p]
         L.vf_last_error.restype = C.c_char_p
@@ -108,6 +120,24 @@ class Index:
         st = VfStats()
         _check(load_library().vf_index_stats(self._h, C.byref(st)))
         return {n: getattr(st, n) for n, _ in VfStats._fields_}
+
+    def profile_enable(self, on: bool = True):
+        _check(load_library().vf_profile_enable(self._h, int(on)))
+
+    def profile_read(self, per_query: bool = False):
+        """Durations and work counters of the last profiled search; waits for it."""
+        pf = VfProfile()
+        L = load_library()
+        if per_query:
+            # nq is only known after a first read
+            _check(L.vf_profile_read(self._h, C.byref(pf), None))
+            cn = np.zeros((pf.nq, 4), dtype=np.int32)
+            _check(L.vf_profile_read(self._h, C.byref(pf), _np_ptr(cn)))
+        else:
+            cn = None
+            _check(L.vf_profile_read(self._h, C.byref(pf), None))
+        out = {n: getattr(pf, n) for n, _ in VfProfile._fields_}
+        return (out, cn) if per_query else out
 
     def export(self, name: str) -> np.ndarray:
         L = load_library()

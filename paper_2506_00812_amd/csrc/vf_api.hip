@@ -77,7 +77,14 @@ struct vf_index {
     // device
     DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
     // search workspace
-    DevBuf ws_blob, tmp_blk, tmp_norm;
+    DevBuf ws_blob, tmp_blk, tmp_norm, counters;
+    // profiling
+    bool profiling = false, prof_valid = false;
+    hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};
+    vf_profile prof{};
+    double prof_scan_sum = 0, prof_beam_sum = 0;
+    int64_t prof_calls = 0;
+    bool prof_folded = true;  // the last call's durations are already in the sums
     Staging stage[2];
     int stage_next = 0;
 
@@ -97,8 +104,10 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters};
     for (DevBuf *b : bufs) b->release();
+    for (hipEvent_t e : ix->prof_ev)
+        if (e) (void)hipEventDestroy(e);
     for (Staging &s : ix->stage) {
         if (s.pending) (void)hipEventSynchronize(s.done);
         if (s.done) (void)hipEventDestroy(s.done);
@@ -294,6 +303,20 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
 }
 
 // ---------------------------------------------------------------- routing
+
+// Add the durations of the last profiled call to the running sums (waits for it).
+static int fold_profile(vf_index *ix)
+{
+    if (!ix->prof_valid || ix->prof_folded) return VF_OK;
+    VF_HIP(hipEventSynchronize(ix->prof_ev[2]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.scan_ms, ix->prof_ev[0], ix->prof_ev[1]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[1], ix->prof_ev[2]));
+    ix->prof_scan_sum += ix->prof.scan_ms;
+    ix->prof_beam_sum += ix->prof.beam_ms;
+    ix->prof_calls++;
+    ix->prof_folded = true;
+    return VF_OK;
+}
 
 namespace {
 
@@ -491,6 +514,19 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         launch_fill_out(out_ids, out_dists, nq * (int64_t)k, s);
 
+        const bool prof = ix->profiling && !exact;
+        if (prof) {
+            if ((rc = fold_profile(ix)) != VF_OK) return rc;
+            if ((rc = ix->counters.reserve((size_t)nq * 16)) != VF_OK) return rc;
+            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 16, s));
+            vf_profile &pf = ix->prof;
+            pf = vf_profile{};
+            pf.nq = nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)qrow.size();
+            pf.n_scan_items = (int64_t)items.size();
+            for (const ScanItem &it : items) { pf.scan_list_entries += it.n; pf.scan_pairs += (int64_t)it.n * it.q_count; }
+            VF_HIP(hipEventRecord(ix->prof_ev[0], s));
+        }
+
         const int32_t *d_others_off = r.any_and ? (const int32_t *)(dp + L.off_others_off) : nullptr;
         const int32_t *d_others = (const int32_t *)(dp + L.off_others);
 
@@ -517,6 +553,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 launch_scan(ix->dtype, sp, (int)(run.item_hi - run.item_lo), s);
             }
         }
+        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], s));
         if (n_gq) {
             BeamParams bp{};
             bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>();
@@ -528,14 +565,16 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             int32_t LP = 128;
             while (LP < itopk + std::max(64, width * ix->R)) LP <<= 1;
             bp.LP = LP;
-            const int64_t visits = (int64_t)itopk + (int64_t)iters * width * ix->R;
+            const int64_t visits = (int64_t)iters * width * ix->R;
             int32_t hb = 9;
             while (hb < 13 && ((int64_t)1 << hb) < 2 * visits) ++hb;
             bp.hash_bits = hb;
             bp.out_ids = out_ids; bp.out_dists = out_dists;
+            bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
             VF_REQUIRE(beam_lds_bytes(bp, ix->dtype) <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
             launch_beam(ix->dtype, bp, (int)n_gq, s);
         }
+        if (prof) { VF_HIP(hipEventRecord(ix->prof_ev[2], s)); ix->prof_valid = true; ix->prof_folded = false; }
         VF_HIP(hipGetLastError());
         if (exact) {
             VF_HIP(hipStreamSynchronize(s));
@@ -608,6 +647,43 @@ extern "C" int vf_index_stats(const vf_index *ix, vf_stats *out)
     out->bytes_bitsets = (int64_t)ix->graph_labels.size() * ix->bitset_words * 4;
     out->bytes_meta = (int64_t)ix->n_labels * (4 + 8 + 8 + 4);
     out->bytes_total = out->bytes_graph + out->bytes_maps + out->bytes_x_ls + out->bytes_bitsets + out->bytes_meta;
+    return VF_OK;
+}
+
+extern "C" int vf_profile_enable(vf_index *ix, int on)
+{
+    VF_REQUIRE(ix != nullptr, "index is NULL");
+    if (on)
+        for (hipEvent_t &e : ix->prof_ev)
+            if (!e) VF_HIP(hipEventCreate(&e));
+    ix->profiling = on != 0;
+    ix->prof_valid = false;
+    ix->prof_folded = true;
+    ix->prof_scan_sum = ix->prof_beam_sum = 0;
+    ix->prof_calls = 0;
+    return VF_OK;
+}
+
+extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query)
+{
+    VF_REQUIRE(ix && out, "NULL argument");
+    VF_REQUIRE(ix->prof_valid, "no profiled vf_search call to report");
+    int rc = fold_profile(ix);
+    if (rc != VF_OK) return rc;
+    vf_profile pf = ix->prof;
+    pf.scan_ms_sum = ix->prof_scan_sum; pf.beam_ms_sum = ix->prof_beam_sum; pf.calls = ix->prof_calls;
+    try {
+        std::vector<int32_t> cn((size_t)pf.nq * 4);
+        VF_HIP(hipMemcpy(cn.data(), ix->counters.p, cn.size() * 4, hipMemcpyDeviceToHost));
+        for (int64_t j = 0; j < pf.nq; ++j) {
+            pf.beam_scored += cn[(size_t)j * 4]; pf.beam_expanded += cn[(size_t)j * 4 + 1]; pf.beam_tested += cn[(size_t)j * 4 + 2];
+        }
+        if (per_query) memcpy(per_query, cn.data(), cn.size() * 4);
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return VF_ENOMEM;
+    }
+    *out = pf;
     return VF_OK;
 }
 

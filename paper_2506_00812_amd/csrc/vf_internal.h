@@ -75,6 +75,7 @@ struct BeamParams {
     int32_t hash_bits; // visited table has 1 << hash_bits slots
     int64_t *out_ids;
     float *out_dists;
+    int32_t *counters; // optional [nq][4]: distances computed, rows expanded, predicate tests, method
 };
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype);

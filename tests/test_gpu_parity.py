@@ -241,3 +241,28 @@ def test_uint8_dim192_mixed_queries(vf):
     ie, de = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10)
     io, do = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, force_scan=True)
     assert_exact(to_np(ie), to_np(de), io, do, "dim192 exact")
+
+
+def test_work_counters_equal_oracle_counts(vf, tiny, tiny_oracle, tiny_gpu):
+    """The beam kernel's own counts of distances, expansions and predicate tests are
+    what the roofline's algorithmic bytes are computed from; they must equal the
+    oracle's (whose visited set is exact)."""
+    ix, Q = tiny_gpu
+    nq = 600
+    qoff, qids = _and_queries(nq, tiny.spec.n_labels, 23)
+    ix.profile_enable(True)
+    try:
+        for (qo, qi, n) in ((tiny.qlabel_offsets, tiny.qlabel_ids, tiny.spec.nq), (qoff, qids, nq)):
+            for params in (dict(itopk=32, width=1, iters=20, n_seeds=0), dict(itopk=64, width=2, iters=24, n_seeds=700)):
+                ig, dg = _search(vf, ix, Q[:n], qo, qi, 10, **params)
+                pf, cn = ix.profile_read(per_query=True)
+                io, do, info = tiny_oracle.search(tiny.queries[:n], qo, qi, 10, with_info=True, **params)
+                assert_exact(ig, dg, io, do, "profiled search")
+                g = info["method"] == 2
+                assert np.array_equal(cn[:, 3] == 2, g)
+                assert np.array_equal(cn[g, :3], info["counters"][g]), params
+                assert pf["beam_scored"] == info["counters"][g, 0].sum()
+                assert pf["n_graph_queries"] == g.sum() and pf["n_scan_queries"] == (info["method"] == 1).sum()
+                assert pf["beam_ms"] > 0
+    finally:
+        ix.profile_enable(False)
