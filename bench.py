@@ -209,6 +209,8 @@ def main():
             reps += 1
             spent = time.perf_counter() - t0
         cpu_qps = reps * len(sample) / spent
+        vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
+        torch.cuda.synchronize()
         gpu_rows = out_ids.cpu().numpy()[sample]     # same parameters as the timed region
         agree = float(np.mean([np.array_equal(a, b) for a, b in zip(gpu_rows, ids_o)]))
         cpu = {"value": round(cpu_qps, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",

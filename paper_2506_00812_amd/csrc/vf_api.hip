@@ -77,7 +77,7 @@ struct vf_index {
     // device
     DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
     // search workspace
-    DevBuf ws_blob, tmp_blk, tmp_norm, counters;
+    DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits;
     // profiling
     bool profiling = false, prof_valid = false;
     hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};
@@ -104,7 +104,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits};
     for (DevBuf *b : bufs) b->release();
     for (hipEvent_t e : ix->prof_ev)
         if (e) (void)hipEventDestroy(e);
@@ -138,10 +138,11 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     std::vector<ScanItem> items((size_t)n_groups);
     for (int64_t t = 0; t < n_groups; ++t) {
         ScanItem &it = items[(size_t)t];
-        it.group0 = 0; it.map_off = 0; it.n = nl;
+        it.group0 = 0; it.map_off = 0; it.entry0 = 0; it.n = nl;
         it.q_begin = (int32_t)(t * 32);
         it.q_count = (int32_t)std::min<int64_t>(32, nl - t * 32);
         it.self_base = it.q_begin;
+        it.part_row = it.q_begin;
     }
     int rc = upload(d_items, items, s);
     if (rc != VF_OK) return rc;
@@ -149,8 +150,8 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     ScanParams p{};
     p.xblk = ix->tmp_blk.as<uint4>(); p.xnorm = ix->tmp_norm.p; p.map = map;
     p.qsrc = ix->X; p.qrow = map; p.items = d_items.as<ScanItem>();
-    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.mode = 1;
-    p.res_idx = cand_idx.as<int32_t>(); p.res_dist = cand_dist.as<float>();
+    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K;
+    p.res_idx = cand_idx.as<int32_t>(); p.res_bits = cand_dist.as<uint32_t>();
     p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
     launch_scan(ix->dtype, p, (int)n_groups, s);
     launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
@@ -375,7 +376,7 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
 }
 
 struct BlobLayout {
-    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, total;
+    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, total;
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -409,29 +410,48 @@ static int check_search_args(const vf_index *ix, const void *queries, int64_t nq
     return VF_OK;
 }
 
-// Groups the (label, query) pairs of `pairs[lo, hi)` into tiles of <= 32 queries per label.
-// group0/map_off/n of each item are filled by `locate(label, item)`.
-template <class Locate>
-static void make_items(const std::vector<uint64_t> &pairs, size_t lo, size_t hi, std::vector<int32_t> &qrow,
-                       std::vector<ScanItem> &items, Locate locate)
-{
-    size_t i = lo;
-    while (i < hi) {
-        const int32_t l = (int32_t)(pairs[i] >> 32);
-        size_t e = i;
-        while (e < hi && (int32_t)(pairs[e] >> 32) == l) ++e;
-        for (size_t t = i; t < e; t += 32) {
-            ScanItem it{};
-            locate(l, it);
-            it.q_begin = (int32_t)qrow.size();
-            it.q_count = (int32_t)std::min<size_t>(32, e - t);
-            it.self_base = -1;
-            for (size_t u = t; u < t + (size_t)it.q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
-            items.push_back(it);
+// Work list of the scan path.  The (label, query) pairs of one label are cut into
+// tiles of <= 32 queries; a long list is cut into segments of whole 32-vector groups
+// so that many waves share it, and a merge item per query then combines the segments.
+constexpr int kSegGroups = 16;   // 512 vectors per segment
+constexpr int kMaxSegs = 64;
+
+struct ItemBuilder {
+    std::vector<int32_t> qrow;
+    std::vector<ScanItem> items;
+    std::vector<MergeItem> merges;
+    int64_t part_rows = 0;
+    int32_t max_nseg = 1;
+
+    // pairs[lo, hi) all carry the same label, whose list is (group0, map_off, n)
+    void add_label(const std::vector<uint64_t> &pairs, size_t lo, size_t hi, int64_t group0, int64_t map_off, int32_t n)
+    {
+        const int32_t n_groups = (n + 31) / 32;
+        const int32_t seg_groups = std::max(kSegGroups, (n_groups + kMaxSegs - 1) / kMaxSegs);
+        const int32_t nseg = (n_groups + seg_groups - 1) / seg_groups;
+        max_nseg = std::max(max_nseg, nseg);
+        for (size_t t = lo; t < hi; t += 32) {
+            const int32_t q_begin = (int32_t)qrow.size();
+            const int32_t q_count = (int32_t)std::min<size_t>(32, hi - t);
+            for (size_t u = t; u < t + (size_t)q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
+            for (int32_t sg = 0; sg < nseg; ++sg) {
+                ScanItem it{};
+                it.group0 = group0 + (int64_t)sg * seg_groups;
+                it.map_off = map_off;
+                it.entry0 = sg * seg_groups * 32;
+                it.n = std::min(seg_groups * 32, n - it.entry0);
+                it.q_begin = q_begin; it.q_count = q_count; it.self_base = -1;
+                it.part_row = nseg == 1 ? -1 : (int32_t)(part_rows + (int64_t)sg * q_count);
+                items.push_back(it);
+            }
+            if (nseg > 1) {
+                for (int32_t r = 0; r < q_count; ++r)
+                    merges.push_back(MergeItem{map_off, qrow[(size_t)q_begin + r], (int32_t)(part_rows + r), q_count, nseg});
+                part_rows += (int64_t)nseg * q_count;
+            }
         }
-        i = e;
     }
-}
+};
 
 static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
                        int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, bool exact, int64_t *out_ids,
@@ -452,21 +472,24 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if ((rc = route_queries(ix, nq, qoff, qids, exact, r)) != VF_OK) return rc;
 
         // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
-        std::vector<int32_t> qrow;
-        std::vector<ScanItem> items;
+        ItemBuilder ib;
         size_t first_hs = r.scan_pairs.size();
         if (exact) {
-            first_hs = 0;
-            // scan labels first, graph labels after them: sort key (is_graph, label)
+            // scan labels first, graph labels after them (both still ordered by label)
             std::stable_partition(r.scan_pairs.begin(), r.scan_pairs.end(), [&](uint64_t pr) {
                 return ix->O_LS[(size_t)(pr >> 32)] >= 0;
             });
+            first_hs = 0;
             while (first_hs < r.scan_pairs.size() && ix->O_LS[(size_t)(r.scan_pairs[first_hs] >> 32)] >= 0) ++first_hs;
         }
-        make_items(r.scan_pairs, 0, first_hs, qrow, items, [&](int32_t l, ScanItem &it) {
-            it.group0 = ix->GO_LS[(size_t)l]; it.map_off = ix->O_LS[(size_t)l]; it.n = ix->S[(size_t)l];
-        });
-        const size_t n_ls_items = items.size();
+        for (size_t i = 0; i < first_hs;) {
+            const int32_t l = (int32_t)(r.scan_pairs[i] >> 32);
+            size_t e = i;
+            while (e < first_hs && (int32_t)(r.scan_pairs[e] >> 32) == l) ++e;
+            ib.add_label(r.scan_pairs, i, e, ix->GO_LS[(size_t)l], ix->O_LS[(size_t)l], ix->S[(size_t)l]);
+            i = e;
+        }
+        const size_t n_ls_items = ib.items.size(), n_ls_merges = ib.merges.size();
         // exact mode: one temporary interleaved copy per graph label, used right after it is made
         struct HsRun { int32_t label; size_t item_lo, item_hi; };
         std::vector<HsRun> hs_runs;
@@ -475,14 +498,14 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             const int32_t l = (int32_t)(r.scan_pairs[i] >> 32);
             size_t e = i;
             while (e < r.scan_pairs.size() && (int32_t)(r.scan_pairs[e] >> 32) == l) ++e;
-            const size_t lo = items.size();
-            make_items(r.scan_pairs, i, e, qrow, items, [&](int32_t ll, ScanItem &it) {
-                it.group0 = 0; it.map_off = ix->O_HS[(size_t)ll]; it.n = ix->S[(size_t)ll];
-            });
-            hs_runs.push_back({l, lo, items.size()});
+            const size_t lo = ib.items.size();
+            ib.add_label(r.scan_pairs, i, e, 0, ix->O_HS[(size_t)l], ix->S[(size_t)l]);
+            hs_runs.push_back({l, lo, ib.items.size()});
             max_hs_list = std::max(max_hs_list, ix->S[(size_t)l]);
             i = e;
         }
+        std::vector<int32_t> &qrow = ib.qrow;
+        std::vector<ScanItem> &items = ib.items;
 
         const size_t n_gq = r.gq_query.size();
         BlobLayout L;
@@ -493,6 +516,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         L.off_others = o; o = align_up(o + std::max<size_t>(r.others.size(), 1) * 4);
         L.off_qrow = o; o = align_up(o + std::max<size_t>(qrow.size(), 1) * 4);
         L.off_items = o; o = align_up(o + std::max<size_t>(items.size(), 1) * sizeof(ScanItem));
+        L.off_merges = o; o = align_up(o + std::max<size_t>(ib.merges.size(), 1) * sizeof(MergeItem));
         L.total = o;
 
         Staging *st = nullptr;
@@ -506,6 +530,12 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (!r.others.empty()) memcpy(hp + L.off_others, r.others.data(), r.others.size() * 4);
         if (!qrow.empty()) memcpy(hp + L.off_qrow, qrow.data(), qrow.size() * 4);
         if (!items.empty()) memcpy(hp + L.off_items, items.data(), items.size() * sizeof(ScanItem));
+        if (!ib.merges.empty()) memcpy(hp + L.off_merges, ib.merges.data(), ib.merges.size() * sizeof(MergeItem));
+        if (ib.part_rows > 0) {
+            VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
+            if ((rc = ix->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
+            if ((rc = ix->part_bits.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
+        }
         if ((rc = ix->ws_blob.reserve(L.total)) != VF_OK) return rc;
         char *dp = ix->ws_blob.as<char>();
         VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, s));
@@ -532,13 +562,17 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         ScanParams sp{};
         sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
-        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.mode = 0;
-        sp.out_ids = out_ids; sp.out_dists = out_dists; sp.out_k = k;
+        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k;
+        sp.out_ids = out_ids; sp.out_dists = out_dists;
+        sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
+        const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);
         sp.others_off = d_others_off; sp.others = d_others; sp.meta = ix->meta();
         if (n_ls_items) {
             sp.xblk = ix->d_X_LS.as<uint4>(); sp.xnorm = ix->d_xnorm_LS.p; sp.map = ix->d_M_LS.as<int32_t>();
             sp.items = (const ScanItem *)(dp + L.off_items);
             launch_scan(ix->dtype, sp, (int)n_ls_items, s);
+            launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
+                              ix->d_M_LS.as<int32_t>(), out_ids, out_dists, s);
         }
         if (!hs_runs.empty()) {
             const int64_t max_groups = (max_hs_list + 31) / 32;
@@ -552,6 +586,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 sp.items = (const ScanItem *)(dp + L.off_items) + run.item_lo;
                 launch_scan(ix->dtype, sp, (int)(run.item_hi - run.item_lo), s);
             }
+            launch_scan_merge(ix->dtype, d_merges + n_ls_merges, (int)(ib.merges.size() - n_ls_merges), sp.res_idx,
+                              sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
         }
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], s));
         if (n_gq) {

@@ -37,6 +37,16 @@ __device__ __forceinline__ bool visit(uint32_t *tab, int bits, uint32_t id)
     return true;
 }
 
+// Is local id c one of the ns stratified seeds floor(j * n / ns), j < ns?  (ns <= n.)
+// Seeds are scored up front, so a child that is a seed has been visited already;
+// answering this arithmetically keeps the seeds out of the visited table.
+__device__ __forceinline__ bool is_seed(uint32_t c, uint32_t n, uint32_t ns)
+{
+    if (ns >= n) return true;
+    const uint64_t j = ((uint64_t)c * ns + n - 1) / n;  // smallest j with floor(j * n / ns) >= c
+    return j < ns && (uint32_t)((j * n) / ns) == c;
+}
+
 struct BeamLds {
     uint64_t *list;   // [LP]
     int32_t *cand_c;  // [128]
@@ -102,9 +112,11 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     uint64_t thr = KEY_MAX;  // key of list[itopk-1] after the last sort
     int pc = 0;              // pending candidates appended behind the list
+    int n_scored = 0, n_expanded = 0, n_tested = 0;  // work counters (uniform across the wave)
 
     // Score cand[0..cnt) (eight at a time, one per team) and append those that beat thr.
     auto score_and_append = [&](int cnt) {
+        n_scored += cnt;
         for (int r0 = 0; r0 < cnt; r0 += 8) {
             const int my = r0 + team;
             const bool valid = my < cnt;
@@ -125,6 +137,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     // Keep the candidates that pass the AND predicate, compacted into cand[].
     auto filter_and_compact = [&](bool valid, int c, int cnt) -> int {
         int g = 0;
+        if (o_cnt > 0) n_tested += __popcll(__ballot(valid));
         if (valid) {
             g = p.meta.M_HS[base + c];
             for (int o = 0; o < o_cnt && valid; ++o) valid = has_label(p.meta, p.others[o_begin + o], g);
@@ -158,11 +171,6 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         score_and_append(cnt);
     }
     flush();
-    for (int i = lane; i < itopk; i += 64) {
-        const uint64_t key = s.list[i];
-        if (key != KEY_MAX) visit(s.hash, p.hash_bits, (uint32_t)(key >> 1) & 0x7FFFFFFFu);
-    }
-    __syncthreads();
 
     // ---- iterations: expand the best unexpanded entries, score their unvisited children, merge
     for (int it = 0; it < p.iters; ++it) {
@@ -183,6 +191,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         }
         __syncthreads();
         if (np == 0) break;
+        n_expanded += np;
         int cnt = 0;
         for (int j0 = 0; j0 < np * R; j0 += 64) {
             const int j = j0 + lane;
@@ -191,7 +200,8 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             if (valid) {
                 const int pa = s.parents[j / R];
                 c = p.G[(base + pa) * R + (j % R)];
-                valid = c >= 0 && visit(s.hash, p.hash_bits, (uint32_t)c);
+                valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns) &&
+                        visit(s.hash, p.hash_bits, (uint32_t)c);
             }
             cnt = filter_and_compact(valid, c, cnt);
         }
@@ -200,6 +210,11 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         if (pc > 0) flush();
     }
     __syncthreads();
+
+    if (p.counters != nullptr && lane == 0) {
+        int32_t *cn = p.counters + (int64_t)qi * 4;
+        cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2;
+    }
 
     // ---- first k entries, local -> global through M
     if (lane < p.k) {

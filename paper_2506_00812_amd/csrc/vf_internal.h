@@ -30,13 +30,25 @@ struct LabelMeta {
 
 // ---------------------------------------------------------------- scan / contraction kernel
 
+// One wave's work: a tile of <= 32 queries against one segment of a list.
 struct ScanItem {
-    int64_t group0;    // first 32-vector group of the list in the interleaved buffer
+    int64_t group0;    // first 32-vector group of the segment in the interleaved buffer
     int64_t map_off;   // start of the list in `map` (local -> global id)
-    int32_t n;         // list entries
+    int32_t entry0;    // list-relative index of the segment's first entry
+    int32_t n;         // entries in the segment
     int32_t q_begin;   // first tile row in qrow[]
     int32_t q_count;   // tile rows, 1..32
-    int32_t self_base; // >= 0: entry self_base + r is skipped for tile row r (graph build)
+    int32_t self_base; // >= 0: list entry self_base + r is skipped for tile row r (graph build)
+    int32_t part_row;  // >= 0: K candidates of tile row r go to partial row part_row + r; < 0: final output
+};
+
+// Merge of the per-segment candidates of one query into its final top-k.
+struct MergeItem {
+    int64_t map_off;   // start of the list in `map`
+    int32_t qrow;      // query index (output row)
+    int32_t part_row;  // partial row of segment 0
+    int32_t stride;    // partial rows between consecutive segments
+    int32_t nseg;
 };
 
 struct ScanParams {
@@ -46,18 +58,20 @@ struct ScanParams {
     const void *qsrc;       // row-major [*][dim] query rows
     const int32_t *qrow;    // row of qsrc for each tile row
     const ScanItem *items;
-    int32_t dim, ncp, K, mode; // mode 0: final (ids via map, row = qrow value); 1: local candidates
-    int64_t *out_ids;
+    int32_t dim, ncp, K;
+    int64_t *out_ids;       // final output [*][K] (items with part_row < 0): row = qrow value
     float *out_dists;
-    int32_t out_k;
-    int32_t *res_idx;
-    float *res_dist;
+    int32_t *res_idx;       // partial output [*][K]: list-relative entry index, -1 = none
+    uint32_t *res_bits;     //                        distance bits (float bits / integer)
     const int32_t *others_off; // [*] per query row value: AND partner labels (mode 0 only), may be null
     const int32_t *others;
     LabelMeta meta;
 };
 
 void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s);
+void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,
+                       int32_t K, int32_t max_keys, const int32_t *map, int64_t *out_ids, float *out_dists,
+                       hipStream_t s);
 
 // ---------------------------------------------------------------- beam search kernel
 

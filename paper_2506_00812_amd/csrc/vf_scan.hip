@@ -135,8 +135,8 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
             }
         }
-        const int entry = grp * kGroup + n32;
-        const bool col_ok = entry < it.n;
+        const int entry = it.entry0 + grp * kGroup + n32;   // list-relative
+        const bool col_ok = grp * kGroup + n32 < it.n;
         const int64_t slot = (it.group0 + grp) * kGroup + n32;
         uint32_t xn;
         if (DT == 0) xn = (uint32_t)((const int32_t *)p.xnorm)[slot];
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
                 mask &= mask - 1;
                 const int hh = b >> 5, row = rowbase + 4 * hh;
                 const uint32_t kd = __shfl(bits, b);
-                const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(grp * kGroup + (b & 31));
+                const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(it.entry0 + grp * kGroup + (b & 31));
                 const uint64_t cur = lane < K ? best[row * K + lane] : KEY_MAX;
                 const uint64_t worst = shfl64(cur, K - 1);
                 if (key >= worst) continue;
@@ -188,26 +188,68 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         const uint64_t key = best[r * K + lane];
         const bool none = key == KEY_MAX;
         const uint32_t hi = (uint32_t)(key >> 32), idx = (uint32_t)key;
-        float d;
-        if (none) d = __builtin_inff();
-        else d = DT == 0 ? (float)(int)hi : __uint_as_float(hi);
-        if (p.mode == 0) {
-            if (lane < p.out_k) {
-                const int64_t o = (int64_t)qrow_s[r] * p.out_k + lane;
-                p.out_ids[o] = none ? -1 : (int64_t)p.map[it.map_off + idx];
-                p.out_dists[o] = d;
-            }
+        if (it.part_row < 0) {
+            const int64_t o = (int64_t)qrow_s[r] * K + lane;
+            p.out_ids[o] = none ? -1 : (int64_t)p.map[it.map_off + idx];
+            p.out_dists[o] = none ? __builtin_inff() : (DT == 0 ? (float)(int)hi : __uint_as_float(hi));
         } else {
-            const int64_t o = (int64_t)(it.q_begin + r) * K + lane;
+            const int64_t o = (int64_t)(it.part_row + r) * K + lane;
             p.res_idx[o] = none ? -1 : (int32_t)idx;
-            p.res_dist[o] = d;
+            p.res_bits[o] = hi;
         }
+    }
+}
+
+// Final top-K of a query whose list was scanned in several segments: sort the
+// segments' candidates by (distance, entry) and keep the first K.  One wave per query.
+template <int DT>
+__global__ __launch_bounds__(64) void scan_merge_kernel(const MergeItem *items, const int32_t *res_idx,
+                                                        const uint32_t *res_bits, int32_t K, int32_t P,
+                                                        const int32_t *map, int64_t *out_ids, float *out_dists)
+{
+    extern __shared__ uint4 smem[];
+    uint64_t *keys = (uint64_t *)smem;  // [P], P a power of two >= nseg * K
+    const MergeItem it = items[blockIdx.x];
+    const int lane = threadIdx.x;
+    const int total = it.nseg * K;
+    for (int i = lane; i < P; i += 64) {
+        uint64_t key = KEY_MAX;
+        if (i < total) {
+            const int64_t o = (int64_t)(it.part_row + (i / K) * it.stride) * K + (i % K);
+            const int32_t idx = res_idx[o];
+            if (idx >= 0) key = ((uint64_t)res_bits[o] << 32) | (uint32_t)idx;
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    wave_bitonic_sort(keys, P, lane);
+    if (lane < K) {
+        const uint64_t key = keys[lane];
+        const bool none = key == KEY_MAX;
+        const uint32_t hi = (uint32_t)(key >> 32);
+        const int64_t o = (int64_t)it.qrow * K + lane;
+        out_ids[o] = none ? -1 : (int64_t)map[it.map_off + (uint32_t)key];
+        out_dists[o] = none ? __builtin_inff() : (DT == 0 ? (float)(int)hi : __uint_as_float(hi));
     }
 }
 
 static size_t scan_lds_bytes(const ScanParams &p)
 {
     return (size_t)2 * p.ncp * 32 * 16 + (size_t)32 * p.K * 8 + 32 * 4 + 32 * 4;
+}
+
+void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,
+                       int32_t K, int32_t max_keys, const int32_t *map, int64_t *out_ids, float *out_dists, hipStream_t s)
+{
+    if (n_items <= 0) return;
+    int32_t P = 64;
+    while (P < max_keys) P <<= 1;
+    if (dtype == 0)
+        hipLaunchKernelGGL(scan_merge_kernel<0>, dim3(n_items), dim3(64), (size_t)P * 8, s, items, res_idx, res_bits, K, P,
+                           map, out_ids, out_dists);
+    else
+        hipLaunchKernelGGL(scan_merge_kernel<1>, dim3(n_items), dim3(64), (size_t)P * 8, s, items, res_idx, res_bits, K, P,
+                           map, out_ids, out_dists);
 }
 
 void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s)
