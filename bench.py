@@ -39,6 +39,24 @@ CANDIDATES = [
 ]
 
 
+def committed_traffic(workload, params):
+    """HBM bytes per beam_kernel launch from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled), if it was taken at these parameters; else None."""
+    path = os.path.join(ROOT, "profiles", f"beam_kernel_{workload}_bench.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    want = "params = " + repr(dict(zip(("itopk", "width", "iters", "n_seeds"), params)))
+    if want not in text:
+        return None
+    import re
+    vals = re.findall(r"beam_kernel, \d+ timed-region launches: raw [0-9.]+ -> ([0-9.]+) GB per launch", text)
+    if len(vals) != 2:
+        return None
+    return int(round((float(vals[0]) + float(vals[1])) * 1e9))
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -80,6 +98,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=64)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (scale reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -167,7 +187,8 @@ def main():
     achieved = beam_bytes / (beam_avg_ms * 1e-3) / 1e9 if beam_avg_ms > 0 else 0.0
     roofline = {
         "kernel": "beam_kernel (IVF-Graph search)", "bound": "hbm", "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": committed_traffic(s.name, headline[0]),
         "algorithmic_bytes_per_launch": int(beam_bytes), "avg_launch_ms": round(beam_avg_ms, 4),
         "graph_queries_per_launch": int(pf["n_graph_queries"]),
         "distances_per_graph_query": round(pf["beam_scored"] / max(pf["n_graph_queries"], 1), 1),
@@ -175,6 +196,14 @@ def main():
                         "achieved_GBs": round(scan_bytes / (max(scan_avg_ms, 1e-6) * 1e-3) / 1e9, 1),
                         "flops_per_launch": int(2 * pf["scan_pairs"] * s.dim)},
     }
+
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # second operating point, timed the plain way
     extra = {}
