@@ -29,7 +29,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
 
 # (itopk, width, iters, n_seeds), roughly by increasing cost
 CANDIDATES = [
@@ -39,10 +40,10 @@ CANDIDATES = [
 ]
 
 
-def committed_traffic(workload, params):
-    """HBM bytes per beam_kernel launch from the committed rocprofv3 --pmc summary
+def committed_traffic(kernel, workload, params):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, scaled), if it was taken at these parameters; else None."""
-    path = os.path.join(ROOT, "profiles", f"beam_kernel_{workload}_bench.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_bench.txt")
     try:
         text = open(path).read()
     except OSError:
@@ -51,7 +52,7 @@ def committed_traffic(workload, params):
     if want not in text:
         return None
     import re
-    vals = re.findall(r"beam_kernel, \d+ timed-region launches: raw [0-9.]+ -> ([0-9.]+) GB per launch", text)
+    vals = re.findall(kernel + r", \d+ timed-region launches: raw [0-9.]+ -> ([0-9.]+) GB per launch", text)
     if len(vals) != 2:
         return None
     return int(round((float(vals[0]) + float(vals[1])) * 1e9))
@@ -176,25 +177,49 @@ def main():
     assert pf["calls"] == args.steps
     beam_avg_ms = pf["beam_ms_sum"] / pf["calls"]
     scan_avg_ms = pf["scan_ms_sum"] / pf["calls"]
+    seed_avg_ms = pf["seed_ms_sum"] / pf["calls"]
     ix.profile_enable(False)
     recall_head = recall_at_k(out_ids.cpu().numpy(), gt)
 
     eb = 1 if s.dtype == "uint8" else 4
     vec_bytes = s.dim * eb
-    beam_bytes = (pf["beam_scored"] * (vec_bytes + 4) + pf["beam_expanded"] * s.graph_degree * 4
-                  + pf["beam_tested"] * 4 + pf["n_graph_queries"] * (vec_bytes + k * 12))
-    scan_bytes = pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12)
-    achieved = beam_bytes / (beam_avg_ms * 1e-3) / 1e9 if beam_avg_ms > 0 else 0.0
+    n_gq = pf["n_graph_queries"]
+    # algorithmic work of each kernel of one step (one vf_search call)
+    gathered = pf["beam_scored"] - pf["seed_pairs"]          # distances whose vector the beam kernel gathers itself
+    kernels = {
+        "beam_kernel": {
+            "ms": beam_avg_ms, "bound": "hbm",
+            "bytes": gathered * (vec_bytes + 4) + pf["seed_pairs"] * 4 + pf["beam_expanded"] * s.graph_degree * 4
+                     + pf["beam_tested"] * 4 + n_gq * (vec_bytes + k * 12),
+            "flops": 3 * gathered * s.dim},
+        "seed_dist_kernel": {
+            "ms": seed_avg_ms, "bound": "alu",
+            "bytes": pf["seed_tile_seeds"] * (vec_bytes + 4) + n_gq * vec_bytes + pf["seed_pairs"] * 4,
+            "flops": 3 * pf["seed_pairs"] * s.dim},          # per element: one subtract, one fused multiply-add
+        "scan_topk_kernel": {
+            "ms": scan_avg_ms, "bound": "hbm",
+            "bytes": pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),
+            "flops": 2 * pf["scan_pairs"] * s.dim},
+    }
+    dom = max(kernels, key=lambda n: kernels[n]["ms"])
+    kd = kernels[dom]
+    if kd["bound"] == "hbm":
+        achieved, peak, unit = kd["bytes"] / (kd["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = kd["flops"] / (kd["ms"] * 1e-3) / 1e12, FP32_VECTOR_PEAK_TFLOPS, "TFLOP/s"
     roofline = {
-        "kernel": "beam_kernel (IVF-Graph search)", "bound": "hbm", "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": committed_traffic(s.name, headline[0]),
-        "algorithmic_bytes_per_launch": int(beam_bytes), "avg_launch_ms": round(beam_avg_ms, 4),
-        "graph_queries_per_launch": int(pf["n_graph_queries"]),
-        "distances_per_graph_query": round(pf["beam_scored"] / max(pf["n_graph_queries"], 1), 1),
-        "scan_kernel": {"avg_launch_ms": round(scan_avg_ms, 4), "algorithmic_bytes_per_launch": int(scan_bytes),
-                        "achieved_GBs": round(scan_bytes / (max(scan_avg_ms, 1e-6) * 1e-3) / 1e9, 1),
-                        "flops_per_launch": int(2 * pf["scan_pairs"] * s.dim)},
+        "kernel": dom, "bound": kd["bound"], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+        "frac": round(achieved / peak, 4),
+        "traffic": committed_traffic(dom, s.name, headline[0]),
+        "algorithmic_bytes_per_launch": int(kd["bytes"]), "algorithmic_flops_per_launch": int(kd["flops"]),
+        "avg_launch_ms": round(kd["ms"], 4),
+        "graph_queries_per_launch": int(n_gq), "scan_queries_per_launch": int(pf["n_scan_queries"]),
+        "distances_per_graph_query": round(pf["beam_scored"] / max(n_gq, 1), 1),
+        "all_kernels": {n: {"avg_launch_ms": round(v["ms"], 4), "bound": v["bound"],
+                            "algorithmic_bytes_per_launch": int(v["bytes"]), "flops_per_launch": int(v["flops"]),
+                            "GBs": round(v["bytes"] / (max(v["ms"], 1e-6) * 1e-3) / 1e9, 1),
+                            "TFLOPs": round(v["flops"] / (max(v["ms"], 1e-6) * 1e-3) / 1e12, 2)}
+                        for n, v in kernels.items()},
     }
 
     if args.calib_copy:

@@ -146,13 +146,16 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  *               took the graph path (0 otherwise; the first three are then 0)
  */
 typedef struct vf_profile {
-    float scan_ms, beam_ms;            /* kernel durations of the last call            */
-    double scan_ms_sum, beam_ms_sum;   /* sums over all calls since profiling was enabled */
+    float scan_ms, seed_ms, beam_ms;   /* durations of the last call: IVF-BFS kernels, dense seed scoring, beam search */
+    double scan_ms_sum, seed_ms_sum, beam_ms_sum; /* sums over all calls since profiling was enabled */
     int64_t calls;                     /* number of calls in those sums                */
     int64_t nq, n_scan_queries, n_graph_queries, n_scan_items;
     int64_t scan_list_entries;         /* sum over scan items of the list length       */
     int64_t scan_pairs;                /* sum over scan items of queries x list length */
     int64_t beam_scored, beam_expanded, beam_tested;
+    int64_t n_seed_tiles;              /* tiles of <= 64 same-label graph queries scored densely (0: seeds were gathered) */
+    int64_t seed_pairs;                /* sum over graph queries of the seeds scored for them                            */
+    int64_t seed_tile_seeds;           /* sum over seed tiles of the seeds they read                                     */
 } vf_profile;
 
 int vf_profile_enable(vf_index *index, int on);

@@ -86,7 +86,7 @@ typedef struct vfo_index {
 
 /* fp32 squared L2 in the order the GPU kernel uses: eight partial sums a_t,
  * a_t taking elements e = 32*s + 4*t + c (s ascending, then c = 0..3), each term
- * rounded as d = q-x, p = d*d, a_t = a_t + p; then the fixed tree
+ * as d = q-x (rounded), a_t = fma(d, d, a_t) (one rounding); then the fixed tree
  * ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7)). */
 float vfo_dist_f32_ordered(const float *q, const float *x, int32_t dim)
 {
@@ -98,8 +98,7 @@ float vfo_dist_f32_ordered(const float *q, const float *x, int32_t dim)
                 int e = s * 32 + t * 4 + c;
                 if (e < dim) {
                     float d = q[e] - x[e];
-                    float p = d * d;
-                    a[t] = a[t] + p;
+                    a[t] = fmaf(d, d, a[t]);
                 }
             }
     float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];

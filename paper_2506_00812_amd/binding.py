@@ -32,11 +32,11 @@ class VfStats(C.Structure):
 
 
 class VfProfile(C.Structure):
-    _fields_ = [("scan_ms", C.c_float), ("beam_ms", C.c_float), ("scan_ms_sum", C.c_double),
-                ("beam_ms_sum", C.c_double), ("calls", C.c_int64)] + \
+    _fields_ = [("scan_ms", C.c_float), ("seed_ms", C.c_float), ("beam_ms", C.c_float), ("scan_ms_sum", C.c_double),
+                ("seed_ms_sum", C.c_double), ("beam_ms_sum", C.c_double), ("calls", C.c_int64)] + \
                [(n, C.c_int64) for n in ("nq", "n_scan_queries", "n_graph_queries", "n_scan_items",
                                          "scan_list_entries", "scan_pairs", "beam_scored", "beam_expanded",
-                                         "beam_tested")]
+                                         "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds")]
 
 
 class VecflowError(RuntimeError):

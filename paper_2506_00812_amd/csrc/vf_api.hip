@@ -77,12 +77,12 @@ struct vf_index {
     // device
     DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
     // search workspace
-    DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits;
+    DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
     // profiling
     bool profiling = false, prof_valid = false;
-    hipEvent_t prof_ev[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t prof_ev[4] = {nullptr, nullptr, nullptr, nullptr};
     vf_profile prof{};
-    double prof_scan_sum = 0, prof_beam_sum = 0;
+    double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
     bool prof_folded = true;  // the last call's durations are already in the sums
     Staging stage[2];
@@ -104,7 +104,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed};
     for (DevBuf *b : bufs) b->release();
     for (hipEvent_t e : ix->prof_ev)
         if (e) (void)hipEventDestroy(e);
@@ -309,10 +309,12 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
 static int fold_profile(vf_index *ix)
 {
     if (!ix->prof_valid || ix->prof_folded) return VF_OK;
-    VF_HIP(hipEventSynchronize(ix->prof_ev[2]));
+    VF_HIP(hipEventSynchronize(ix->prof_ev[3]));
     VF_HIP(hipEventElapsedTime(&ix->prof.scan_ms, ix->prof_ev[0], ix->prof_ev[1]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[1], ix->prof_ev[2]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.seed_ms, ix->prof_ev[1], ix->prof_ev[2]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[2], ix->prof_ev[3]));
     ix->prof_scan_sum += ix->prof.scan_ms;
+    ix->prof_seed_sum += ix->prof.seed_ms;
     ix->prof_beam_sum += ix->prof.beam_ms;
     ix->prof_calls++;
     ix->prof_folded = true;
@@ -372,11 +374,20 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
         r.others_off[(size_t)j + 1] = (int32_t)r.others.size();
     }
     std::sort(r.scan_pairs.begin(), r.scan_pairs.end());
+    // graph queries grouped by label (stable in query order) so that the queries of a
+    // label form tiles for the dense seed kernel
+    {
+        const size_t n_gq = r.gq_query.size();
+        std::vector<uint64_t> pairs(n_gq);
+        for (size_t i = 0; i < n_gq; ++i) pairs[i] = ((uint64_t)(uint32_t)r.gq_label[i] << 32) | (uint32_t)r.gq_query[i];
+        std::sort(pairs.begin(), pairs.end());
+        for (size_t i = 0; i < n_gq; ++i) { r.gq_label[i] = (int32_t)(pairs[i] >> 32); r.gq_query[i] = (int32_t)(uint32_t)pairs[i]; }
+    }
     return VF_OK;
 }
 
 struct BlobLayout {
-    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, total;
+    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, off_tiles, total;
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -508,6 +519,20 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         std::vector<ScanItem> &items = ib.items;
 
         const size_t n_gq = r.gq_query.size();
+        // dense seed scoring: tiles of <= 64 graph queries that search the same label
+        std::vector<SeedTile> tiles;
+        const int32_t ns_stride = (n_seeds + 31) & ~31;
+        const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) &&
+                                 (uint64_t)n_gq * (uint64_t)ns_stride * 4 <= ((uint64_t)8 << 30);
+        if (dense_seeds) {
+            for (size_t i = 0; i < n_gq;) {
+                size_t e = i;
+                while (e < n_gq && r.gq_label[e] == r.gq_label[i]) ++e;
+                for (size_t t = i; t < e; t += 64)
+                    tiles.push_back(SeedTile{r.gq_label[i], (int32_t)t, (int32_t)std::min<size_t>(64, e - t)});
+                i = e;
+            }
+        }
         BlobLayout L;
         size_t o = 0;
         L.off_gq_query = o; o = align_up(o + n_gq * 4);
@@ -517,6 +542,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         L.off_qrow = o; o = align_up(o + std::max<size_t>(qrow.size(), 1) * 4);
         L.off_items = o; o = align_up(o + std::max<size_t>(items.size(), 1) * sizeof(ScanItem));
         L.off_merges = o; o = align_up(o + std::max<size_t>(ib.merges.size(), 1) * sizeof(MergeItem));
+        L.off_tiles = o; o = align_up(o + std::max<size_t>(tiles.size(), 1) * sizeof(SeedTile));
         L.total = o;
 
         Staging *st = nullptr;
@@ -531,6 +557,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (!qrow.empty()) memcpy(hp + L.off_qrow, qrow.data(), qrow.size() * 4);
         if (!items.empty()) memcpy(hp + L.off_items, items.data(), items.size() * sizeof(ScanItem));
         if (!ib.merges.empty()) memcpy(hp + L.off_merges, ib.merges.data(), ib.merges.size() * sizeof(MergeItem));
+        if (!tiles.empty()) memcpy(hp + L.off_tiles, tiles.data(), tiles.size() * sizeof(SeedTile));
+        if (dense_seeds && (rc = ix->dseed.reserve((size_t)n_gq * ns_stride * 4)) != VF_OK) return rc;
         if (ib.part_rows > 0) {
             VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
             if ((rc = ix->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
@@ -554,6 +582,12 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             pf.nq = nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)qrow.size();
             pf.n_scan_items = (int64_t)items.size();
             for (const ScanItem &it : items) { pf.scan_list_entries += it.n; pf.scan_pairs += (int64_t)it.n * it.q_count; }
+            pf.n_seed_tiles = (int64_t)tiles.size();
+            for (const SeedTile &t : tiles) {
+                const int64_t ns_l = std::min<int64_t>(n_seeds, ix->S[(size_t)t.label]);
+                pf.seed_pairs += ns_l * t.q_count;
+                pf.seed_tile_seeds += ns_l;
+            }
             VF_HIP(hipEventRecord(ix->prof_ev[0], s));
         }
 
@@ -607,10 +641,25 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             bp.hash_bits = hb;
             bp.out_ids = out_ids; bp.out_dists = out_dists;
             bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
+            bp.dseed = nullptr; bp.ns_stride = ns_stride;
+            if (dense_seeds) {
+                SeedParams sd{};
+                sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
+                sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
+                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride; sd.max_chunks = ns_stride / 32;
+                sd.dseed = ix->dseed.as<uint32_t>();
+                launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
+                bp.dseed = sd.dseed;
+            }
+            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
             VF_REQUIRE(beam_lds_bytes(bp, ix->dtype) <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
             launch_beam(ix->dtype, bp, (int)n_gq, s);
         }
-        if (prof) { VF_HIP(hipEventRecord(ix->prof_ev[2], s)); ix->prof_valid = true; ix->prof_folded = false; }
+        if (prof) {
+            if (!n_gq) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
+            VF_HIP(hipEventRecord(ix->prof_ev[3], s));
+            ix->prof_valid = true; ix->prof_folded = false;
+        }
         VF_HIP(hipGetLastError());
         if (exact) {
             VF_HIP(hipStreamSynchronize(s));
@@ -695,7 +744,7 @@ extern "C" int vf_profile_enable(vf_index *ix, int on)
     ix->profiling = on != 0;
     ix->prof_valid = false;
     ix->prof_folded = true;
-    ix->prof_scan_sum = ix->prof_beam_sum = 0;
+    ix->prof_scan_sum = ix->prof_seed_sum = ix->prof_beam_sum = 0;
     ix->prof_calls = 0;
     return VF_OK;
 }
@@ -707,7 +756,8 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
     int rc = fold_profile(ix);
     if (rc != VF_OK) return rc;
     vf_profile pf = ix->prof;
-    pf.scan_ms_sum = ix->prof_scan_sum; pf.beam_ms_sum = ix->prof_beam_sum; pf.calls = ix->prof_calls;
+    pf.scan_ms_sum = ix->prof_scan_sum; pf.seed_ms_sum = ix->prof_seed_sum; pf.beam_ms_sum = ix->prof_beam_sum;
+    pf.calls = ix->prof_calls;
     try {
         std::vector<int32_t> cn((size_t)pf.nq * 4);
         VF_HIP(hipMemcpy(cn.data(), ix->counters.p, cn.size() * 4, hipMemcpyDeviceToHost));

@@ -17,7 +17,7 @@
 //
 // fp32 distances are evaluated in a fixed order so that results can be compared
 // bit for bit with a CPU evaluation: lane t of a team sums (q_e - x_e)^2 over
-// e = 32 s + 4 t + c (s ascending, c = 0..3) without fused multiply-add, and the
+// e = 32 s + 4 t + c (s ascending, c = 0..3) as acc = fma(d, d, acc), d = q - x, and the
 // team combines ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7)).
 #include "vf_device.h"
 
@@ -160,6 +160,36 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     // ---- InitializeSearch: stratified seeds floor(j * n / ns)
     const int ns = p.n_seeds < n ? p.n_seeds : n;
+    if (p.dseed != nullptr) {
+        // distances were computed densely per label; stream this query's row and keep the best
+        const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
+        for (int j0 = 0; j0 < ns; j0 += 64) {
+            if (pc + 64 > CB) flush();
+            const int j = j0 + lane;
+            const bool valid = j < ns;
+            const uint32_t bits = valid ? drow[j] : 0u;
+            bool pass = valid;
+            int c = 0;
+            if (o_cnt > 0) {
+                n_tested += __popcll(__ballot(valid));
+                if (valid) {
+                    c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
+                    const int g = p.meta.M_HS[base + c];
+                    for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, p.others[o_begin + o], g);
+                }
+                n_scored += __popcll(__ballot(pass));
+            } else {
+                n_scored += __popcll(__ballot(valid));
+            }
+            pass = pass && bits <= (uint32_t)(thr >> 32);
+            if (pass && o_cnt == 0) c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
+            const uint64_t key = ((uint64_t)bits << 32) | ((uint64_t)(uint32_t)c << 1) | 1ull;
+            pass = pass && key < thr;
+            const uint64_t m = __ballot(pass);
+            if (pass) s.list[itopk + pc + __popcll(m & ((1ull << lane) - 1ull))] = key;
+            pc += __popcll(m);
+        }
+    } else
     for (int j0 = 0; j0 < ns; j0 += 64) {
         if (pc + 64 > CB) flush();
         const int j = j0 + lane;

@@ -47,8 +47,8 @@ __device__ __forceinline__ int team_sum_i(int v)
 
 // Squared L2 distance between the query (16-byte chunks in qv) and the row at xrow,
 // computed by one 8-lane team; tl = lane within the team.  Lane tl handles chunks
-// tl, tl+8, ... .  fp32: lane-sequential sum of rounded (q-x)*(q-x) terms, then
-// team_sum_f -- the order that a CPU evaluation can reproduce bit for bit.
+// tl, tl+8, ... .  fp32: lane-sequential acc = fma(d, d, acc) with d = q-x rounded, then
+// team_sum_f -- an order that a CPU evaluation (C fmaf) reproduces bit for bit.
 __device__ __forceinline__ uint32_t team_dist_bits_f32(const uint4 *qv, const char *xrow, int nchunks, int tl)
 {
     const int steps = (nchunks + 7) >> 3;
@@ -60,10 +60,10 @@ __device__ __forceinline__ uint32_t team_dist_bits_f32(const uint4 *qv, const ch
             const uint4 x = *(const uint4 *)(xrow + ci * kChunkBytes);
             const uint4 q = qv[ci];
             float d;
-            d = __uint_as_float(q.x) - __uint_as_float(x.x); acc = acc + d * d;
-            d = __uint_as_float(q.y) - __uint_as_float(x.y); acc = acc + d * d;
-            d = __uint_as_float(q.z) - __uint_as_float(x.z); acc = acc + d * d;
-            d = __uint_as_float(q.w) - __uint_as_float(x.w); acc = acc + d * d;
+            d = __uint_as_float(q.x) - __uint_as_float(x.x); acc = __builtin_fmaf(d, d, acc);
+            d = __uint_as_float(q.y) - __uint_as_float(x.y); acc = __builtin_fmaf(d, d, acc);
+            d = __uint_as_float(q.z) - __uint_as_float(x.z); acc = __builtin_fmaf(d, d, acc);
+            d = __uint_as_float(q.w) - __uint_as_float(x.w); acc = __builtin_fmaf(d, d, acc);
         }
     }
     return __float_as_uint(team_sum_f(acc));

@@ -90,7 +90,30 @@ struct BeamParams {
     int64_t *out_ids;
     float *out_dists;
     int32_t *counters; // optional [nq][4]: distances computed, rows expanded, predicate tests, method
+    const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel
+    int32_t ns_stride;
 };
+
+// ---------------------------------------------------------------- dense seed distances
+
+struct SeedTile {
+    int32_t label;
+    int32_t gq_begin;  // first graph query (position in gq_query) of the tile
+    int32_t q_count;   // 1..64 queries, all searching `label`
+};
+
+struct SeedParams {
+    const void *X;
+    const void *Q;
+    const int32_t *gq_query;
+    const SeedTile *tiles;
+    LabelMeta meta;
+    int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = ceil(n_seeds / 32)
+    uint32_t *dseed;
+};
+
+bool seed_dist_supported(int dtype, int dim);
+void launch_seed_dist(int dtype, const SeedParams &p, int n_tiles, hipStream_t s);
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype);
 void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s);

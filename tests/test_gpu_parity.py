@@ -266,3 +266,28 @@ def test_work_counters_equal_oracle_counts(vf, tiny, tiny_oracle, tiny_gpu):
                 assert pf["beam_ms"] > 0
     finally:
         ix.profile_enable(False)
+
+
+@pytest.mark.parametrize("name,dim", [("tiny", 48), ("c2", 40)])
+def test_dims_without_dense_seed_kernel(vf, name, dim):
+    """Dimensions the dense seed kernel is not instantiated for fall back to gathering
+    the seeds inside the beam kernel; results must not change."""
+    import torch
+    w = make_workload(name, n=6000, nq=400, n_labels=30, n_clusters=16, T=300, graph_degree=16, dim=dim)
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    assert np.array_equal(ix.export("G_HS").reshape(-1, s.graph_degree), ixo.G_HS)
+    Q = torch.from_numpy(w.queries).cuda()
+    qoff, qids = _and_queries(400, s.n_labels, 31, hi_a=8, hi_b=30)
+    for qo, qi in ((w.qlabel_offsets, w.qlabel_ids), (qoff, qids)):
+        params = dict(itopk=64, width=2, iters=16, n_seeds=300)
+        ig, dg = _search(vf, ix, Q, qo, qi, 10, **params)
+        io, do, info = ixo.search(w.queries, qo, qi, 10, with_info=True, **params)
+        g = info["method"] == 2
+        assert g.sum() > 50
+        assert_exact(ig[g], dg[g], io[g], do[g], f"{name} dim {dim} graph")
+        if s.dtype == "uint8":
+            assert_exact(ig[~g], dg[~g], io[~g], do[~g], f"{name} dim {dim} scan")
+        else:
+            assert_close_with_ties(ig[~g], dg[~g], io[~g], do[~g], RTOL, f"{name} dim {dim} scan")
