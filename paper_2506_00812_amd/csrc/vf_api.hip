@@ -80,7 +80,10 @@ struct vf_index {
     DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
     // profiling
     bool profiling = false, prof_valid = false;
-    hipEvent_t prof_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t prof_ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};  // scan begin/end, graph begin, seeds end, beam end
+    // the scan path runs beside the graph path on a second stream of the same (default) priority
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     vf_profile prof{};
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
@@ -108,6 +111,9 @@ static void free_index(vf_index *ix)
     for (DevBuf *b : bufs) b->release();
     for (hipEvent_t e : ix->prof_ev)
         if (e) (void)hipEventDestroy(e);
+    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+    if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
+    if (ix->side) { (void)hipStreamSynchronize(ix->side); (void)hipStreamDestroy(ix->side); }
     for (Staging &s : ix->stage) {
         if (s.pending) (void)hipEventSynchronize(s.done);
         if (s.done) (void)hipEventDestroy(s.done);
@@ -298,6 +304,9 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
         set_error("out of host memory");
         return VF_ENOMEM;
     }
+    VF_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
+    VF_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
+    VF_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
     guard.ix = nullptr;
     *out = ix;
     return VF_OK;
@@ -309,10 +318,11 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
 static int fold_profile(vf_index *ix)
 {
     if (!ix->prof_valid || ix->prof_folded) return VF_OK;
-    VF_HIP(hipEventSynchronize(ix->prof_ev[3]));
+    VF_HIP(hipEventSynchronize(ix->prof_ev[4]));
+    VF_HIP(hipEventSynchronize(ix->prof_ev[1]));
     VF_HIP(hipEventElapsedTime(&ix->prof.scan_ms, ix->prof_ev[0], ix->prof_ev[1]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.seed_ms, ix->prof_ev[1], ix->prof_ev[2]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[2], ix->prof_ev[3]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.seed_ms, ix->prof_ev[2], ix->prof_ev[3]));
+    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[3], ix->prof_ev[4]));
     ix->prof_scan_sum += ix->prof.scan_ms;
     ix->prof_seed_sum += ix->prof.seed_ms;
     ix->prof_beam_sum += ix->prof.beam_ms;
@@ -477,6 +487,16 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         VF_REQUIRE(n_seeds >= 0, "n_seeds must be >= 0");
         if (n_seeds == 0) n_seeds = itopk;
     }
+    // beam kernel geometry: list slots and visited-table size; checked before anything is launched
+    int32_t beam_LP = 128, beam_hb = 9;
+    if (!exact) {
+        while (beam_LP < itopk + std::max(64, width * ix->R)) beam_LP <<= 1;
+        const int64_t visits = (int64_t)iters * width * ix->R;
+        while (beam_hb < 13 && ((int64_t)1 << beam_hb) < 2 * visits) ++beam_hb;
+        BeamParams chk{};
+        chk.dim = ix->dim; chk.LP = beam_LP; chk.hash_bits = beam_hb;
+        VF_REQUIRE(beam_lds_bytes(chk, ix->dtype) <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
+    }
     if (nq == 0) return VF_OK;
     try {
         Routed r;
@@ -588,8 +608,16 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 pf.seed_pairs += ns_l * t.q_count;
                 pf.seed_tile_seeds += ns_l;
             }
-            VF_HIP(hipEventRecord(ix->prof_ev[0], s));
         }
+        // fork: scan kernels on the side stream, graph kernels on the caller's stream
+        hipStream_t ss = s;
+        const bool forked = !exact && n_gq > 0 && !items.empty();
+        if (forked) {
+            VF_HIP(hipEventRecord(ix->ev_fork, s));
+            VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+            ss = ix->side;
+        }
+        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[0], ss));
 
         const int32_t *d_others_off = r.any_and ? (const int32_t *)(dp + L.off_others_off) : nullptr;
         const int32_t *d_others = (const int32_t *)(dp + L.off_others);
@@ -604,9 +632,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (n_ls_items) {
             sp.xblk = ix->d_X_LS.as<uint4>(); sp.xnorm = ix->d_xnorm_LS.p; sp.map = ix->d_M_LS.as<int32_t>();
             sp.items = (const ScanItem *)(dp + L.off_items);
-            launch_scan(ix->dtype, sp, (int)n_ls_items, s);
+            launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
             launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
-                              ix->d_M_LS.as<int32_t>(), out_ids, out_dists, s);
+                              ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
         }
         if (!hs_runs.empty()) {
             const int64_t max_groups = (max_hs_list + 31) / 32;
@@ -623,7 +651,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             launch_scan_merge(ix->dtype, d_merges + n_ls_merges, (int)(ib.merges.size() - n_ls_merges), sp.res_idx,
                               sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
         }
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], s));
+        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
+        if (forked) VF_HIP(hipEventRecord(ix->ev_join, ss));
+        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
         if (n_gq) {
             BeamParams bp{};
             bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>();
@@ -632,13 +662,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             bp.others_off = d_others_off; bp.others = d_others; bp.meta = ix->meta();
             bp.dim = ix->dim; bp.R = ix->R; bp.k = k; bp.itopk = itopk; bp.width = width; bp.iters = iters;
             bp.n_seeds = n_seeds;
-            int32_t LP = 128;
-            while (LP < itopk + std::max(64, width * ix->R)) LP <<= 1;
-            bp.LP = LP;
-            const int64_t visits = (int64_t)iters * width * ix->R;
-            int32_t hb = 9;
-            while (hb < 13 && ((int64_t)1 << hb) < 2 * visits) ++hb;
-            bp.hash_bits = hb;
+            bp.LP = beam_LP;
+            bp.hash_bits = beam_hb;
             bp.out_ids = out_ids; bp.out_dists = out_dists;
             bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
             bp.dseed = nullptr; bp.ns_stride = ns_stride;
@@ -651,15 +676,15 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
                 bp.dseed = sd.dseed;
             }
-            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
-            VF_REQUIRE(beam_lds_bytes(bp, ix->dtype) <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
+            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
             launch_beam(ix->dtype, bp, (int)n_gq, s);
         }
         if (prof) {
-            if (!n_gq) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
-            VF_HIP(hipEventRecord(ix->prof_ev[3], s));
+            if (!n_gq) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
+            VF_HIP(hipEventRecord(ix->prof_ev[4], s));
             ix->prof_valid = true; ix->prof_folded = false;
         }
+        if (forked) VF_HIP(hipStreamWaitEvent(s, ix->ev_join, 0));
         VF_HIP(hipGetLastError());
         if (exact) {
             VF_HIP(hipStreamSynchronize(s));

@@ -113,6 +113,20 @@ __device__ __forceinline__ uint64_t shfl_up64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// value of lane `src` (wave-uniform index) in every lane
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, int src)
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, src), hi = __builtin_amdgcn_readlane((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
+}
+// lane i receives the value of lane i - 1 (lane 0 keeps its own): DPP wave_shr:1
+__device__ __forceinline__ uint64_t wave_shr1_64(uint64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, 0x138, 0xF, 0xF, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32), 0x138, 0xF, 0xF, false);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 // Bitonic sort of keys[0..n) ascending in LDS by one wave; n a power of two.
 __device__ __forceinline__ void wave_bitonic_sort(uint64_t *keys, int n, int lane)
 {

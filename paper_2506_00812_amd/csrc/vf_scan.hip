@@ -30,13 +30,19 @@ template <int DT> struct Acc;
 template <> struct Acc<0> { using type = v16i; };
 template <> struct Acc<1> { using type = v16f; };
 
-template <int DT>
+// NCP > 0: the number of chunk pairs per vector is known at compile time; the B
+// operand of the NEXT group (NCP 1-KiB loads) is then fetched into registers while
+// the MFMAs of the current group run, which is what keeps HBM busy at the skinny
+// shapes of the search (a handful of queries per list).  NCP == 0: any p.ncp, no
+// prefetch.
+template <int DT, int NCP>
 __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
     const ScanItem it = p.items[blockIdx.x];
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
-    const int nchunks = 2 * p.ncp, K = p.K;
+    const int ncp = NCP > 0 ? NCP : p.ncp;
+    const int nchunks = 2 * ncp, K = p.K;
     const int row_bytes = p.dim * (DT == 0 ? 1 : 4);
     const int real_chunks = row_bytes / kChunkBytes;
 
@@ -114,14 +120,33 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     const bool any_and = __any(and_rows != 0);
 
     const int n_groups = (it.n + kGroup - 1) / kGroup;
+    constexpr int NB = NCP > 0 ? NCP : 1;
+    uint4 bnext[NB];
+    if constexpr (NCP > 0) {
+        const uint4 *blk0 = p.xblk + it.group0 * (int64_t)(nchunks * 32);
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) bnext[cp] = blk0[(2 * cp + h) * 32 + n32];
+    }
     for (int grp = 0; grp < n_groups; ++grp) {
         const uint4 *blk = p.xblk + (it.group0 + grp) * (int64_t)(nchunks * 32);
         typename Acc<DT>::type acc;
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0;
-#pragma unroll 4
-        for (int cp = 0; cp < p.ncp; ++cp) {
-            uint4 b = blk[(2 * cp + h) * 32 + n32];
+        uint4 bcur[NB];
+        if constexpr (NCP > 0) {
+#pragma unroll
+            for (int cp = 0; cp < NCP; ++cp) bcur[cp] = bnext[cp];
+            if (grp + 1 < n_groups) {
+                const uint4 *nblk = blk + nchunks * 32;
+#pragma unroll
+                for (int cp = 0; cp < NCP; ++cp) bnext[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+        }
+#pragma unroll
+        for (int cp = 0; cp < ncp; ++cp) {
+            uint4 b;
+            if constexpr (NCP > 0) b = bcur[cp];
+            else b = blk[(2 * cp + h) * 32 + n32];
             const uint4 a = qtile[(2 * cp + h) * 32 + n32];
             if constexpr (DT == 0) {
                 b.x ^= 0x80808080u; b.y ^= 0x80808080u; b.z ^= 0x80808080u; b.w ^= 0x80808080u;
@@ -161,22 +186,33 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
                     for (int o = 0; o < o_cnt[j] && pass; ++o) pass = has_label(p.meta, p.others[o_begin[j] + o], gid);
                 }
             }
-            uint64_t mask = __ballot(pass);
-            while (mask) {
-                const int b = __builtin_ctzll(mask);
-                mask &= mask - 1;
-                const int hh = b >> 5, row = rowbase + 4 * hh;
-                const uint32_t kd = __shfl(bits, b);
-                const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(it.entry0 + grp * kGroup + (b & 31));
-                const uint64_t cur = lane < K ? best[row * K + lane] : KEY_MAX;
-                const uint64_t worst = shfl64(cur, K - 1);
-                if (key >= worst) continue;
-                const int pos = __popcll(__ballot(cur < key));
-                const uint64_t up = shfl_up64(cur);
-                const uint64_t nw = lane < pos ? cur : (lane == pos ? key : up);
-                if (lane < K) best[row * K + lane] = nw;
-                const uint32_t t = (uint32_t)(shfl64(nw, K - 1) >> 32);
-                if (h == hh) thr[j] = t;
+            const uint64_t mask = __ballot(pass);
+            // the two rows this register holds (lanes 0..31: rowbase, lanes 32..63: rowbase + 4) are
+            // updated in registers, one slot of the row's sorted list per lane
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                uint32_t m = (uint32_t)(mask >> (32 * hh));
+                if (m == 0) continue;
+                const int row = rowbase + 4 * hh;
+                uint64_t cur = lane < K ? best[row * K + lane] : KEY_MAX;
+                bool dirty = false;
+                while (m) {
+                    const int b = __builtin_ctz(m);
+                    m &= m - 1;
+                    const uint32_t kd = __builtin_amdgcn_readlane(bits, 32 * hh + b);
+                    const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(it.entry0 + grp * kGroup + b);
+                    const uint64_t worst = readlane64(cur, K - 1);
+                    if (key >= worst) continue;
+                    const int pos = __popcll(__ballot(cur < key));
+                    const uint64_t up = wave_shr1_64(cur);
+                    cur = lane < pos ? cur : (lane == pos ? key : up);
+                    dirty = true;
+                }
+                if (dirty) {
+                    if (lane < K) best[row * K + lane] = cur;
+                    const uint32_t t = (uint32_t)(readlane64(cur, K - 1) >> 32);
+                    if (h == hh) thr[j] = t;
+                }
             }
         }
     }
@@ -256,8 +292,20 @@ void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
     const size_t lds = scan_lds_bytes(p);
-    if (dtype == 0) hipLaunchKernelGGL(scan_topk_kernel<0>, dim3(n_items), dim3(64), lds, s, p);
-    else hipLaunchKernelGGL(scan_topk_kernel<1>, dim3(n_items), dim3(64), lds, s, p);
+    const dim3 grid(n_items), block(64);
+    if (dtype == 0) {
+        switch (p.ncp) {
+        case 4: hipLaunchKernelGGL((scan_topk_kernel<0, 4>), grid, block, lds, s, p); break;   // dim 128
+        case 6: hipLaunchKernelGGL((scan_topk_kernel<0, 6>), grid, block, lds, s, p); break;   // dim 192
+        default: hipLaunchKernelGGL((scan_topk_kernel<0, 0>), grid, block, lds, s, p); break;
+        }
+    } else {
+        switch (p.ncp) {
+        case 12: hipLaunchKernelGGL((scan_topk_kernel<1, 12>), grid, block, lds, s, p); break; // dim 96
+        case 16: hipLaunchKernelGGL((scan_topk_kernel<1, 16>), grid, block, lds, s, p); break; // dim 128
+        default: hipLaunchKernelGGL((scan_topk_kernel<1, 0>), grid, block, lds, s, p); break;
+        }
+    }
 }
 
 }  // namespace vf
