@@ -2,18 +2,23 @@
 // virtual graph G_l of its label, with the greedy AND policy of Section 4.3.2.
 //
 // Mapping to CDNA4.  One wave64 per query (a one-wave workgroup: every step is
-// wave-synchronous, barriers cost nothing, and up to 32 queries are resident per
-// CU so that many independent gathers are in flight).  The top-M list ("itopk"),
-// the pending candidates and the visited hash live in LDS.  A wave is split into
-// eight 8-lane teams; a team fetches one candidate vector with 16-byte loads
-// (128 contiguous bytes per team and step) and reduces its partial sums with
-// DPP adds, so eight candidate rows are gathered at a time.
+// wave-synchronous and up to 32 queries are resident per CU, so many independent
+// gathers are in flight).  The top-M list ("itopk") lives in REGISTERS, sorted, one
+// slot per lane and E = ceil(itopk / 64) registers: a candidate that beats the
+// current worst entry is inserted by the whole wave with a ballot, a population
+// count and a DPP wave shift -- no sort, no LDS traffic, and the list is always
+// ordered, so picking the next parents is a ballot over the "unexpanded" bits.
+// LDS only holds the query vector, the visited hash and the candidate staging area.
+// A wave is split into eight 8-lane teams; a team fetches one candidate vector with
+// 16-byte loads (128 contiguous bytes per team and step) and reduces its partial
+// sums with DPP adds, so eight candidate rows are gathered at a time.
 //
 // Keys are (distance bits << 32 | local id << 1 | unexpanded): unsigned order is
-// (distance, local id) order with ties to the lower id; an expanded entry sorts
-// before an unexpanded duplicate of itself, which the merge then drops.  The
-// visited table may forget (bounded probing); by construction this changes the
-// number of distances computed, never the result.
+// (distance, local id) order with ties to the lower id.  The visited table may
+// forget (bounded probing); a forgotten vertex is scored again and then either loses
+// against the worst entry (the list only tightens) or is recognised as a duplicate
+// of an entry at insertion, so forgetting changes the number of distances computed,
+// never the result.
 //
 // fp32 distances are evaluated in a fixed order so that results can be compared
 // bit for bit with a CPU evaluation: lane t of a team sums (q_e - x_e)^2 over
@@ -47,38 +52,53 @@ __device__ __forceinline__ bool is_seed(uint32_t c, uint32_t n, uint32_t ns)
     return j < ns && (uint32_t)((j * n) / ns) == c;
 }
 
-struct BeamLds {
-    uint64_t *list;   // [LP]
-    int32_t *cand_c;  // [128]
-    int32_t *cand_g;  // [128]
-    int32_t *parents; // [8]
-    uint32_t *hash;   // [1 << hash_bits]
-    uint4 *qv;        // [row_bytes / 16]
+// The sorted top-M list: element i sits in register i / 64 of lane i % 64.
+template <int E> struct TopM {
+    uint64_t cur[E];
+    int itopk;
+    uint64_t worst;  // key of element itopk - 1 (KEY_MAX while the list is not full)
+
+    __device__ __forceinline__ void init(int itopk_)
+    {
+        itopk = itopk_;
+        worst = KEY_MAX;
+#pragma unroll
+        for (int r = 0; r < E; ++r) cur[r] = KEY_MAX;
+    }
+
+    // Insert a key (wave-uniform value).  Rejects keys that do not beat the worst entry
+    // and keys whose (distance, id) the list already holds.
+    __device__ __forceinline__ void insert(uint64_t key, int lane)
+    {
+        if (key >= worst) return;
+        int pos = 0;
+        bool dup = false;
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            dup = dup || __any((cur[r] >> 1) == (key >> 1));
+            pos += __popcll(__ballot(cur[r] < key));
+        }
+        if (dup) return;
+#pragma unroll
+        for (int r = E - 1; r >= 0; --r) {
+            uint64_t up = wave_shr1_64(cur[r]);
+            if (r > 0) {
+                const uint64_t carry = readlane64(cur[r - 1], 63);
+                if (lane == 0) up = carry;
+            }
+            const int idx = r * 64 + lane;
+            uint64_t nw = idx < pos ? cur[r] : (idx == pos ? key : up);
+            if (idx >= itopk) nw = KEY_MAX;
+            cur[r] = nw;
+        }
+        const int wl = (itopk - 1) & 63, wr = (itopk - 1) >> 6;
+#pragma unroll
+        for (int r = 0; r < E; ++r)
+            if (r == wr) worst = readlane64(cur[r], wl);
+    }
 };
 
-// Sort list[0..LP) ascending, drop duplicates of (distance, id) -- they sit next to
-// each other, the expanded copy first -- and everything beyond itopk.  LP <= 512.
-__device__ void sort_list(uint64_t *list, int LP, int itopk, int lane)
-{
-    for (;;) {
-        wave_bitonic_sort(list, LP, lane);
-        uint32_t dups = 0;
-        for (int i0 = 0, w = 0; i0 < LP; i0 += 64, ++w) {
-            const int i = i0 + lane;
-            const uint64_t cur = list[i], prev = i > 0 ? list[i - 1] : KEY_MAX;
-            if (i > 0 && cur != KEY_MAX && (cur >> 1) == (prev >> 1)) dups |= 1u << w;
-        }
-        __syncthreads();
-        if (!__any(dups != 0)) break;
-        for (int i0 = 0, w = 0; i0 < LP; i0 += 64, ++w)
-            if ((dups >> w) & 1u) list[i0 + lane] = KEY_MAX;
-        __syncthreads();
-    }
-    for (int i = itopk + lane; i < LP; i += 64) list[i] = KEY_MAX;
-    __syncthreads();
-}
-
-template <int DT>
+template <int DT, int E>
 __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 {
     extern __shared__ uint4 smem[];
@@ -87,50 +107,60 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     const int qi = p.gq_query[gq], label = p.gq_label[gq];
     const int n = p.meta.S[label];
     const int64_t base = p.meta.O_HS[label];
-    const int itopk = p.itopk, LP = p.LP, CB = LP - itopk, R = p.R;
+    const int itopk = p.itopk, R = p.R;
     const int row_bytes = p.dim * (DT == 0 ? 1 : 4);
     const int nchunks = row_bytes / kChunkBytes;
 
-    BeamLds s;
-    s.qv = smem;
-    s.list = (uint64_t *)(smem + nchunks);
-    s.cand_c = (int32_t *)(s.list + LP);
-    s.cand_g = s.cand_c + 128;
-    s.parents = s.cand_g + 128;
-    s.hash = (uint32_t *)(s.parents + 8);
+    uint4 *qv = smem;                                  // [nchunks]
+    int32_t *cand_c = (int32_t *)(smem + nchunks);     // [128] local ids
+    int32_t *cand_g = cand_c + 128;                    // [128] global ids
+    uint32_t *cand_d = (uint32_t *)(cand_g + 128);     // [128] distance bits
+    int32_t *parents = (int32_t *)(cand_d + 128);      // [8]
+    uint32_t *hash = (uint32_t *)(parents + 8);        // [1 << hash_bits]
 
     for (int i = lane; i < nchunks; i += 64)
-        s.qv[i] = *(const uint4 *)((const char *)p.Q + (int64_t)qi * row_bytes + i * kChunkBytes);
-    for (int i = lane; i < LP; i += 64) s.list[i] = KEY_MAX;
-    for (int i = lane; i < (1 << p.hash_bits); i += 64) s.hash[i] = 0xFFFFFFFFu;
+        qv[i] = *(const uint4 *)((const char *)p.Q + (int64_t)qi * row_bytes + i * kChunkBytes);
+    for (int i = lane; i < (1 << p.hash_bits); i += 64) hash[i] = 0xFFFFFFFFu;
     __syncthreads();
 
     int o_begin = 0, o_cnt = 0;
     if (p.others_off != nullptr) { o_begin = p.others_off[qi]; o_cnt = p.others_off[qi + 1] - o_begin; }
+    const int qq_lane = DT == 0 ? lane_qq_u8(qv, nchunks, tl) : 0;
 
-    const int qq_lane = DT == 0 ? lane_qq_u8(s.qv, nchunks, tl) : 0;
-
-    uint64_t thr = KEY_MAX;  // key of list[itopk-1] after the last sort
-    int pc = 0;              // pending candidates appended behind the list
+    TopM<E> top;
+    top.init(itopk);
     int n_scored = 0, n_expanded = 0, n_tested = 0;  // work counters (uniform across the wave)
 
-    // Score cand[0..cnt) (eight at a time, one per team) and append those that beat thr.
-    auto score_and_append = [&](int cnt) {
+    // Offer the candidates held one per lane (valid lanes, distance bits, local id) to the list.
+    auto offer = [&](bool valid, uint32_t bits, int c) {
+        uint64_t m = __ballot(valid && bits <= (uint32_t)(top.worst >> 32));
+        while (m) {
+            const int b = __builtin_ctzll(m);
+            m &= m - 1;
+            const uint32_t kb = __builtin_amdgcn_readlane(bits, b);
+            const uint32_t kc = (uint32_t)__builtin_amdgcn_readlane(c, b);
+            top.insert(((uint64_t)kb << 32) | ((uint64_t)kc << 1) | 1ull, lane);
+        }
+    };
+
+    // Distances of cand[0..cnt) (eight at a time, one per team) into cand_d.
+    auto score = [&](int cnt) {
         n_scored += cnt;
+#pragma unroll 2
         for (int r0 = 0; r0 < cnt; r0 += 8) {
             const int my = r0 + team;
-            const bool valid = my < cnt;
-            const int c = s.cand_c[valid ? my : 0];
-            const int g = s.cand_g[valid ? my : 0];
+            const int g = cand_g[my < cnt ? my : 0];
             const char *xrow = (const char *)p.X + (int64_t)g * row_bytes;
             uint32_t bits;
-            if (DT == 0) bits = team_dist_bits_u8(s.qv, qq_lane, xrow, nchunks, tl);
-            else bits = team_dist_bits_f32(s.qv, xrow, nchunks, tl);
-            const uint64_t key = ((uint64_t)bits << 32) | ((uint64_t)(uint32_t)c << 1) | 1ull;
-            const bool pass = valid && tl == 0 && key < thr;
-            const uint64_t m = __ballot(pass);
-            if (pass) s.list[itopk + pc + __popcll(m & ((1ull << lane) - 1ull))] = key;
-            pc += __popcll(m);
+            if (DT == 0) bits = team_dist_bits_u8(qv, qq_lane, xrow, nchunks, tl);
+            else bits = team_dist_bits_f32(qv, xrow, nchunks, tl);
+            if (tl == 0 && my < cnt) cand_d[my] = bits;
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < cnt; i0 += 64) {
+            const int i = i0 + lane;
+            const bool valid = i < cnt;
+            offer(valid, valid ? cand_d[i] : 0u, valid ? cand_c[i] : 0);
         }
     };
 
@@ -145,17 +175,10 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         const uint64_t m = __ballot(valid);
         if (valid) {
             const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
-            s.cand_c[at] = c;
-            s.cand_g[at] = g;
+            cand_c[at] = c;
+            cand_g[at] = g;
         }
         return cnt + __popcll(m);
-    };
-
-    auto flush = [&]() {
-        __syncthreads();
-        sort_list(s.list, LP, itopk, lane);
-        thr = s.list[itopk - 1];
-        pc = 0;
     };
 
     // ---- InitializeSearch: stratified seeds floor(j * n / ns)
@@ -164,7 +187,6 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         // distances were computed densely per label; stream this query's row and keep the best
         const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
         for (int j0 = 0; j0 < ns; j0 += 64) {
-            if (pc + 64 > CB) flush();
             const int j = j0 + lane;
             const bool valid = j < ns;
             const uint32_t bits = valid ? drow[j] : 0u;
@@ -180,44 +202,44 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 n_scored += __popcll(__ballot(pass));
             } else {
                 n_scored += __popcll(__ballot(valid));
+                if (pass && bits <= (uint32_t)(top.worst >> 32)) c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
             }
-            pass = pass && bits <= (uint32_t)(thr >> 32);
-            if (pass && o_cnt == 0) c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
-            const uint64_t key = ((uint64_t)bits << 32) | ((uint64_t)(uint32_t)c << 1) | 1ull;
-            pass = pass && key < thr;
-            const uint64_t m = __ballot(pass);
-            if (pass) s.list[itopk + pc + __popcll(m & ((1ull << lane) - 1ull))] = key;
-            pc += __popcll(m);
+            offer(pass, bits, c);
         }
-    } else
-    for (int j0 = 0; j0 < ns; j0 += 64) {
-        if (pc + 64 > CB) flush();
-        const int j = j0 + lane;
-        const bool valid = j < ns;
-        const int c = valid ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
-        __syncthreads();
-        const int cnt = filter_and_compact(valid, c, 0);
-        __syncthreads();
-        score_and_append(cnt);
+    } else {
+        for (int j0 = 0; j0 < ns; j0 += 64) {
+            const int j = j0 + lane;
+            const bool valid = j < ns;
+            const int c = valid ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
+            __syncthreads();
+            const int cnt = filter_and_compact(valid, c, 0);
+            __syncthreads();
+            score(cnt);
+        }
     }
-    flush();
 
     // ---- iterations: expand the best unexpanded entries, score their unvisited children, merge
     for (int it = 0; it < p.iters; ++it) {
         int np = 0;
-        for (int blk = 0; blk < itopk && np < p.width; blk += 64) {
-            const int i = blk + lane;
-            const uint64_t key = i < itopk ? s.list[i] : KEY_MAX;
-            uint64_t m = __ballot(key != KEY_MAX && (key & 1ull));
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            uint64_t m = __ballot(top.cur[r] != KEY_MAX && (top.cur[r] & 1ull));
             while (m && np < p.width) {
                 const int b = __builtin_ctzll(m);
                 m &= m - 1;
                 if (lane == b) {
-                    s.list[i] = key & ~1ull;
-                    s.parents[np] = (int32_t)((key >> 1) & 0x7FFFFFFFu);
+                    parents[np] = (int32_t)((top.cur[r] >> 1) & 0x7FFFFFFFu);
+                    top.cur[r] &= ~1ull;
                 }
                 ++np;
             }
+        }
+        // clearing the flag lowers a key by one: refresh the cached worst key
+        {
+            const int wl = (itopk - 1) & 63, wr = (itopk - 1) >> 6;
+#pragma unroll
+            for (int r = 0; r < E; ++r)
+                if (r == wr) top.worst = readlane64(top.cur[r], wl);
         }
         __syncthreads();
         if (np == 0) break;
@@ -228,27 +250,25 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             bool valid = j < np * R;
             int c = -1;
             if (valid) {
-                const int pa = s.parents[j / R];
+                const int pa = parents[j / R];
                 c = p.G[(base + pa) * R + (j % R)];
                 valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns) &&
-                        visit(s.hash, p.hash_bits, (uint32_t)c);
+                        visit(hash, p.hash_bits, (uint32_t)c);
             }
             cnt = filter_and_compact(valid, c, cnt);
         }
         __syncthreads();
-        score_and_append(cnt);
-        if (pc > 0) flush();
+        score(cnt);
     }
-    __syncthreads();
 
     if (p.counters != nullptr && lane == 0) {
         int32_t *cn = p.counters + (int64_t)qi * 4;
         cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2;
     }
 
-    // ---- first k entries, local -> global through M
+    // ---- first k entries (k <= 64: register 0), local -> global through M
     if (lane < p.k) {
-        const uint64_t key = s.list[lane];
+        const uint64_t key = top.cur[0];
         const int64_t o = (int64_t)qi * p.k + lane;
         if (key == KEY_MAX) {
             p.out_ids[o] = -1;
@@ -264,15 +284,23 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 size_t beam_lds_bytes(const BeamParams &p, int dtype)
 {
     const size_t row_bytes = (size_t)p.dim * (dtype == 0 ? 1 : 4);
-    return row_bytes + (size_t)p.LP * 8 + 128 * 4 * 2 + 8 * 4 + ((size_t)4 << p.hash_bits);
+    return row_bytes + 128 * 4 * 3 + 8 * 4 + ((size_t)4 << p.hash_bits);
+}
+
+template <int DT> static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s)
+{
+    const dim3 grid(n_gq), block(64);
+    if (p.itopk <= 64) hipLaunchKernelGGL((beam_kernel<DT, 1>), grid, block, lds, s, p);
+    else if (p.itopk <= 128) hipLaunchKernelGGL((beam_kernel<DT, 2>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((beam_kernel<DT, 4>), grid, block, lds, s, p);
 }
 
 void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s)
 {
     if (n_gq <= 0) return;
     const size_t lds = beam_lds_bytes(p, dtype);
-    if (dtype == 0) hipLaunchKernelGGL(beam_kernel<0>, dim3(n_gq), dim3(64), lds, s, p);
-    else hipLaunchKernelGGL(beam_kernel<1>, dim3(n_gq), dim3(64), lds, s, p);
+    if (dtype == 0) launch_beam_dt<0>(p, n_gq, lds, s);
+    else launch_beam_dt<1>(p, n_gq, lds, s);
 }
 
 }  // namespace vf
