@@ -3,6 +3,7 @@
 // Section 4.3.2), kernel launches, export.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -84,6 +85,7 @@ struct vf_index {
     // the scan path runs beside the graph path on a second stream of the same (default) priority
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool overlap = true;  // VF_NO_OVERLAP=1 in the environment serialises the two paths (for per-kernel timing)
     vf_profile prof{};
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
@@ -303,6 +305,10 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
     } catch (const std::bad_alloc &) {
         set_error("out of host memory");
         return VF_ENOMEM;
+    }
+    {
+        const char *e = getenv("VF_NO_OVERLAP");
+        ix->overlap = !(e && e[0] == '1');
     }
     VF_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
     VF_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
@@ -611,7 +617,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         }
         // fork: scan kernels on the side stream, graph kernels on the caller's stream
         hipStream_t ss = s;
-        const bool forked = !exact && n_gq > 0 && !items.empty();
+        const bool forked = ix->overlap && !exact && n_gq > 0 && !items.empty();
         if (forked) {
             VF_HIP(hipEventRecord(ix->ev_fork, s));
             VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
@@ -671,7 +677,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 SeedParams sd{};
                 sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
                 sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
-                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride; sd.max_chunks = ns_stride / 32;
+                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride; sd.max_chunks = ns_stride / kSeedChunk;
                 sd.dseed = ix->dseed.as<uint32_t>();
                 launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
                 bp.dseed = sd.dseed;

@@ -53,17 +53,25 @@ __device__ __forceinline__ uint32_t team_dist_bits_f32(const uint4 *qv, const ch
 {
     const int steps = (nchunks + 7) >> 3;
     float acc = 0.0f;
-#pragma unroll 4
-    for (int st = 0; st < steps; ++st) {
-        const int ci = st * 8 + tl;
-        if (ci < nchunks) {
-            const uint4 x = *(const uint4 *)(xrow + ci * kChunkBytes);
-            const uint4 q = qv[ci];
-            float d;
-            d = __uint_as_float(q.x) - __uint_as_float(x.x); acc = __builtin_fmaf(d, d, acc);
-            d = __uint_as_float(q.y) - __uint_as_float(x.y); acc = __builtin_fmaf(d, d, acc);
-            d = __uint_as_float(q.z) - __uint_as_float(x.z); acc = __builtin_fmaf(d, d, acc);
-            d = __uint_as_float(q.w) - __uint_as_float(x.w); acc = __builtin_fmaf(d, d, acc);
+    for (int st0 = 0; st0 < steps; st0 += 4) {
+        uint4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {   // all loads of the batch are issued before the first use
+            const int ci = (st0 + u) * 8 + tl;
+            x[u] = make_uint4(0, 0, 0, 0);
+            if (ci < nchunks) x[u] = *(const uint4 *)(xrow + ci * kChunkBytes);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ci = (st0 + u) * 8 + tl;
+            if (ci < nchunks) {
+                const uint4 q = qv[ci];
+                float d;
+                d = __uint_as_float(q.x) - __uint_as_float(x[u].x); acc = __builtin_fmaf(d, d, acc);
+                d = __uint_as_float(q.y) - __uint_as_float(x[u].y); acc = __builtin_fmaf(d, d, acc);
+                d = __uint_as_float(q.z) - __uint_as_float(x[u].z); acc = __builtin_fmaf(d, d, acc);
+                d = __uint_as_float(q.w) - __uint_as_float(x[u].w); acc = __builtin_fmaf(d, d, acc);
+            }
         }
     }
     return __float_as_uint(team_sum_f(acc));

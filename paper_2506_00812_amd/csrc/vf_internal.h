@@ -14,6 +14,7 @@ constexpr uint64_t KEY_MAX = ~0ull;
 constexpr int kGroup = 32;       // vectors per interleaved group (Section 4.2.2)
 constexpr int kChunkBytes = 16;  // bytes per interleaved chunk  (Section 4.2.2)
 constexpr int kMaxOthers = 7;    // AND partners per query besides the searched label
+constexpr int kSeedChunk = 16;   // seeds per wave of the dense seed kernel
 
 // Per-label metadata on the device, used by the predicate and by the kernels to
 // slice a label's part of the compacted arrays (S, O, M of Alg. 1).
@@ -108,7 +109,7 @@ struct SeedParams {
     const int32_t *gq_query;
     const SeedTile *tiles;
     LabelMeta meta;
-    int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = ceil(n_seeds / 32)
+    int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = ceil(n_seeds / kSeedChunk)
     uint32_t *dseed;
 };
 

@@ -56,15 +56,31 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     __syncthreads();
 
     // ---- stage the query tile, chunk-major, and its norms
-    for (int idx = lane; idx < nchunks * 32; idx += 64) {
-        const int c = idx >> 5, r = idx & 31;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        const int qr = qrow_s[r];
-        if (qr >= 0 && c < real_chunks) {
-            v = *(const uint4 *)((const char *)p.qsrc + (int64_t)qr * row_bytes + c * kChunkBytes);
-            if (DT == 0) { v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u; }
+    {
+        // lane (r = n32, h) copies chunks h, h+2, ... of query row r; eight loads are issued
+        // before the first is stored so that their latencies overlap
+        const int qr = qrow_s[n32];
+        const char *qp = (const char *)p.qsrc + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
+        for (int c0 = h; c0 < nchunks; c0 += 16) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + 2 * u;
+                v[u] = make_uint4(0, 0, 0, 0);
+                if (qr >= 0 && c < real_chunks) v[u] = *(const uint4 *)(qp + c * kChunkBytes);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + 2 * u;
+                if (c < nchunks) {
+                    uint4 w = v[u];
+                    if (DT == 0 && qr >= 0 && c < real_chunks) {
+                        w.x ^= 0x80808080u; w.y ^= 0x80808080u; w.z ^= 0x80808080u; w.w ^= 0x80808080u;
+                    }
+                    qtile[c * 32 + n32] = w;
+                }
+            }
         }
-        qtile[idx] = v;
     }
     __syncthreads();
     {
@@ -127,6 +143,10 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 #pragma unroll
         for (int cp = 0; cp < NCP; ++cp) bnext[cp] = blk0[(2 * cp + h) * 32 + n32];
     }
+    // norm (and, for AND tiles, global id) of this lane's entry, fetched one group ahead as well
+    uint32_t xn_next = ((const uint32_t *)p.xnorm)[it.group0 * kGroup + n32];
+    int32_t gid_next = -1;
+    if (any_and && n32 < it.n) gid_next = p.map[it.map_off + it.entry0 + n32];
     for (int grp = 0; grp < n_groups; ++grp) {
         const uint4 *blk = p.xblk + (it.group0 + grp) * (int64_t)(nchunks * 32);
         typename Acc<DT>::type acc;
@@ -141,6 +161,13 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 #pragma unroll
                 for (int cp = 0; cp < NCP; ++cp) bnext[cp] = nblk[(2 * cp + h) * 32 + n32];
             }
+        }
+        const uint32_t xn = xn_next;
+        const int32_t gid = gid_next;
+        if (grp + 1 < n_groups) {
+            xn_next = ((const uint32_t *)p.xnorm)[(it.group0 + grp + 1) * kGroup + n32];
+            if (any_and && (grp + 1) * kGroup + n32 < it.n)
+                gid_next = p.map[it.map_off + it.entry0 + (grp + 1) * kGroup + n32];
         }
 #pragma unroll
         for (int cp = 0; cp < ncp; ++cp) {
@@ -162,16 +189,11 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         }
         const int entry = it.entry0 + grp * kGroup + n32;   // list-relative
         const bool col_ok = grp * kGroup + n32 < it.n;
-        const int64_t slot = (it.group0 + grp) * kGroup + n32;
-        uint32_t xn;
-        if (DT == 0) xn = (uint32_t)((const int32_t *)p.xnorm)[slot];
-        else xn = __float_as_uint(((const float *)p.xnorm)[slot]);
-        int32_t gid = -1;
-        if (any_and && col_ok) gid = p.map[it.map_off + entry];
 
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int rowbase = 8 * (j >> 2) + (j & 3);
+            if (rowbase >= it.q_count) continue;   // neither row of this register holds a query
             uint32_t bits;
             if constexpr (DT == 0) {
                 bits = (uint32_t)((int)qn[j] + (int)xn - 2 * acc[j]);

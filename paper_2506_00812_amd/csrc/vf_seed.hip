@@ -5,7 +5,7 @@
 // The seeds of a label -- local ids floor(j * n / ns) -- do not depend on the query,
 // so all queries of a label score the same vectors.  Instead of every query gathering
 // its seeds from HBM, one wave takes up to 64 queries of one label (one query per lane,
-// the query vector held in registers) and a chunk of 32 seeds staged once in LDS and
+// the query vector held in registers) and a chunk of kSeedChunk seeds staged once in LDS and
 // read back as broadcasts: the seed vectors are fetched once per 64 queries and the
 // inner loop is pure VALU work with no cross-lane traffic.  A lane evaluates the
 // distance in exactly the order the 8-lane teams of the beam kernel use (partial sum t
@@ -21,23 +21,24 @@ namespace vf {
 template <int DT, int NCH>
 __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 {
-    __shared__ uint4 xs[32 * NCH];
-    __shared__ uint32_t outb[64 * 33];
+    constexpr int SC = kSeedChunk;
+    __shared__ uint4 xs[SC * NCH];
+    __shared__ uint32_t outb[64 * (SC + 1)];
     const int lane = threadIdx.x;
     const int tile = blockIdx.x / p.max_chunks, chunk = blockIdx.x % p.max_chunks;
     const SeedTile t = p.tiles[tile];
     const int n = p.meta.S[t.label];
     const int64_t base = p.meta.O_HS[t.label];
     const int ns = p.n_seeds < n ? p.n_seeds : n;
-    const int j0 = chunk * 32;
+    const int j0 = chunk * SC;
     if (j0 >= ns) return;
-    const int cnt = ns - j0 < 32 ? ns - j0 : 32;
+    const int cnt = ns - j0 < SC ? ns - j0 : SC;
     constexpr int row_bytes = NCH * kChunkBytes;
 
     // seeds of this chunk -> global ids; stage their vectors
     int g = 0;
     if (lane < cnt) g = p.meta.M_HS[base + (int64_t)(((uint64_t)(j0 + lane) * (uint64_t)n) / (uint64_t)ns)];
-    for (int idx = lane; idx < 32 * NCH; idx += 64) {
+    for (int idx = lane; idx < SC * NCH; idx += 64) {
         const int i = idx / NCH, ch = idx % NCH;
         const int gi = __shfl(g, i);
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -93,15 +94,15 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
             const float c0 = b0 + b1, c1 = b2 + b3;
             bits = __float_as_uint(c0 + c1);
         }
-        outb[lane * 33 + i] = bits;
+        outb[lane * (SC + 1) + i] = bits;
     }
     __syncthreads();
 
-    // rows of dseed, 32 seeds (128 contiguous bytes) per query
-    for (int r0 = 0; r0 < t.q_count; r0 += 2) {
-        const int r = r0 + (lane >> 5), col = lane & 31;
+    // rows of dseed: SC consecutive seeds per query
+    for (int r0 = 0; r0 < t.q_count; r0 += 64 / SC) {
+        const int r = r0 + lane / SC, col = lane % SC;
         if (r < t.q_count && col < cnt)
-            p.dseed[(int64_t)(t.gq_begin + r) * p.ns_stride + j0 + col] = outb[r * 33 + col];
+            p.dseed[(int64_t)(t.gq_begin + r) * p.ns_stride + j0 + col] = outb[r * (SC + 1) + col];
     }
 }
 
