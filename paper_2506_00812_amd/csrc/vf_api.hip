@@ -440,8 +440,18 @@ static int check_search_args(const vf_index *ix, const void *queries, int64_t nq
 // Work list of the scan path.  The (label, query) pairs of one label are cut into
 // tiles of <= 32 queries; a long list is cut into segments of whole 32-vector groups
 // so that many waves share it, and a merge item per query then combines the segments.
-constexpr int kSegGroups = 16;   // 512 vectors per segment
 constexpr int kMaxSegs = 64;
+
+static int env_int(const char *name, int dflt, int lo, int hi)
+{
+    const char *e = getenv(name);
+    if (!e || !*e) return dflt;
+    const int v = atoi(e);
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+// tuning knobs (the environment overrides exist for experiments)
+static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
+static const int kTileRows = env_int("VF_TILE_ROWS", 16, 1, 32);      // queries per scan tile
 
 struct ItemBuilder {
     std::vector<int32_t> qrow;
@@ -457,9 +467,9 @@ struct ItemBuilder {
         const int32_t seg_groups = std::max(kSegGroups, (n_groups + kMaxSegs - 1) / kMaxSegs);
         const int32_t nseg = (n_groups + seg_groups - 1) / seg_groups;
         max_nseg = std::max(max_nseg, nseg);
-        for (size_t t = lo; t < hi; t += 32) {
+        for (size_t t = lo; t < hi; t += (size_t)kTileRows) {
             const int32_t q_begin = (int32_t)qrow.size();
-            const int32_t q_count = (int32_t)std::min<size_t>(32, hi - t);
+            const int32_t q_count = (int32_t)std::min<size_t>((size_t)kTileRows, hi - t);
             for (size_t u = t; u < t + (size_t)q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
             for (int32_t sg = 0; sg < nseg; ++sg) {
                 ScanItem it{};
