@@ -15,8 +15,12 @@
 //
 // Top-K.  Each lane ends up with the distances of 16 query rows to one list entry
 // (the MFMA accumulator layout).  A per-row threshold (the current K-th best) is
-// kept in registers; survivors are inserted, one at a time, into the row's sorted
-// list in LDS by the whole wave (one slot per lane, K <= 64).  Keys are
+// kept in registers; a lane appends its survivors to the rows' pending queues in LDS
+// (slot from an LDS atomic counter -- no cross-lane step).  When a queue could
+// overflow, the wave merges queue after queue into the row's sorted K best: bitonic
+// sort of the 64 pending keys in registers, element-wise minimum against the reversed
+// sorted list, bitonic merge -- and broadcasts the tightened thresholds.  The result
+// does not depend on the order in which candidates were queued.  Keys are
 // (distance bits << 32 | entry index): unsigned order == (distance, id) order.
 #include "vf_device.h"
 
@@ -35,6 +39,46 @@ template <> struct Acc<1> { using type = v16f; };
 // the MFMAs of the current group run, which is what keeps HBM busy at the skinny
 // shapes of the search (a handful of queries per list).  NCP == 0: any p.ncp, no
 // prefetch.
+// Ascending bitonic sort of the keys held one per lane, independently inside every
+// aligned segment of SEG lanes (SEG = 16, 32 or 64).
+template <int SEG> __device__ __forceinline__ uint64_t wave_sort_segments(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= SEG; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)v, j), hi = __shfl_xor((uint32_t)(v >> 32), j);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            const bool up = k == SEG ? true : (lane & k) == 0;
+            const bool take_min = ((lane & j) == 0) == up;
+            const uint64_t mn = v < o ? v : o, mx = v < o ? o : v;
+            v = take_min ? mn : mx;
+        }
+    }
+    return v;
+}
+
+// Ascending sort of a bitonic sequence held one key per lane (last stage of the network above).
+__device__ __forceinline__ uint64_t wave_bitonic_merge64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, j), hi = __shfl_xor((uint32_t)(v >> 32), j);
+        const uint64_t o = ((uint64_t)hi << 32) | lo;
+        const uint64_t mn = v < o ? v : o, mx = v < o ? o : v;
+        v = (lane & j) == 0 ? mn : mx;
+    }
+    return v;
+}
+
+// Orders the LDS accesses of a one-wave workgroup without waiting for outstanding global loads
+// (a wave's DS instructions execute in issue order; only the compiler must not reorder them).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <int DT, int NCP>
 __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 {
@@ -47,12 +91,16 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     const int real_chunks = row_bytes / kChunkBytes;
 
     uint4 *qtile = smem;                                         // [nchunks][32]
-    uint64_t *best = (uint64_t *)(smem + nchunks * 32);          // [32][K]
-    int32_t *qrow_s = (int32_t *)(best + 32 * K);                // [32]
+    const int KS = K | 1;                                        // row stride of `best` (odd: spreads LDS banks)
+    constexpr int PC = 64;                                       // pending slots per row: drained before a group could overflow them
+    uint64_t *pend = (uint64_t *)(smem + nchunks * 32);          // [tile_rows][PC] candidates not yet merged
+    uint64_t *best = pend + p.tile_rows * PC;                    // [tile_rows][KS] K best so far, ascending, KEY_MAX padded
+    int32_t *qrow_s = (int32_t *)(best + p.tile_rows * KS);      // [32]
     uint32_t *qnorm_s = (uint32_t *)(qrow_s + 32);               // [32] float bits / int
+    uint32_t *pcnt = qnorm_s + 32;                               // [32] keys waiting in pend[r]
 
-    if (lane < 32) qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1;
-    for (int i = lane; i < 32 * K; i += 64) best[i] = KEY_MAX;
+    if (lane < 32) { qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1; pcnt[lane] = 0; }
+    for (int i = lane; i < p.tile_rows * KS; i += 64) best[i] = KEY_MAX;
     __syncthreads();
 
     // ---- stage the query tile, chunk-major, and its norms
@@ -134,6 +182,39 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         }
     }
     const bool any_and = __any(and_rows != 0);
+    // state of tile row r, held by lane r (r < 32)
+    int pcv = 0;                  // keys waiting in pend[r] (copy of pcnt[r])
+    uint64_t row_kth = KEY_MAX;   // K-th best key of row r so far; a candidate must be smaller to enter
+
+    // Merge the pending queue of every row into its sorted K best, one row at a time with the whole
+    // wave, then broadcast the thresholds to the accumulator layout (thr[j] of lane (n32, h)
+    // belongs to row 8*(j/4) + 4*h + (j%4)).
+    auto drain = [&]() {
+        wave_lds_sync();
+        for (int r = 0; r < it.q_count; ++r) {
+            const int pc = __builtin_amdgcn_readlane(pcv, r);
+            if (pc == 0) continue;
+            const uint64_t kth = readlane64(row_kth, r);
+            uint64_t v = lane < pc ? pend[r * PC + lane] : KEY_MAX;
+            v = v < kth ? v : KEY_MAX;
+            if (!__any(v != KEY_MAX)) continue;
+            v = wave_sort_segments<64>(v, lane);
+            const uint64_t w = lane < K ? best[r * KS + lane] : KEY_MAX;
+            const uint32_t lo = __shfl((uint32_t)v, 63 - lane), hi = __shfl((uint32_t)(v >> 32), 63 - lane);
+            const uint64_t vr = ((uint64_t)hi << 32) | lo;
+            uint64_t m = w < vr ? w : vr;   // the 64 smallest of both, as a bitonic sequence
+            m = wave_bitonic_merge64(m, lane);
+            if (lane < K) best[r * KS + lane] = m;
+            const uint64_t nk = readlane64(m, K - 1);
+            if (lane == r) row_kth = nk;
+        }
+        if (lane < 32) pcnt[lane] = 0;
+        pcv = 0;
+        wave_lds_sync();
+        const uint32_t t = (uint32_t)(row_kth >> 32);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) thr[j] = __shfl(t, 8 * (j >> 2) + 4 * h + (j & 3));
+    };
 
     const int n_groups = (it.n + kGroup - 1) / kGroup;
     constexpr int NB = NCP > 0 ? NCP : 1;
@@ -147,6 +228,8 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     uint32_t xn_next = ((const uint32_t *)p.xnorm)[it.group0 * kGroup + n32];
     int32_t gid_next = -1;
     if (any_and && n32 < it.n) gid_next = p.map[it.map_off + it.entry0 + n32];
+    // graph build: the entry that is the query itself is skipped (entry == self0 + row base)
+    const int self0 = it.self_base >= 0 ? it.self_base + 4 * h : -0x40000000;
     for (int grp = 0; grp < n_groups; ++grp) {
         const uint4 *blk = p.xblk + (it.group0 + grp) * (int64_t)(nchunks * 32);
         typename Acc<DT>::type acc;
@@ -190,60 +273,55 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         const int entry = it.entry0 + grp * kGroup + n32;   // list-relative
         const bool col_ok = grp * kGroup + n32 < it.n;
 
+        // phase 1 (pure VALU, branch-free): distances and threshold tests of this lane's 16 rows
+        uint32_t bitsv[16];
+        uint32_t pm = 0;   // bit j: the entry of this lane is a candidate for row(j)
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int rowbase = 8 * (j >> 2) + (j & 3);
-            if (rowbase >= it.q_count) continue;   // neither row of this register holds a query
-            uint32_t bits;
             if constexpr (DT == 0) {
-                bits = (uint32_t)((int)qn[j] + (int)xn - 2 * acc[j]);
+                bitsv[j] = (uint32_t)((int)qn[j] + (int)xn - 2 * acc[j]);
             } else {
-                float d = (__uint_as_float(qn[j]) + __uint_as_float(xn)) - 2.0f * acc[j];
-                bits = __float_as_uint(fmaxf(d, 0.0f));
+                const float d = (__uint_as_float(qn[j]) + __uint_as_float(xn)) - 2.0f * acc[j];
+                bitsv[j] = __float_as_uint(fmaxf(d, 0.0f));
             }
-            bool pass = col_ok && ((live_rows >> j) & 1u) && bits <= thr[j];
-            if (it.self_base >= 0) pass = pass && (entry != it.self_base + rowbase + 4 * h);
-            if (any_and) {
-                if (pass && ((and_rows >> j) & 1u)) {
-                    for (int o = 0; o < o_cnt[j] && pass; ++o) pass = has_label(p.meta, p.others[o_begin[j] + o], gid);
-                }
-            }
-            const uint64_t mask = __ballot(pass);
-            // the two rows this register holds (lanes 0..31: rowbase, lanes 32..63: rowbase + 4) are
-            // updated in registers, one slot of the row's sorted list per lane
+            const uint32_t below = bitsv[j] <= thr[j] ? 1u : 0u;
+            const uint32_t not_self = entry != self0 + 8 * (j >> 2) + (j & 3) ? 1u : 0u;
+            pm |= (below & not_self) << j;
+        }
+        pm &= col_ok ? live_rows : 0u;
+        if (any_and && pm != 0) {
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                uint32_t m = (uint32_t)(mask >> (32 * hh));
-                if (m == 0) continue;
-                const int row = rowbase + 4 * hh;
-                uint64_t cur = lane < K ? best[row * K + lane] : KEY_MAX;
-                bool dirty = false;
-                while (m) {
-                    const int b = __builtin_ctz(m);
-                    m &= m - 1;
-                    const uint32_t kd = __builtin_amdgcn_readlane(bits, 32 * hh + b);
-                    const uint64_t key = ((uint64_t)kd << 32) | (uint32_t)(it.entry0 + grp * kGroup + b);
-                    const uint64_t worst = readlane64(cur, K - 1);
-                    if (key >= worst) continue;
-                    const int pos = __popcll(__ballot(cur < key));
-                    const uint64_t up = wave_shr1_64(cur);
-                    cur = lane < pos ? cur : (lane == pos ? key : up);
-                    dirty = true;
-                }
-                if (dirty) {
-                    if (lane < K) best[row * K + lane] = cur;
-                    const uint32_t t = (uint32_t)(readlane64(cur, K - 1) >> 32);
-                    if (h == hh) thr[j] = t;
+            for (int j = 0; j < 16; ++j) {
+                if (((pm & and_rows) >> j) & 1u) {
+                    bool ok = true;
+                    for (int o = 0; o < o_cnt[j] && ok; ++o) ok = has_label(p.meta, p.others[o_begin[j] + o], gid);
+                    if (!ok) pm &= ~(1u << j);
                 }
             }
         }
+        // phase 2: every lane queues its candidates (slot from the row's LDS counter)
+        if (pm != 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if ((pm >> j) & 1u) {
+                    const int row = 8 * (j >> 2) + 4 * h + (j & 3);
+                    const uint32_t slot = atomicAdd(&pcnt[row], 1u);
+                    pend[row * PC + slot] = ((uint64_t)bitsv[j] << 32) | (uint32_t)entry;
+                }
+            }
+        }
+        if (__any(pm != 0)) {
+            wave_lds_sync();
+            pcv = lane < 32 ? (int)pcnt[lane] : 0;
+        }
+        if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
     }
     __syncthreads();
 
-    // ---- results
+    // ---- results: every row's K best are already in ascending order
     for (int r = 0; r < it.q_count; ++r) {
         if (lane >= K) continue;
-        const uint64_t key = best[r * K + lane];
+        const uint64_t key = best[r * KS + lane];
         const bool none = key == KEY_MAX;
         const uint32_t hi = (uint32_t)(key >> 32), idx = (uint32_t)key;
         if (it.part_row < 0) {
@@ -293,7 +371,26 @@ __global__ __launch_bounds__(64) void scan_merge_kernel(const MergeItem *items, 
 
 static size_t scan_lds_bytes(const ScanParams &p)
 {
-    return (size_t)2 * p.ncp * 32 * 16 + (size_t)32 * p.K * 8 + 32 * 4 + 32 * 4;
+    return (size_t)2 * p.ncp * 32 * 16 + (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;
+}
+
+template <int DT> static void launch_scan_dt(const ScanParams &p, int n_items, hipStream_t s)
+{
+    const size_t lds = scan_lds_bytes(p);
+    const dim3 grid(n_items), block(64);
+    if (DT == 0) {
+        switch (p.ncp) {
+        case 4: hipLaunchKernelGGL((scan_topk_kernel<DT, 4>), grid, block, lds, s, p); break;   // uint8 dim 128
+        case 6: hipLaunchKernelGGL((scan_topk_kernel<DT, 6>), grid, block, lds, s, p); break;   // uint8 dim 192
+        default: hipLaunchKernelGGL((scan_topk_kernel<DT, 0>), grid, block, lds, s, p); break;
+        }
+    } else {
+        switch (p.ncp) {
+        case 12: hipLaunchKernelGGL((scan_topk_kernel<DT, 12>), grid, block, lds, s, p); break; // float dim 96
+        case 16: hipLaunchKernelGGL((scan_topk_kernel<DT, 16>), grid, block, lds, s, p); break; // float dim 128
+        default: hipLaunchKernelGGL((scan_topk_kernel<DT, 0>), grid, block, lds, s, p); break;
+        }
+    }
 }
 
 void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,
@@ -313,21 +410,8 @@ void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int
 void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
-    const size_t lds = scan_lds_bytes(p);
-    const dim3 grid(n_items), block(64);
-    if (dtype == 0) {
-        switch (p.ncp) {
-        case 4: hipLaunchKernelGGL((scan_topk_kernel<0, 4>), grid, block, lds, s, p); break;   // dim 128
-        case 6: hipLaunchKernelGGL((scan_topk_kernel<0, 6>), grid, block, lds, s, p); break;   // dim 192
-        default: hipLaunchKernelGGL((scan_topk_kernel<0, 0>), grid, block, lds, s, p); break;
-        }
-    } else {
-        switch (p.ncp) {
-        case 12: hipLaunchKernelGGL((scan_topk_kernel<1, 12>), grid, block, lds, s, p); break; // dim 96
-        case 16: hipLaunchKernelGGL((scan_topk_kernel<1, 16>), grid, block, lds, s, p); break; // dim 128
-        default: hipLaunchKernelGGL((scan_topk_kernel<1, 0>), grid, block, lds, s, p); break;
-        }
-    }
+    if (dtype == 0) launch_scan_dt<0>(p, n_items, s);
+    else launch_scan_dt<1>(p, n_items, s);
 }
 
 }  // namespace vf
