@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=64)
+    ap.add_argument("--latency", action="store_true",
+                    help="also measure small-batch latency (batches of 1, 8 and 64 queries, half graph / half scan labels)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (scale reference for HBM byte counters)")
     args = ap.parse_args()
@@ -239,6 +241,36 @@ def main():
                  "params_0.99": dict(zip(("itopk", "width", "iters", "n_seeds"), p99[0]))}
     else:
         extra = {"qps_at_recall_0.99": None, "recall_ceiling": round(max(t[1] for t in table), 4)}
+
+    # ---- small-batch latency on the same index (batches of 1, 8, 64; labels half graph lists, half scan lists)
+    if args.latency:
+        S_host = ix.export("S")
+        lab = w.qlabel_ids[w.qlabel_offsets[:-1]]
+        gq_idx = np.flatnonzero(S_host[lab] >= s.T)
+        sq_idx = np.flatnonzero((S_host[lab] < s.T) & (S_host[lab] > 0))
+        rng = np.random.default_rng(4321)
+        lat = {}
+        p_lat = (p99 or headline)[0]
+        for bs in (1, 8, 64):
+            times = []
+            n_batches = 1200
+            for b in range(n_batches):
+                ng = bs // 2 if bs > 1 else (b % 2)
+                pick = np.concatenate([rng.choice(gq_idx, size=ng, replace=False),
+                                       rng.choice(sq_idx, size=bs - ng, replace=False)])
+                Qb = Q[torch.from_numpy(pick).cuda()].contiguous()
+                qo = np.arange(bs + 1, dtype=np.int64)
+                ql = np.ascontiguousarray(lab[pick])
+                oi = out_ids[:bs]; od = out_dists[:bs]
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                vf.search(ix, Qb, qo, ql, k, *p_lat, oi, od)
+                torch.cuda.synchronize()
+                times.append((time.perf_counter() - t0) * 1e3)
+            t = np.sort(np.array(times[200:]))      # first 200 batches are warm-up
+            lat[f"batch_{bs}"] = {"p50_ms": round(float(t[len(t) // 2]), 4), "p99_ms": round(float(t[int(len(t) * 0.99)]), 4),
+                                  "qps": round(bs / float(np.mean(t)) * 1e3, 1)}
+        extra["latency"] = {"params": dict(zip(("itopk", "width", "iters", "n_seeds"), p_lat)), **lat}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same queries
     cpu = None

@@ -102,3 +102,37 @@ def test_full_size_ground_truth_spot_check(c2):
         order = np.lexsort((lst, d))[:s.k]
         assert_close_with_ties(gi[j:j + 1], gd[j:j + 1], lst[order][None, :].astype(np.int64),
                                d[order][None, :].astype(np.float32), 1e-4, f"ground truth query {j}")
+
+
+def test_c3_like_midscale_sampled_against_oracle():
+    """YFCC-like structure (uint8, dim 192, 200,000 labels with a long tail, 30 % two-label AND
+    queries) at one million vectors: bit-exact parity on sampled queries, graph and scan path,
+    single label and AND, against the oracle's lazily built graph rows."""
+    import torch
+    from paper_2506_00812_amd import binding as vf
+    w = make_workload("c3", n=1_000_000, nq=5000)
+    s = w.spec
+    X = torch.from_numpy(w.vectors).cuda()
+    Q = torch.from_numpy(w.queries).cuda()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True)
+    for name in ("S", "O_HS", "O_LS", "M_HS", "M_LS"):
+        assert np.array_equal(ix.export(name), getattr(ixo, name)), name
+    params = dict(itopk=64, width=1, iters=16, n_seeds=1024)
+    ids, dists = vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, s.k, **params)
+    torch.cuda.synchronize()
+    ids, dists = to_np(ids), to_np(dists)
+    two = np.diff(w.qlabel_offsets) > 1
+    rng = np.random.default_rng(8)
+    sample = np.sort(np.concatenate([rng.choice(np.flatnonzero(two), size=16, replace=False),
+                                     rng.choice(np.flatnonzero(~two), size=24, replace=False)]))
+    qo = np.zeros(len(sample) + 1, dtype=np.int64)
+    np.cumsum(np.diff(w.qlabel_offsets)[sample], out=qo[1:])
+    ql = np.concatenate([w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]] for j in sample])
+    io, do, info = ixo.search(w.queries[sample], qo, ql, s.k, with_info=True, **params)
+    assert (info["method"] == 2).sum() >= 10 and (info["method"] == 1).sum() >= 3
+    assert_exact(ids[sample], dists[sample], io, do, "c3-like sampled")
+    # exact mode on the same sample
+    gi, gd = vf.search_exact(ix, Q[torch.from_numpy(sample).cuda()].contiguous(), qo, ql, s.k)
+    eo, ed = ixo.search(w.queries[sample], qo, ql, s.k, force_scan=True)
+    assert_exact(to_np(gi), to_np(gd), eo, ed, "c3-like exact")
