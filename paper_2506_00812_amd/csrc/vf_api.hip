@@ -60,6 +60,18 @@ struct Staging {  // pinned host blob + the event that says its last upload has 
     bool pending = false;
 };
 
+// Result of routing one batch (host side) and the scratch it reuses between calls.
+struct Routed {
+    std::vector<int32_t> gq_query, gq_label;          // graph queries, grouped by label (ascending), stable in query order
+    std::vector<int32_t> others_off, others;          // [nq+1], AND partner labels per query
+    std::vector<uint64_t> scan_pairs;                 // (label << 32 | query) of scan queries, ascending
+    bool any_and = false;
+    // scratch kept between calls
+    std::vector<int32_t> q_best;                      // searched label of each query, -1: empty result
+    std::vector<int32_t> cnt;                         // [n_labels] queries per searched label (zero between calls)
+    std::vector<int32_t> touched;                     // labels with cnt > 0
+};
+
 }  // namespace vf
 
 using namespace vf;
@@ -92,6 +104,7 @@ struct vf_index {
     bool prof_folded = true;  // the last call's durations are already in the sums
     Staging stage[2];
     int stage_next = 0;
+    Routed routed;
 
     LabelMeta meta() const
     {
@@ -339,21 +352,22 @@ static int fold_profile(vf_index *ix)
 
 namespace {
 
-struct Routed {
-    std::vector<int32_t> gq_query, gq_label;          // graph queries
-    std::vector<int32_t> others_off, others;          // [nq+1], AND partner labels per query
-    std::vector<uint64_t> scan_pairs;                 // (label << 32 | query) of scan queries
-    bool any_and = false;
-};
-
-// ClassifyQueries (Alg. 2) + smallest-list choice (Section 4.3.2).
+// ClassifyQueries (Alg. 2) + smallest-list choice (Section 4.3.2).  Queries are grouped by the
+// label they search with a counting sort: O(nq + labels touched), no comparison sort of the batch.
 int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int32_t *qids, bool all_scan, Routed &r)
 {
     VF_REQUIRE(qoff && qids, "NULL query label arrays");
     VF_REQUIRE(qoff[0] >= 0, "qlabel_offsets[0] must be >= 0");
     r.others_off.assign((size_t)nq + 1, 0);
     r.others.clear();
-    r.gq_query.clear(); r.gq_label.clear(); r.scan_pairs.clear();
+    r.any_and = false;
+    r.q_best.resize((size_t)nq);
+    if (r.cnt.size() != (size_t)ix->n_labels) r.cnt.assign((size_t)ix->n_labels, 0);
+    r.touched.clear();
+    struct Reset {   // the counters must be zero again on every exit path
+        Routed &r;
+        ~Reset() { for (int32_t l : r.touched) r.cnt[(size_t)l] = 0; }
+    } reset{r};
     int32_t labs[kMaxOthers + 1];
     for (int64_t j = 0; j < nq; ++j) {
         const int64_t b = qoff[j], e = qoff[j + 1];
@@ -380,24 +394,35 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
             for (int32_t i = 0; i < nl; ++i)
                 if (labs[i] != best) r.others.push_back(labs[i]);
             if (nl > 1) r.any_and = true;
-            if (!all_scan && ix->S[(size_t)best] >= ix->T) {
-                r.gq_query.push_back((int32_t)j);
-                r.gq_label.push_back(best);
-            } else {
-                r.scan_pairs.push_back(((uint64_t)(uint32_t)best << 32) | (uint32_t)j);
-            }
+            if (r.cnt[(size_t)best]++ == 0) r.touched.push_back(best);
         }
+        r.q_best[(size_t)j] = empty ? -1 : best;
         r.others_off[(size_t)j + 1] = (int32_t)r.others.size();
     }
-    std::sort(r.scan_pairs.begin(), r.scan_pairs.end());
-    // graph queries grouped by label (stable in query order) so that the queries of a
-    // label form tiles for the dense seed kernel
-    {
-        const size_t n_gq = r.gq_query.size();
-        std::vector<uint64_t> pairs(n_gq);
-        for (size_t i = 0; i < n_gq; ++i) pairs[i] = ((uint64_t)(uint32_t)r.gq_label[i] << 32) | (uint32_t)r.gq_query[i];
-        std::sort(pairs.begin(), pairs.end());
-        for (size_t i = 0; i < n_gq; ++i) { r.gq_label[i] = (int32_t)(pairs[i] >> 32); r.gq_query[i] = (int32_t)(uint32_t)pairs[i]; }
+    // offsets per touched label, graph labels and scan labels in separate outputs, each by ascending label
+    std::sort(r.touched.begin(), r.touched.end());
+    size_t n_g = 0, n_s = 0;
+    for (int32_t l : r.touched) {
+        const bool graph = !all_scan && ix->S[(size_t)l] >= ix->T;
+        const int32_t c = r.cnt[(size_t)l];
+        // reuse the counter as "next free position" (graph positions are stored negated - 1)
+        if (graph) { r.cnt[(size_t)l] = -(int32_t)n_g - 1; n_g += (size_t)c; }
+        else { r.cnt[(size_t)l] = (int32_t)n_s + 1; n_s += (size_t)c; }
+    }
+    r.gq_query.resize(n_g); r.gq_label.resize(n_g); r.scan_pairs.resize(n_s);
+    for (int64_t j = 0; j < nq; ++j) {
+        const int32_t l = r.q_best[(size_t)j];
+        if (l < 0) continue;
+        int32_t &c = r.cnt[(size_t)l];
+        if (c < 0) {
+            const size_t at = (size_t)(-c - 1);
+            r.gq_query[at] = (int32_t)j; r.gq_label[at] = l;
+            --c;
+        } else {
+            const size_t at = (size_t)(c - 1);
+            r.scan_pairs[at] = ((uint64_t)(uint32_t)l << 32) | (uint32_t)j;
+            ++c;
+        }
     }
     return VF_OK;
 }
@@ -515,7 +540,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
     }
     if (nq == 0) return VF_OK;
     try {
-        Routed r;
+        Routed &r = ix->routed;
         if ((rc = route_queries(ix, nq, qoff, qids, exact, r)) != VF_OK) return rc;
 
         // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
