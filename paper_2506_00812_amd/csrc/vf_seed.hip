@@ -5,9 +5,10 @@
 // The seeds of a label -- local ids floor(j * n / ns) -- do not depend on the query,
 // so all queries of a label score the same vectors.  Instead of every query gathering
 // its seeds from HBM, one wave takes up to 64 queries of one label (one query per lane,
-// the query vector held in registers) and a chunk of kSeedChunk seeds staged once in LDS and
-// read back as broadcasts: the seed vectors are fetched once per 64 queries and the
-// inner loop is pure VALU work with no cross-lane traffic.  A lane evaluates the
+// the query vector held in registers) and a chunk of kSeedChunk seeds; a seed vector is the
+// same for all lanes, so it is fetched with scalar loads and used as a scalar operand: the
+// seed vectors are fetched once per 64 queries and the inner loop is pure VALU work with
+// no LDS or cross-lane traffic.  A lane evaluates the
 // distance in exactly the order the 8-lane teams of the beam kernel use (partial sum t
 // takes the 16-byte chunks 8s + t, fused multiply-add, fixed tree), so the bits are
 // identical to a gathered evaluation and to the CPU evaluation.
@@ -22,7 +23,6 @@ template <int DT, int NCH>
 __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 {
     constexpr int SC = kSeedChunk;
-    __shared__ uint4 xs[SC * NCH];
     __shared__ uint32_t outb[64 * (SC + 1)];
     const int lane = threadIdx.x;
     const int tile = blockIdx.x / p.max_chunks, chunk = blockIdx.x % p.max_chunks;
@@ -35,16 +35,9 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
     const int cnt = ns - j0 < SC ? ns - j0 : SC;
     constexpr int row_bytes = NCH * kChunkBytes;
 
-    // seeds of this chunk -> global ids; stage their vectors
+    // seeds of this chunk -> global ids (lane i holds seed j0 + i)
     int g = 0;
     if (lane < cnt) g = p.meta.M_HS[base + (int64_t)(((uint64_t)(j0 + lane) * (uint64_t)n) / (uint64_t)ns)];
-    for (int idx = lane; idx < SC * NCH; idx += 64) {
-        const int i = idx / NCH, ch = idx % NCH;
-        const int gi = __shfl(g, i);
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (i < cnt) v = *(const uint4 *)((const char *)p.X + (int64_t)gi * row_bytes + ch * kChunkBytes);
-        xs[idx] = v;
-    }
 
     // this lane's query
     uint32_t q[NCH * 4];
@@ -62,19 +55,20 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 #pragma unroll
         for (int w = 0; w < NCH * 4; ++w) qq = __builtin_amdgcn_udot4(q[w], q[w], qq, false);
     }
-    __syncthreads();
 
     for (int i = 0; i < cnt; ++i) {
+        // the seed vector is wave uniform: it comes in through scalar loads and feeds the VALU
+        // as a scalar operand -- no LDS staging, no cross-lane traffic
+        const int gi = __builtin_amdgcn_readlane(g, i);
+        const uint32_t *__restrict__ xp = (const uint32_t *)((const char *)p.X + (int64_t)gi * row_bytes);
         uint32_t bits;
         if (DT == 0) {
             uint32_t xx = 0, qx = 0;
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) {
-                const uint4 x = xs[i * NCH + ch];
-                xx = __builtin_amdgcn_udot4(x.x, x.x, xx, false); qx = __builtin_amdgcn_udot4(q[ch * 4], x.x, qx, false);
-                xx = __builtin_amdgcn_udot4(x.y, x.y, xx, false); qx = __builtin_amdgcn_udot4(q[ch * 4 + 1], x.y, qx, false);
-                xx = __builtin_amdgcn_udot4(x.z, x.z, xx, false); qx = __builtin_amdgcn_udot4(q[ch * 4 + 2], x.z, qx, false);
-                xx = __builtin_amdgcn_udot4(x.w, x.w, xx, false); qx = __builtin_amdgcn_udot4(q[ch * 4 + 3], x.w, qx, false);
+            for (int w = 0; w < NCH * 4; ++w) {
+                const uint32_t x = xp[w];
+                xx = __builtin_amdgcn_udot4(x, x, xx, false);
+                qx = __builtin_amdgcn_udot4(q[w], x, qx, false);
             }
             bits = (uint32_t)((int)qq + (int)xx - 2 * (int)qx);
         } else {
@@ -83,12 +77,11 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
             for (int u = 0; u < 8; ++u) a[u] = 0.0f;
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const uint4 x = xs[i * NCH + ch];
-                float d;
-                d = __uint_as_float(q[ch * 4]) - __uint_as_float(x.x); a[ch & 7] = __builtin_fmaf(d, d, a[ch & 7]);
-                d = __uint_as_float(q[ch * 4 + 1]) - __uint_as_float(x.y); a[ch & 7] = __builtin_fmaf(d, d, a[ch & 7]);
-                d = __uint_as_float(q[ch * 4 + 2]) - __uint_as_float(x.z); a[ch & 7] = __builtin_fmaf(d, d, a[ch & 7]);
-                d = __uint_as_float(q[ch * 4 + 3]) - __uint_as_float(x.w); a[ch & 7] = __builtin_fmaf(d, d, a[ch & 7]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float d = __uint_as_float(q[ch * 4 + c]) - __uint_as_float(xp[ch * 4 + c]);
+                    a[ch & 7] = __builtin_fmaf(d, d, a[ch & 7]);
+                }
             }
             const float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];
             const float c0 = b0 + b1, c1 = b2 + b3;
