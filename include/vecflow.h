@@ -141,6 +141,10 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * vf_profile_read waits for the last profiled call and reports it, together with
  * the duration sums over all calls since vf_profile_enable(index, 1).  (A profiled
  * call waits for the previous profiled call's kernels before it launches its own.)
+ * on = 1 leaves the launch schedule as it is (IVF-BFS runs on a second stream beside
+ * IVF-Graph, so the two intervals overlap and each kernel shares the chip); on = 2 also
+ * puts every launch on the caller's stream, one after the other, so each interval is
+ * that kernel's duration with the chip to itself; on = 0 switches both off.
  *   per_query   optional host buffer [nq][4] int32 of the last call:
  *               distances computed, rows expanded, predicate tests, 2 if the query
  *               took the graph path (0 otherwise; the first three are then 0)

@@ -98,6 +98,7 @@ struct vf_index {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool overlap = true;  // VF_NO_OVERLAP=1 in the environment serialises the two paths (for per-kernel timing)
+    bool prof_serial = false;  // vf_profile_enable(index, 2): same, switched at run time
     vf_profile prof{};
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
@@ -652,7 +653,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         }
         // fork: scan kernels on the side stream, graph kernels on the caller's stream
         hipStream_t ss = s;
-        const bool forked = ix->overlap && !exact && n_gq > 0 && !items.empty();
+        const bool forked = ix->overlap && !ix->prof_serial && !exact && n_gq > 0 && !items.empty();
         if (forked) {
             VF_HIP(hipEventRecord(ix->ev_fork, s));
             VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
@@ -808,6 +809,7 @@ extern "C" int vf_profile_enable(vf_index *ix, int on)
         for (hipEvent_t &e : ix->prof_ev)
             if (!e) VF_HIP(hipEventCreate(&e));
     ix->profiling = on != 0;
+    ix->prof_serial = on == 2;
     ix->prof_valid = false;
     ix->prof_folded = true;
     ix->prof_scan_sum = ix->prof_seed_sum = ix->prof_beam_sum = 0;
