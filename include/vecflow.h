@@ -135,7 +135,7 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
 
 /*
  * Measurement support (not part of the paper's method).  While profiling is on,
- * every vf_search call brackets its IVF-BFS launch and its IVF-Graph launch with HIP
+ * every vf_search / vf_search_exact call brackets its IVF-BFS launch and its IVF-Graph launch with HIP
  * events on the caller's stream and has the graph kernel record, per query, how
  * many distances it computed, rows it expanded and predicate tests it made.
  * vf_profile_read waits for the last profiled call and reports it, together with

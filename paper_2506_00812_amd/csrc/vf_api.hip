@@ -485,6 +485,7 @@ struct ItemBuilder {
     std::vector<MergeItem> merges;
     int64_t part_rows = 0;
     int32_t max_nseg = 1;
+    int32_t tile_rows = kTileRows;
 
     // pairs[lo, hi) all carry the same label, whose list is (group0, map_off, n)
     void add_label(const std::vector<uint64_t> &pairs, size_t lo, size_t hi, int64_t group0, int64_t map_off, int32_t n)
@@ -493,9 +494,9 @@ struct ItemBuilder {
         const int32_t seg_groups = std::max(kSegGroups, (n_groups + kMaxSegs - 1) / kMaxSegs);
         const int32_t nseg = (n_groups + seg_groups - 1) / seg_groups;
         max_nseg = std::max(max_nseg, nseg);
-        for (size_t t = lo; t < hi; t += (size_t)kTileRows) {
+        for (size_t t = lo; t < hi; t += (size_t)tile_rows) {
             const int32_t q_begin = (int32_t)qrow.size();
-            const int32_t q_count = (int32_t)std::min<size_t>((size_t)kTileRows, hi - t);
+            const int32_t q_count = (int32_t)std::min<size_t>((size_t)tile_rows, hi - t);
             for (size_t u = t; u < t + (size_t)q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
             for (int32_t sg = 0; sg < nseg; ++sg) {
                 ScanItem it{};
@@ -634,7 +635,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         launch_fill_out(out_ids, out_dists, nq * (int64_t)k, s);
 
-        const bool prof = ix->profiling && !exact;
+        const bool prof = ix->profiling;
         if (prof) {
             if ((rc = fold_profile(ix)) != VF_OK) return rc;
             if ((rc = ix->counters.reserve((size_t)nq * 16)) != VF_OK) return rc;
@@ -666,7 +667,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         ScanParams sp{};
         sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
-        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = kTileRows; sp.sort_partials = 0;
+        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows; sp.sort_partials = 0;
         sp.out_ids = out_ids; sp.out_dists = out_dists;
         sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
         const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);

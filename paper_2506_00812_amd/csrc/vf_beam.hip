@@ -26,6 +26,10 @@
 // team combines ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7)).
 #include "vf_device.h"
 
+#ifndef VF_SEED_BLOCKS
+#define VF_SEED_BLOCKS 16
+#endif
+
 namespace vf {
 
 // true: id was not in the table (it is now, unless the probe budget ran out)
@@ -183,10 +187,63 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     // ---- InitializeSearch: stratified seeds floor(j * n / ns)
     const int ns = p.n_seeds < n ? p.n_seeds : n;
-    if (p.dseed != nullptr) {
-        // distances were computed densely per label; stream this query's row and keep the best
+    int j_begin = 0;   // seeds below j_begin have been dealt with
+    if (E == 1 && p.dseed != nullptr && o_cnt == 0) {
+        // Distances were computed densely per label.  Selection in two passes over chunks of
+        // 64 * NBLK seeds held in registers: the itopk-th smallest of the 64 per-lane minima is an
+        // upper bound of the itopk-th smallest distance of the chunk, so only the few seeds at or
+        // below it (and below the list's worst entry) are offered to the list.  Same result as
+        // offering every seed, at a fraction of the insertions.
+        constexpr int NBLK = VF_SEED_BLOCKS;
         const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
-        for (int j0 = 0; j0 < ns; j0 += 64) {
+        for (int jc = 0; jc < ns; jc += 64 * NBLK) {
+            uint32_t v[NBLK];
+#pragma unroll
+            for (int i = 0; i < NBLK; ++i) {
+                const int j = jc + i * 64 + lane;
+                v[i] = j < ns ? drow[j] : 0xFFFFFFFFu;
+            }
+            uint32_t mn = v[0];
+#pragma unroll
+            for (int i = 1; i < NBLK; ++i) mn = v[i] < mn ? v[i] : mn;
+            const uint32_t sorted = wave_sort_u32(mn, lane);
+            uint32_t tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, itopk - 1);
+            const uint32_t wb = (uint32_t)(top.worst >> 32);
+            tau = tau < wb ? tau : wb;
+            int total = 0;
+#pragma unroll
+            for (int i = 0; i < NBLK; ++i) total += __popcll(__ballot(v[i] <= tau && jc + i * 64 + lane < ns));
+            if (total > 128) break;   // no useful bound (fewer than itopk lanes hold a seed): plain path below
+            __syncthreads();
+            int cnt = 0;
+#pragma unroll
+            for (int i = 0; i < NBLK; ++i) {
+                const int j = jc + i * 64 + lane;
+                const bool pass = v[i] <= tau && j < ns;
+                const uint64_t m = __ballot(pass);
+                if (pass) {
+                    const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
+                    cand_d[at] = v[i];
+                    cand_c[at] = j;
+                }
+                cnt += __popcll(m);
+            }
+            __syncthreads();
+            for (int i0 = 0; i0 < cnt; i0 += 64) {
+                const int i = i0 + lane;
+                const bool valid = i < cnt;
+                const int c = valid ? (int)(((uint64_t)cand_c[i] * (uint64_t)n) / (uint64_t)ns) : 0;
+                offer(valid, valid ? cand_d[i] : 0u, c);
+            }
+            const int done = ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK;
+            n_scored += done;
+            j_begin = jc + done;
+        }
+    }
+    if (p.dseed != nullptr) {
+        // plain path (AND queries, long lists of candidates): stream the row and offer every seed
+        const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
+        for (int j0 = j_begin; j0 < ns; j0 += 64) {
             const int j = j0 + lane;
             const bool valid = j < ns;
             const uint32_t bits = valid ? drow[j] : 0u;

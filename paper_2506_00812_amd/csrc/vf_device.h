@@ -135,6 +135,23 @@ __device__ __forceinline__ uint64_t wave_shr1_64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Ascending bitonic sort of the 64 values held one per lane.
+__device__ __forceinline__ uint32_t wave_sort_u32(uint32_t v, int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)v, j);
+            const bool up = k == 64 ? true : (lane & k) == 0;
+            const bool take_min = ((lane & j) == 0) == up;
+            const uint32_t mn = v < o ? v : o, mx = v < o ? o : v;
+            v = take_min ? mn : mx;
+        }
+    }
+    return v;
+}
+
 // Bitonic sort of keys[0..n) ascending in LDS by one wave; n a power of two.
 __device__ __forceinline__ void wave_bitonic_sort(uint64_t *keys, int n, int lane)
 {

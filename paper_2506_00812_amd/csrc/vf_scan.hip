@@ -30,6 +30,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+#ifndef VF_DRAIN_ROWS
+#define VF_DRAIN_ROWS 4
+#endif
 template <int DT> struct Acc;
 template <> struct Acc<0> { using type = v16i; };
 template <> struct Acc<1> { using type = v16f; };
@@ -71,6 +74,41 @@ __device__ __forceinline__ uint64_t wave_bitonic_merge64(uint64_t v, int lane)
     return v;
 }
 
+// The same two networks over NR independent key sets at once: the chains of dependent
+// cross-lane moves of the NR sets interleave, which hides their latency.
+template <int NR> __device__ __forceinline__ void wave_sort64_multi(uint64_t (&v)[NR], int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const bool up = k == 64 ? true : (lane & k) == 0;
+            const bool take_min = ((lane & j) == 0) == up;
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                const uint32_t lo = __shfl_xor((uint32_t)v[u], j), hi = __shfl_xor((uint32_t)(v[u] >> 32), j);
+                const uint64_t o = ((uint64_t)hi << 32) | lo;
+                const uint64_t mn = v[u] < o ? v[u] : o, mx = v[u] < o ? o : v[u];
+                v[u] = take_min ? mn : mx;
+            }
+        }
+    }
+}
+
+template <int NR> __device__ __forceinline__ void wave_bitonic_merge64_multi(uint64_t (&v)[NR], int lane)
+{
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const uint32_t lo = __shfl_xor((uint32_t)v[u], j), hi = __shfl_xor((uint32_t)(v[u] >> 32), j);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            const uint64_t mn = v[u] < o ? v[u] : o, mx = v[u] < o ? o : v[u];
+            v[u] = (lane & j) == 0 ? mn : mx;
+        }
+    }
+}
+
 // Orders the LDS accesses of a one-wave workgroup without waiting for outstanding global loads
 // (a wave's DS instructions execute in issue order; only the compiler must not reorder them).
 __device__ __forceinline__ void wave_lds_sync()
@@ -80,7 +118,7 @@ __device__ __forceinline__ void wave_lds_sync()
 }
 
 template <int DT, int NCP>
-__global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
+__global__ __launch_bounds__(64, 2) void scan_topk_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
     const ScanItem it = p.items[blockIdx.x];
@@ -90,10 +128,11 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     const int row_bytes = p.dim * (DT == 0 ? 1 : 4);
     const int real_chunks = row_bytes / kChunkBytes;
 
-    uint4 *qtile = smem;                                         // [nchunks][32]
+    const int TR = p.tile_rows;                                  // rows the LDS buffers hold (16 or 32)
+    uint4 *qtile = smem;                                         // [nchunks][TR]
     const int KS = K | 1;                                        // row stride of `best` (odd: spreads LDS banks)
     constexpr int PC = 64;                                       // pending slots per row: drained before a group could overflow them
-    uint64_t *pend = (uint64_t *)(smem + nchunks * 32);          // [tile_rows][PC] candidates not yet merged
+    uint64_t *pend = (uint64_t *)(smem + nchunks * TR);          // [tile_rows][PC] candidates not yet merged
     uint64_t *best = pend + p.tile_rows * PC;                    // [tile_rows][KS] K best so far, ascending, KEY_MAX padded
     int32_t *qrow_s = (int32_t *)(best + p.tile_rows * KS);      // [32]
     uint32_t *qnorm_s = (uint32_t *)(qrow_s + 32);               // [32] float bits / int
@@ -120,12 +159,12 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int c = c0 + 2 * u;
-                if (c < nchunks) {
+                if (c < nchunks && n32 < TR) {
                     uint4 w = v[u];
                     if (DT == 0 && qr >= 0 && c < real_chunks) {
                         w.x ^= 0x80808080u; w.y ^= 0x80808080u; w.z ^= 0x80808080u; w.w ^= 0x80808080u;
                     }
-                    qtile[c * 32 + n32] = w;
+                    qtile[c * TR + n32] = w;
                 }
             }
         }
@@ -135,8 +174,8 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         // row n32, chunks h, h+2, ...
         if (DT == 0) {
             int acc = 0;
-            for (int c = h; c < nchunks; c += 2) {
-                const uint4 v = qtile[c * 32 + n32];
+            for (int c = h; c < nchunks && n32 < TR; c += 2) {
+                const uint4 v = qtile[c * TR + n32];
                 const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
@@ -150,8 +189,8 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
             if (h == 0) qnorm_s[n32] = (uint32_t)acc;
         } else {
             float acc = 0.f;
-            for (int c = h; c < nchunks; c += 2) {
-                const uint4 v = qtile[c * 32 + n32];
+            for (int c = h; c < nchunks && n32 < TR; c += 2) {
+                const uint4 v = qtile[c * TR + n32];
                 const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
@@ -166,19 +205,15 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     uint32_t qn[16], thr[16];
     uint32_t and_rows = 0;  // bit j: row(j) is an AND query
     uint32_t live_rows = 0; // bit j: row(j) holds a query
-    int32_t o_begin[16], o_cnt[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const int row = 8 * (j >> 2) + 4 * h + (j & 3);
         qn[j] = qnorm_s[row];
         thr[j] = 0xFFFFFFFFu;
         if (row < it.q_count) live_rows |= 1u << j;
-        o_begin[j] = 0; o_cnt[j] = 0;
         if (p.others_off != nullptr && row < it.q_count) {
             const int qr = qrow_s[row];
-            o_begin[j] = p.others_off[qr];
-            o_cnt[j] = p.others_off[qr + 1] - o_begin[j];
-            if (o_cnt[j] > 0) and_rows |= 1u << j;
+            if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << j;
         }
     }
     const bool any_and = __any(and_rows != 0);
@@ -190,23 +225,43 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     // wave, then broadcast the thresholds to the accumulator layout (thr[j] of lane (n32, h)
     // belongs to row 8*(j/4) + 4*h + (j%4)).
     auto drain = [&]() {
+        constexpr int NR = VF_DRAIN_ROWS;   // rows merged at once
         wave_lds_sync();
-        for (int r = 0; r < it.q_count; ++r) {
-            const int pc = __builtin_amdgcn_readlane(pcv, r);
-            if (pc == 0) continue;
-            const uint64_t kth = readlane64(row_kth, r);
-            uint64_t v = lane < pc ? pend[r * PC + lane] : KEY_MAX;
-            v = v < kth ? v : KEY_MAX;
-            if (!__any(v != KEY_MAX)) continue;
-            v = wave_sort_segments<64>(v, lane);
-            const uint64_t w = lane < K ? best[r * KS + lane] : KEY_MAX;
-            const uint32_t lo = __shfl((uint32_t)v, 63 - lane), hi = __shfl((uint32_t)(v >> 32), 63 - lane);
-            const uint64_t vr = ((uint64_t)hi << 32) | lo;
-            uint64_t m = w < vr ? w : vr;   // the 64 smallest of both, as a bitonic sequence
-            m = wave_bitonic_merge64(m, lane);
-            if (lane < K) best[r * KS + lane] = m;
-            const uint64_t nk = readlane64(m, K - 1);
-            if (lane == r) row_kth = nk;
+        uint32_t todo = (uint32_t)__ballot(lane < 32 && pcv > 0);
+        while (todo != 0) {
+            int rr[NR];
+            bool on[NR];
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                on[u] = todo != 0;
+                rr[u] = on[u] ? __builtin_ctz(todo) : rr[0];
+                todo &= todo - 1;
+            }
+            uint64_t v[NR];
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                const int pc = __builtin_amdgcn_readlane(pcv, rr[u]);
+                const uint64_t kth = readlane64(row_kth, rr[u]);
+                const uint64_t x = (on[u] && lane < pc) ? pend[rr[u] * PC + lane] : KEY_MAX;
+                v[u] = x < kth ? x : KEY_MAX;
+            }
+            wave_sort64_multi<NR>(v, lane);
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                const uint64_t w = lane < K ? best[rr[u] * KS + lane] : KEY_MAX;
+                const uint32_t lo = __shfl((uint32_t)v[u], 63 - lane), hi = __shfl((uint32_t)(v[u] >> 32), 63 - lane);
+                const uint64_t vr = ((uint64_t)hi << 32) | lo;
+                v[u] = w < vr ? w : vr;   // the 64 smallest of both, as a bitonic sequence
+            }
+            wave_bitonic_merge64_multi<NR>(v, lane);
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                if (on[u]) {   // wave uniform
+                    if (lane < K) best[rr[u] * KS + lane] = v[u];
+                    const uint64_t nk = readlane64(v[u], K - 1);
+                    if (lane == rr[u]) row_kth = nk;
+                }
+            }
         }
         if (lane < 32) pcnt[lane] = 0;
         pcv = 0;
@@ -217,12 +272,17 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
     };
 
     const int n_groups = (it.n + kGroup - 1) / kGroup;
+    // B operand registers: the whole group is resident; each half is refilled with the next
+    // group's chunks right after its own MFMAs have been issued, so the loads have the other
+    // half's MFMAs and the selection to complete in -- a full group of prefetch distance for
+    // one group's worth of registers.
     constexpr int NB = NCP > 0 ? NCP : 1;
-    uint4 bnext[NB];
+    constexpr int H0 = (NB + 1) / 2;
+    uint4 breg[NB];
     if constexpr (NCP > 0) {
         const uint4 *blk0 = p.xblk + it.group0 * (int64_t)(nchunks * 32);
 #pragma unroll
-        for (int cp = 0; cp < NCP; ++cp) bnext[cp] = blk0[(2 * cp + h) * 32 + n32];
+        for (int cp = 0; cp < NCP; ++cp) breg[cp] = blk0[(2 * cp + h) * 32 + n32];
     }
     // norm (and, for AND tiles, global id) of this lane's entry, fetched one group ahead as well
     uint32_t xn_next = ((const uint32_t *)p.xnorm)[it.group0 * kGroup + n32];
@@ -235,16 +295,6 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
         typename Acc<DT>::type acc;
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0;
-        uint4 bcur[NB];
-        if constexpr (NCP > 0) {
-#pragma unroll
-            for (int cp = 0; cp < NCP; ++cp) bcur[cp] = bnext[cp];
-            if (grp + 1 < n_groups) {
-                const uint4 *nblk = blk + nchunks * 32;
-#pragma unroll
-                for (int cp = 0; cp < NCP; ++cp) bnext[cp] = nblk[(2 * cp + h) * 32 + n32];
-            }
-        }
         const uint32_t xn = xn_next;
         const int32_t gid = gid_next;
         if (grp + 1 < n_groups) {
@@ -252,12 +302,10 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
             if (any_and && (grp + 1) * kGroup + n32 < it.n)
                 gid_next = p.map[it.map_off + it.entry0 + (grp + 1) * kGroup + n32];
         }
-#pragma unroll
-        for (int cp = 0; cp < ncp; ++cp) {
-            uint4 b;
-            if constexpr (NCP > 0) b = bcur[cp];
-            else b = blk[(2 * cp + h) * 32 + n32];
-            const uint4 a = qtile[(2 * cp + h) * 32 + n32];
+        auto contract = [&](int cp, uint4 b) {
+            // rows the tile does not hold contribute zeros without touching LDS
+            uint4 a = make_uint4(0, 0, 0, 0);
+            if (n32 < TR) a = qtile[(2 * cp + h) * TR + n32];
             if constexpr (DT == 0) {
                 b.x ^= 0x80808080u; b.y ^= 0x80808080u; b.z ^= 0x80808080u; b.w ^= 0x80808080u;
                 const v4i av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w};
@@ -269,6 +317,24 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
             }
+        };
+        if constexpr (NCP > 0) {
+            const bool more = grp + 1 < n_groups;
+            const uint4 *nblk = blk + nchunks * 32;
+#pragma unroll
+            for (int cp = 0; cp < H0; ++cp) contract(cp, breg[cp]);
+            if (more) {
+#pragma unroll
+                for (int cp = 0; cp < H0; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+#pragma unroll
+            for (int cp = H0; cp < NCP; ++cp) contract(cp, breg[cp]);
+            if (more) {
+#pragma unroll
+                for (int cp = H0; cp < NCP; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+        } else {
+            for (int cp = 0; cp < ncp; ++cp) contract(cp, blk[(2 * cp + h) * 32 + n32]);
         }
         const int entry = it.entry0 + grp * kGroup + n32;   // list-relative
         const bool col_ok = grp * kGroup + n32 < it.n;
@@ -293,8 +359,11 @@ __global__ __launch_bounds__(64) void scan_topk_kernel(ScanParams p)
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 if (((pm & and_rows) >> j) & 1u) {
+                    // partner labels of the row's query (looked up on demand: few pairs get here)
+                    const int qr = qrow_s[8 * (j >> 2) + 4 * h + (j & 3)];
+                    const int o_begin = p.others_off[qr], o_end = p.others_off[qr + 1];
                     bool ok = true;
-                    for (int o = 0; o < o_cnt[j] && ok; ++o) ok = has_label(p.meta, p.others[o_begin[j] + o], gid);
+                    for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(p.meta, p.others[o], gid);
                     if (!ok) pm &= ~(1u << j);
                 }
             }
@@ -371,7 +440,7 @@ __global__ __launch_bounds__(64) void scan_merge_kernel(const MergeItem *items, 
 
 static size_t scan_lds_bytes(const ScanParams &p)
 {
-    return (size_t)2 * p.ncp * 32 * 16 + (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;
+    return (size_t)2 * p.ncp * p.tile_rows * 16 + (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;
 }
 
 template <int DT> static void launch_scan_dt(const ScanParams &p, int n_items, hipStream_t s)
