@@ -146,8 +146,11 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * puts every launch on the caller's stream, one after the other, so each interval is
  * that kernel's duration with the chip to itself; on = 0 switches both off.
  *   per_query   optional host buffer [nq][4] int32 of the last call:
- *               distances computed, rows expanded, predicate tests, 2 if the query
- *               took the graph path (0 otherwise; the first three are then 0)
+ *               distances computed, rows expanded, predicate tests, and a mode word:
+ *               0 = scan path (the first three are then 0); low byte 2 = graph path,
+ *               3 = graph path whose matrix-core seed scores could not be proven
+ *               sufficient (the kernel then scored every seed itself); bits 8 and up =
+ *               seeds re-scored with the ordered distance after matrix-core scoring
  */
 typedef struct vf_profile {
     float scan_ms, seed_ms, beam_ms;   /* durations of the last call: IVF-BFS kernels, dense seed scoring, beam search */
@@ -160,6 +163,9 @@ typedef struct vf_profile {
     int64_t n_seed_tiles;              /* tiles of <= 64 same-label graph queries scored densely (0: seeds were gathered) */
     int64_t seed_pairs;                /* sum over graph queries of the seeds scored for them                            */
     int64_t seed_tile_seeds;           /* sum over seed tiles of the seeds they read                                     */
+    int64_t seeds_on_matrix_cores;     /* 1: float32 seeds were scored on MFMA (approximate) and re-ranked by the beam kernel */
+    int64_t seed_rescored;             /* ordered distances computed for that re-ranking                                 */
+    int64_t seed_fallbacks;            /* queries whose proof failed and that scored every seed themselves               */
 } vf_profile;
 
 int vf_profile_enable(vf_index *index, int on);

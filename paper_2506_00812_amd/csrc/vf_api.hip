@@ -89,6 +89,12 @@ struct vf_index {
     int32_t n_scan_labels = 0;
     // device
     DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
+    // float32 indexes with graph labels: squared norm of every row of X and the largest of them,
+    // for the matrix-core seed scoring (its error bound needs the largest norm)
+    DevBuf d_xnorm_all;
+    float xn_max = 0.f;
+    float seed_err_bound = 0.f;  // relative to |q|^2 + xn_max; VF_SEED_SLACK in the environment scales it (tests)
+    bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
     // search workspace
     DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
     // profiling
@@ -123,7 +129,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed};
     for (DevBuf *b : bufs) b->release();
     for (hipEvent_t e : ix->prof_ev)
         if (e) (void)hipEventDestroy(e);
@@ -314,6 +320,29 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
             VF_HIP(hipStreamSynchronize(s));
             ix->tmp_blk.release();
             ix->tmp_norm.release();
+            if (seed_mfma_supported(ix->dtype, ix->dim)) {
+                const char *ex = getenv("VF_SEED_EXACT");
+                if (!(ex && ex[0] == '1')) {
+                    if ((rc = ix->d_xnorm_all.reserve((size_t)n * 4)) != VF_OK) return rc;
+                    launch_row_norms(ix->X, ix->dim, n, ix->d_xnorm_all.as<float>(), s);
+                    std::vector<float> hn((size_t)n);
+                    VF_HIP(hipMemcpyAsync(hn.data(), ix->d_xnorm_all.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+                    VF_HIP(hipStreamSynchronize(s));
+                    float mx = 0.f;
+                    bool finite = true;
+                    for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+                    if (finite) {   // a table with NaN or overflowing norms keeps the exact kernel
+                        ix->xn_max = mx;
+                        // |approximation - ordered distance| <= 300 u (|q|^2 + |x|^2), u = 2^-24 (dot product of
+                        // <= 512 terms in any order, two norms, the final additions, the ordered sum's own
+                        // error); 512 u = 2^-15 is used
+                        float slack = 1.0f;
+                        if (const char *e = getenv("VF_SEED_SLACK")) slack = (float)atof(e);
+                        ix->seed_err_bound = slack * 3.0517578125e-05f;
+                        ix->seed_mfma = true;
+                    }
+                }
+            }
         }
         VF_HIP(hipGetLastError());
     } catch (const std::bad_alloc &) {
@@ -587,12 +616,15 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         const int32_t ns_stride = (n_seeds + 31) & ~31;
         const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) &&
                                  (uint64_t)n_gq * (uint64_t)ns_stride * 4 <= ((uint64_t)8 << 30);
+        // matrix-core scoring (approximate, re-ranked by the beam kernel) where the beam kernel supports it
+        const bool seeds_mfma = dense_seeds && ix->seed_mfma && !r.any_and && itopk <= 48 && n_seeds > 64;
         if (dense_seeds) {
+            const size_t tile_q = seeds_mfma ? 32 : 64;
             for (size_t i = 0; i < n_gq;) {
                 size_t e = i;
                 while (e < n_gq && r.gq_label[e] == r.gq_label[i]) ++e;
-                for (size_t t = i; t < e; t += 64)
-                    tiles.push_back(SeedTile{r.gq_label[i], (int32_t)t, (int32_t)std::min<size_t>(64, e - t)});
+                for (size_t t = i; t < e; t += tile_q)
+                    tiles.push_back(SeedTile{r.gq_label[i], (int32_t)t, (int32_t)std::min<size_t>(tile_q, e - t)});
                 i = e;
             }
         }
@@ -646,6 +678,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             pf.n_scan_items = (int64_t)items.size();
             for (const ScanItem &it : items) { pf.scan_list_entries += it.n; pf.scan_pairs += (int64_t)it.n * it.q_count; }
             pf.n_seed_tiles = (int64_t)tiles.size();
+            pf.seeds_on_matrix_cores = seeds_mfma ? 1 : 0;
             for (const SeedTile &t : tiles) {
                 const int64_t ns_l = std::min<int64_t>(n_seeds, ix->S[(size_t)t.label]);
                 pf.seed_pairs += ns_l * t.q_count;
@@ -714,9 +747,17 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 SeedParams sd{};
                 sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
                 sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
-                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride; sd.max_chunks = ns_stride / kSeedChunk;
+                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
                 sd.dseed = ix->dseed.as<uint32_t>();
-                launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
+                if (seeds_mfma) {
+                    sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
+                    sd.xnorm_all = ix->d_xnorm_all.as<float>();
+                    launch_seed_mfma(sd, (int)tiles.size(), s);
+                    bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
+                } else {
+                    sd.max_chunks = ns_stride / kSeedChunk;
+                    launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
+                }
                 bp.dseed = sd.dseed;
             }
             if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
@@ -832,6 +873,9 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
         VF_HIP(hipMemcpy(cn.data(), ix->counters.p, cn.size() * 4, hipMemcpyDeviceToHost));
         for (int64_t j = 0; j < pf.nq; ++j) {
             pf.beam_scored += cn[(size_t)j * 4]; pf.beam_expanded += cn[(size_t)j * 4 + 1]; pf.beam_tested += cn[(size_t)j * 4 + 2];
+            const int32_t m = cn[(size_t)j * 4 + 3];
+            pf.seed_fallbacks += (m & 0xFF) == 3;
+            pf.seed_rescored += m >> 8;
         }
         if (per_query) memcpy(per_query, cn.data(), cn.size() * 4);
     } catch (const std::bad_alloc &) {

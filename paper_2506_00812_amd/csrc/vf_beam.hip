@@ -136,16 +136,17 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     int n_scored = 0, n_expanded = 0, n_tested = 0;  // work counters (uniform across the wave)
 
     // Offer the candidates held one per lane (valid lanes, distance bits, local id) to the list.
-    auto offer = [&](bool valid, uint32_t bits, int c) {
-        uint64_t m = __ballot(valid && bits <= (uint32_t)(top.worst >> 32));
+    auto offer_to = [&](auto &list, bool valid, uint32_t bits, int c) {
+        uint64_t m = __ballot(valid && bits <= (uint32_t)(list.worst >> 32));
         while (m) {
             const int b = __builtin_ctzll(m);
             m &= m - 1;
             const uint32_t kb = __builtin_amdgcn_readlane(bits, b);
             const uint32_t kc = (uint32_t)__builtin_amdgcn_readlane(c, b);
-            top.insert(((uint64_t)kb << 32) | ((uint64_t)kc << 1) | 1ull, lane);
+            list.insert(((uint64_t)kb << 32) | ((uint64_t)kc << 1) | 1ull, lane);
         }
     };
+    auto offer = [&](bool valid, uint32_t bits, int c) { offer_to(top, valid, bits, c); };
 
     // Distances of cand[0..cnt) (eight at a time, one per team) into cand_d.
     auto score = [&](int cnt) {
@@ -188,14 +189,17 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     // ---- InitializeSearch: stratified seeds floor(j * n / ns)
     const int ns = p.n_seeds < n ? p.n_seeds : n;
     int j_begin = 0;   // seeds below j_begin have been dealt with
-    if (E == 1 && p.dseed != nullptr && o_cnt == 0) {
-        // Distances were computed densely per label.  Selection in two passes over chunks of
-        // 64 * NBLK seeds held in registers: the itopk-th smallest of the 64 per-lane minima is an
-        // upper bound of the itopk-th smallest distance of the chunk, so only the few seeds at or
-        // below it (and below the list's worst entry) are offered to the list.  Same result as
-        // offering every seed, at a fraction of the insertions.
+
+    // Selection from a dense row of seed distances in two passes over chunks of 64 * NBLK seeds
+    // held in registers: an upper bound of the M-th smallest distance of the chunk (M = list
+    // capacity <= 64) comes from the lanes' own two smallest values, and only the few seeds at or
+    // below it (and below the list's worst entry) are offered to the list.  Same result as offering
+    // every seed, at a fraction of the insertions.  as_index: the list stores the seed index j
+    // instead of the local id floor(j * n / ns).  Returns the number of seeds dealt with (a chunk
+    // whose bound lets more than 128 seeds through ends the selection early).
+    auto select_seeds = [&](TopM<1> &list, const uint32_t *drow, bool as_index) -> int {
         constexpr int NBLK = VF_SEED_BLOCKS;
-        const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
+        int done_to = 0;
         for (int jc = 0; jc < ns; jc += 64 * NBLK) {
             uint32_t v[NBLK];
 #pragma unroll
@@ -203,17 +207,26 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 const int j = jc + i * 64 + lane;
                 v[i] = j < ns ? drow[j] : 0xFFFFFFFFu;
             }
-            uint32_t mn = v[0];
+            // the two smallest values of every lane; the M-th smallest of those 128 bounds the M-th
+            // smallest of the chunk: sort both sets across the wave, take the 64 smallest of their
+            // union (element-wise minimum against the reversed other set), sort those
+            uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
 #pragma unroll
-            for (int i = 1; i < NBLK; ++i) mn = v[i] < mn ? v[i] : mn;
-            const uint32_t sorted = wave_sort_u32(mn, lane);
-            uint32_t tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, itopk - 1);
-            const uint32_t wb = (uint32_t)(top.worst >> 32);
+            for (int i = 1; i < NBLK; ++i) {
+                const uint32_t hi = v[i] > m1 ? v[i] : m1;
+                m2 = hi < m2 ? hi : m2;
+                m1 = v[i] < m1 ? v[i] : m1;
+            }
+            const uint32_t s1 = wave_sort_u32(m1, lane), s2 = wave_sort_u32(m2, lane);
+            const uint32_t s2r = (uint32_t)__shfl((int)s2, 63 - lane);
+            const uint32_t sorted = wave_merge_u32(s1 < s2r ? s1 : s2r, lane);
+            uint32_t tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, list.itopk - 1);
+            const uint32_t wb = (uint32_t)(list.worst >> 32);
             tau = tau < wb ? tau : wb;
             int total = 0;
 #pragma unroll
             for (int i = 0; i < NBLK; ++i) total += __popcll(__ballot(v[i] <= tau && jc + i * 64 + lane < ns));
-            if (total > 128) break;   // no useful bound (fewer than itopk lanes hold a seed): plain path below
+            if (total > 128) break;
             __syncthreads();
             int cnt = 0;
 #pragma unroll
@@ -232,15 +245,67 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             for (int i0 = 0; i0 < cnt; i0 += 64) {
                 const int i = i0 + lane;
                 const bool valid = i < cnt;
-                const int c = valid ? (int)(((uint64_t)cand_c[i] * (uint64_t)n) / (uint64_t)ns) : 0;
-                offer(valid, valid ? cand_d[i] : 0u, c);
+                int c = valid ? cand_c[i] : 0;
+                if (!as_index) c = (int)(((uint64_t)c * (uint64_t)n) / (uint64_t)ns);
+                offer_to(list, valid, valid ? cand_d[i] : 0u, c);
             }
-            const int done = ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK;
-            n_scored += done;
-            j_begin = jc + done;
+            done_to = jc + 64 * NBLK < ns ? jc + 64 * NBLK : ns;
+        }
+        return done_to;
+    };
+
+    bool seeds_done = false;
+    int n_rescored = 0, seed_fallback = 0;   // profiling only
+    if constexpr (E == 1 && DT == 1) {
+        if (p.dseed != nullptr && p.seed_approx != 0) {
+            // dseed holds matrix-core approximations.  Keep the 64 best of them, re-score those
+            // with the ordered distance, and accept the result only if every other seed is provably
+            // worse than the list's worst entry: its approximation is at least T (the 64th best),
+            // its ordered distance therefore at least T - B.
+            TopM<1> tmp;
+            tmp.init(64);
+            const int got = select_seeds(tmp, p.dseed + (int64_t)gq * p.ns_stride, true);
+            if (got == ns) {
+                const uint64_t key = tmp.cur[0];
+                const bool valid = key != KEY_MAX;
+                const int c = valid ? (int)(((uint64_t)((uint32_t)(key >> 1) & 0x7FFFFFFFu) * (uint64_t)n) / (uint64_t)ns) : 0;
+                __syncthreads();
+                const int cnt = filter_and_compact(valid, c, 0);
+                __syncthreads();
+                score(cnt);
+                float qn = 0.f;
+                for (int i = lane; i < nchunks; i += 64) {
+                    const uint4 v = qv[i];
+                    const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+                    qn += f[0] * f[0] + f[1] * f[1] + f[2] * f[2] + f[3] * f[3];
+                }
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) qn += __shfl_xor(qn, o);
+                const float B = p.err_bound * (qn + p.xn_max);
+                const bool all_kept = tmp.worst == KEY_MAX;
+                const bool proven = top.worst != KEY_MAX &&
+                                    __uint_as_float((uint32_t)(top.worst >> 32)) < __uint_as_float((uint32_t)(tmp.worst >> 32)) - B;
+                if (all_kept || proven) {
+                    seeds_done = true;
+                    n_scored = ns;
+                    n_rescored = cnt;
+                }
+            }
+            if (!seeds_done) {   // start over; the gather path below scores every seed
+                top.init(itopk);
+                n_scored = 0;
+                seed_fallback = 1;
+            }
         }
     }
-    if (p.dseed != nullptr) {
+    if constexpr (E == 1) {
+        if (!seeds_done && p.dseed != nullptr && p.seed_approx == 0 && o_cnt == 0) {
+            j_begin = select_seeds(top, p.dseed + (int64_t)gq * p.ns_stride, false);
+            n_scored += j_begin;
+        }
+    }
+    if (seeds_done) {
+    } else if (p.dseed != nullptr && p.seed_approx == 0) {
         // plain path (AND queries, long lists of candidates): stream the row and offer every seed
         const uint32_t *drow = p.dseed + (int64_t)gq * p.ns_stride;
         for (int j0 = j_begin; j0 < ns; j0 += 64) {
@@ -320,7 +385,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     if (p.counters != nullptr && lane == 0) {
         int32_t *cn = p.counters + (int64_t)qi * 4;
-        cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2;
+        cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2 + seed_fallback + (n_rescored << 8);
     }
 
     // ---- first k entries (k <= 64: register 0), local -> global through M

@@ -152,6 +152,18 @@ __device__ __forceinline__ uint32_t wave_sort_u32(uint32_t v, int lane)
     return v;
 }
 
+// Ascending sort of a bitonic sequence of 64 values held one per lane.
+__device__ __forceinline__ uint32_t wave_merge_u32(uint32_t v, int lane)
+{
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, j);
+        const uint32_t mn = v < o ? v : o, mx = v < o ? o : v;
+        v = (lane & j) == 0 ? mn : mx;
+    }
+    return v;
+}
+
 // Bitonic sort of keys[0..n) ascending in LDS by one wave; n a power of two.
 __device__ __forceinline__ void wave_bitonic_sort(uint64_t *keys, int n, int lane)
 {

@@ -93,8 +93,12 @@ struct BeamParams {
     int64_t *out_ids;
     float *out_dists;
     int32_t *counters; // optional [nq][4]: distances computed, rows expanded, predicate tests, method
-    const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel
+    const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel / seed_mfma_kernel
     int32_t ns_stride;
+    // dseed holds MFMA approximations (float32 only): the kernel re-scores the best of them with the
+    // ordered distance and proves, with err_bound * (|q|^2 + xn_max), that no other seed can matter
+    int32_t seed_approx;
+    float err_bound, xn_max;
 };
 
 // ---------------------------------------------------------------- dense seed distances
@@ -102,7 +106,7 @@ struct BeamParams {
 struct SeedTile {
     int32_t label;
     int32_t gq_begin;  // first graph query (position in gq_query) of the tile
-    int32_t q_count;   // 1..64 queries, all searching `label`
+    int32_t q_count;   // queries, all searching `label`: 1..64 (seed_dist_kernel), 1..32 (seed_mfma_kernel)
 };
 
 struct SeedParams {
@@ -111,12 +115,20 @@ struct SeedParams {
     const int32_t *gq_query;
     const SeedTile *tiles;
     LabelMeta meta;
-    int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = ceil(n_seeds / kSeedChunk)
+    int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = seed chunks per tile (kSeedChunk or kSeedMfmaChunk seeds each)
     uint32_t *dseed;
+    const float *xnorm_all;  // [n] squared norms of the rows of X (seed_mfma_kernel only)
 };
+
+constexpr int kSeedMfmaChunk = 128;  // seeds per wave of the MFMA seed kernel (four 32-seed groups)
 
 bool seed_dist_supported(int dtype, int dim);
 void launch_seed_dist(int dtype, const SeedParams &p, int n_tiles, hipStream_t s);
+// float32 only: approximate distances |q|^2 + |x|^2 - 2 q.x through the matrix cores
+bool seed_mfma_supported(int dtype, int dim);
+void launch_seed_mfma(const SeedParams &p, int n_tiles, hipStream_t s);
+// squared norms of all rows of a float32 table
+void launch_row_norms(const void *X, int32_t dim, int64_t n, float *out, hipStream_t s);
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype);
 void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s);

@@ -99,6 +99,142 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// float32, matrix cores.  queries x seeds of one label is a dense contraction, so the bulk of the
+// work can run on MFMA as |q|^2 + |x|^2 - 2 q.x.  That value is rounded differently from the
+// ordered distance the search is defined with, so it is used as a filter only: the beam kernel
+// keeps the 64 best approximations per query, re-scores those with the ordered distance, and
+// checks that the gap to the 65th exceeds the rounding-error bound (else it scores every seed
+// itself).  One wave: a tile of <= 32 queries (A operand, staged in LDS) against kSeedMfmaChunk
+// seeds in groups of 32 (B operand gathered row-wise from X: lane (v, h) reads the 16-byte
+// chunks 2c + h of seed v, the operand layout of v_mfma_f32_32x32x2_f32).
+typedef float v16f_seed __attribute__((ext_vector_type(16)));
+
+template <int NCP>
+__global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
+{
+    constexpr int NCH = 2 * NCP, row_bytes = NCH * kChunkBytes, NG = kSeedMfmaChunk / 32;
+    __shared__ uint4 qtile[NCH * 32];
+    __shared__ float qnorm_s[32];
+    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int tile = blockIdx.x / p.max_chunks, chunk = blockIdx.x % p.max_chunks;
+    const SeedTile t = p.tiles[tile];
+    const int n = p.meta.S[t.label];
+    const int64_t base = p.meta.O_HS[t.label];
+    const int ns = p.n_seeds < n ? p.n_seeds : n;
+    const int j0 = chunk * kSeedMfmaChunk;
+    if (j0 >= ns) return;
+
+    // global ids and norms of this lane's seed in each group (issued first: the longest dependent chain)
+    int gid[NG];
+    float xn[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int j = j0 + g * 32 + n32;
+        const int c = j < ns ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
+        gid[g] = p.meta.M_HS[base + c];
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) xn[g] = p.xnorm_all[gid[g]];
+
+    // query tile, chunk-major; rows without a query are zero
+    {
+        const int qr = n32 < t.q_count ? p.gq_query[t.gq_begin + n32] : -1;
+        const char *qp = (const char *)p.Q + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
+        float acc = 0.f;
+#pragma unroll
+        for (int c0 = 0; c0 < NCP; ++c0) {
+            const int c = 2 * c0 + h;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (qr >= 0) v = *(const uint4 *)(qp + c * kChunkBytes);
+            qtile[c * 32 + n32] = v;
+            const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
+        }
+        acc += __shfl_xor(acc, 32);
+        if (h == 0) qnorm_s[n32] = acc;
+    }
+    __syncthreads();
+    float qn[16];
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) qn[jj] = qnorm_s[8 * (jj >> 2) + 4 * h + (jj & 3)];
+
+    uint4 bnext[NCP];
+    {
+        const char *xrow = (const char *)p.X + (int64_t)gid[0] * row_bytes;
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        if (j0 + g * 32 >= ns) break;   // wave uniform
+        uint4 b[NCP];
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) b[cp] = bnext[cp];
+        if (g + 1 < NG && j0 + (g + 1) * 32 < ns) {
+            const char *xrow = (const char *)p.X + (int64_t)gid[g + 1 < NG ? g + 1 : g] * row_bytes;
+#pragma unroll
+            for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
+        }
+        v16f_seed acc;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) {
+            const uint4 a = qtile[(2 * cp + h) * 32 + n32];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b[cp].x), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b[cp].y), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b[cp].z), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b[cp].w), acc, 0, 0, 0);
+        }
+        const int j = j0 + g * 32 + n32;
+        if (j < ns) {
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const int row = 8 * (jj >> 2) + 4 * h + (jj & 3);
+                if (row < t.q_count) {
+                    const float d = (qn[jj] + xn[g]) - 2.0f * acc[jj];
+                    p.dseed[(int64_t)(t.gq_begin + row) * p.ns_stride + j] = __float_as_uint(fmaxf(d, 0.0f));
+                }
+            }
+        }
+    }
+}
+
+bool seed_mfma_supported(int dtype, int dim)
+{
+    return dtype == 1 && (dim == 96 || dim == 128);
+}
+
+void launch_seed_mfma(const SeedParams &p, int n_tiles, hipStream_t s)
+{
+    if (n_tiles <= 0) return;
+    const unsigned grid = (unsigned)n_tiles * (unsigned)p.max_chunks;
+    if (p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<16>), dim3(grid), dim3(64), 0, s, p);
+    else if (p.dim == 96) hipLaunchKernelGGL((seed_mfma_kernel<12>), dim3(grid), dim3(64), 0, s, p);
+}
+
+// One thread per row, elements in ascending order.
+__global__ void row_norm_kernel(const float *X, int32_t dim, int64_t n, float *out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float4 *x = (const float4 *)(X + i * dim);
+    float acc = 0.f;
+    for (int e = 0; e < dim / 4; ++e) {
+        const float4 v = x[e];
+        acc += v.x * v.x; acc += v.y * v.y; acc += v.z * v.z; acc += v.w * v.w;
+    }
+    out[i] = acc;
+}
+
+void launch_row_norms(const void *X, int32_t dim, int64_t n, float *out, hipStream_t s)
+{
+    if (n <= 0) return;
+    hipLaunchKernelGGL(row_norm_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float *)X, dim, n, out);
+}
+
 bool seed_dist_supported(int dtype, int dim)
 {
     const int nch = dim * (dtype == 0 ? 1 : 4) / kChunkBytes;
