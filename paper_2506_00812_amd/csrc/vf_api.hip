@@ -506,6 +506,7 @@ static int env_int(const char *name, int dflt, int lo, int hi)
 }
 // tuning knobs (the environment overrides exist for experiments)
 static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
+static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
 static const int kTileRows = env_int("VF_TILE_ROWS", 16, 1, 32);      // queries per scan tile
 
 struct ItemBuilder {
@@ -754,6 +755,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                     sd.xnorm_all = ix->d_xnorm_all.as<float>();
                     launch_seed_mfma(sd, (int)tiles.size(), s);
                     bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
+                    bp.seed_keep = std::min(64, itopk + kSeedMargin);
                 } else {
                     sd.max_chunks = ns_stride / kSeedChunk;
                     launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);

@@ -258,12 +258,12 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     int n_rescored = 0, seed_fallback = 0;   // profiling only
     if constexpr (E == 1 && DT == 1) {
         if (p.dseed != nullptr && p.seed_approx != 0) {
-            // dseed holds matrix-core approximations.  Keep the 64 best of them, re-score those
+            // dseed holds matrix-core approximations.  Keep the seed_keep best of them, re-score those
             // with the ordered distance, and accept the result only if every other seed is provably
-            // worse than the list's worst entry: its approximation is at least T (the 64th best),
+            // worse than the list's worst entry: its approximation is at least T (the last one kept),
             // its ordered distance therefore at least T - B.
             TopM<1> tmp;
-            tmp.init(64);
+            tmp.init(p.seed_keep);
             const int got = select_seeds(tmp, p.dseed + (int64_t)gq * p.ns_stride, true);
             if (got == ns) {
                 const uint64_t key = tmp.cur[0];

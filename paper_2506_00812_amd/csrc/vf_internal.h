@@ -98,6 +98,7 @@ struct BeamParams {
     // dseed holds MFMA approximations (float32 only): the kernel re-scores the best of them with the
     // ordered distance and proves, with err_bound * (|q|^2 + xn_max), that no other seed can matter
     int32_t seed_approx;
+    int32_t seed_keep;  // approximations kept for re-ranking (itopk < seed_keep <= 64)
     float err_bound, xn_max;
 };
 
