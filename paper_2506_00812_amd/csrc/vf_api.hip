@@ -507,6 +507,7 @@ static int env_int(const char *name, int dflt, int lo, int hi)
 // tuning knobs (the environment overrides exist for experiments)
 static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
 static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
+static const int kScanValu = env_int("VF_SCAN_VALU", 1, 0, 2);      // float32 FMA scan kernel: 0 never, 1 for small batches, 2 always
 static const int kTileRows = env_int("VF_TILE_ROWS", 16, 1, 32);      // queries per scan tile
 
 struct ItemBuilder {
@@ -686,53 +687,14 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 pf.seed_tile_seeds += ns_l;
             }
         }
-        // fork: scan kernels on the side stream, graph kernels on the caller's stream
+        // The scan path runs on the side stream beside the graph path on the caller's stream.
         hipStream_t ss = s;
         const bool forked = ix->overlap && !ix->prof_serial && !exact && n_gq > 0 && !items.empty();
-        if (forked) {
-            VF_HIP(hipEventRecord(ix->ev_fork, s));
-            VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
-            ss = ix->side;
-        }
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[0], ss));
-
         const int32_t *d_others_off = r.any_and ? (const int32_t *)(dp + L.off_others_off) : nullptr;
         const int32_t *d_others = (const int32_t *)(dp + L.off_others);
 
-        ScanParams sp{};
-        sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
-        sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows; sp.sort_partials = 0;
-        sp.out_ids = out_ids; sp.out_dists = out_dists;
-        sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
-        const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);
-        sp.others_off = d_others_off; sp.others = d_others; sp.meta = ix->meta();
-        if (n_ls_items) {
-            sp.xblk = ix->d_X_LS.as<uint4>(); sp.xnorm = ix->d_xnorm_LS.p; sp.map = ix->d_M_LS.as<int32_t>();
-            sp.items = (const ScanItem *)(dp + L.off_items);
-            launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
-            launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
-                              ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
-        }
-        if (!hs_runs.empty()) {
-            const int64_t max_groups = (max_hs_list + 31) / 32;
-            if ((rc = ix->tmp_blk.reserve((size_t)max_groups * ix->group_bytes())) != VF_OK) return rc;
-            if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
-            for (const HsRun &run : hs_runs) {
-                const int32_t nl = ix->S[(size_t)run.label];
-                launch_interleave(ix->dtype, ix->X, ix->dim, ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)run.label], nullptr,
-                                  nullptr, nl, (nl + 31) / 32, ix->ncp, ix->tmp_blk.as<uint4>(), ix->tmp_norm.p, s);
-                sp.xblk = ix->tmp_blk.as<uint4>(); sp.xnorm = ix->tmp_norm.p; sp.map = ix->d_M_HS.as<int32_t>();
-                sp.items = (const ScanItem *)(dp + L.off_items) + run.item_lo;
-                launch_scan(ix->dtype, sp, (int)(run.item_hi - run.item_lo), s);
-            }
-            launch_scan_merge(ix->dtype, d_merges + n_ls_merges, (int)(ib.merges.size() - n_ls_merges), sp.res_idx,
-                              sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
-        }
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
-        if (forked) VF_HIP(hipEventRecord(ix->ev_join, ss));
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
+        BeamParams bp{};
         if (n_gq) {
-            BeamParams bp{};
             bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>();
             bp.gq_query = (const int32_t *)(dp + L.off_gq_query);
             bp.gq_label = (const int32_t *)(dp + L.off_gq_label);
@@ -744,29 +706,83 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             bp.out_ids = out_ids; bp.out_dists = out_dists;
             bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
             bp.dseed = nullptr; bp.ns_stride = ns_stride;
-            if (dense_seeds) {
-                SeedParams sd{};
-                sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
-                sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
-                sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
-                sd.dseed = ix->dseed.as<uint32_t>();
-                if (seeds_mfma) {
-                    sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
-                    sd.xnorm_all = ix->d_xnorm_all.as<float>();
-                    launch_seed_mfma(sd, (int)tiles.size(), s);
-                    bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
-                    bp.seed_keep = std::min(64, itopk + kSeedMargin);
-                } else {
-                    sd.max_chunks = ns_stride / kSeedChunk;
-                    launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
+        }
+        auto run_seeds = [&]() -> int {
+            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
+            if (n_gq) {
+                if (dense_seeds) {
+                    SeedParams sd{};
+                    sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
+                    sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
+                    sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
+                    sd.dseed = ix->dseed.as<uint32_t>();
+                    if (seeds_mfma) {
+                        sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
+                        sd.xnorm_all = ix->d_xnorm_all.as<float>();
+                        launch_seed_mfma(sd, (int)tiles.size(), s);
+                        bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
+                        bp.seed_keep = std::min(64, itopk + kSeedMargin);
+                    } else {
+                        sd.max_chunks = ns_stride / kSeedChunk;
+                        launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
+                    }
+                    bp.dseed = sd.dseed;
                 }
-                bp.dseed = sd.dseed;
             }
             if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
-            launch_beam(ix->dtype, bp, (int)n_gq, s);
-        }
+            return VF_OK;
+        };
+        auto run_scan = [&]() -> int {
+            if (forked) {
+                VF_HIP(hipEventRecord(ix->ev_fork, s));
+                VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+                ss = ix->side;
+            }
+            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[0], ss));
+
+            ScanParams sp{};
+            sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
+            sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows; sp.sort_partials = 0;
+            sp.out_ids = out_ids; sp.out_dists = out_dists;
+            sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
+            const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);
+            sp.others_off = d_others_off; sp.others = d_others; sp.meta = ix->meta();
+            if (n_ls_items) {
+                sp.xblk = ix->d_X_LS.as<uint4>(); sp.xnorm = ix->d_xnorm_LS.p; sp.map = ix->d_M_LS.as<int32_t>();
+                sp.items = (const ScanItem *)(dp + L.off_items);
+                // small batches are latency-bound: the FMA kernel finishes a one-query tile three times sooner;
+                // large batches keep the matrix-core kernel, which leaves the vector ALU to the beam search
+                const bool small_batch = kScanValu == 2 || (kScanValu == 1 && qrow.size() <= 256);
+                if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) launch_scan_valu(sp, (int)n_ls_items, ss);
+                else launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
+                launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
+                                  ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
+            }
+            if (!hs_runs.empty()) {
+                const int64_t max_groups = (max_hs_list + 31) / 32;
+                if ((rc = ix->tmp_blk.reserve((size_t)max_groups * ix->group_bytes())) != VF_OK) return rc;
+                if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
+                for (const HsRun &run : hs_runs) {
+                    const int32_t nl = ix->S[(size_t)run.label];
+                    launch_interleave(ix->dtype, ix->X, ix->dim, ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)run.label], nullptr,
+                                      nullptr, nl, (nl + 31) / 32, ix->ncp, ix->tmp_blk.as<uint4>(), ix->tmp_norm.p, s);
+                    sp.xblk = ix->tmp_blk.as<uint4>(); sp.xnorm = ix->tmp_norm.p; sp.map = ix->d_M_HS.as<int32_t>();
+                    sp.items = (const ScanItem *)(dp + L.off_items) + run.item_lo;
+                    launch_scan(ix->dtype, sp, (int)(run.item_hi - run.item_lo), s);
+                }
+                launch_scan_merge(ix->dtype, d_merges + n_ls_merges, (int)(ib.merges.size() - n_ls_merges), sp.res_idx,
+                                  sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
+            }
+            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
+            if (forked) VF_HIP(hipEventRecord(ix->ev_join, ss));
+            return VF_OK;
+        };
+        // the scan goes first: its longest work items decide when it ends (measured: forking it
+        // after the seed kernel costs 20 % of the step)
+        if ((rc = run_scan()) != VF_OK) return rc;
+        if ((rc = run_seeds()) != VF_OK) return rc;
+        if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
         if (prof) {
-            if (!n_gq) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
             VF_HIP(hipEventRecord(ix->prof_ev[4], s));
             ix->prof_valid = true; ix->prof_folded = false;
         }

@@ -72,6 +72,9 @@ struct ScanParams {
 };
 
 void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s);
+// float32, dim 96 / 128, <= 16 queries per tile, no self exclusion: FMAs with scalar query operands
+bool scan_valu_supported(int dtype, int dim, int tile_rows);
+void launch_scan_valu(const ScanParams &p, int n_items, hipStream_t s);
 void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,
                        int32_t K, int32_t max_keys, const int32_t *map, int64_t *out_ids, float *out_dists,
                        hipStream_t s);

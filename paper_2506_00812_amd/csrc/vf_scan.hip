@@ -117,6 +117,63 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// Merge the pending queues of all tile rows into their sorted K best, NR rows at a time with
+// the whole wave.  Lane r (r < 32) holds row r's pending count `pcv` (<= 2 * 64) and its K-th
+// best key `row_kth`; pend is [rows][PC], best is [rows][KS] ascending, KEY_MAX padded.
+// A row's 64 pending keys are sorted, the 64 smallest of them and the row's reversed best list
+// form a bitonic sequence (element-wise minimum), and one merge network sorts that.
+template <int NR>
+__device__ __forceinline__ void wave_drain_rows(uint64_t *pend, int PC, uint64_t *best, int KS, int K, int &pcv,
+                                                uint64_t &row_kth, int lane)
+{
+    uint32_t todo = (uint32_t)__ballot(lane < 32 && pcv > 0);
+    while (todo != 0) {
+        int rr[NR];
+        bool on[NR];
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            on[u] = todo != 0;
+            rr[u] = on[u] ? __builtin_ctz(todo) : rr[0];
+            todo &= todo - 1;
+        }
+        int pc_max = 0;
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const int pc = on[u] ? __builtin_amdgcn_readlane(pcv, rr[u]) : 0;
+            pc_max = pc > pc_max ? pc : pc_max;
+        }
+        for (int off = 0; off < pc_max; off += 64) {
+            uint64_t v[NR];
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                const int pc = __builtin_amdgcn_readlane(pcv, rr[u]);
+                const uint64_t kth = readlane64(row_kth, rr[u]);
+                const uint64_t x = (on[u] && off + lane < pc) ? pend[rr[u] * PC + off + lane] : KEY_MAX;
+                v[u] = x < kth ? x : KEY_MAX;
+            }
+            wave_sort64_multi<NR>(v, lane);
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                const uint64_t w = lane < K ? best[rr[u] * KS + lane] : KEY_MAX;
+                const uint32_t lo = __shfl((uint32_t)v[u], 63 - lane), hi = __shfl((uint32_t)(v[u] >> 32), 63 - lane);
+                const uint64_t vr = ((uint64_t)hi << 32) | lo;
+                v[u] = w < vr ? w : vr;
+            }
+            wave_bitonic_merge64_multi<NR>(v, lane);
+#pragma unroll
+            for (int u = 0; u < NR; ++u) {
+                if (on[u]) {   // wave uniform
+                    if (lane < K) best[rr[u] * KS + lane] = v[u];
+                    const uint64_t nk = readlane64(v[u], K - 1);
+                    if (lane == rr[u]) row_kth = nk;
+                }
+            }
+            if (off + 64 < pc_max) wave_lds_sync();   // the next round reads the lists just written
+        }
+    }
+    pcv = 0;
+}
+
 template <int DT, int NCP>
 __global__ __launch_bounds__(64, 2) void scan_topk_kernel(ScanParams p)
 {
@@ -225,46 +282,9 @@ __global__ __launch_bounds__(64, 2) void scan_topk_kernel(ScanParams p)
     // wave, then broadcast the thresholds to the accumulator layout (thr[j] of lane (n32, h)
     // belongs to row 8*(j/4) + 4*h + (j%4)).
     auto drain = [&]() {
-        constexpr int NR = VF_DRAIN_ROWS;   // rows merged at once
         wave_lds_sync();
-        uint32_t todo = (uint32_t)__ballot(lane < 32 && pcv > 0);
-        while (todo != 0) {
-            int rr[NR];
-            bool on[NR];
-#pragma unroll
-            for (int u = 0; u < NR; ++u) {
-                on[u] = todo != 0;
-                rr[u] = on[u] ? __builtin_ctz(todo) : rr[0];
-                todo &= todo - 1;
-            }
-            uint64_t v[NR];
-#pragma unroll
-            for (int u = 0; u < NR; ++u) {
-                const int pc = __builtin_amdgcn_readlane(pcv, rr[u]);
-                const uint64_t kth = readlane64(row_kth, rr[u]);
-                const uint64_t x = (on[u] && lane < pc) ? pend[rr[u] * PC + lane] : KEY_MAX;
-                v[u] = x < kth ? x : KEY_MAX;
-            }
-            wave_sort64_multi<NR>(v, lane);
-#pragma unroll
-            for (int u = 0; u < NR; ++u) {
-                const uint64_t w = lane < K ? best[rr[u] * KS + lane] : KEY_MAX;
-                const uint32_t lo = __shfl((uint32_t)v[u], 63 - lane), hi = __shfl((uint32_t)(v[u] >> 32), 63 - lane);
-                const uint64_t vr = ((uint64_t)hi << 32) | lo;
-                v[u] = w < vr ? w : vr;   // the 64 smallest of both, as a bitonic sequence
-            }
-            wave_bitonic_merge64_multi<NR>(v, lane);
-#pragma unroll
-            for (int u = 0; u < NR; ++u) {
-                if (on[u]) {   // wave uniform
-                    if (lane < K) best[rr[u] * KS + lane] = v[u];
-                    const uint64_t nk = readlane64(v[u], K - 1);
-                    if (lane == rr[u]) row_kth = nk;
-                }
-            }
-        }
+        wave_drain_rows<VF_DRAIN_ROWS>(pend, PC, best, KS, K, pcv, row_kth, lane);
         if (lane < 32) pcnt[lane] = 0;
-        pcv = 0;
         wave_lds_sync();
         const uint32_t t = (uint32_t)(row_kth >> 32);
 #pragma unroll
@@ -405,6 +425,128 @@ __global__ __launch_bounds__(64, 2) void scan_topk_kernel(ScanParams p)
     }
 }
 
+// float32 lists with few queries per tile.  The fp32 matrix core runs at only twice the VALU
+// FMA rate and a 32-row tile with a handful of queries wastes most of it, so below ~16 queries
+// per tile plain FMAs are faster: a lane holds one list entry's whole vector in registers (two
+// 32-vector groups per step), the tile's queries are walked one after the other, and a query
+// row -- the same for all lanes -- comes in through scalar loads and feeds the FMAs as a scalar
+// operand.  Distances are |q|^2 + |x|^2 - 2 q.x as in the MFMA kernel; selection uses the same
+// per-row queues and merge.  Lane r (r < 32) holds the state of tile row r.
+template <int NCH>
+__global__ __launch_bounds__(64) void scan_valu_kernel(ScanParams p)
+{
+    extern __shared__ uint4 smem[];
+    const ScanItem it = p.items[blockIdx.x];
+    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int K = p.K, KS = K | 1, TR = p.tile_rows;
+    constexpr int PC = 96;   // a step adds <= 64 keys to a row and rows above 32 are drained after every step
+    constexpr int row_bytes = NCH * kChunkBytes;
+    uint64_t *pend = (uint64_t *)smem;                  // [TR][PC]
+    uint64_t *best = pend + TR * PC;                    // [TR][KS]
+    int32_t *qrow_s = (int32_t *)(best + TR * KS);      // [32]
+    float *qnorm_s = (float *)(qrow_s + 32);            // [32]
+
+    if (lane < 32) qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1;
+    for (int i = lane; i < TR * KS; i += 64) best[i] = KEY_MAX;
+    __syncthreads();
+    for (int r = 0; r < it.q_count; ++r) {
+        float acc = 0.f;
+        if (lane < NCH) {
+            const uint4 v = *(const uint4 *)((const char *)p.qsrc + (int64_t)qrow_s[r] * row_bytes + lane * kChunkBytes);
+            const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+            acc = (f[0] * f[0] + f[1] * f[1]) + (f[2] * f[2] + f[3] * f[3]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) qnorm_s[r] = acc;
+    }
+    __syncthreads();
+
+    // state of tile row r, held by lane r
+    int pcv = 0;
+    uint64_t row_kth = KEY_MAX;
+    const float qn_lane = lane < it.q_count ? qnorm_s[lane] : 0.f;
+    const int qr_lane = lane < 32 ? qrow_s[lane] : -1;
+    uint32_t and_rows = 0;
+    if (p.others_off != nullptr)
+        and_rows = (uint32_t)__ballot(lane < it.q_count && p.others_off[qr_lane >= 0 ? qr_lane + 1 : 0] > p.others_off[qr_lane >= 0 ? qr_lane : 0]);
+
+    const int n_groups = (it.n + kGroup - 1) / kGroup;
+    const int n_steps = (n_groups + 1) / 2;
+    for (int step = 0; step < n_steps; ++step) {
+        const int grp = 2 * step + h;
+        const int g_eff = grp < n_groups ? grp : n_groups - 1;   // the odd tail group does not exist: re-read the last one, masked
+        const int rel = grp * kGroup + n32;
+        const bool col_ok = rel < it.n;
+        const int entry = it.entry0 + rel;
+        const uint4 *blk = p.xblk + (it.group0 + g_eff) * (int64_t)(NCH * 32);
+        uint32_t x[NCH * 4];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const uint4 v = blk[c * 32 + n32];
+            x[4 * c] = v.x; x[4 * c + 1] = v.y; x[4 * c + 2] = v.z; x[4 * c + 3] = v.w;
+        }
+        const float xn = ((const float *)p.xnorm)[(it.group0 + g_eff) * kGroup + n32];
+        int32_t gid = -1;
+        if (and_rows != 0 && col_ok) gid = p.map[it.map_off + entry];
+
+        for (int r = 0; r < it.q_count; ++r) {
+            const int qr = __builtin_amdgcn_readlane(qr_lane, r);
+            // the queries are not written while the kernel runs: reading them through the constant
+            // address space makes these wave-uniform loads scalar loads
+            typedef const float __attribute__((address_space(4))) *const_f32;
+            const const_f32 qp = (const_f32)(uintptr_t)((const char *)p.qsrc + (int64_t)qr * row_bytes);
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll
+            for (int e = 0; e < NCH * 4; e += 4) {
+                a0 = __builtin_fmaf(__uint_as_float(x[e]), qp[e], a0);
+                a1 = __builtin_fmaf(__uint_as_float(x[e + 1]), qp[e + 1], a1);
+                a2 = __builtin_fmaf(__uint_as_float(x[e + 2]), qp[e + 2], a2);
+                a3 = __builtin_fmaf(__uint_as_float(x[e + 3]), qp[e + 3], a3);
+            }
+            const float dot = (a0 + a1) + (a2 + a3);
+            const float qn = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(qn_lane), r));
+            const uint32_t bits = __float_as_uint(fmaxf((qn + xn) - 2.0f * dot, 0.0f));
+            const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(row_kth >> 32), r);
+            bool pass = col_ok && bits <= thr;
+            if ((and_rows >> r) & 1u) {
+                if (pass) {
+                    const int o_begin = p.others_off[qr], o_end = p.others_off[qr + 1];
+                    for (int o = o_begin; o < o_end && pass; ++o) pass = has_label(p.meta, p.others[o], gid);
+                }
+            }
+            const uint64_t m = __ballot(pass);
+            if (m != 0) {
+                const int base = __builtin_amdgcn_readlane(pcv, r);
+                if (pass) pend[r * PC + base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint64_t)bits << 32) | (uint32_t)entry;
+                if (lane == r) pcv = base + __popcll(m);
+            }
+        }
+        if (__any(pcv > PC - 64) || (step + 1 == n_steps && __any(pcv != 0))) {
+            wave_lds_sync();
+            wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
+            wave_lds_sync();
+        }
+    }
+    __syncthreads();
+
+    for (int r = 0; r < it.q_count; ++r) {
+        if (lane >= K) continue;
+        const uint64_t key = best[r * KS + lane];
+        const bool none = key == KEY_MAX;
+        const uint32_t hi = (uint32_t)(key >> 32), idx = (uint32_t)key;
+        if (it.part_row < 0) {
+            const int64_t o = (int64_t)qrow_s[r] * K + lane;
+            p.out_ids[o] = none ? -1 : (int64_t)p.map[it.map_off + idx];
+            p.out_dists[o] = none ? __builtin_inff() : __uint_as_float(hi);
+        } else {
+            const int64_t o = (int64_t)(it.part_row + r) * K + lane;
+            p.res_idx[o] = none ? -1 : (int32_t)idx;
+            p.res_bits[o] = hi;
+        }
+    }
+}
+
 // Final top-K of a query whose list was scanned in several segments: sort the
 // segments' candidates by (distance, entry) and keep the first K.  One wave per query.
 template <int DT>
@@ -460,6 +602,20 @@ template <int DT> static void launch_scan_dt(const ScanParams &p, int n_items, h
         default: hipLaunchKernelGGL((scan_topk_kernel<DT, 0>), grid, block, lds, s, p); break;
         }
     }
+}
+
+bool scan_valu_supported(int dtype, int dim, int tile_rows)
+{
+    return dtype == 1 && (dim == 128 || dim == 96) && tile_rows <= 16;
+}
+
+// float32 search tiles (no self exclusion): see scan_valu_kernel
+void launch_scan_valu(const ScanParams &p, int n_items, hipStream_t s)
+{
+    if (n_items <= 0) return;
+    const size_t lds = (size_t)p.tile_rows * (96 + (p.K | 1)) * 8 + 2 * 32 * 4;
+    if (p.dim == 128) hipLaunchKernelGGL((scan_valu_kernel<32>), dim3(n_items), dim3(64), lds, s, p);
+    else hipLaunchKernelGGL((scan_valu_kernel<24>), dim3(n_items), dim3(64), lds, s, p);
 }
 
 void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,

@@ -343,3 +343,45 @@ def test_float_seed_scoring_variants(vf, env, name):
             assert pf["seed_rescored"] > 0
         else:
             assert pf["seed_fallbacks"] == 0 and pf["seed_rescored"] == 0
+
+
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_float_small_batches_use_fma_scan(vf, name):
+    """Batches with few scan queries go through the float32 FMA scan kernel (one list entry per
+    lane, query rows as scalar operands) instead of the matrix-core kernel: same tolerance
+    against the oracle, single-label and AND, dim 128 and dim 96, batch sizes 1 to 200."""
+    import torch
+    if name == "c2":
+        w = _float_small()
+    else:
+        w = make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    S = ixo.S
+    first = w.qlabel_ids[w.qlabel_offsets[:-1]]
+    scan_q = np.flatnonzero((S[first] < s.T) & (S[first] > 0))
+    rng = np.random.default_rng(77)
+    params = dict(itopk=32, width=1, iters=8, n_seeds=200)
+    n_checked = 0
+    for bs in (1, 1, 1, 8, 64, 200):
+        pick = np.sort(rng.choice(scan_q, size=bs, replace=False))
+        # the workload's own label sets (AND pairs for c5), and single labels
+        for single in (True, False):
+            if single:
+                qo = np.arange(bs + 1, dtype=np.int64)
+                ql = np.ascontiguousarray(first[pick])
+            else:
+                cnt = np.diff(w.qlabel_offsets)[pick]
+                qo = np.zeros(bs + 1, dtype=np.int64)
+                np.cumsum(cnt, out=qo[1:])
+                ql = np.concatenate([w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]] for j in pick])
+            Qb = torch.from_numpy(np.ascontiguousarray(w.queries[pick])).cuda()
+            ig, dg = _search(vf, ix, Qb, qo, ql, 10, **params)
+            io, do, info = ixo.search(np.ascontiguousarray(w.queries[pick]), qo, ql, 10, with_info=True, **params)
+            sc = info["method"] == 1
+            n_checked += int(sc.sum())
+            assert_close_with_ties(ig[sc], dg[sc], io[sc], do[sc], RTOL, f"{name} batch {bs} single={single}")
+            g = info["method"] == 2
+            assert_exact(ig[g], dg[g], io[g], do[g], f"{name} batch {bs} graph rows")
+    assert n_checked > 300
