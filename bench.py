@@ -136,8 +136,27 @@ def main():
 
     k = s.k
     t0 = time.time()
+    ix.profile_enable(True)
     gt_ids, _ = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, k)
     gt = gt_ids.cpu().numpy()
+    pfe = ix.profile_read()
+    ix.profile_enable(False)
+    # the dense invocations of the contraction kernel: ground truth (hundreds of queries share the
+    # popular lists) and the per-list kNN self-joins of the index build (every vertex is a query)
+    flops_per_pair = 2 * s.dim
+    S_all = ix.export("S").astype(np.float64)
+    knn_flops = float((S_all[S_all >= s.T] ** 2).sum()) * flops_per_pair
+    mfma_peak = FP32_VECTOR_PEAK_TFLOPS if s.dtype == "float32" else 5000.0
+    dense = {
+        "unit": "TFLOP/s" if s.dtype == "float32" else "TOP/s", "peak": mfma_peak,
+        "ground_truth": {"pairs": int(pfe["scan_pairs"]), "ms": round(pfe["scan_ms"], 3),
+                         "achieved": round(pfe["scan_pairs"] * flops_per_pair / (pfe["scan_ms"] * 1e-3) / 1e12, 1)},
+        "index_build_knn": {"pairs": int(knn_flops / flops_per_pair), "s": round(build_s, 3),
+                            "achieved_lower_bound": round(knn_flops / build_s / 1e12, 1),
+                            "note": "whole vf_build_index call, host work included"},
+    }
+    dense["ground_truth"]["frac"] = round(dense["ground_truth"]["achieved"] / mfma_peak, 4)
+    dense["index_build_knn"]["frac"] = round(dense["index_build_knn"]["achieved_lower_bound"] / mfma_peak, 4)
     log(f"[bench] exact filtered ground truth in {time.time() - t0:.1f}s")
 
     out_ids = torch.empty((s.nq, k), dtype=torch.int64, device="cuda")
@@ -195,7 +214,8 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_serial = (time.perf_counter() - t0) * 1e3 / args.steps
     pfs = ix.profile_read()
-    alone_ms = {"beam_kernel": pfs["beam_ms_sum"] / pfs["calls"], "seed_dist_kernel": pfs["seed_ms_sum"] / pfs["calls"],
+    alone_ms = {"beam_kernel": pfs["beam_ms_sum"] / pfs["calls"],
+                ("seed_mfma_kernel" if pfs["seeds_on_matrix_cores"] else "seed_dist_kernel"): pfs["seed_ms_sum"] / pfs["calls"],
                 "scan_topk_kernel": pfs["scan_ms_sum"] / pfs["calls"]}
     ix.profile_enable(False)
 
@@ -203,17 +223,21 @@ def main():
     vec_bytes = s.dim * eb
     n_gq = pf["n_graph_queries"]
     # algorithmic work of each kernel of one step (one vf_search call)
-    gathered = pf["beam_scored"] - pf["seed_pairs"]          # distances whose vector the beam kernel gathers itself
+    # distances whose vector the beam kernel gathers itself: children, and (when the seeds went through
+    # the matrix cores) the best approximate seeds it re-scores with the ordered distance
+    gathered = pf["beam_scored"] - pf["seed_pairs"] + pf["seed_rescored"]
+    seed_kernel = "seed_mfma_kernel" if pf["seeds_on_matrix_cores"] else "seed_dist_kernel"
     kernels = {
         "beam_kernel": {
             "ms": beam_avg_ms, "bound": "hbm",
             "bytes": gathered * (vec_bytes + 4) + pf["seed_pairs"] * 4 + pf["beam_expanded"] * s.graph_degree * 4
                      + pf["beam_tested"] * 4 + n_gq * (vec_bytes + k * 12),
             "flops": 3 * gathered * s.dim},
-        "seed_dist_kernel": {
-            "ms": seed_avg_ms, "bound": "alu",
+        seed_kernel: {
+            "ms": seed_avg_ms, "bound": "mfma" if pf["seeds_on_matrix_cores"] else "alu",
             "bytes": pf["seed_tile_seeds"] * (vec_bytes + 4) + n_gq * vec_bytes + pf["seed_pairs"] * 4,
-            "flops": 3 * pf["seed_pairs"] * s.dim},          # per element: one subtract, one fused multiply-add
+            # matrix cores: one multiply-add per element of q.x; vector ALU: one subtract + one fused multiply-add
+            "flops": (2 if pf["seeds_on_matrix_cores"] else 3) * pf["seed_pairs"] * s.dim},
         "scan_topk_kernel": {
             "ms": scan_avg_ms, "bound": "hbm",
             "bytes": pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),
@@ -223,7 +247,7 @@ def main():
     kd = kernels[dom]
     if kd["bound"] == "hbm":
         achieved, peak, unit = kd["bytes"] / (kd["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
-    else:
+    else:   # fp32 vector ALU and fp32 dense MFMA have the same published peak
         achieved, peak, unit = kd["flops"] / (kd["ms"] * 1e-3) / 1e12, FP32_VECTOR_PEAK_TFLOPS, "TFLOP/s"
     roofline = {
         "kernel": dom, "bound": kd["bound"], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
@@ -235,6 +259,14 @@ def main():
                   "achieved": round((kd["bytes"] / 1e9 if kd["bound"] == "hbm" else kd["flops"] / 1e12) / (alone_ms[dom] * 1e-3), 2),
                   "frac": round((kd["bytes"] / 1e9 if kd["bound"] == "hbm" else kd["flops"] / 1e12) / (alone_ms[dom] * 1e-3) / peak, 4),
                   "ms_per_step_serialised": round(ms_per_step_serial, 4)},
+        # the whole graph path priced as the gathers of the paper's formulation (every query fetches every
+        # vector it scores): bytes per query = scored (D b + 4) + expanded R 4 + tested 4 + D b + k 12
+        "graph_search_as_gathers": (lambda b, ms: {"bytes_per_launch": int(b), "ms_alone": round(ms, 4),
+                                                   "achieved": round(b / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                                                   "frac_of_hbm_peak": round(b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 3)})(
+            pf["beam_scored"] * (vec_bytes + 4) + pf["beam_expanded"] * s.graph_degree * 4 + pf["beam_tested"] * 4
+            + n_gq * (vec_bytes + k * 12), alone_ms["beam_kernel"] + alone_ms[seed_kernel]),
+        "dense_contraction": dense,
         "graph_queries_per_launch": int(n_gq), "scan_queries_per_launch": int(pf["n_scan_queries"]),
         "distances_per_graph_query": round(pf["beam_scored"] / max(n_gq, 1), 1),
         "all_kernels": {n: {"avg_launch_ms": round(v["ms"], 4), "avg_launch_ms_alone": round(alone_ms[n], 4), "bound": v["bound"],
