@@ -49,11 +49,23 @@ __device__ __forceinline__ bool visit(uint32_t *tab, int bits, uint32_t id)
 // Is local id c one of the ns stratified seeds floor(j * n / ns), j < ns?  (ns <= n.)
 // Seeds are scored up front, so a child that is a seed has been visited already;
 // answering this arithmetically keeps the seeds out of the visited table.
-__device__ __forceinline__ bool is_seed(uint32_t c, uint32_t n, uint32_t ns)
+// c is a seed iff some multiple of n lies in [c * ns, c * ns + ns), i.e. iff
+// r = (c * ns) mod n is 0 or larger than n - ns.  The quotient comes from a double-precision
+// multiplication by 1 / n (for n * ns < 2^52 the product is exact in a double and the estimate is off by at most
+// one, which the two corrections absorb); the remainder is exact integer arithmetic.
+__device__ __forceinline__ bool is_seed(uint32_t c, uint32_t n, uint32_t ns, double inv_n)
 {
     if (ns >= n) return true;
-    const uint64_t j = ((uint64_t)c * ns + n - 1) / n;  // smallest j with floor(j * n / ns) >= c
-    return j < ns && (uint32_t)((j * n) / ns) == c;
+    if (((uint64_t)n * ns) >> 52) {   // (not reached with realistic seed counts) plain integer division
+        const uint64_t j = ((uint64_t)c * ns + n - 1) / n;
+        return j < ns && (uint32_t)((j * n) / ns) == c;
+    }
+    const uint64_t prod = (uint64_t)c * ns;
+    const uint32_t q = (uint32_t)((double)c * (double)ns * inv_n);
+    int64_t r = (int64_t)prod - (int64_t)((uint64_t)q * n);
+    if (r < 0) r += n;
+    if (r >= (int64_t)n) r -= n;
+    return r == 0 || r > (int64_t)(n - ns);
 }
 
 // The sorted top-M list: element i sits in register i / 64 of lane i % 64.
@@ -188,6 +200,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     // ---- InitializeSearch: stratified seeds floor(j * n / ns)
     const int ns = p.n_seeds < n ? p.n_seeds : n;
+    const double inv_n = 1.0 / (double)n;
     int j_begin = 0;   // seeds below j_begin have been dealt with
 
     // Selection from a dense row of seed distances in two passes over chunks of 64 * NBLK seeds
@@ -374,7 +387,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             if (valid) {
                 const int pa = parents[j / R];
                 c = p.G[(base + pa) * R + (j % R)];
-                valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns) &&
+                valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns, inv_n) &&
                         visit(hash, p.hash_bits, (uint32_t)c);
             }
             cnt = filter_and_compact(valid, c, cnt);

@@ -30,6 +30,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+#ifndef VF_SCAN_WAVES
+#define VF_SCAN_WAVES 2
+#endif
 #ifndef VF_DRAIN_ROWS
 #define VF_DRAIN_ROWS 4
 #endif
@@ -175,7 +178,7 @@ __device__ __forceinline__ void wave_drain_rows(uint64_t *pend, int PC, uint64_t
 }
 
 template <int DT, int NCP>
-__global__ __launch_bounds__(64, 2) void scan_topk_kernel(ScanParams p)
+__global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
     const ScanItem it = p.items[blockIdx.x];
