@@ -40,6 +40,8 @@ def lib():
         L.vfo_free.argtypes = [p]
         L.vfo_search.restype = C.c_int
         L.vfo_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, i64, C.c_int, p, p, p, p, p, C.c_int]
+        L.vfo_search_multi.argtypes = [p, p, i64, p, p, C.c_int, i32, i32, i32, i32, i32, C.c_int, p, p, p, C.c_int]
+        L.vfo_search_multi.restype = C.c_int
         for name in ("vfo_n_HS", "vfo_n_LS"):
             getattr(L, name).restype = i64
             getattr(L, name).argtypes = [p]
@@ -156,6 +158,34 @@ class OracleIndex:
         if with_info:
             return ids, dists, dict(method=method, route_label=route, counters=counters)
         return ids, dists
+
+
+AND_PARALLEL, OR = 1, 2
+
+
+def _search_multi(self, queries, qlabel_offsets, qlabel_ids, mode, k, itopk=32, width=1, iters=20, n_seeds=0,
+                  force_scan=False, n_threads=None, with_info=False):
+    """Multi-label queries through several single-list searches and a merge: OR (Section 4.3.1)
+    and the parallel AND policy (Section 4.3.2)."""
+    queries = np.ascontiguousarray(queries)
+    assert str(queries.dtype) == self.dtype and queries.shape[1] == self.dim
+    nq = queries.shape[0]
+    qoff = np.ascontiguousarray(qlabel_offsets, dtype=np.int64)
+    qids = np.ascontiguousarray(qlabel_ids, dtype=np.int32)
+    ids = np.empty((nq, k), dtype=np.int64)
+    dists = np.empty((nq, k), dtype=np.float32)
+    ns = np.zeros(nq, dtype=np.int32)
+    rc = lib().vfo_search_multi(self._h, _ptr(queries), nq, _ptr(qoff), _ptr(qids), int(mode), k, itopk, width, iters,
+                                n_seeds, int(force_scan), _ptr(ids), _ptr(dists), _ptr(ns),
+                                self.n_threads if n_threads is None else n_threads)
+    if rc != 0:
+        raise ValueError("vfo_search_multi rejected its arguments")
+    if with_info:
+        return ids, dists, dict(n_searches=ns)
+    return ids, dists
+
+
+OracleIndex.search_multi = _search_multi
 
 
 def dist_f32_ordered(q, x):

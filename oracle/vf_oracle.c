@@ -554,3 +554,119 @@ int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, co
     }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------
+ * Multi-label queries answered by several single-list searches whose results are
+ * merged (Section 4.3.1 for OR; the parallel policy at the end of Section 4.3.2
+ * for AND).
+ *
+ * mode VFO_OR: one plain single-label search per distinct query label with a
+ *   non-empty list (graph if |C_l| >= T, else scan), no predicate.
+ * mode VFO_AND_PARALLEL: the AND of all query labels.  An empty list gives an empty
+ *   result.  If the smallest list is below T its filtered scan is already exact and
+ *   is the answer.  Otherwise every list is a graph list and each is searched with
+ *   the remaining labels as the predicate.
+ * Merge: the union of the searches' (id, distance) pairs; an id found more than once
+ *   keeps its smallest distance; order by (distance, id); the first k.
+ * Readings: the paper does not say how duplicates or distance ties are merged, nor
+ *   what the parallel policy does when a label is in the LS partition (its text is
+ *   about the HS partition).
+ * force_scan != 0 replaces every search by the exact scan of the same list.
+ * n_searches_out (optional, [nq]): searches run for the query. */
+enum { VFO_AND_PARALLEL = 1, VFO_OR = 2 };
+
+typedef struct { float d; int64_t id; } merge_entry;
+
+static int cmp_merge_id(const void *a, const void *b)
+{
+    const merge_entry *x = (const merge_entry *)a, *y = (const merge_entry *)b;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return (x->d > y->d) - (x->d < y->d);
+}
+
+static int cmp_merge_dist(const void *a, const void *b)
+{
+    const merge_entry *x = (const merge_entry *)a, *y = (const merge_entry *)b;
+    if (x->d != y->d) return x->d < y->d ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+int vfo_search_multi(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, const int32_t *qids, int mode,
+                     int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, int force_scan,
+                     int64_t *out_ids, float *out_dists, int32_t *n_searches_out, int n_threads)
+{
+    if (!ix || nq < 0 || k <= 0 || (mode != VFO_AND_PARALLEL && mode != VFO_OR)) return -1;
+    if (!force_scan && (itopk < k || width <= 0 || iters < 0)) return -1;
+    if (n_seeds <= 0) n_seeds = itopk;
+    for (int64_t j = 0; j < nq; ++j) {
+        if (qoff[j + 1] <= qoff[j]) return -1;
+        for (int64_t p = qoff[j]; p < qoff[j + 1]; ++p)
+            if (qids[p] < 0 || qids[p] >= ix->n_labels) return -1;
+    }
+    int64_t max_list = 1;
+    for (int32_t l = 0; l < ix->n_labels; ++l) if (ix->S[l] > max_list) max_list = ix->S[l];
+    size_t es = ix->dtype == VFO_U8 ? 1 : 4;
+
+#pragma omp parallel num_threads(n_threads > 0 ? n_threads : 1)
+    {
+        visit_state vs;
+        vs.stamp_len = max_list; vs.tick = 0;
+        vs.stamp = (int32_t *)calloc(max_list, sizeof(int32_t));
+        vs.fcap = 0; vs.ftab = NULL;
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t j = 0; j < nq; ++j) {
+            int32_t nl = (int32_t)(qoff[j + 1] - qoff[j]);
+            int32_t *ql = (int32_t *)malloc(sizeof(int32_t) * nl);
+            int32_t *others = (int32_t *)malloc(sizeof(int32_t) * nl);
+            memcpy(ql, qids + qoff[j], sizeof(int32_t) * nl);
+            qsort(ql, nl, sizeof(int32_t), cmp_i32);
+            int32_t u = 0;
+            for (int32_t p = 0; p < nl; ++p) if (p == 0 || ql[p] != ql[p - 1]) ql[u++] = ql[p];
+            nl = u;
+            const void *q = (const char *)Q + j * ix->dim * es;
+            merge_entry *pool = (merge_entry *)malloc(sizeof(merge_entry) * (size_t)nl * k);
+            int64_t *ti = (int64_t *)malloc(sizeof(int64_t) * k);
+            float *td = (float *)malloc(sizeof(float) * k);
+            int32_t n_pool = 0, n_searches = 0;
+
+            int32_t smallest = ql[0], empty = 0;
+            for (int32_t p = 0; p < nl; ++p) {
+                if (ix->S[ql[p]] == 0) empty = 1;
+                if (ix->S[ql[p]] < ix->S[smallest]) smallest = ql[p];
+            }
+            for (int32_t p = 0; p < nl; ++p) {
+                const int32_t l = ql[p];
+                int32_t n_others = 0;
+                if (mode == VFO_OR) {
+                    if (ix->S[l] == 0) continue;
+                } else {
+                    if (empty) break;
+                    if (ix->S[smallest] < ix->T && l != smallest) continue; /* the smallest list's scan is exact */
+                    for (int32_t t = 0; t < nl; ++t) if (ql[t] != l) others[n_others++] = ql[t]; /* stays sorted */
+                }
+                if (force_scan || ix->S[l] < ix->T) {
+                    scan_search(ix, q, l, others, n_others, k, ti, td, NULL);
+                } else {
+                    vs.tick++;
+                    graph_search(ix, q, l, others, n_others, k, itopk, width, iters, n_seeds, &vs, ti, td, NULL);
+                }
+                ++n_searches;
+                for (int32_t i = 0; i < k; ++i)
+                    if (ti[i] >= 0) { pool[n_pool].id = ti[i]; pool[n_pool].d = td[i]; ++n_pool; }
+            }
+            /* an id found by several searches keeps its smallest distance */
+            qsort(pool, n_pool, sizeof(merge_entry), cmp_merge_id);
+            int32_t m = 0;
+            for (int32_t i = 0; i < n_pool; ++i) if (i == 0 || pool[i].id != pool[i - 1].id) pool[m++] = pool[i];
+            qsort(pool, m, sizeof(merge_entry), cmp_merge_dist);
+            for (int32_t i = 0; i < k; ++i) {
+                if (i < m) { out_ids[j * k + i] = pool[i].id; out_dists[j * k + i] = pool[i].d; }
+                else { out_ids[j * k + i] = -1; out_dists[j * k + i] = INFINITY; }
+            }
+            if (n_searches_out) n_searches_out[j] = n_searches;
+            free(pool); free(ti); free(td); free(ql); free(others);
+        }
+        free(vs.stamp);
+    }
+    return 0;
+}

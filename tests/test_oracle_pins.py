@@ -405,3 +405,115 @@ def test_memory_model_worked_numbers():
     assert abs(hs + ls - g["total_GiB"]) < 0.011
     assert round(N * (D + R) * b / GiB, 2) == g["single_index_GiB"]
     assert round(N * g["F"] * b / GiB, 2) == g["mapping_GiB"]
+
+
+# ------------------------------------------------------------------ OR and the parallel AND policy (Section 4.3.1, 4.3.2)
+
+def _multi_label_queries(nq, n_labels, seed, lo=1, hi=4):
+    rng = np.random.default_rng(seed)
+    counts = rng.integers(lo, hi + 1, size=nq)
+    qoff = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum(counts, out=qoff[1:])
+    # a mix of popular labels (graph lists) and rare ones (scan lists), duplicates allowed
+    qids = np.where(rng.random(qoff[-1]) < 0.6, rng.integers(0, 8, size=qoff[-1]), rng.integers(0, n_labels, size=qoff[-1]))
+    return qoff, qids.astype(np.int32)
+
+
+def test_or_with_exact_searches_is_brute_force_over_the_union(tiny, tiny_oracle):
+    """OR = nearest neighbours carrying ANY query label (Section 4.3.1).  With every
+    per-label search exact, the merge must give exact kNN over the union of the lists,
+    written here from the definition in numpy."""
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    nq = 150
+    qoff, qids = _multi_label_queries(nq, s.n_labels, 5)
+    ids, dists = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, oracle.OR, s.k, force_scan=True)
+    for j in range(nq):
+        ls = np.unique(qids[qoff[j]:qoff[j + 1]])
+        cand = np.flatnonzero(mem[:, ls].any(axis=1))
+        d = ((tiny.vectors[cand].astype(np.float64) - tiny.queries[j].astype(np.float64)) ** 2).sum(axis=1)
+        order = np.lexsort((cand, d))[:s.k]
+        want = np.full(s.k, -1, dtype=np.int64)
+        want[:len(order)] = cand[order]
+        assert np.array_equal(ids[j], want), j
+        assert np.array_equal(dists[j][:len(order)], d[order].astype(np.float32))
+        assert len(np.unique(ids[j][ids[j] >= 0])) == (ids[j] >= 0).sum()       # an id shared by two lists appears once
+
+
+def test_parallel_and_with_exact_searches_is_brute_force_over_the_intersection(tiny, tiny_oracle):
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    nq = 150
+    qoff, qids = _multi_label_queries(nq, s.n_labels, 6, lo=2, hi=3)
+    ids, dists = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, oracle.AND_PARALLEL, s.k, force_scan=True)
+    n_nonempty = 0
+    for j in range(nq):
+        want, wd = filtered_knn(tiny.vectors, mem, tiny.queries[j], np.unique(qids[qoff[j]:qoff[j + 1]]), s.k)
+        assert np.array_equal(ids[j], want), j
+        n_nonempty += int(want[0] >= 0)
+    assert n_nonempty > 20
+
+
+def test_multi_search_with_one_label_is_the_single_label_search(tiny, tiny_oracle):
+    s = tiny.spec
+    params = dict(itopk=32, width=1, iters=12, n_seeds=96)
+    i0, d0 = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, s.k, **params)
+    for mode in (oracle.OR, oracle.AND_PARALLEL):
+        i1, d1, info = tiny_oracle.search_multi(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, mode, s.k,
+                                                with_info=True, **params)
+        assert np.array_equal(i0, i1) and np.array_equal(d0, d1)
+        assert (info["n_searches"] == 1).all()
+
+
+def test_parallel_and_contains_the_greedy_search_and_stays_valid(tiny, tiny_oracle):
+    """The greedy policy's search (smallest list, others as predicate) is one of the
+    parallel policy's searches, so the merged top-k can only be at least as close, rank by
+    rank; every id still carries every label; graph-only queries run one search per label and
+    scan-routed queries exactly one."""
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    rng = np.random.default_rng(9)
+    nq = 300
+    a = rng.integers(0, 7, size=nq)                    # the 7 largest labels are the graph lists of this workload
+    b = rng.integers(0, 12, size=nq)
+    qoff = np.arange(0, 2 * nq + 1, 2, dtype=np.int64)
+    qids = np.stack([a, b], axis=1).reshape(-1).astype(np.int32)
+    params = dict(itopk=32, width=1, iters=10, n_seeds=64)
+    ig, dg, info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, with_info=True, **params)
+    ip, dp, pinfo = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, oracle.AND_PARALLEL, s.k, with_info=True,
+                                             **params)
+    S, T = tiny_oracle.S, s.T
+    better = 0
+    for j in range(nq):
+        ls = np.unique(qids[qoff[j]:qoff[j + 1]])
+        for g in ip[j][ip[j] >= 0]:
+            assert mem[g, ls].all()
+        fin = dp[j][np.isfinite(dp[j])]
+        assert (np.diff(fin) >= 0).all() and (ip[j][len(fin):] == -1).all()
+        assert (dp[j] <= dg[j]).all()
+        better += int((dp[j] < dg[j]).any())
+        all_graph = (S[ls] >= T).all()
+        assert pinfo["n_searches"][j] == (len(ls) if all_graph and (S[ls] > 0).all() else int((S[ls] > 0).all()))
+    assert better > 5                                  # the policy exists because it finds closer points
+    gt, _ = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, force_scan=True)
+    assert recall_at_k(ip, gt) >= recall_at_k(ig, gt)
+
+
+def test_or_is_at_least_as_close_as_every_single_label_search(tiny, tiny_oracle):
+    s = tiny.spec
+    nq = 200
+    qoff, qids = _multi_label_queries(nq, s.n_labels, 11, lo=2, hi=3)
+    params = dict(itopk=32, width=1, iters=10, n_seeds=64)
+    io, do = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, oracle.OR, s.k, **params)
+    for t in range(2):                                  # first and second label of every query, searched alone
+        one = np.array([qids[qoff[j] + min(t, qoff[j + 1] - qoff[j] - 1)] for j in range(nq)], dtype=np.int32)
+        i1, d1 = tiny_oracle.search(tiny.queries[:nq], np.arange(nq + 1), one, s.k, **params)
+        assert (do <= d1).all()
+    assert all(len(np.unique(r[r >= 0])) == (r >= 0).sum() for r in io)
+
+
+def test_multi_search_rejects_bad_arguments(tiny, tiny_oracle):
+    with pytest.raises(ValueError):
+        tiny_oracle.search_multi(tiny.queries[:4], np.arange(5), np.zeros(4, dtype=np.int32), 7, 10)
+    with pytest.raises(ValueError):
+        tiny_oracle.search_multi(tiny.queries[:4], np.arange(5), np.full(4, 10 ** 6, dtype=np.int32), oracle.OR, 10)
