@@ -100,6 +100,27 @@ int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *q
               int64_t *out_ids, float *out_dists, void *hip_stream);
 
 /*
+ * Multi-label queries through one search per label and a merge.
+ *   mode VF_AND_GREEDY    the same as vf_search (smallest list + predicate, Section 4.3.2).
+ *   mode VF_AND_PARALLEL  the parallel policy at the end of Section 4.3.2: when every query label
+ *                         is a graph label, each label's list is searched with the other labels
+ *                         as the predicate and the results are merged.  When the smallest list
+ *                         is below T its filtered scan is exact already and is the answer.
+ *   mode VF_OR            Section 4.3.1: one plain single-label search per distinct query label
+ *                         (graph or scan by its size), merged: the nearest vectors that carry ANY
+ *                         of the labels.
+ * Merge: an id found by several searches keeps its smallest distance; the k best by
+ * (distance, id).  Other arguments, layout and error behaviour as in vf_search; the searches of
+ * all queries run as one batch of up to 8 * nq single-list searches.
+ */
+#define VF_AND_GREEDY 0
+#define VF_AND_PARALLEL 1
+#define VF_OR 2
+int vf_search_multi(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                    const int32_t *qlabel_ids, int32_t mode, int32_t k, int32_t itopk, int32_t width, int32_t iters,
+                    int32_t n_seeds, int64_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
  * Exact filtered top-k (Section 3, Def. 1) for every query, graph lists included,
  * by exhaustive scan of the smallest list with the predicate applied: the ground
  * truth against which recall (Section 3, Eq. 1) is measured.  Arguments as in

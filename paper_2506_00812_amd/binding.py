@@ -20,7 +20,7 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
                   GO_LS=np.int64, X_LS=np.uint8, BITSET=np.uint32)
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
-                    "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read")
+                    "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi")
 
 
 class VfStats(C.Structure):
@@ -66,6 +66,9 @@ def load_library():
         L.vf_index_export.argtypes = [p, C.c_int, p, C.POINTER(C.c_size_t)]
         L.vf_index_stats.restype = C.c_int
         L.vf_index_stats.argtypes = [p, C.POINTER(VfStats)]
+        L.vf_search_multi.restype = C.c_int
+        L.vf_search_multi.argtypes = [p, p, C.c_int64, p, p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, p, p, p]
         L.vf_profile_enable.restype = C.c_int
         L.vf_profile_enable.argtypes = [p, C.c_int]
         L.vf_profile_read.restype = C.c_int
@@ -194,6 +197,26 @@ def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width
                                     int(itopk), int(width), int(iters), int(n_seeds),
                                     C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
                                     _stream_handle(stream)))
+    return out_ids, out_dists
+
+
+AND_GREEDY, AND_PARALLEL, OR = 0, 1, 2
+
+
+def search_multi(index: Index, queries, qlabel_offsets, qlabel_ids, mode, k, itopk=64, width=1, iters=32, n_seeds=0,
+                 out_ids=None, out_dists=None, stream=None):
+    """OR queries and the parallel AND policy: one search per query label, merged.  Asynchronous."""
+    import torch
+    off, ids = _prep_queries(index, queries, qlabel_offsets, qlabel_ids)
+    nq = queries.shape[0]
+    if out_ids is None:
+        out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+    if out_dists is None:
+        out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    _check(load_library().vf_search_multi(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids),
+                                          int(mode), int(k), int(itopk), int(width), int(iters), int(n_seeds),
+                                          C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
+                                          _stream_handle(stream)))
     return out_ids, out_dists
 
 

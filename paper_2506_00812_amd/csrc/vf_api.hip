@@ -97,6 +97,11 @@ struct vf_index {
     bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
     // search workspace
     DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
+    // vf_search_multi: gathered query rows, results of the sub-searches, their parents
+    DevBuf multi_q, multi_ids, multi_dists, multi_meta;
+    std::vector<int32_t> multi_host;      // [n_sub parents | nq + 1 first sub-search of each query], alive until the next call
+    std::vector<int64_t> multi_qoff;
+    std::vector<int32_t> multi_qids;
     // profiling
     bool profiling = false, prof_valid = false;
     hipEvent_t prof_ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};  // scan begin/end, graph begin, seeds end, beam end
@@ -129,7 +134,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
     for (hipEvent_t e : ix->prof_ev)
         if (e) (void)hipEventDestroy(e);
@@ -384,7 +389,8 @@ namespace {
 
 // ClassifyQueries (Alg. 2) + smallest-list choice (Section 4.3.2).  Queries are grouped by the
 // label they search with a counting sort: O(nq + labels touched), no comparison sort of the batch.
-int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int32_t *qids, bool all_scan, Routed &r)
+int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int32_t *qids, bool all_scan,
+                  bool first_is_searched, Routed &r)
 {
     VF_REQUIRE(qoff && qids, "NULL query label arrays");
     VF_REQUIRE(qoff[0] >= 0, "qlabel_offsets[0] must be >= 0");
@@ -418,7 +424,7 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
             const int32_t l = labs[i];
             const int32_t sl = ix->S[(size_t)l], sb = ix->S[(size_t)best];
             if (sl == 0) empty = true;
-            if (sl < sb || (sl == sb && l < best)) best = l;
+            if (!first_is_searched && (sl < sb || (sl == sb && l < best))) best = l;
         }
         if (!empty) {
             for (int32_t i = 0; i < nl; ++i)
@@ -548,9 +554,11 @@ struct ItemBuilder {
     }
 };
 
+// first_is_searched: every query searches the list of its first label (the others are the
+// predicate) instead of its smallest list -- the sub-searches of vf_search_multi.
 static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
                        int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, bool exact, int64_t *out_ids,
-                       float *out_dists, hipStream_t s)
+                       float *out_dists, hipStream_t s, bool first_is_searched = false)
 {
     int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
     if (rc != VF_OK) return rc;
@@ -574,7 +582,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
     if (nq == 0) return VF_OK;
     try {
         Routed &r = ix->routed;
-        if ((rc = route_queries(ix, nq, qoff, qids, exact, r)) != VF_OK) return rc;
+        if ((rc = route_queries(ix, nq, qoff, qids, exact, first_is_searched, r)) != VF_OK) return rc;
 
         // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
         ItemBuilder ib;
@@ -813,6 +821,94 @@ extern "C" int vf_search_exact(vf_index *index, const void *queries, int64_t nq,
 {
     return search_impl(index, queries, nq, qlabel_offsets, qlabel_ids, k, 0, 0, 0, 0, true, out_ids, out_dists,
                        (hipStream_t)hip_stream);
+}
+
+// OR queries (Section 4.3.1) and the parallel AND policy (end of Section 4.3.2): every query becomes
+// one search per label, the searches run as one ordinary batch, and a merge kernel combines them.
+extern "C" int vf_search_multi(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids,
+                               int32_t mode, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
+                               int64_t *out_ids, float *out_dists, void *hip_stream)
+{
+    hipStream_t s = (hipStream_t)hip_stream;
+    VF_REQUIRE(mode == VF_AND_GREEDY || mode == VF_AND_PARALLEL || mode == VF_OR, "mode must be VF_AND_GREEDY, VF_AND_PARALLEL or VF_OR");
+    if (mode == VF_AND_GREEDY)
+        return search_impl(ix, queries, nq, qoff, qids, k, itopk, width, iters, n_seeds, false, out_ids, out_dists, s);
+    int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
+    if (rc != VF_OK) return rc;
+    VF_REQUIRE(qoff && qids, "NULL query label arrays");
+    if (nq == 0) return VF_OK;
+    try {
+        std::vector<int32_t> &host = ix->multi_host;
+        std::vector<int64_t> &sqoff = ix->multi_qoff;
+        std::vector<int32_t> &sqids = ix->multi_qids;
+        host.clear(); sqoff.assign(1, 0); sqids.clear();
+        std::vector<int32_t> first((size_t)nq + 1, 0);
+        int32_t labs[kMaxOthers + 1];
+        for (int64_t j = 0; j < nq; ++j) {
+            const int64_t b = qoff[j], e = qoff[j + 1];
+            VF_REQUIRE(e > b, "every query needs at least one label");
+            int32_t nl = 0;
+            for (int64_t p = b; p < e; ++p) {
+                const int32_t l = qids[p];
+                VF_REQUIRE(l >= 0 && l < ix->n_labels, "query label outside [0, n_labels)");
+                bool seen = false;
+                for (int32_t i = 0; i < nl; ++i) seen = seen || labs[i] == l;
+                if (seen) continue;
+                VF_REQUIRE(nl <= kMaxOthers, "more than 8 distinct labels in one query");
+                labs[nl++] = l;
+            }
+            auto add = [&](int32_t searched, bool with_others) {
+                host.push_back((int32_t)j);
+                sqids.push_back(searched);
+                if (with_others)
+                    for (int32_t i = 0; i < nl; ++i)
+                        if (labs[i] != searched) sqids.push_back(labs[i]);
+                sqoff.push_back((int64_t)sqids.size());
+            };
+            if (mode == VF_OR) {
+                for (int32_t i = 0; i < nl; ++i)
+                    if (ix->S[(size_t)labs[i]] > 0) add(labs[i], false);
+            } else {
+                int32_t best = labs[0];
+                bool empty = false;
+                for (int32_t i = 0; i < nl; ++i) {
+                    const int32_t sl = ix->S[(size_t)labs[i]], sb = ix->S[(size_t)best];
+                    if (sl == 0) empty = true;
+                    if (sl < sb || (sl == sb && labs[i] < best)) best = labs[i];
+                }
+                if (!empty) {
+                    if (ix->S[(size_t)best] < ix->T) add(best, true);   // the filtered scan of the smallest list is exact
+                    else for (int32_t i = 0; i < nl; ++i) add(labs[i], true);
+                }
+            }
+            first[(size_t)j + 1] = (int32_t)host.size();
+        }
+        const int64_t n_sub = (int64_t)host.size();
+        if (n_sub == 0) {
+            launch_fill_out(out_ids, out_dists, nq * (int64_t)k, s);
+            VF_HIP(hipGetLastError());
+            return VF_OK;
+        }
+        host.insert(host.end(), first.begin(), first.end());
+        const size_t row_bytes = (size_t)ix->dim * ix->elem();
+        if ((rc = ix->multi_meta.reserve(host.size() * 4)) != VF_OK) return rc;
+        if ((rc = ix->multi_q.reserve((size_t)n_sub * row_bytes)) != VF_OK) return rc;
+        if ((rc = ix->multi_ids.reserve((size_t)n_sub * k * 8)) != VF_OK) return rc;
+        if ((rc = ix->multi_dists.reserve((size_t)n_sub * k * 4)) != VF_OK) return rc;
+        VF_HIP(hipMemcpyAsync(ix->multi_meta.p, host.data(), host.size() * 4, hipMemcpyHostToDevice, s));
+        const int32_t *d_parent = ix->multi_meta.as<int32_t>();
+        const int32_t *d_first = d_parent + n_sub;
+        launch_gather_rows(queries, (int32_t)row_bytes, d_parent, n_sub, ix->multi_q.p, s);
+        rc = search_impl(ix, ix->multi_q.p, n_sub, sqoff.data(), sqids.data(), k, itopk, width, iters, n_seeds, false,
+                         ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), s, true);
+        if (rc != VF_OK) return rc;
+        launch_multi_merge(d_first, nq, ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), k, out_ids, out_dists, s);
+        VF_HIP(hipGetLastError());
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return VF_ENOMEM;
+    }
+    return VF_OK;
 }
 
 // ---------------------------------------------------------------- export / stats

@@ -163,4 +163,69 @@ void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s)
     hipLaunchKernelGGL(fill_out_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, ids, dists, count);
 }
 
+__global__ void gather_rows_kernel(const uint4 *rows, int32_t chunks, const int32_t *parent, int64_t n, uint4 *out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * chunks) return;
+    const int64_t i = t / chunks;
+    const int c = (int)(t % chunks);
+    out[t] = rows[(int64_t)parent[i] * chunks + c];
+}
+
+void launch_gather_rows(const void *rows, int32_t row_bytes, const int32_t *parent, int64_t n, void *out, hipStream_t s)
+{
+    if (n <= 0) return;
+    const int32_t chunks = row_bytes / kChunkBytes;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((n * chunks + 255) / 256)), dim3(256), 0, s, (const uint4 *)rows,
+                       chunks, parent, n, (uint4 *)out);
+}
+
+// One wave per query.  Keys (id << 32 | distance bits) sorted: equal ids become neighbours with the
+// smallest distance first; the survivors, re-keyed (distance bits << 32 | id), are sorted again.
+// Distances are non-negative floats, whose bit patterns order like the values.
+__global__ __launch_bounds__(64) void multi_merge_kernel(const int32_t *first, const int64_t *sub_ids, const float *sub_dists,
+                                                         int32_t k, int32_t P, int64_t *out_ids, float *out_dists)
+{
+    extern __shared__ uint4 smem[];
+    uint64_t *keys = (uint64_t *)smem;        // [P]
+    uint64_t *keys2 = keys + P;               // [P]
+    const int lane = threadIdx.x;
+    const int64_t q = blockIdx.x;
+    const int64_t lo = first[q], hi = first[q + 1];
+    const int total = (int)(hi - lo) * k;
+    for (int i = lane; i < P; i += 64) {
+        uint64_t key = KEY_MAX;
+        if (i < total) {
+            const int64_t id = sub_ids[lo * k + i];
+            if (id >= 0) key = ((uint64_t)id << 32) | __float_as_uint(sub_dists[lo * k + i]);
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    wave_bitonic_sort(keys, P, lane);
+    for (int i = lane; i < P; i += 64) {
+        const uint64_t key = keys[i];
+        const bool keep = key != KEY_MAX && (i == 0 || (keys[i - 1] >> 32) != (key >> 32));
+        keys2[i] = keep ? ((key << 32) | (key >> 32)) : KEY_MAX;
+    }
+    __syncthreads();
+    wave_bitonic_sort(keys2, P, lane);
+    if (lane < k) {
+        const uint64_t key = lane < P ? keys2[lane] : KEY_MAX;
+        const bool none = key == KEY_MAX;
+        out_ids[q * k + lane] = none ? -1 : (int64_t)(uint32_t)key;
+        out_dists[q * k + lane] = none ? __builtin_inff() : __uint_as_float((uint32_t)(key >> 32));
+    }
+}
+
+void launch_multi_merge(const int32_t *first, int64_t nq, const int64_t *sub_ids, const float *sub_dists, int32_t k,
+                        int64_t *out_ids, float *out_dists, hipStream_t s)
+{
+    if (nq <= 0) return;
+    int32_t P = 64;
+    while (P < (kMaxOthers + 1) * k) P <<= 1;
+    hipLaunchKernelGGL(multi_merge_kernel, dim3((unsigned)nq), dim3(64), (size_t)P * 16, s, first, sub_ids, sub_dists, k, P,
+                       out_ids, out_dists);
+}
+
 }  // namespace vf

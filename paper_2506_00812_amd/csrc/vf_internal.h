@@ -156,6 +156,15 @@ void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map
 
 void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s);
 
+// ---------------------------------------------------------------- multi-label queries (OR, parallel AND)
+
+// out[i] = row parent[i] of a row-major table (rows of row_bytes, a multiple of 16)
+void launch_gather_rows(const void *rows, int32_t row_bytes, const int32_t *parent, int64_t n, void *out, hipStream_t s);
+// Query j owns the sub-search results first[j] .. first[j+1] (<= 8 rows of k (id, distance) pairs, id -1 = none):
+// an id found more than once keeps its smallest distance; the k best by (distance, id) are written.
+void launch_multi_merge(const int32_t *first, int64_t nq, const int64_t *sub_ids, const float *sub_dists, int32_t k,
+                        int64_t *out_ids, float *out_dists, hipStream_t s);
+
 // ---------------------------------------------------------------- errors
 
 void set_error(const std::string &msg);

@@ -36,6 +36,20 @@ def test_stats_struct_matches_header():
     assert names == [n for n, _ in binding.VfStats._fields_]
 
 
+def test_profile_struct_matches_header():
+    hdr = open(os.path.join(ROOT, "include", "vecflow.h")).read()
+    body = re.search(r"typedef struct vf_profile \{(.*?)\} vf_profile;", hdr, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = [n.strip() for line in body.split(";")
+             for n in re.sub(r"\b(float|double|int64_t|int32_t)\b", "", line).split(",") if n.strip()]
+    assert names == [n for n, _ in binding.VfProfile._fields_]
+
+
+def test_search_multi_rejects_bad_mode_without_gpu(lib):
+    assert lib.vf_search_multi(None, None, 0, None, None, 9, 10, 32, 1, 8, 0, None, None, None) == -1
+    assert b"mode" in lib.vf_last_error()
+
+
 def test_build_rejects_bad_arguments_without_gpu(lib):
     h = C.c_void_p()
     off = np.array([0, 1, 2], dtype=np.int64)

@@ -385,3 +385,61 @@ def test_float_small_batches_use_fma_scan(vf, name):
             g = info["method"] == 2
             assert_exact(ig[g], dg[g], io[g], do[g], f"{name} batch {bs} graph rows")
     assert n_checked > 300
+
+
+def _multi_queries(nq, n_labels, seed, lo, hi, popular):
+    rng = np.random.default_rng(seed)
+    counts = rng.integers(lo, hi + 1, size=nq)
+    qoff = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum(counts, out=qoff[1:])
+    qids = np.where(rng.random(qoff[-1]) < 0.6, rng.integers(0, popular, size=qoff[-1]),
+                    rng.integers(0, n_labels, size=qoff[-1]))
+    return qoff, qids.astype(np.int32)
+
+
+@pytest.mark.parametrize("mode_name", ["OR", "AND_PARALLEL"])
+def test_tiny_multi_search_bit_exact(vf, tiny, tiny_oracle, tiny_gpu, mode_name):
+    """OR queries and the parallel AND policy on uint8 data: one search per label and a merge,
+    bit-exact against the oracle (graph and scan lists mixed, duplicates and unknown-empty labels)."""
+    import oracle
+    ix, Q = tiny_gpu
+    s = tiny.spec
+    nq = 800
+    lo, hi = (1, 4) if mode_name == "OR" else (2, 3)
+    qoff, qids = _multi_queries(nq, s.n_labels, 41, lo, hi, popular=9)
+    for params in (dict(itopk=32, width=1, iters=12, n_seeds=96), dict(itopk=64, width=2, iters=8, n_seeds=400)):
+        ig, dg = vf.search_multi(ix, Q[:nq], qoff, qids, getattr(vf, mode_name), s.k, **params)
+        io, do, info = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, getattr(oracle, mode_name), s.k,
+                                                with_info=True, **params)
+        assert (info["n_searches"] > 1).sum() > 100
+        assert_exact(to_np(ig), to_np(dg), io, do, f"{mode_name} {params}")
+    # mode 0 is vf_search
+    ig, dg = vf.search_multi(ix, Q[:nq], qoff, qids, vf.AND_GREEDY, s.k, itopk=32, width=1, iters=12, n_seeds=96)
+    i0, d0 = _search(vf, ix, Q[:nq], qoff, qids, s.k, itopk=32, width=1, iters=12, n_seeds=96)
+    assert_exact(to_np(ig), to_np(dg), i0, d0, "greedy through vf_search_multi")
+
+
+@pytest.mark.parametrize("mode_name", ["OR", "AND_PARALLEL"])
+def test_float_multi_search(vf, mode_name):
+    """float32: queries whose searches all ran on graph lists must match the oracle bit for bit
+    (ordered distances on both sides); queries that involve a scan list within the scan tolerance."""
+    import oracle
+    import torch
+    w = _float_small()
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    Q = torch.from_numpy(w.queries).cuda()
+    nq = 600
+    lo, hi = (1, 3) if mode_name == "OR" else (2, 2)
+    qoff, qids = _multi_queries(nq, s.n_labels, 43, lo, hi, popular=10)
+    params = dict(itopk=32, width=1, iters=8, n_seeds=300)
+    ig, dg = vf.search_multi(ix, Q[:nq], qoff, qids, getattr(vf, mode_name), 10, **params)
+    ig, dg = to_np(ig), to_np(dg)
+    io, do = ixo.search_multi(w.queries[:nq], qoff, qids, getattr(oracle, mode_name), 10, **params)
+    S = ixo.S
+    all_graph = np.array([(S[np.unique(qids[qoff[j]:qoff[j + 1]])] >= s.T).all() for j in range(nq)])
+    assert all_graph.sum() > 80 and (~all_graph).sum() > 80
+    assert_exact(ig[all_graph], dg[all_graph], io[all_graph], do[all_graph], f"float {mode_name}, graph lists only")
+    assert_close_with_ties(ig[~all_graph], dg[~all_graph], io[~all_graph], do[~all_graph], RTOL,
+                           f"float {mode_name}, scan lists involved")
