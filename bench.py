@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=64)
+    ap.add_argument("--multi", action="store_true",
+                    help="also measure two-label AND (greedy and parallel policy) and OR queries on the same index")
     ap.add_argument("--latency", action="store_true",
                     help="also measure small-batch latency (batches of 1, 8 and 64 queries, half graph / half scan labels)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -293,6 +295,39 @@ def main():
                  "params_0.99": dict(zip(("itopk", "width", "iters", "n_seeds"), p99[0]))}
     else:
         extra = {"qps_at_recall_0.99": None, "recall_ceiling": round(max(t[1] for t in table), 4)}
+
+    # ---- two-label queries on the same index: greedy AND, parallel AND policy, OR
+    if args.multi:
+        rng = np.random.default_rng(2468)
+        cnt = np.diff(w.label_offsets)
+        multi = np.flatnonzero(cnt >= 2)
+        pick = rng.choice(multi, size=s.nq, replace=True)          # both labels of a pair occur on one data point
+        qids2 = np.empty((s.nq, 2), dtype=np.int32)
+        for t, v in enumerate(pick):
+            labs = np.unique(w.label_ids[w.label_offsets[v]:w.label_offsets[v + 1]])
+            if len(labs) < 2:
+                labs = np.array([labs[0], (labs[0] + 1) % s.n_labels])
+            qids2[t] = rng.choice(labs, size=2, replace=False)
+        qoff2 = np.arange(0, 2 * s.nq + 1, 2, dtype=np.int64)
+        qids2 = qids2.reshape(-1)
+        res = {}
+        for name, mode in (("and_greedy", vf.AND_GREEDY), ("and_parallel", vf.AND_PARALLEL), ("or", vf.OR)):
+            gi, _ = vf.search_multi(ix, Q, qoff2, qids2, mode | vf.MULTI_EXACT, k)
+            gtm = gi.cpu().numpy()
+            row = {}
+            for tag, prm in (("p90", headline[0]), ("p99", (p99 or headline)[0])):
+                for _ in range(args.warmup):
+                    vf.search_multi(ix, Q, qoff2, qids2, mode, k, *prm, out_ids, out_dists)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    vf.search_multi(ix, Q, qoff2, qids2, mode, k, *prm, out_ids, out_dists)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3 / args.steps
+                row[tag] = {"params": list(prm), "qps": round(s.nq / ms * 1e3, 1),
+                            "recall_at_10": round(recall_at_k(out_ids.cpu().numpy(), gtm), 4)}
+            res[name] = row
+        extra["two_label_queries"] = res
 
     # ---- small-batch latency on the same index (batches of 1, 8, 64; labels half graph lists, half scan lists)
     if args.latency:

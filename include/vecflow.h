@@ -116,6 +116,7 @@ int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *q
 #define VF_AND_GREEDY 0
 #define VF_AND_PARALLEL 1
 #define VF_OR 2
+#define VF_MULTI_EXACT 0x100 /* or-ed into mode: every search is the exact scan of its list (ground truth; synchronises) */
 int vf_search_multi(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
                     const int32_t *qlabel_ids, int32_t mode, int32_t k, int32_t itopk, int32_t width, int32_t iters,
                     int32_t n_seeds, int64_t *out_ids, float *out_dists, void *hip_stream);

@@ -201,6 +201,7 @@ def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width
 
 
 AND_GREEDY, AND_PARALLEL, OR = 0, 1, 2
+MULTI_EXACT = 0x100
 
 
 def search_multi(index: Index, queries, qlabel_offsets, qlabel_ids, mode, k, itopk=64, width=1, iters=32, n_seeds=0,

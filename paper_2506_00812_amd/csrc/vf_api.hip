@@ -830,9 +830,11 @@ extern "C" int vf_search_multi(vf_index *ix, const void *queries, int64_t nq, co
                                int64_t *out_ids, float *out_dists, void *hip_stream)
 {
     hipStream_t s = (hipStream_t)hip_stream;
+    const bool exact = (mode & VF_MULTI_EXACT) != 0;
+    mode &= ~VF_MULTI_EXACT;
     VF_REQUIRE(mode == VF_AND_GREEDY || mode == VF_AND_PARALLEL || mode == VF_OR, "mode must be VF_AND_GREEDY, VF_AND_PARALLEL or VF_OR");
     if (mode == VF_AND_GREEDY)
-        return search_impl(ix, queries, nq, qoff, qids, k, itopk, width, iters, n_seeds, false, out_ids, out_dists, s);
+        return search_impl(ix, queries, nq, qoff, qids, k, itopk, width, iters, n_seeds, exact, out_ids, out_dists, s);
     int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
     if (rc != VF_OK) return rc;
     VF_REQUIRE(qoff && qids, "NULL query label arrays");
@@ -899,7 +901,7 @@ extern "C" int vf_search_multi(vf_index *ix, const void *queries, int64_t nq, co
         const int32_t *d_parent = ix->multi_meta.as<int32_t>();
         const int32_t *d_first = d_parent + n_sub;
         launch_gather_rows(queries, (int32_t)row_bytes, d_parent, n_sub, ix->multi_q.p, s);
-        rc = search_impl(ix, ix->multi_q.p, n_sub, sqoff.data(), sqids.data(), k, itopk, width, iters, n_seeds, false,
+        rc = search_impl(ix, ix->multi_q.p, n_sub, sqoff.data(), sqids.data(), k, itopk, width, iters, n_seeds, exact,
                          ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), s, true);
         if (rc != VF_OK) return rc;
         launch_multi_merge(d_first, nq, ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), k, out_ids, out_dists, s);

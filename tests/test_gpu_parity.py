@@ -413,6 +413,10 @@ def test_tiny_multi_search_bit_exact(vf, tiny, tiny_oracle, tiny_gpu, mode_name)
                                                 with_info=True, **params)
         assert (info["n_searches"] > 1).sum() > 100
         assert_exact(to_np(ig), to_np(dg), io, do, f"{mode_name} {params}")
+    # exact variant (ground truth for recall): every search is a scan
+    ig, dg = vf.search_multi(ix, Q[:nq], qoff, qids, getattr(vf, mode_name) | vf.MULTI_EXACT, s.k)
+    io, do = tiny_oracle.search_multi(tiny.queries[:nq], qoff, qids, getattr(oracle, mode_name), s.k, force_scan=True)
+    assert_exact(to_np(ig), to_np(dg), io, do, f"{mode_name} exact")
     # mode 0 is vf_search
     ig, dg = vf.search_multi(ix, Q[:nq], qoff, qids, vf.AND_GREEDY, s.k, itopk=32, width=1, iters=12, n_seeds=96)
     i0, d0 = _search(vf, ix, Q[:nq], qoff, qids, s.k, itopk=32, width=1, iters=12, n_seeds=96)
