@@ -137,3 +137,50 @@ def test_c3_like_midscale_sampled_against_oracle():
     gi, gd = vf.search_exact(ix, Q[torch.from_numpy(sample).cuda()].contiguous(), qo, ql, s.k)
     eo, ed = ixo.search(w.queries[sample], qo, ql, s.k, force_scan=True)
     assert_exact(to_np(gi), to_np(gd), eo, ed, "c3-like exact")
+
+
+def test_c5_like_midscale_and_queries_sampled_against_oracle():
+    """DEEP-like structure (float32, dim 96, 10,000 labels, every query a 2-label AND with
+    intersection selectivity spread over decades) at one million vectors: bit-exact parity on
+    sampled graph-routed queries, tolerance on scan-routed ones, against the oracle's lazily
+    built graph rows; greedy and parallel policy."""
+    import oracle
+    import torch
+    from paper_2506_00812_amd import binding as vf
+    w = make_workload("c5", n=1_000_000, nq=4000)
+    s = w.spec
+    X = torch.from_numpy(w.vectors).cuda()
+    Q = torch.from_numpy(w.queries).cuda()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True)
+    for name in ("S", "O_HS", "O_LS", "M_HS", "M_LS"):
+        assert np.array_equal(ix.export(name), getattr(ixo, name)), name
+    params = dict(itopk=32, width=1, iters=12, n_seeds=1024)
+    ids, dists = vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, s.k, **params)
+    idp, ddp = vf.search_multi(ix, Q, w.qlabel_offsets, w.qlabel_ids, vf.AND_PARALLEL, s.k, **params)
+    torch.cuda.synchronize()
+    ids, dists, idp, ddp = to_np(ids), to_np(dists), to_np(idp), to_np(ddp)
+    S = ixo.S
+    smallest = np.array([min(S[w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]]]) for j in range(s.nq)])
+    rng = np.random.default_rng(9)
+    gq, sq = np.flatnonzero(smallest >= s.T), np.flatnonzero(smallest < s.T)
+    assert len(gq) > 100 and len(sq) > 100
+    sample = np.sort(np.concatenate([rng.choice(gq, size=20, replace=False), rng.choice(sq, size=16, replace=False)]))
+    qo = np.zeros(len(sample) + 1, dtype=np.int64)
+    np.cumsum(np.diff(w.qlabel_offsets)[sample], out=qo[1:])
+    ql = np.concatenate([w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]] for j in sample])
+    io, do, info = ixo.search(w.queries[sample], qo, ql, s.k, with_info=True, **params)
+    g = info["method"] == 2
+    assert g.sum() == 20
+    assert_exact(ids[sample][g], dists[sample][g], io[g], do[g], "c5-like greedy AND, graph")
+    assert_close_with_ties(ids[sample][~g], dists[sample][~g], io[~g], do[~g], 1e-4, "c5-like greedy AND, scan")
+    ip, dp = ixo.search_multi(w.queries[sample], qo, ql, oracle.AND_PARALLEL, s.k, **params)
+    assert_exact(idp[sample][g], ddp[sample][g], ip[g], dp[g], "c5-like parallel AND, graph")
+    assert_close_with_ties(idp[sample][~g], ddp[sample][~g], ip[~g], dp[~g], 1e-4, "c5-like parallel AND, scan")
+    # every returned id carries both labels (whole batch, through the exported posting lists)
+    M_HS, M_LS, O_HS, O_LS = ixo.M_HS, ixo.M_LS, ixo.O_HS, ixo.O_LS
+    for j in range(0, s.nq, 40):
+        for l in w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]]:
+            lst = M_HS[O_HS[l]:O_HS[l] + S[l]] if O_HS[l] >= 0 else M_LS[O_LS[l]:O_LS[l] + S[l]]
+            for res in (ids[j], idp[j]):
+                assert np.isin(res[res >= 0], lst).all()
