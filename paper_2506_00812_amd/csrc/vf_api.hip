@@ -514,6 +514,7 @@ static int env_int(const char *name, int dflt, int lo, int hi)
 static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
 static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
 static const int kScanValu = env_int("VF_SCAN_VALU", 1, 0, 2);      // float32 FMA scan kernel: 0 never, 1 for small batches, 2 always
+static const int kScan16 = env_int("VF_SCAN16", 1, 0, 1);          // 0: float32 search tiles keep the 32-row matrix-core kernel
 static const int kTileRows = env_int("VF_TILE_ROWS", 16, 1, 32);      // queries per scan tile
 
 struct ItemBuilder {
@@ -762,6 +763,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 // large batches keep the matrix-core kernel, which leaves the vector ALU to the beam search
                 const bool small_batch = kScanValu == 2 || (kScanValu == 1 && qrow.size() <= 256);
                 if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) launch_scan_valu(sp, (int)n_ls_items, ss);
+                else if (!exact && kScan16 && scan16_supported(ix->dtype, ix->dim, sp.tile_rows)) launch_scan16(sp, (int)n_ls_items, ss);
                 else launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
                 launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
                                   ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);

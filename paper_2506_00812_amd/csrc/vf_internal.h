@@ -72,6 +72,9 @@ struct ScanParams {
 };
 
 void launch_scan(int dtype, const ScanParams &p, int n_items, hipStream_t s);
+// float32, dim 96 / 128, <= 16 queries per tile, no self exclusion: 16-row matrix-core tiles
+bool scan16_supported(int dtype, int dim, int tile_rows);
+void launch_scan16(const ScanParams &p, int n_items, hipStream_t s);
 // float32, dim 96 / 128, <= 16 queries per tile, no self exclusion: FMAs with scalar query operands
 bool scan_valu_supported(int dtype, int dim, int tile_rows);
 void launch_scan_valu(const ScanParams &p, int n_items, hipStream_t s);

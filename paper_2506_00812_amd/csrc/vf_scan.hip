@@ -428,6 +428,197 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
     }
 }
 
+// float32 search tiles of <= 16 queries: the same selection around v_mfma_f32_16x16x4_f32, which
+// spends half the matrix-core time of a 32-row tile on them.  Lane (c = lane % 16, kq = lane / 16):
+//   A operand  row c of the query tile, the 16-byte chunks 4 s + kq (s = 0 .. chunks / 4 - 1);
+//   B operand  list entries c (column block 0) and 16 + c (block 1) of the group, the same chunks;
+//              the four components of a chunk feed four consecutive MFMAs, so the contraction
+//              index runs over (s, kq, component) on both operands alike;
+//   D          rows 4 kq + i (i = 0..3) x entry c of each column block.
+template <int NCP>
+__global__ __launch_bounds__(64) void scan_topk16_kernel(ScanParams p)
+{
+    extern __shared__ uint4 smem[];
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    constexpr int NCH = 2 * NCP, NS = NCH / 4, row_bytes = NCH * kChunkBytes, PC = 64;
+    static_assert(NCH % 4 == 0, "the chunk count must be a multiple of four");
+    const ScanItem it = p.items[blockIdx.x];
+    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5, c16 = lane & 15, kq = lane >> 4;
+    const int K = p.K, KS = K | 1, TR = p.tile_rows;   // TR <= 16
+
+    uint4 *qtile = smem;                                         // [NCH][TR]
+    uint64_t *pend = (uint64_t *)(smem + NCH * TR);              // [TR][PC]
+    uint64_t *best = pend + TR * PC;                             // [TR][KS]
+    int32_t *qrow_s = (int32_t *)(best + TR * KS);               // [32]
+    uint32_t *qnorm_s = (uint32_t *)(qrow_s + 32);               // [32]
+    uint32_t *pcnt = qnorm_s + 32;                               // [32]
+
+    if (lane < 32) { qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1; pcnt[lane] = 0; }
+    for (int i = lane; i < TR * KS; i += 64) best[i] = KEY_MAX;
+    __syncthreads();
+    {
+        // lane (r = n32, h) copies chunks h, h+2, ... of query row r and sums their squares
+        const int qr = n32 < TR ? qrow_s[n32] : -1;
+        const char *qp = (const char *)p.qsrc + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
+        float acc = 0.f;
+#pragma unroll
+        for (int c0 = 0; c0 < NCP; ++c0) {
+            const int c = 2 * c0 + h;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (qr >= 0) v = *(const uint4 *)(qp + c * kChunkBytes);
+            if (n32 < TR) qtile[c * TR + n32] = v;
+            const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
+        }
+        acc += __shfl_xor(acc, 32);
+        if (h == 0) qnorm_s[n32] = __float_as_uint(acc);
+    }
+    __syncthreads();
+
+    // this lane's four rows: 4 kq + i
+    float qn[4];
+    uint32_t thr[4];
+    uint32_t live = 0, and_rows = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 4 * kq + i;
+        qn[i] = __uint_as_float(qnorm_s[row]);
+        thr[i] = 0xFFFFFFFFu;
+        if (row < it.q_count) {
+            live |= 1u << i;
+            if (p.others_off != nullptr) {
+                const int qr = qrow_s[row];
+                if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << i;
+            }
+        }
+    }
+    const bool any_and = __any(and_rows != 0);
+    int pcv = 0;                  // state of tile row r, held by lane r
+    uint64_t row_kth = KEY_MAX;
+
+    auto drain = [&]() {
+        wave_lds_sync();
+        wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
+        if (lane < 32) pcnt[lane] = 0;
+        wave_lds_sync();
+        const uint32_t t = (uint32_t)(row_kth >> 32);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) thr[i] = __shfl(t, 4 * kq + i);
+    };
+
+    const int n_groups = (it.n + kGroup - 1) / kGroup;
+    // B registers of both column blocks; each block is refilled with the next group's chunks right
+    // after its own MFMAs have been issued
+    uint4 breg[2][NS];
+    float xn_next[2];
+    int32_t gid_next[2] = {-1, -1};
+    {
+        const uint4 *blk0 = p.xblk + it.group0 * (int64_t)(NCH * 32);
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+#pragma unroll
+            for (int sq = 0; sq < NS; ++sq) breg[cb][sq] = blk0[(4 * sq + kq) * 32 + cb * 16 + c16];
+            xn_next[cb] = ((const float *)p.xnorm)[it.group0 * kGroup + cb * 16 + c16];
+            if (any_and && cb * 16 + c16 < it.n) gid_next[cb] = p.map[it.map_off + it.entry0 + cb * 16 + c16];
+        }
+    }
+    for (int grp = 0; grp < n_groups; ++grp) {
+        const bool more = grp + 1 < n_groups;
+        const uint4 *nblk = p.xblk + (it.group0 + grp + 1) * (int64_t)(NCH * 32);
+        v4f acc[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) acc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
+        uint4 areg[NS];
+#pragma unroll
+        for (int sq = 0; sq < NS; ++sq) {
+            areg[sq] = make_uint4(0, 0, 0, 0);
+            if (c16 < TR) areg[sq] = qtile[(4 * sq + kq) * TR + c16];
+        }
+        const float xn[2] = {xn_next[0], xn_next[1]};
+        const int32_t gid[2] = {gid_next[0], gid_next[1]};
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+#pragma unroll
+            for (int sq = 0; sq < NS; ++sq) {
+                const uint4 a = areg[sq], b = breg[cb][sq];
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc[cb], 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc[cb], 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc[cb], 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc[cb], 0, 0, 0);
+            }
+            if (more) {
+#pragma unroll
+                for (int sq = 0; sq < NS; ++sq) breg[cb][sq] = nblk[(4 * sq + kq) * 32 + cb * 16 + c16];
+                xn_next[cb] = ((const float *)p.xnorm)[(it.group0 + grp + 1) * kGroup + cb * 16 + c16];
+                if (any_and && (grp + 1) * kGroup + cb * 16 + c16 < it.n)
+                    gid_next[cb] = p.map[it.map_off + it.entry0 + (grp + 1) * kGroup + cb * 16 + c16];
+            }
+        }
+
+        // phase 1 (branch-free): distances and threshold tests of this lane's 4 rows x 2 entries
+        uint32_t bitsv[8];
+        uint32_t pm = 0;   // bit cb * 4 + i
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const uint32_t col_ok = grp * kGroup + cb * 16 + c16 < it.n ? live : 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d = (qn[i] + xn[cb]) - 2.0f * acc[cb][i];
+                bitsv[cb * 4 + i] = __float_as_uint(fmaxf(d, 0.0f));
+                const uint32_t below = bitsv[cb * 4 + i] <= thr[i] ? 1u : 0u;
+                pm |= (below & (col_ok >> i) & 1u) << (cb * 4 + i);
+            }
+        }
+        if (any_and && pm != 0) {
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                if (((pm >> b) & 1u) && ((and_rows >> (b & 3)) & 1u)) {
+                    const int qr = qrow_s[4 * kq + (b & 3)];
+                    const int o_begin = p.others_off[qr], o_end = p.others_off[qr + 1];
+                    bool ok = true;
+                    for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(p.meta, p.others[o], gid[b >> 2]);
+                    if (!ok) pm &= ~(1u << b);
+                }
+            }
+        }
+        // phase 2: queue the candidates (slot from the row's LDS counter)
+        if (pm != 0) {
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                if ((pm >> b) & 1u) {
+                    const int row = 4 * kq + (b & 3);
+                    const int entry = it.entry0 + grp * kGroup + (b >> 2) * 16 + c16;
+                    const uint32_t slot = atomicAdd(&pcnt[row], 1u);
+                    pend[row * PC + slot] = ((uint64_t)bitsv[b] << 32) | (uint32_t)entry;
+                }
+            }
+        }
+        if (__any(pm != 0)) {
+            wave_lds_sync();
+            pcv = lane < 32 ? (int)pcnt[lane] : 0;
+        }
+        if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
+    }
+    __syncthreads();
+
+    for (int r = 0; r < it.q_count; ++r) {
+        if (lane >= K) continue;
+        const uint64_t key = best[r * KS + lane];
+        const bool none = key == KEY_MAX;
+        const uint32_t hi = (uint32_t)(key >> 32), idx = (uint32_t)key;
+        if (it.part_row < 0) {
+            const int64_t o = (int64_t)qrow_s[r] * K + lane;
+            p.out_ids[o] = none ? -1 : (int64_t)p.map[it.map_off + idx];
+            p.out_dists[o] = none ? __builtin_inff() : __uint_as_float(hi);
+        } else {
+            const int64_t o = (int64_t)(it.part_row + r) * K + lane;
+            p.res_idx[o] = none ? -1 : (int32_t)idx;
+            p.res_bits[o] = hi;
+        }
+    }
+}
+
 // float32 lists with few queries per tile.  The fp32 matrix core runs at only twice the VALU
 // FMA rate and a 32-row tile with a handful of queries wastes most of it, so below ~16 queries
 // per tile plain FMAs are faster: a lane holds one list entry's whole vector in registers (two
@@ -605,6 +796,20 @@ template <int DT> static void launch_scan_dt(const ScanParams &p, int n_items, h
         default: hipLaunchKernelGGL((scan_topk_kernel<DT, 0>), grid, block, lds, s, p); break;
         }
     }
+}
+
+bool scan16_supported(int dtype, int dim, int tile_rows)
+{
+    return dtype == 1 && (dim == 128 || dim == 96) && tile_rows <= 16;
+}
+
+// float32 search tiles of <= 16 queries (no self exclusion): see scan_topk16_kernel
+void launch_scan16(const ScanParams &p, int n_items, hipStream_t s)
+{
+    if (n_items <= 0) return;
+    const size_t lds = scan_lds_bytes(p);
+    if (p.dim == 128) hipLaunchKernelGGL((scan_topk16_kernel<16>), dim3(n_items), dim3(64), lds, s, p);
+    else hipLaunchKernelGGL((scan_topk16_kernel<12>), dim3(n_items), dim3(64), lds, s, p);
 }
 
 bool scan_valu_supported(int dtype, int dim, int tile_rows)
