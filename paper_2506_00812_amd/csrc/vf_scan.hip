@@ -436,7 +436,7 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
 //              index runs over (s, kq, component) on both operands alike;
 //   D          rows 4 kq + i (i = 0..3) x entry c of each column block.
 template <int NCP>
-__global__ __launch_bounds__(64) void scan_topk16_kernel(ScanParams p)
+__global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
     typedef float v4f __attribute__((ext_vector_type(4)));
