@@ -161,8 +161,8 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * events on the caller's stream and has the graph kernel record, per query, how
  * many distances it computed, rows it expanded and predicate tests it made.
  * vf_profile_read waits for the last profiled call and reports it, together with
- * the duration sums over all calls since vf_profile_enable(index, 1).  (A profiled
- * call waits for the previous profiled call's kernels before it launches its own.)
+ * the duration sums over all calls since vf_profile_enable(index, 1).  (Up to 64 profiled
+ * calls can be outstanding; a further one first waits for the oldest.)
  * on = 1 leaves the launch schedule as it is (IVF-BFS runs on a second stream beside
  * IVF-Graph, so the two intervals overlap and each kernel shares the chip); on = 2 also
  * puts every launch on the caller's stream, one after the other, so each interval is

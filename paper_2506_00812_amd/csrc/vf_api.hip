@@ -104,7 +104,12 @@ struct vf_index {
     std::vector<int32_t> multi_qids;
     // profiling
     bool profiling = false, prof_valid = false;
-    hipEvent_t prof_ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};  // scan begin/end, graph begin, seeds end, beam end
+    // a ring of event sets (scan begin/end, graph begin, seeds end, beam end), one set per profiled call:
+    // a call never waits for an earlier one unless kProfRing calls are still unread
+    static constexpr int kProfRing = 64;
+    hipEvent_t prof_ring[kProfRing][5] = {};
+    hipEvent_t *prof_ev = prof_ring[0];   // the set of the call being issued
+    int prof_next = 0, prof_unfolded = 0; // next ring slot; recorded sets whose durations are not in the sums yet
     // the scan path runs beside the graph path on a second stream of the same (default) priority
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -113,7 +118,6 @@ struct vf_index {
     vf_profile prof{};
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
-    bool prof_folded = true;  // the last call's durations are already in the sums
     Staging stage[2];
     int stage_next = 0;
     Routed routed;
@@ -136,8 +140,9 @@ static void free_index(vf_index *ix)
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
                       &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
-    for (hipEvent_t e : ix->prof_ev)
-        if (e) (void)hipEventDestroy(e);
+    for (auto &set : ix->prof_ring)
+        for (hipEvent_t e : set)
+            if (e) (void)hipEventDestroy(e);
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
     if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
     if (ix->side) { (void)hipStreamSynchronize(ix->side); (void)hipStreamDestroy(ix->side); }
@@ -369,19 +374,22 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
 // ---------------------------------------------------------------- routing
 
 // Add the durations of the last profiled call to the running sums (waits for it).
-static int fold_profile(vf_index *ix)
+// Adds the durations of the oldest `count` unread profiled calls to the sums (waits for them).
+static int fold_profile(vf_index *ix, int count)
 {
-    if (!ix->prof_valid || ix->prof_folded) return VF_OK;
-    VF_HIP(hipEventSynchronize(ix->prof_ev[4]));
-    VF_HIP(hipEventSynchronize(ix->prof_ev[1]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.scan_ms, ix->prof_ev[0], ix->prof_ev[1]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.seed_ms, ix->prof_ev[2], ix->prof_ev[3]));
-    VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ix->prof_ev[3], ix->prof_ev[4]));
-    ix->prof_scan_sum += ix->prof.scan_ms;
-    ix->prof_seed_sum += ix->prof.seed_ms;
-    ix->prof_beam_sum += ix->prof.beam_ms;
-    ix->prof_calls++;
-    ix->prof_folded = true;
+    for (; count > 0 && ix->prof_unfolded > 0; --count, --ix->prof_unfolded) {
+        const int slot = (ix->prof_next - ix->prof_unfolded + 2 * vf_index::kProfRing) % vf_index::kProfRing;
+        hipEvent_t *ev = ix->prof_ring[slot];
+        VF_HIP(hipEventSynchronize(ev[4]));
+        VF_HIP(hipEventSynchronize(ev[1]));
+        VF_HIP(hipEventElapsedTime(&ix->prof.scan_ms, ev[0], ev[1]));
+        VF_HIP(hipEventElapsedTime(&ix->prof.seed_ms, ev[2], ev[3]));
+        VF_HIP(hipEventElapsedTime(&ix->prof.beam_ms, ev[3], ev[4]));
+        ix->prof_scan_sum += ix->prof.scan_ms;
+        ix->prof_seed_sum += ix->prof.seed_ms;
+        ix->prof_beam_sum += ix->prof.beam_ms;
+        ix->prof_calls++;
+    }
     return VF_OK;
 }
 
@@ -680,7 +688,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         const bool prof = ix->profiling;
         if (prof) {
-            if ((rc = fold_profile(ix)) != VF_OK) return rc;
+            if (ix->prof_unfolded == vf_index::kProfRing && (rc = fold_profile(ix, 1)) != VF_OK) return rc;
+            ix->prof_ev = ix->prof_ring[ix->prof_next];
             if ((rc = ix->counters.reserve((size_t)nq * 16)) != VF_OK) return rc;
             VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 16, s));
             vf_profile &pf = ix->prof;
@@ -794,7 +803,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
         if (prof) {
             VF_HIP(hipEventRecord(ix->prof_ev[4], s));
-            ix->prof_valid = true; ix->prof_folded = false;
+            ix->prof_valid = true;
+            ix->prof_next = (ix->prof_next + 1) % vf_index::kProfRing;
+            ++ix->prof_unfolded;
         }
         if (forked) VF_HIP(hipStreamWaitEvent(s, ix->ev_join, 0));
         VF_HIP(hipGetLastError());
@@ -966,12 +977,13 @@ extern "C" int vf_profile_enable(vf_index *ix, int on)
 {
     VF_REQUIRE(ix != nullptr, "index is NULL");
     if (on)
-        for (hipEvent_t &e : ix->prof_ev)
-            if (!e) VF_HIP(hipEventCreate(&e));
+        for (auto &set : ix->prof_ring)
+            for (hipEvent_t &e : set)
+                if (!e) VF_HIP(hipEventCreate(&e));
     ix->profiling = on != 0;
     ix->prof_serial = on == 2;
     ix->prof_valid = false;
-    ix->prof_folded = true;
+    ix->prof_next = 0; ix->prof_unfolded = 0;
     ix->prof_scan_sum = ix->prof_seed_sum = ix->prof_beam_sum = 0;
     ix->prof_calls = 0;
     return VF_OK;
@@ -981,7 +993,7 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
 {
     VF_REQUIRE(ix && out, "NULL argument");
     VF_REQUIRE(ix->prof_valid, "no profiled vf_search call to report");
-    int rc = fold_profile(ix);
+    int rc = fold_profile(ix, vf_index::kProfRing);
     if (rc != VF_OK) return rc;
     vf_profile pf = ix->prof;
     pf.scan_ms_sum = ix->prof_scan_sum; pf.seed_ms_sum = ix->prof_seed_sum; pf.beam_ms_sum = ix->prof_beam_sum;
