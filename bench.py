@@ -61,6 +61,17 @@ def committed_traffic(kernel, workload, params):
     return int(round((float(vals[0]) + float(vals[1])) * 1e9))
 
 
+def committed_params(workload):
+    """(itopk, width, iters, n_seeds) the committed counter summary was taken at, or None."""
+    import re
+    try:
+        text = open(os.path.join(ROOT, "profiles", f"bench_{workload}.txt")).read()
+    except OSError:
+        return None
+    m = re.search(r"params = \{'itopk': (\d+), 'width': (\d+), 'iters': (\d+), 'n_seeds': (\d+)\}", text)
+    return tuple(int(g) for g in m.groups()) if m else None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -186,6 +197,14 @@ def main():
         return max(ok, key=lambda t: t[2]) if ok else None
 
     p90, p99 = best(0.90), best(0.99)
+    # several settings are within measurement noise of one another; among those within 3 % of the
+    # fastest, the one the committed rocprofv3 counters were taken at is preferred, so that the
+    # `traffic` figure applies to the run
+    pref = committed_params(s.name)
+    if p90 is not None and pref is not None:
+        for t in table:
+            if t[0] == pref and t[1] >= 0.90 and t[2] >= 0.97 * p90[2]:
+                p90 = t
     headline = p90 or max(table, key=lambda t: t[1])
 
     # ---- timed region: exactly K steps at the recall >= 0.90 operating point, profiling events on
@@ -233,7 +252,7 @@ def main():
     pfs = ix.profile_read()
     alone_ms = {"beam_kernel": pfs["beam_ms_sum"] / pfs["calls"],
                 ("seed_mfma_kernel" if pfs["seeds_on_matrix_cores"] else "seed_dist_kernel"): pfs["seed_ms_sum"] / pfs["calls"],
-                "scan_topk_kernel": pfs["scan_ms_sum"] / pfs["calls"]}
+                ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel")[pfs["scan_kernel"]]: pfs["scan_ms_sum"] / pfs["calls"]}
     ix.profile_enable(False)
 
     eb = 1 if s.dtype == "uint8" else 4
@@ -244,6 +263,7 @@ def main():
     # the matrix cores) the best approximate seeds it re-scores with the ordered distance
     gathered = pf["beam_scored"] - pf["seed_pairs"] + pf["seed_rescored"]
     seed_kernel = "seed_mfma_kernel" if pf["seeds_on_matrix_cores"] else "seed_dist_kernel"
+    scan_kernel = ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel")[pf["scan_kernel"]]
     kernels = {
         "beam_kernel": {
             "ms": beam_avg_ms, "bound": "hbm",
@@ -255,7 +275,7 @@ def main():
             "bytes": pf["seed_tile_seeds"] * (vec_bytes + 4) + n_gq * vec_bytes + pf["seed_pairs"] * 4,
             # matrix cores: one multiply-add per element of q.x; vector ALU: one subtract + one fused multiply-add
             "flops": (2 if pf["seeds_on_matrix_cores"] else 3) * pf["seed_pairs"] * s.dim},
-        "scan_topk_kernel": {
+        scan_kernel: {
             "ms": scan_avg_ms, "bound": "hbm",
             "bytes": pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),
             "flops": 2 * pf["scan_pairs"] * s.dim},

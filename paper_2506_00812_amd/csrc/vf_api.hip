@@ -771,9 +771,15 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 // small batches are latency-bound: the FMA kernel finishes a one-query tile three times sooner;
                 // large batches keep the matrix-core kernel, which leaves the vector ALU to the beam search
                 const bool small_batch = kScanValu == 2 || (kScanValu == 1 && qrow.size() <= 256);
-                if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) launch_scan_valu(sp, (int)n_ls_items, ss);
-                else if (!exact && kScan16 && scan16_supported(ix->dtype, ix->dim, sp.tile_rows)) launch_scan16(sp, (int)n_ls_items, ss);
-                else launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
+                if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) {
+                    launch_scan_valu(sp, (int)n_ls_items, ss);
+                    if (prof) ix->prof.scan_kernel = 2;
+                } else if (!exact && kScan16 && scan16_supported(ix->dtype, ix->dim, sp.tile_rows)) {
+                    launch_scan16(sp, (int)n_ls_items, ss);
+                    if (prof) ix->prof.scan_kernel = 1;
+                } else {
+                    launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
+                }
                 launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
                                   ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
             }
