@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=64)
+    ap.add_argument("--gt-sample", type=int, default=0,
+                    help="measure recall on this many randomly chosen queries (ground truth of the full set "
+                         "of a 10M-vector workload would take many minutes)")
     ap.add_argument("--multi", action="store_true",
                     help="also measure two-label AND (greedy and parallel policy) and OR queries on the same index")
     ap.add_argument("--latency", action="store_true",
@@ -133,6 +136,7 @@ def main():
     vf.load_library()
 
     t0 = time.time()
+    log(f"[bench] generating workload {args.workload} ...")
     w = make_workload(args.workload, n=args.n, nq=args.nq, T=args.T)
     s = w.spec
     log(f"[bench] workload {s.name}: n={s.n} dim={s.dim} {s.dtype} labels={s.n_labels} T={s.T} R={s.graph_degree} "
@@ -140,6 +144,7 @@ def main():
     X = torch.from_numpy(w.vectors).cuda()
     Q = torch.from_numpy(w.queries).cuda()
     t0 = time.time()
+    log("[bench] building the index ...")
     ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
     torch.cuda.synchronize()
     build_s = time.time() - t0
@@ -157,10 +162,22 @@ def main():
     torch.cuda.synchronize()
     t0 = time.time()
     ix.profile_enable(True)
-    gt_ids, _ = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, k)
+    gt_rows = None        # recall is measured on these query rows (all of them unless --gt-sample)
+    if args.gt_sample and args.gt_sample < s.nq:
+        gt_rows = np.sort(np.random.default_rng(97531).choice(s.nq, size=args.gt_sample, replace=False))
+        cnt = np.diff(w.qlabel_offsets)[gt_rows]
+        sub_off = np.zeros(len(gt_rows) + 1, dtype=np.int64)
+        np.cumsum(cnt, out=sub_off[1:])
+        sub_ids = np.concatenate([w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]] for j in gt_rows])
+        gt_ids, _ = vf.search_exact(ix, Q[torch.from_numpy(gt_rows).cuda()].contiguous(), sub_off, sub_ids, k)
+    else:
+        gt_ids, _ = vf.search_exact(ix, Q, w.qlabel_offsets, w.qlabel_ids, k)
     gt = gt_ids.cpu().numpy()
     pfe = ix.profile_read()
     ix.profile_enable(False)
+
+    def recall_of(found):
+        return recall_at_k(found if gt_rows is None else found[gt_rows], gt)
     # the dense invocations of the contraction kernel: ground truth (hundreds of queries share the
     # popular lists) and the per-list kNN self-joins of the index build (every vertex is a query)
     flops_per_pair = 2 * s.dim
@@ -182,11 +199,15 @@ def main():
 
     # ---- pick the operating points: cheapest candidates reaching recall 0.90 and 0.99
     table = []
-    for params in CANDIDATES:
+    cands = CANDIDATES
+    if s.n > 2_000_000:   # long lists need more seeds: a coarser grid reaching further
+        cands = sorted({(itopk, 1, iters, ns) for itopk in (32, 64) for iters in (8, 16, 32)
+                        for ns in (2048, 4096, 8192, 16384, 32768)}, key=lambda c: c[3] + c[2] * 32)
+    for params in cands:
         if params[1] * s.graph_degree > 128:
             continue
         ms = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, params, 3, 1, out_ids, out_dists)
-        rec = recall_at_k(out_ids.cpu().numpy(), gt)
+        rec = recall_of(out_ids.cpu().numpy())
         table.append((params, rec, s.nq / ms * 1e3))
         if args.sweep:
             log(f"[sweep] itopk={params[0]:3d} width={params[1]} iters={params[2]:2d} n_seeds={params[3]:5d} "
@@ -235,7 +256,7 @@ def main():
     scan_avg_ms = pf["scan_ms_sum"] / pf["calls"]
     seed_avg_ms = pf["seed_ms_sum"] / pf["calls"]
     ix.profile_enable(False)
-    recall_head = recall_at_k(out_ids.cpu().numpy(), gt)
+    recall_head = recall_of(out_ids.cpu().numpy())
 
     # ---- the same K steps once more with the launches serialised on one stream: in the timed
     # region the IVF-BFS kernel runs beside the IVF-Graph kernels and each shares the chip;

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <ctime>
 #include <new>
 #include <numeric>
 
@@ -322,7 +323,19 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
             if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
             if ((rc = cand_idx.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
             if ((rc = cand_dist.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
+            // VF_BUILD_PROGRESS=1: a line on stderr every few seconds (index builds of 10^7 vectors take minutes)
+            const char *prog_env = getenv("VF_BUILD_PROGRESS");
+            const bool progress = prog_env && prog_env[0] == '1';
+            time_t last_print = time(nullptr);
+            size_t done = 0;
             for (int32_t l : ix->graph_labels) {
+                if (progress && time(nullptr) - last_print >= 10) {
+                    fprintf(stderr, "[vf_build_index] %zu of %zu label graphs built, next list holds %d vectors\n", done,
+                            ix->graph_labels.size(), ix->S[(size_t)l]);
+                    fflush(stderr);
+                    last_print = time(nullptr);
+                }
+                ++done;
                 launch_bitset_fill(ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)l], ix->S[(size_t)l],
                                    ix->d_bitsets.as<uint32_t>() + (int64_t)ix->hs_slot[(size_t)l] * ix->bitset_words, s);
                 if ((rc = build_graph_for_label(ix, l, K, cand_idx, cand_dist, d_items, s)) != VF_OK) return rc;
