@@ -280,9 +280,9 @@ def main():
     vec_bytes = s.dim * eb
     n_gq = pf["n_graph_queries"]
     # algorithmic work of each kernel of one step (one vf_search call)
-    # distances whose vector the beam kernel gathers itself: children, and (when the seeds went through
-    # the matrix cores) the best approximate seeds it re-scores with the ordered distance
-    gathered = pf["beam_scored"] - pf["seed_pairs"] + pf["seed_rescored"]
+    # distances whose vector the beam kernel gathers itself (counted by the kernel): children, and, when
+    # float32 seeds went through the matrix cores, the best approximate seeds it re-scores
+    gathered = pf["beam_gathered"]
     seed_kernel = "seed_mfma_kernel" if pf["seeds_on_matrix_cores"] else "seed_dist_kernel"
     scan_kernel = ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel")[pf["scan_kernel"]]
     kernels = {
@@ -293,6 +293,8 @@ def main():
             "flops": 3 * gathered * s.dim},
         seed_kernel: {
             "ms": seed_avg_ms, "bound": "mfma" if pf["seeds_on_matrix_cores"] else "alu",
+            "peak": (FP32_VECTOR_PEAK_TFLOPS if s.dtype == "float32" else 5000.0) if pf["seeds_on_matrix_cores"]
+                    else FP32_VECTOR_PEAK_TFLOPS,
             "bytes": pf["seed_tile_seeds"] * (vec_bytes + 4) + n_gq * vec_bytes + pf["seed_pairs"] * 4,
             # matrix cores: one multiply-add per element of q.x; vector ALU: one subtract + one fused multiply-add
             "flops": (2 if pf["seeds_on_matrix_cores"] else 3) * pf["seed_pairs"] * s.dim},
@@ -305,8 +307,9 @@ def main():
     kd = kernels[dom]
     if kd["bound"] == "hbm":
         achieved, peak, unit = kd["bytes"] / (kd["ms"] * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
-    else:   # fp32 vector ALU and fp32 dense MFMA have the same published peak
-        achieved, peak, unit = kd["flops"] / (kd["ms"] * 1e-3) / 1e12, FP32_VECTOR_PEAK_TFLOPS, "TFLOP/s"
+    else:   # fp32 vector ALU and fp32 dense MFMA have the same published peak; int8 MFMA 5 POP/s
+        achieved, peak, unit = kd["flops"] / (kd["ms"] * 1e-3) / 1e12, kd.get("peak", FP32_VECTOR_PEAK_TFLOPS), \
+            ("TFLOP/s" if s.dtype == "float32" else "TOP/s")
     roofline = {
         "kernel": dom, "bound": kd["bound"], "achieved": round(achieved, 2), "peak": peak, "unit": unit,
         "frac": round(achieved / peak, 4),

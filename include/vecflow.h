@@ -188,6 +188,7 @@ typedef struct vf_profile {
     int64_t seeds_on_matrix_cores;     /* 1: float32 seeds were scored on MFMA (approximate) and re-ranked by the beam kernel */
     int64_t seed_rescored;             /* ordered distances computed for that re-ranking                                 */
     int64_t seed_fallbacks;            /* queries whose proof failed and that scored every seed themselves               */
+    int64_t beam_gathered;             /* distances whose vector the beam kernel fetched itself (children, re-ranked seeds, seeds when not scored densely) */
     int64_t scan_kernel;               /* IVF-BFS kernel of the call: 0 = 32-row matrix-core tiles, 1 = 16-row matrix-core tiles, 2 = FMA */
 } vf_profile;
 

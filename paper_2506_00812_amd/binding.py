@@ -37,7 +37,8 @@ class VfProfile(C.Structure):
                [(n, C.c_int64) for n in ("nq", "n_scan_queries", "n_graph_queries", "n_scan_items",
                                          "scan_list_entries", "scan_pairs", "beam_scored", "beam_expanded",
                                          "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds",
-                                         "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "scan_kernel")]
+                                         "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "beam_gathered",
+                                         "scan_kernel")]
 
 
 class VecflowError(RuntimeError):

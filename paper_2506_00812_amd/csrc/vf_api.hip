@@ -347,13 +347,15 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
                 const char *ex = getenv("VF_SEED_EXACT");
                 if (!(ex && ex[0] == '1')) {
                     if ((rc = ix->d_xnorm_all.reserve((size_t)n * 4)) != VF_OK) return rc;
-                    launch_row_norms(ix->X, ix->dim, n, ix->d_xnorm_all.as<float>(), s);
-                    std::vector<float> hn((size_t)n);
-                    VF_HIP(hipMemcpyAsync(hn.data(), ix->d_xnorm_all.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
-                    VF_HIP(hipStreamSynchronize(s));
+                    launch_row_norms(ix->dtype, ix->X, ix->dim, n, ix->d_xnorm_all.as<uint32_t>(), s);
                     float mx = 0.f;
                     bool finite = true;
-                    for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+                    if (ix->dtype == VF_F32) {
+                        std::vector<float> hn((size_t)n);
+                        VF_HIP(hipMemcpyAsync(hn.data(), ix->d_xnorm_all.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+                        VF_HIP(hipStreamSynchronize(s));
+                        for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+                    }
                     if (finite) {   // a table with NaN or overflowing norms keeps the exact kernel
                         ix->xn_max = mx;
                         // |approximation - ordered distance| <= 300 u (|q|^2 + |x|^2), u = 2^-24 (dot product of
@@ -649,7 +651,10 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) &&
                                  (uint64_t)n_gq * (uint64_t)ns_stride * 4 <= ((uint64_t)8 << 30);
         // matrix-core scoring (approximate, re-ranked by the beam kernel) where the beam kernel supports it
-        const bool seeds_mfma = dense_seeds && ix->seed_mfma && !r.any_and && itopk <= 48 && n_seeds > 64;
+        // uint8: the matrix cores give the exact integer distances, nothing else changes.
+        // float32: approximations, re-ranked by the beam kernel, where that kernel supports it.
+        const bool seeds_mfma = dense_seeds && ix->seed_mfma && n_seeds > 64 &&
+                                (ix->dtype == VF_U8 || (!r.any_and && itopk <= 48));
         if (dense_seeds) {
             const size_t tile_q = seeds_mfma ? 32 : 64;
             for (size_t i = 0; i < n_gq;) {
@@ -703,8 +708,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (prof) {
             if (ix->prof_unfolded == vf_index::kProfRing && (rc = fold_profile(ix, 1)) != VF_OK) return rc;
             ix->prof_ev = ix->prof_ring[ix->prof_next];
-            if ((rc = ix->counters.reserve((size_t)nq * 16)) != VF_OK) return rc;
-            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 16, s));
+            if ((rc = ix->counters.reserve((size_t)nq * 16 + 16)) != VF_OK) return rc;   // per-query counters + one 64-bit sum
+            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 16 + 16, s));
             vf_profile &pf = ix->prof;
             pf = vf_profile{};
             pf.nq = nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)qrow.size();
@@ -736,6 +741,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             bp.hash_bits = beam_hb;
             bp.out_ids = out_ids; bp.out_dists = out_dists;
             bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
+            bp.gathered = prof ? (unsigned long long *)(ix->counters.as<char>() + (size_t)nq * 16) : nullptr;
             bp.dseed = nullptr; bp.ns_stride = ns_stride;
         }
         auto run_seeds = [&]() -> int {
@@ -749,10 +755,12 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                     sd.dseed = ix->dseed.as<uint32_t>();
                     if (seeds_mfma) {
                         sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
-                        sd.xnorm_all = ix->d_xnorm_all.as<float>();
-                        launch_seed_mfma(sd, (int)tiles.size(), s);
-                        bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
-                        bp.seed_keep = std::min(64, itopk + kSeedMargin);
+                        sd.xnorm_all = ix->d_xnorm_all.as<uint32_t>();
+                        launch_seed_mfma(ix->dtype, sd, (int)tiles.size(), s);
+                        if (ix->dtype == VF_F32) {
+                            bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
+                            bp.seed_keep = std::min(64, itopk + kSeedMargin);
+                        }
                     } else {
                         sd.max_chunks = ns_stride / kSeedChunk;
                         launch_seed_dist(ix->dtype, sd, (int)tiles.size(), s);
@@ -1027,6 +1035,9 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
             pf.seed_rescored += m >> 8;
         }
         if (per_query) memcpy(per_query, cn.data(), cn.size() * 4);
+        unsigned long long g = 0;
+        VF_HIP(hipMemcpy(&g, ix->counters.as<char>() + (size_t)pf.nq * 16, 8, hipMemcpyDeviceToHost));
+        pf.beam_gathered = (int64_t)g;
     } catch (const std::bad_alloc &) {
         set_error("out of host memory");
         return VF_ENOMEM;

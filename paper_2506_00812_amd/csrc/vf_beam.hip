@@ -146,6 +146,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     TopM<E> top;
     top.init(itopk);
     int n_scored = 0, n_expanded = 0, n_tested = 0;  // work counters (uniform across the wave)
+    int n_gathered = 0;                              // distances whose vector this wave fetched itself
 
     // Offer the candidates held one per lane (valid lanes, distance bits, local id) to the list.
     auto offer_to = [&](auto &list, bool valid, uint32_t bits, int c) {
@@ -163,6 +164,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     // Distances of cand[0..cnt) (eight at a time, one per team) into cand_d.
     auto score = [&](int cnt) {
         n_scored += cnt;
+        n_gathered += cnt;
 #pragma unroll 2
         for (int r0 = 0; r0 < cnt; r0 += 8) {
             const int my = r0 + team;
@@ -399,6 +401,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     if (p.counters != nullptr && lane == 0) {
         int32_t *cn = p.counters + (int64_t)qi * 4;
         cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2 + seed_fallback + (n_rescored << 8);
+        if (p.gathered != nullptr) atomicAdd(p.gathered, (unsigned long long)n_gathered);
     }
 
     // ---- first k entries (k <= 64: register 0), local -> global through M

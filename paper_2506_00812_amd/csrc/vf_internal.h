@@ -99,6 +99,7 @@ struct BeamParams {
     int64_t *out_ids;
     float *out_dists;
     int32_t *counters; // optional [nq][4]: distances computed, rows expanded, predicate tests, method
+    unsigned long long *gathered; // optional: sum over queries of the distances whose vector the kernel fetched itself
     const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel / seed_mfma_kernel
     int32_t ns_stride;
     // dseed holds MFMA approximations (float32 only): the kernel re-scores the best of them with the
@@ -124,18 +125,18 @@ struct SeedParams {
     LabelMeta meta;
     int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = seed chunks per tile (kSeedChunk or kSeedMfmaChunk seeds each)
     uint32_t *dseed;
-    const float *xnorm_all;  // [n] squared norms of the rows of X (seed_mfma_kernel only)
+    const uint32_t *xnorm_all;  // [n] squared norms of the rows of X, float bits / int32 of the -128 shifted bytes (seed_mfma_kernel only)
 };
 
 constexpr int kSeedMfmaChunk = 128;  // seeds per wave of the MFMA seed kernel (four 32-seed groups)
 
 bool seed_dist_supported(int dtype, int dim);
 void launch_seed_dist(int dtype, const SeedParams &p, int n_tiles, hipStream_t s);
-// float32 only: approximate distances |q|^2 + |x|^2 - 2 q.x through the matrix cores
+// |q|^2 + |x|^2 - 2 q.x through the matrix cores: approximate for float32, exact for uint8
 bool seed_mfma_supported(int dtype, int dim);
-void launch_seed_mfma(const SeedParams &p, int n_tiles, hipStream_t s);
-// squared norms of all rows of a float32 table
-void launch_row_norms(const void *X, int32_t dim, int64_t n, float *out, hipStream_t s);
+void launch_seed_mfma(int dtype, const SeedParams &p, int n_tiles, hipStream_t s);
+// squared norms of all rows of a table (float bits, or int32 of the -128 shifted bytes)
+void launch_row_norms(int dtype, const void *X, int32_t dim, int64_t n, uint32_t *out, hipStream_t s);
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype);
 void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s);

@@ -108,14 +108,19 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 // itself).  One wave: a tile of <= 32 queries (A operand, staged in LDS) against kSeedMfmaChunk
 // seeds in groups of 32 (B operand gathered row-wise from X: lane (v, h) reads the 16-byte
 // chunks 2c + h of seed v, the operand layout of v_mfma_f32_32x32x2_f32).
+// uint8 data go through the same kernel with v_mfma_i32_32x32x32_i8 on the vectors shifted by -128
+// (the shift cancels in q - x): the int32 result is the exact distance, so nothing is approximate
+// there and the rows of dseed are used as they are.
 typedef float v16f_seed __attribute__((ext_vector_type(16)));
+typedef int v16i_seed __attribute__((ext_vector_type(16)));
+typedef int v4i_seed __attribute__((ext_vector_type(4)));
 
-template <int NCP>
+template <int DT, int NCP>
 __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 {
     constexpr int NCH = 2 * NCP, row_bytes = NCH * kChunkBytes, NG = kSeedMfmaChunk / 32;
     __shared__ uint4 qtile[NCH * 32];
-    __shared__ float qnorm_s[32];
+    __shared__ uint32_t qnorm_s[32];   // float bits / int
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
     const int tile = blockIdx.x / p.max_chunks, chunk = blockIdx.x % p.max_chunks;
     const SeedTile t = p.tiles[tile];
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 
     // global ids and norms of this lane's seed in each group (issued first: the longest dependent chain)
     int gid[NG];
-    float xn[NG];
+    uint32_t xn[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const int j = j0 + g * 32 + n32;
@@ -141,22 +146,41 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
     {
         const int qr = n32 < t.q_count ? p.gq_query[t.gq_begin + n32] : -1;
         const char *qp = (const char *)p.Q + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
-        float acc = 0.f;
+        float facc = 0.f;
+        int iacc = 0;
 #pragma unroll
         for (int c0 = 0; c0 < NCP; ++c0) {
             const int c = 2 * c0 + h;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (qr >= 0) v = *(const uint4 *)(qp + c * kChunkBytes);
+            if (qr >= 0) {
+                v = *(const uint4 *)(qp + c * kChunkBytes);
+                if (DT == 0) { v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u; }
+            }
             qtile[c * 32 + n32] = v;
-            const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
+            for (int i = 0; i < 4; ++i) {
+                if (DT == 0) {
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const int e = (int)(int8_t)(w[i] >> (8 * bb));
+                        iacc += e * e;
+                    }
+                } else {
+                    facc += __uint_as_float(w[i]) * __uint_as_float(w[i]);
+                }
+            }
         }
-        acc += __shfl_xor(acc, 32);
-        if (h == 0) qnorm_s[n32] = acc;
+        if (DT == 0) {
+            iacc += __shfl_xor(iacc, 32);
+            if (h == 0) qnorm_s[n32] = (uint32_t)iacc;
+        } else {
+            facc += __shfl_xor(facc, 32);
+            if (h == 0) qnorm_s[n32] = __float_as_uint(facc);
+        }
     }
     __syncthreads();
-    float qn[16];
+    uint32_t qn[16];
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) qn[jj] = qnorm_s[8 * (jj >> 2) + 4 * h + (jj & 3)];
 
@@ -177,26 +201,46 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 #pragma unroll
             for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
         }
-        v16f_seed acc;
+        uint32_t bits[16];
+        if constexpr (DT == 0) {
+            v16i_seed acc;
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
+            for (int jj = 0; jj < 16; ++jj) acc[jj] = 0;
 #pragma unroll
-        for (int cp = 0; cp < NCP; ++cp) {
-            const uint4 a = qtile[(2 * cp + h) * 32 + n32];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b[cp].x), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b[cp].y), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b[cp].z), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b[cp].w), acc, 0, 0, 0);
+            for (int cp = 0; cp < NCP; ++cp) {
+                const uint4 a = qtile[(2 * cp + h) * 32 + n32];
+                uint4 bb = b[cp];
+                bb.x ^= 0x80808080u; bb.y ^= 0x80808080u; bb.z ^= 0x80808080u; bb.w ^= 0x80808080u;
+                const v4i_seed av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+                const v4i_seed bv = {(int)bb.x, (int)bb.y, (int)bb.z, (int)bb.w};
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) bits[jj] = (uint32_t)((int)qn[jj] + (int)xn[g] - 2 * acc[jj]);
+        } else {
+            v16f_seed acc;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
+#pragma unroll
+            for (int cp = 0; cp < NCP; ++cp) {
+                const uint4 a = qtile[(2 * cp + h) * 32 + n32];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b[cp].x), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b[cp].y), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b[cp].z), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b[cp].w), acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const float d = (__uint_as_float(qn[jj]) + __uint_as_float(xn[g])) - 2.0f * acc[jj];
+                bits[jj] = __float_as_uint(fmaxf(d, 0.0f));
+            }
         }
         const int j = j0 + g * 32 + n32;
         if (j < ns) {
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) {
                 const int row = 8 * (jj >> 2) + 4 * h + (jj & 3);
-                if (row < t.q_count) {
-                    const float d = (qn[jj] + xn[g]) - 2.0f * acc[jj];
-                    p.dseed[(int64_t)(t.gq_begin + row) * p.ns_stride + j] = __float_as_uint(fmaxf(d, 0.0f));
-                }
+                if (row < t.q_count) p.dseed[(int64_t)(t.gq_begin + row) * p.ns_stride + j] = bits[jj];
             }
         }
     }
@@ -204,35 +248,57 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 
 bool seed_mfma_supported(int dtype, int dim)
 {
-    return dtype == 1 && (dim == 96 || dim == 128);
+    return dtype == 1 ? (dim == 96 || dim == 128) : (dim == 128 || dim == 192);
 }
 
-void launch_seed_mfma(const SeedParams &p, int n_tiles, hipStream_t s)
+void launch_seed_mfma(int dtype, const SeedParams &p, int n_tiles, hipStream_t s)
 {
     if (n_tiles <= 0) return;
-    const unsigned grid = (unsigned)n_tiles * (unsigned)p.max_chunks;
-    if (p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<16>), dim3(grid), dim3(64), 0, s, p);
-    else if (p.dim == 96) hipLaunchKernelGGL((seed_mfma_kernel<12>), dim3(grid), dim3(64), 0, s, p);
+    const dim3 grid((unsigned)n_tiles * (unsigned)p.max_chunks), block(64);
+    if (dtype == 1 && p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<1, 16>), grid, block, 0, s, p);
+    else if (dtype == 1 && p.dim == 96) hipLaunchKernelGGL((seed_mfma_kernel<1, 12>), grid, block, 0, s, p);
+    else if (dtype == 0 && p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<0, 4>), grid, block, 0, s, p);
+    else if (dtype == 0 && p.dim == 192) hipLaunchKernelGGL((seed_mfma_kernel<0, 6>), grid, block, 0, s, p);
 }
 
-// One thread per row, elements in ascending order.
-__global__ void row_norm_kernel(const float *X, int32_t dim, int64_t n, float *out)
+// One thread per row, elements in ascending order.  float32: sum of squares (float bits);
+// uint8: sum of (x - 128)^2 (int32).
+template <int DT> __global__ void row_norm_kernel(const void *X, int32_t dim, int64_t n, uint32_t *out)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const float4 *x = (const float4 *)(X + i * dim);
-    float acc = 0.f;
-    for (int e = 0; e < dim / 4; ++e) {
-        const float4 v = x[e];
-        acc += v.x * v.x; acc += v.y * v.y; acc += v.z * v.z; acc += v.w * v.w;
+    if (DT == 1) {
+        const float4 *x = (const float4 *)((const float *)X + i * dim);
+        float acc = 0.f;
+        for (int e = 0; e < dim / 4; ++e) {
+            const float4 v = x[e];
+            acc += v.x * v.x; acc += v.y * v.y; acc += v.z * v.z; acc += v.w * v.w;
+        }
+        out[i] = __float_as_uint(acc);
+    } else {
+        const uint4 *x = (const uint4 *)((const uint8_t *)X + i * dim);
+        int acc = 0;
+        for (int e = 0; e < dim / 16; ++e) {
+            const uint4 v = x[e];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int d = (int)((w[a] >> (8 * b)) & 0xFFu) - 128;
+                    acc += d * d;
+                }
+        }
+        out[i] = (uint32_t)acc;
     }
-    out[i] = acc;
 }
 
-void launch_row_norms(const void *X, int32_t dim, int64_t n, float *out, hipStream_t s)
+void launch_row_norms(int dtype, const void *X, int32_t dim, int64_t n, uint32_t *out, hipStream_t s)
 {
     if (n <= 0) return;
-    hipLaunchKernelGGL(row_norm_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float *)X, dim, n, out);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (dtype == 1) hipLaunchKernelGGL(row_norm_kernel<1>, grid, block, 0, s, X, dim, n, out);
+    else hipLaunchKernelGGL(row_norm_kernel<0>, grid, block, 0, s, X, dim, n, out);
 }
 
 bool seed_dist_supported(int dtype, int dim)
