@@ -648,9 +648,17 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         // dense seed scoring: tiles of <= 64 graph queries that search the same label
         std::vector<SeedTile> tiles;
         const int32_t ns_stride = (n_seeds + 31) & ~31;
-        const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) &&
-                                 (uint64_t)n_gq * (uint64_t)ns_stride * 4 <= ((uint64_t)8 << 30);
-        // matrix-core scoring (approximate, re-ranked by the beam kernel) where the beam kernel supports it
+        // the seed distance matrix must fit: reuse what is allocated, or grow into at most half of the free memory
+        bool dseed_fits = true;
+        {
+            const uint64_t need = (uint64_t)n_gq * (uint64_t)ns_stride * 4;
+            if (need > ix->dseed.cap) {
+                size_t free_b = 0, total_b = 0;
+                VF_HIP(hipMemGetInfo(&free_b, &total_b));
+                dseed_fits = need + need / 4 + 256 <= (free_b + ix->dseed.cap) / 2;
+            }
+        }
+        const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) && dseed_fits;
         // uint8: the matrix cores give the exact integer distances, nothing else changes.
         // float32: approximations, re-ranked by the beam kernel, where that kernel supports it.
         const bool seeds_mfma = dense_seeds && ix->seed_mfma && n_seeds > 64 &&
