@@ -660,9 +660,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         }
         const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) && dseed_fits;
         // uint8: the matrix cores give the exact integer distances, nothing else changes.
-        // float32: approximations, re-ranked by the beam kernel, where that kernel supports it.
+        // float32: approximations, re-ranked by the beam kernel (its proof needs a list of at most 48 entries).
         const bool seeds_mfma = dense_seeds && ix->seed_mfma && n_seeds > 64 &&
-                                (ix->dtype == VF_U8 || (!r.any_and && itopk <= 48));
+                                (ix->dtype == VF_U8 || itopk <= 48);
         if (dense_seeds) {
             const size_t tile_q = seeds_mfma ? 32 : 64;
             for (size_t i = 0; i < n_gq;) {

@@ -222,6 +222,31 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 const int j = jc + i * 64 + lane;
                 v[i] = j < ns ? drow[j] : 0xFFFFFFFFu;
             }
+            int chunk_scored = (ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK), chunk_tested = 0;
+            if (o_cnt > 0) {
+                // AND: a seed that fails the predicate is taken out before the selection.  Its local id
+                // floor(j n / ns) advances by (64 n) / ns per step of 64 seeds: one division per lane and
+                // chunk, then quotient / remainder increments.
+                const uint64_t t64 = 64ull * (uint64_t)n;
+                const uint32_t Q64 = (uint32_t)(t64 / (uint64_t)ns), R64 = (uint32_t)(t64 % (uint64_t)ns);
+                const uint64_t t0 = (uint64_t)(jc + lane) * (uint64_t)n;
+                uint32_t cq = (uint32_t)(t0 / (uint64_t)ns), cr = (uint32_t)(t0 % (uint64_t)ns);
+                chunk_tested = chunk_scored;
+                chunk_scored = 0;
+#pragma unroll
+                for (int i = 0; i < NBLK; ++i) {
+                    const int j = jc + i * 64 + lane;
+                    bool pass = j < ns;
+                    if (pass) {
+                        const int g = p.meta.M_HS[base + cq];
+                        for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, p.others[o_begin + o], g);
+                    }
+                    if (!pass) v[i] = 0xFFFFFFFFu;
+                    chunk_scored += __popcll(__ballot(pass));
+                    cr += R64; cq += Q64;
+                    if (cr >= (uint32_t)ns) { cr -= (uint32_t)ns; cq += 1; }
+                }
+            }
             // the two smallest values of every lane; the M-th smallest of those 128 bounds the M-th
             // smallest of the chunk: sort both sets across the wave, take the 64 smallest of their
             // union (element-wise minimum against the reversed other set), sort those
@@ -240,14 +265,17 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             tau = tau < wb ? tau : wb;
             int total = 0;
 #pragma unroll
-            for (int i = 0; i < NBLK; ++i) total += __popcll(__ballot(v[i] <= tau && jc + i * 64 + lane < ns));
+            for (int i = 0; i < NBLK; ++i)
+                total += __popcll(__ballot(v[i] <= tau && v[i] != 0xFFFFFFFFu && jc + i * 64 + lane < ns));
             if (total > 128) break;
+            n_scored += chunk_scored;
+            n_tested += chunk_tested;
             __syncthreads();
             int cnt = 0;
 #pragma unroll
             for (int i = 0; i < NBLK; ++i) {
                 const int j = jc + i * 64 + lane;
-                const bool pass = v[i] <= tau && j < ns;
+                const bool pass = v[i] <= tau && v[i] != 0xFFFFFFFFu && j < ns;
                 const uint64_t m = __ballot(pass);
                 if (pass) {
                     const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
@@ -284,8 +312,10 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 const uint64_t key = tmp.cur[0];
                 const bool valid = key != KEY_MAX;
                 const int c = valid ? (int)(((uint64_t)((uint32_t)(key >> 1) & 0x7FFFFFFFu) * (uint64_t)n) / (uint64_t)ns) : 0;
+                // the kept seeds sit in lanes 0 .. cnt - 1 (sorted list) and have passed the predicate already
                 __syncthreads();
-                const int cnt = filter_and_compact(valid, c, 0);
+                const int cnt = __popcll(__ballot(valid));
+                if (valid) { cand_c[lane] = c; cand_g[lane] = p.meta.M_HS[base + c]; }
                 __syncthreads();
                 score(cnt);
                 float qn = 0.f;
@@ -302,22 +332,21 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                                     __uint_as_float((uint32_t)(top.worst >> 32)) < __uint_as_float((uint32_t)(tmp.worst >> 32)) - B;
                 if (all_kept || proven) {
                     seeds_done = true;
-                    n_scored = ns;
+                    n_scored -= cnt;       // the re-scored seeds were counted when they were selected
                     n_rescored = cnt;
                 }
             }
             if (!seeds_done) {   // start over; the gather path below scores every seed
                 top.init(itopk);
                 n_scored = 0;
+                n_tested = 0;
                 seed_fallback = 1;
             }
         }
     }
     if constexpr (E == 1) {
-        if (!seeds_done && p.dseed != nullptr && p.seed_approx == 0 && o_cnt == 0) {
+        if (!seeds_done && p.dseed != nullptr && p.seed_approx == 0)
             j_begin = select_seeds(top, p.dseed + (int64_t)gq * p.ns_stride, false);
-            n_scored += j_begin;
-        }
     }
     if (seeds_done) {
     } else if (p.dseed != nullptr && p.seed_approx == 0) {
