@@ -256,7 +256,35 @@ def main():
     scan_avg_ms = pf["scan_ms_sum"] / pf["calls"]
     seed_avg_ms = pf["seed_ms_sum"] / pf["calls"]
     ix.profile_enable(False)
-    recall_head = recall_of(out_ids.cpu().numpy())
+    found_head = out_ids.cpu().numpy()
+    recall_head = recall_of(found_head)
+
+    # recall per stratum at the headline point: single label / AND, graph-routed / scan-routed; for AND
+    # workloads also per decade of the intersection's selectivity |C_a ∩ C_b| / N (sampled rows only)
+    rows = np.arange(s.nq) if gt_rows is None else gt_rows
+    S_host = ix.export("S")
+    nlab = np.diff(w.qlabel_offsets)[rows]
+    smallest = np.array([S_host[w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]]].min() for j in rows])
+    strata = {}
+    for name, mask in (("single_graph", (nlab == 1) & (smallest >= s.T)), ("single_scan", (nlab == 1) & (smallest < s.T)),
+                       ("and_graph", (nlab > 1) & (smallest >= s.T)), ("and_scan", (nlab > 1) & (smallest < s.T))):
+        if mask.any():
+            strata[name] = {"queries": int(mask.sum()),
+                            "recall_at_10": round(recall_at_k(found_head[rows[mask]], gt[mask]), 4)}
+    if s.query_mode == "and2" and len(rows) <= 5000:
+        M_HS, M_LS, O_HS, O_LS = ix.export("M_HS"), ix.export("M_LS"), ix.export("O_HS"), ix.export("O_LS")
+
+        def plist(l):
+            return M_HS[O_HS[l]:O_HS[l] + S_host[l]] if O_HS[l] >= 0 else M_LS[O_LS[l]:O_LS[l] + S_host[l]]
+        sel = np.empty(len(rows))
+        for t, j in enumerate(rows):
+            a, b = w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j] + 2]
+            sel[t] = len(np.intersect1d(plist(a), plist(b), assume_unique=True)) / s.n
+        dec = np.floor(np.log10(np.maximum(sel, 1e-12))).astype(int)
+        strata["by_selectivity_decade"] = {
+            f"1e{d}": {"queries": int((dec == d).sum()),
+                       "recall_at_10": round(recall_at_k(found_head[rows[dec == d]], gt[dec == d]), 4)}
+            for d in sorted(set(dec.tolist()))}
 
     # ---- the same K steps once more with the launches serialised on one stream: in the timed
     # region the IVF-BFS kernel runs beside the IVF-Graph kernels and each shares the chip;
@@ -462,6 +490,7 @@ def main():
                                f"{s.nq} queries ({s.query_mode}), k={k}, seed {s.seed}",
                    "params": dict(zip(("itopk", "width", "iters", "n_seeds"), headline[0])),
                    "recall_at_10": round(recall_head, 4), "reached_0.90": p90 is not None,
+                   "recall_by_stratum": strata,
                    "index_build_s": round(build_s, 2), **extra},
         "roofline": roofline,
         "cpu_baseline": cpu,
