@@ -3,17 +3,19 @@
 
 One "step" = one vf_search call over the whole query batch of the workload
 (route + IVF-BFS scan + IVF-Graph beam search + AND predicate + finalise), with the
-index, the queries and the outputs already resident in HBM.  The workload is the
-SIFT-1M-like configuration the metric is quoted on: N = 1e6 float32 vectors of
+index, the queries and the outputs already resident in HBM.  The default workload is
+the SIFT-1M-like configuration the metric is quoted on: N = 1e6 float32 vectors of
 dim 128, 1,000 Zipf labels, T = 10,000, graph degree 32, 10,000 single-label
-queries, k = 10 (seeded synthetic stand-in).
+queries, k = 10 (a seeded synthetic stand-in for the paper's dataset).
 
-Prints ONE JSON line.  `value` is queries/s at the cheapest parameter setting of a
-small candidate list whose recall@10, measured in this run against exact filtered
-ground truth, is >= 0.90; the >= 0.99 operating point is reported beside it.
-`roofline` prices the dominant kernel (beam search) against HBM peak using the
-algorithmic bytes its own work counters imply; `cpu_baseline` times the CPU oracle
-on a bounded sample of the same queries.
+Prints ONE JSON line.  `value` is queries/s at the fastest setting of a grid of
+(itopk, width, iters, n_seeds) whose recall@10, measured in this run against exact
+filtered ground truth, is >= 0.90; the >= 0.99 operating point is reported beside it.
+`roofline` prices the kernel that takes longest when it has the chip to itself against
+the roof that bounds it, from the algorithmic bytes / flops its work counters imply and
+its duration from HIP events; `cpu_baseline` times the CPU oracle on a bounded sample
+of the same queries.  --latency, --multi, --sweep, --workload c3|c5 add further
+measurements to `config`.
 """
 from __future__ import annotations
 

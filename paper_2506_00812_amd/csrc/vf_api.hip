@@ -189,7 +189,7 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     ScanParams p{};
     p.xblk = ix->tmp_blk.as<uint4>(); p.xnorm = ix->tmp_norm.p; p.map = map;
     p.qsrc = ix->X; p.qrow = map; p.items = d_items.as<ScanItem>();
-    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.tile_rows = 32; p.sort_partials = 1;
+    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.tile_rows = 32;
     p.res_idx = cand_idx.as<int32_t>(); p.res_bits = cand_dist.as<uint32_t>();
     p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
     launch_scan(ix->dtype, p, (int)n_groups, s);
@@ -789,7 +789,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
             ScanParams sp{};
             sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
-            sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows; sp.sort_partials = 0;
+            sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows;
             sp.out_ids = out_ids; sp.out_dists = out_dists;
             sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
             const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);

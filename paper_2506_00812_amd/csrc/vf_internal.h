@@ -61,7 +61,6 @@ struct ScanParams {
     const ScanItem *items;
     int32_t dim, ncp, K;
     int32_t tile_rows;      // rows of the largest tile (LDS buffers are sized for it), <= 32
-    int32_t sort_partials;  // 1: partial rows are written sorted (graph build); 0: a merge kernel sorts them
     int64_t *out_ids;       // final output [*][K] (items with part_row < 0): row = qrow value
     float *out_dists;
     int32_t *res_idx;       // partial output [*][K]: list-relative entry index, -1 = none

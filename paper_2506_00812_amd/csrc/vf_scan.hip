@@ -22,6 +22,11 @@
 // sorted list, bitonic merge -- and broadcasts the tightened thresholds.  The result
 // does not depend on the order in which candidates were queued.  Keys are
 // (distance bits << 32 | entry index): unsigned order == (distance, id) order.
+//
+// Three kernels share that selection.  scan_topk_kernel: 32-row tiles (uint8 search, and for
+// both types the kNN self-joins of the index build and the ground truth).  scan_topk16_kernel:
+// float32 search tiles, which hold at most 16 queries, on the 16x16x4 MFMA.  scan_valu_kernel:
+// float32 tiles of small batches on plain FMAs.
 #include "vf_device.h"
 
 namespace vf {
