@@ -152,7 +152,7 @@ def test_edge_cases(vf, tiny, tiny_oracle, tiny_gpu):
     qids = np.stack([w.qlabel_ids, w.qlabel_ids], axis=1).reshape(-1).astype(np.int32)
     qids[0:2] = (105, 0)       # AND with a label nobody carries
     qids[2:4] = (109, 109)     # single unknown label
-    for k, itopk in ((1, 32), (32, 32), (10, 64)):
+    for k, itopk in ((1, 32), (32, 32), (10, 64), (64, 64), (64, 256)):
         ig, dg = _search(vf, ixg, Qs, qoff, qids, k, itopk=itopk, width=1, iters=12, n_seeds=64)
         io, do = ixo.search(w.queries, qoff, qids, k, itopk=itopk, width=1, iters=12, n_seeds=64)
         assert_exact(ig, dg, io, do, f"edge k={k}")
