@@ -69,6 +69,7 @@ struct Routed {
     bool any_and = false;
     // scratch kept between calls
     std::vector<int32_t> q_best;                      // searched label of each query, -1: empty result
+    std::vector<int32_t> empty_q;                     // queries with q_best == -1
     std::vector<int32_t> cnt;                         // [n_labels] queries per searched label (zero between calls)
     std::vector<int32_t> touched;                     // labels with cnt > 0
 };
@@ -420,6 +421,7 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
     r.others_off.assign((size_t)nq + 1, 0);
     r.others.clear();
     r.any_and = false;
+    r.empty_q.clear();
     r.q_best.resize((size_t)nq);
     if (r.cnt.size() != (size_t)ix->n_labels) r.cnt.assign((size_t)ix->n_labels, 0);
     r.touched.clear();
@@ -456,6 +458,7 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
             if (r.cnt[(size_t)best]++ == 0) r.touched.push_back(best);
         }
         r.q_best[(size_t)j] = empty ? -1 : best;
+        if (empty) r.empty_q.push_back((int32_t)j);
         r.others_off[(size_t)j + 1] = (int32_t)r.others.size();
     }
     // offsets per touched label, graph labels and scan labels in separate outputs, each by ascending label
@@ -487,7 +490,7 @@ int route_queries(const vf_index *ix, int64_t nq, const int64_t *qoff, const int
 }
 
 struct BlobLayout {
-    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, off_tiles, total;
+    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, off_tiles, off_empty, total;
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -683,6 +686,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         L.off_items = o; o = align_up(o + std::max<size_t>(items.size(), 1) * sizeof(ScanItem));
         L.off_merges = o; o = align_up(o + std::max<size_t>(ib.merges.size(), 1) * sizeof(MergeItem));
         L.off_tiles = o; o = align_up(o + std::max<size_t>(tiles.size(), 1) * sizeof(SeedTile));
+        L.off_empty = o; o = align_up(o + std::max<size_t>(r.empty_q.size(), 1) * 4);
         L.total = o;
 
         Staging *st = nullptr;
@@ -698,6 +702,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (!items.empty()) memcpy(hp + L.off_items, items.data(), items.size() * sizeof(ScanItem));
         if (!ib.merges.empty()) memcpy(hp + L.off_merges, ib.merges.data(), ib.merges.size() * sizeof(MergeItem));
         if (!tiles.empty()) memcpy(hp + L.off_tiles, tiles.data(), tiles.size() * sizeof(SeedTile));
+        if (!r.empty_q.empty()) memcpy(hp + L.off_empty, r.empty_q.data(), r.empty_q.size() * 4);
         if (dense_seeds && (rc = ix->dseed.reserve((size_t)n_gq * ns_stride * 4)) != VF_OK) return rc;
         if (ib.part_rows > 0) {
             VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
@@ -710,7 +715,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         VF_HIP(hipEventRecord(st->done, s));
         st->pending = true;
 
-        launch_fill_out(out_ids, out_dists, nq * (int64_t)k, s);
+        // every routed query's kernel writes all k entries of its row; only queries without any match are padded here
+        launch_fill_rows(out_ids, out_dists, (const int32_t *)(dp + L.off_empty), (int64_t)r.empty_q.size(), k, s);
 
         const bool prof = ix->profiling;
         if (prof) {

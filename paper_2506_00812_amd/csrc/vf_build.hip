@@ -163,6 +163,22 @@ void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s)
     hipLaunchKernelGGL(fill_out_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, ids, dists, count);
 }
 
+__global__ void fill_rows_kernel(int64_t *ids, float *dists, const int32_t *rows, int64_t n_rows, int32_t k)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_rows * k) return;
+    const int64_t o = (int64_t)rows[t / k] * k + t % k;
+    ids[o] = -1;
+    dists[o] = __builtin_inff();
+}
+
+void launch_fill_rows(int64_t *ids, float *dists, const int32_t *rows, int64_t n_rows, int32_t k, hipStream_t s)
+{
+    if (n_rows <= 0) return;
+    hipLaunchKernelGGL(fill_rows_kernel, dim3((unsigned)((n_rows * k + 255) / 256)), dim3(256), 0, s, ids, dists, rows,
+                       n_rows, k);
+}
+
 __global__ void gather_rows_kernel(const uint4 *rows, int32_t chunks, const int32_t *parent, int64_t n, uint4 *out)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

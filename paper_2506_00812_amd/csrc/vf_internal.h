@@ -158,6 +158,8 @@ void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map
                        int32_t K, int32_t R, int32_t *G_rows, hipStream_t s);
 
 void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s);
+// rows[i] of the [*][k] outputs := (-1, +inf)
+void launch_fill_rows(int64_t *ids, float *dists, const int32_t *rows, int64_t n_rows, int32_t k, hipStream_t s);
 
 // ---------------------------------------------------------------- multi-label queries (OR, parallel AND)
 
