@@ -98,7 +98,7 @@ struct vf_index {
     float seed_err_bound = 0.f;  // relative to |q|^2 + xn_max; VF_SEED_SLACK in the environment scales it (tests)
     bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
     // search workspace
-    DevBuf ws_blob, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
+    DevBuf ws_blob, ws_blob_b, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
     // vf_search_multi: gathered query rows, results of the sub-searches, their parents
     DevBuf multi_q, multi_ids, multi_dists, multi_meta;
     std::vector<int32_t> multi_host;      // [n_sub parents | nq + 1 first sub-search of each query], alive until the next call
@@ -114,7 +114,10 @@ struct vf_index {
     int prof_next = 0, prof_unfolded = 0; // next ring slot; recorded sets whose durations are not in the sums yet
     // the scan path runs beside the graph path on a second stream of the same (default) priority
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_copy = nullptr;
+    hipEvent_t ev_blob_done[2] = {nullptr, nullptr};   // recorded on the caller's stream when a call that read blob b ends
+    bool blob_used[2] = {false, false};
+    int blob_next = 0;   // the device blob alternates between two buffers
     bool overlap = true;  // VF_NO_OVERLAP=1 in the environment serialises the two paths (for per-kernel timing)
     bool prof_serial = false;  // vf_profile_enable(index, 2): same, switched at run time
     vf_profile prof{};
@@ -140,13 +143,16 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
     for (auto &set : ix->prof_ring)
         for (hipEvent_t e : set)
             if (e) (void)hipEventDestroy(e);
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
     if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
+    if (ix->ev_copy) (void)hipEventDestroy(ix->ev_copy);
+    for (hipEvent_t e : ix->ev_blob_done)
+        if (e) (void)hipEventDestroy(e);
     if (ix->side) { (void)hipStreamSynchronize(ix->side); (void)hipStreamDestroy(ix->side); }
     for (Staging &s : ix->stage) {
         if (s.pending) (void)hipEventSynchronize(s.done);
@@ -382,6 +388,8 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
     VF_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
     VF_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
     VF_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
+    VF_HIP(hipEventCreateWithFlags(&ix->ev_copy, hipEventDisableTiming));
+    for (hipEvent_t &e : ix->ev_blob_done) VF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     guard.ix = nullptr;
     *out = ix;
     return VF_OK;
@@ -709,11 +717,25 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             if ((rc = ix->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
             if ((rc = ix->part_bits.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
         }
-        if ((rc = ix->ws_blob.reserve(L.total)) != VF_OK) return rc;
-        char *dp = ix->ws_blob.as<char>();
-        VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, s));
-        VF_HIP(hipEventRecord(st->done, s));
+        // The scan path runs on the side stream beside the graph path on the caller's stream.
+        const bool forked = ix->overlap && !ix->prof_serial && !exact && n_gq > 0 && !items.empty();
+        // Two device blobs alternate.  When the call forks, its blob is uploaded on the side stream: there it
+        // follows the previous call's scan, not the previous call's beam search, so the upload is off the
+        // critical path.  The buffer was last read two calls ago; the upload waits for that call's end.
+        const int bsel = ix->blob_next;
+        DevBuf &blob = bsel ? ix->ws_blob_b : ix->ws_blob;
+        ix->blob_next ^= 1;
+        if ((rc = blob.reserve(L.total)) != VF_OK) return rc;
+        char *dp = blob.as<char>();
+        hipStream_t cs = forked ? ix->side : s;
+        if (forked && ix->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, ix->ev_blob_done[bsel], 0));
+        VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, cs));
+        VF_HIP(hipEventRecord(st->done, cs));
         st->pending = true;
+        if (forked) {
+            VF_HIP(hipEventRecord(ix->ev_copy, cs));
+            VF_HIP(hipStreamWaitEvent(s, ix->ev_copy, 0));
+        }
 
         // every routed query's kernel writes all k entries of its row; only queries without any match are padded here
         launch_fill_rows(out_ids, out_dists, (const int32_t *)(dp + L.off_empty), (int64_t)r.empty_q.size(), k, s);
@@ -737,9 +759,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 pf.seed_tile_seeds += ns_l;
             }
         }
-        // The scan path runs on the side stream beside the graph path on the caller's stream.
         hipStream_t ss = s;
-        const bool forked = ix->overlap && !ix->prof_serial && !exact && n_gq > 0 && !items.empty();
         const int32_t *d_others_off = r.any_and ? (const int32_t *)(dp + L.off_others_off) : nullptr;
         const int32_t *d_others = (const int32_t *)(dp + L.off_others);
 
@@ -849,6 +869,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             ++ix->prof_unfolded;
         }
         if (forked) VF_HIP(hipStreamWaitEvent(s, ix->ev_join, 0));
+        VF_HIP(hipEventRecord(ix->ev_blob_done[bsel], s));
+        ix->blob_used[bsel] = true;
         VF_HIP(hipGetLastError());
         if (exact) {
             VF_HIP(hipStreamSynchronize(s));
