@@ -91,6 +91,7 @@ struct vf_index {
     int32_t n_scan_labels = 0;
     // device
     DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
+    DevBuf d_Gg;   // [n_HS][R] the graph rows once more with global ids: saves the search one dependent load per expansion
     // float32 indexes with graph labels: squared norm of every row of X and the largest of them,
     // for the matrix-core seed scoring (its error bound needs the largest norm)
     DevBuf d_xnorm_all;
@@ -142,7 +143,7 @@ struct vf_index {
 static void free_index(vf_index *ix)
 {
     if (!ix) return;
-    DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G,
+    DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G, &ix->d_Gg,
                       &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
     for (auto &set : ix->prof_ring)
@@ -202,6 +203,8 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     launch_scan(ix->dtype, p, (int)n_groups, s);
     launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
                       ix->d_G.as<int32_t>() + base * ix->R, s);
+    launch_graph_global_ids(ix->d_G.as<int32_t>() + base * ix->R, map, (int64_t)nl * ix->R,
+                            ix->d_Gg.as<int32_t>() + base * ix->R, s);
     VF_HIP(hipGetLastError());
     return VF_OK;
 }
@@ -320,6 +323,7 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
             if ((rc = ix->d_bitsets.reserve(bs_bytes)) != VF_OK) return rc;
             VF_HIP(hipMemsetAsync(ix->d_bitsets.p, 0, bs_bytes, s));
             if ((rc = ix->d_G.reserve((size_t)ix->n_HS * ix->R * 4)) != VF_OK) return rc;
+            if ((rc = ix->d_Gg.reserve((size_t)ix->n_HS * ix->R * 4)) != VF_OK) return rc;
             int32_t max_list = 0;
             for (int32_t l : ix->graph_labels) max_list = std::max(max_list, ix->S[(size_t)l]);
             const int32_t K = dtype == VF_U8 ? ix->R : std::min(64, ix->R + 16);
@@ -744,8 +748,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (prof) {
             if (ix->prof_unfolded == vf_index::kProfRing && (rc = fold_profile(ix, 1)) != VF_OK) return rc;
             ix->prof_ev = ix->prof_ring[ix->prof_next];
-            if ((rc = ix->counters.reserve((size_t)nq * 16 + 16)) != VF_OK) return rc;   // per-query counters + one 64-bit sum
-            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 16 + 16, s));
+            if ((rc = ix->counters.reserve((size_t)nq * 20)) != VF_OK) return rc;   // [nq][4] counters, then [nq] gathered
+            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 20, s));
             vf_profile &pf = ix->prof;
             pf = vf_profile{};
             pf.nq = nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)qrow.size();
@@ -765,7 +769,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 
         BeamParams bp{};
         if (n_gq) {
-            bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>();
+            bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>(); bp.Gg = ix->d_Gg.as<int32_t>();
             bp.gq_query = (const int32_t *)(dp + L.off_gq_query);
             bp.gq_label = (const int32_t *)(dp + L.off_gq_label);
             bp.others_off = d_others_off; bp.others = d_others; bp.meta = ix->meta();
@@ -775,7 +779,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             bp.hash_bits = beam_hb;
             bp.out_ids = out_ids; bp.out_dists = out_dists;
             bp.counters = prof ? ix->counters.as<int32_t>() : nullptr;
-            bp.gathered = prof ? (unsigned long long *)(ix->counters.as<char>() + (size_t)nq * 16) : nullptr;
+            bp.gathered = prof ? ix->counters.as<int32_t>() + (size_t)nq * 4 : nullptr;
             bp.dseed = nullptr; bp.ns_stride = ns_stride;
         }
         auto run_seeds = [&]() -> int {
@@ -1027,7 +1031,7 @@ extern "C" int vf_index_stats(const vf_index *ix, vf_stats *out)
     out->dim = ix->dim; out->dtype = ix->dtype; out->n_labels = ix->n_labels; out->T = ix->T; out->graph_degree = ix->R;
     out->n_graph_labels = (int32_t)ix->graph_labels.size(); out->n_scan_labels = ix->n_scan_labels;
     out->chunks_per_vector = 2 * ix->ncp;
-    out->bytes_graph = ix->n_HS * ix->R * 4;
+    out->bytes_graph = 2 * ix->n_HS * ix->R * 4;   // local ids + global ids
     out->bytes_maps = (ix->n_HS + ix->n_LS) * 4;
     out->bytes_x_ls = ix->n_groups_LS * (int64_t)ix->group_bytes() + ix->n_groups_LS * 32 * 4;
     out->bytes_bitsets = (int64_t)ix->graph_labels.size() * ix->bitset_words * 4;
@@ -1071,9 +1075,9 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
             pf.seed_rescored += m >> 8;
         }
         if (per_query) memcpy(per_query, cn.data(), cn.size() * 4);
-        unsigned long long g = 0;
-        VF_HIP(hipMemcpy(&g, ix->counters.as<char>() + (size_t)pf.nq * 16, 8, hipMemcpyDeviceToHost));
-        pf.beam_gathered = (int64_t)g;
+        std::vector<int32_t> gathered((size_t)pf.nq);
+        VF_HIP(hipMemcpy(gathered.data(), ix->counters.as<int32_t>() + (size_t)pf.nq * 4, gathered.size() * 4, hipMemcpyDeviceToHost));
+        for (int32_t g : gathered) pf.beam_gathered += g;
     } catch (const std::bad_alloc &) {
         set_error("out of host memory");
         return VF_ENOMEM;

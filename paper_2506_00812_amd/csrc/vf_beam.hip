@@ -184,11 +184,12 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     };
 
     // Keep the candidates that pass the AND predicate, compacted into cand[].
-    auto filter_and_compact = [&](bool valid, int c, int cnt) -> int {
-        int g = 0;
+    // g_known: the global id of c if the caller has it already (>= 0), else it is looked up in M.
+    auto filter_and_compact = [&](bool valid, int c, int cnt, int g_known = -1) -> int {
+        int g = g_known;
         if (o_cnt > 0) n_tested += __popcll(__ballot(valid));
         if (valid) {
-            g = p.meta.M_HS[base + c];
+            if (g < 0) g = p.meta.M_HS[base + c];
             for (int o = 0; o < o_cnt && valid; ++o) valid = has_label(p.meta, p.others[o_begin + o], g);
         }
         const uint64_t m = __ballot(valid);
@@ -414,14 +415,17 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         for (int j0 = 0; j0 < np * R; j0 += 64) {
             const int j = j0 + lane;
             bool valid = j < np * R;
-            int c = -1;
+            int c = -1, g = -1;
             if (valid) {
+                // the row as local ids (list bookkeeping) and as global ids (where the vector is): two
+                // independent coalesced loads instead of a lookup in M that depends on the first
                 const int pa = parents[j / R];
                 c = p.G[(base + pa) * R + (j % R)];
+                g = p.Gg[(base + pa) * R + (j % R)];
                 valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns, inv_n) &&
                         visit(hash, p.hash_bits, (uint32_t)c);
             }
-            cnt = filter_and_compact(valid, c, cnt);
+            cnt = filter_and_compact(valid, c, cnt, g);
         }
         __syncthreads();
         score(cnt);
@@ -430,7 +434,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     if (p.counters != nullptr && lane == 0) {
         int32_t *cn = p.counters + (int64_t)qi * 4;
         cn[0] = n_scored; cn[1] = n_expanded; cn[2] = n_tested; cn[3] = 2 + seed_fallback + (n_rescored << 8);
-        if (p.gathered != nullptr) atomicAdd(p.gathered, (unsigned long long)n_gathered);
+        if (p.gathered != nullptr) p.gathered[qi] = n_gathered;
     }
 
     // ---- first k entries (k <= 64: register 0), local -> global through M

@@ -149,6 +149,20 @@ void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map
     }
 }
 
+__global__ void graph_global_ids_kernel(const int32_t *rows, const int32_t *map, int64_t count, int32_t *out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const int32_t c = rows[t];
+    out[t] = c >= 0 ? map[c] : -1;
+}
+
+void launch_graph_global_ids(const int32_t *rows, const int32_t *map, int64_t count, int32_t *out, hipStream_t s)
+{
+    if (count <= 0) return;
+    hipLaunchKernelGGL(graph_global_ids_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, rows, map, count, out);
+}
+
 __global__ void fill_out_kernel(int64_t *ids, float *dists, int64_t count)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

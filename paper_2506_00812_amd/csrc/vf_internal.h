@@ -87,6 +87,7 @@ struct BeamParams {
     const void *X;           // global vectors, row-major [n][dim]
     const void *Q;           // queries, row-major [nq][dim]
     const int32_t *G;        // [n_HS][R] local ids
+    const int32_t *Gg;       // [n_HS][R] the same rows as global ids (-1 where G is -1)
     const int32_t *gq_query; // [n_gq] query index
     const int32_t *gq_label; // [n_gq] searched label
     const int32_t *others_off;
@@ -98,7 +99,7 @@ struct BeamParams {
     int64_t *out_ids;
     float *out_dists;
     int32_t *counters; // optional [nq][4]: distances computed, rows expanded, predicate tests, method
-    unsigned long long *gathered; // optional: sum over queries of the distances whose vector the kernel fetched itself
+    int32_t *gathered; // optional [nq]: distances whose vector the kernel fetched itself
     const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel / seed_mfma_kernel
     int32_t ns_stride;
     // dseed holds MFMA approximations (float32 only): the kernel re-scores the best of them with the
@@ -157,6 +158,8 @@ void launch_bitset_fill(const int32_t *map, int64_t n, uint32_t *bits, hipStream
 void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map, int64_t n, const int32_t *cand_idx,
                        int32_t K, int32_t R, int32_t *G_rows, hipStream_t s);
 
+// out[i] = map[rows[i]] (rows[i] >= 0), -1 otherwise: graph rows as global ids
+void launch_graph_global_ids(const int32_t *rows, const int32_t *map, int64_t count, int32_t *out, hipStream_t s);
 void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s);
 // rows[i] of the [*][k] outputs := (-1, +inf)
 void launch_fill_rows(int64_t *ids, float *dists, const int32_t *rows, int64_t n_rows, int32_t k, hipStream_t s);
