@@ -38,9 +38,11 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 
 # workload is governed by the number of seeds (per-list graphs over separated clusters are
 # disconnected), then by the iteration count.
 CANDIDATES = sorted({(itopk, 1, iters, ns)
-                     for itopk in (32, 48)
+                     for itopk in (32,)
                      for iters in (6, 8, 12, 16, 24, 32)
                      for ns in (1536, 2048, 2560, 3072, 4096, 5120, 6144, 8192, 12288)}
+                    | {(32, wd, iters, ns) for wd, its in ((2, (4, 6, 12, 16)), (4, (3, 8, 12))) for iters in its
+                       for ns in (2560, 3072, 4096, 6144, 8192)}
                     | {(64, 1, 24, 8192), (64, 2, 24, 8192), (128, 2, 32, 12288)},
                     key=lambda c: (c[3] + c[2] * c[1] * 32) * (1.0 + c[0] / 256.0))
 
