@@ -122,6 +122,7 @@ struct vf_index {
     bool overlap = true;  // VF_NO_OVERLAP=1 in the environment serialises the two paths (for per-kernel timing)
     bool prof_serial = false;  // vf_profile_enable(index, 2): same, switched at run time
     vf_profile prof{};
+    std::vector<int32_t> prof_graph_queries;   // graph-routed queries of the last profiled call
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
     Staging stage[2];
@@ -748,8 +749,10 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (prof) {
             if (ix->prof_unfolded == vf_index::kProfRing && (rc = fold_profile(ix, 1)) != VF_OK) return rc;
             ix->prof_ev = ix->prof_ring[ix->prof_next];
-            if ((rc = ix->counters.reserve((size_t)nq * 20)) != VF_OK) return rc;   // [nq][4] counters, then [nq] gathered
-            VF_HIP(hipMemsetAsync(ix->counters.p, 0, (size_t)nq * 20, s));
+            // [nq][4] counters, then [nq] gathered; written by the beam kernel for graph queries only (no clearing
+            // pass: the rows of the other queries are never read)
+            if ((rc = ix->counters.reserve((size_t)nq * 20)) != VF_OK) return rc;
+            ix->prof_graph_queries = r.gq_query;
             vf_profile &pf = ix->prof;
             pf = vf_profile{};
             pf.nq = nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)qrow.size();
@@ -1068,16 +1071,17 @@ extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query
     try {
         std::vector<int32_t> cn((size_t)pf.nq * 4);
         VF_HIP(hipMemcpy(cn.data(), ix->counters.p, cn.size() * 4, hipMemcpyDeviceToHost));
-        for (int64_t j = 0; j < pf.nq; ++j) {
-            pf.beam_scored += cn[(size_t)j * 4]; pf.beam_expanded += cn[(size_t)j * 4 + 1]; pf.beam_tested += cn[(size_t)j * 4 + 2];
-            const int32_t m = cn[(size_t)j * 4 + 3];
-            pf.seed_fallbacks += (m & 0xFF) == 3;
-            pf.seed_rescored += m >> 8;
-        }
-        if (per_query) memcpy(per_query, cn.data(), cn.size() * 4);
         std::vector<int32_t> gathered((size_t)pf.nq);
         VF_HIP(hipMemcpy(gathered.data(), ix->counters.as<int32_t>() + (size_t)pf.nq * 4, gathered.size() * 4, hipMemcpyDeviceToHost));
-        for (int32_t g : gathered) pf.beam_gathered += g;
+        if (per_query) memset(per_query, 0, cn.size() * 4);
+        for (int32_t j : ix->prof_graph_queries) {   // the other rows of the device arrays hold nothing
+            const int32_t *row = &cn[(size_t)j * 4];
+            pf.beam_scored += row[0]; pf.beam_expanded += row[1]; pf.beam_tested += row[2];
+            pf.seed_fallbacks += (row[3] & 0xFF) == 3;
+            pf.seed_rescored += row[3] >> 8;
+            pf.beam_gathered += gathered[(size_t)j];
+            if (per_query) memcpy(per_query + (size_t)j * 4, row, 16);
+        }
     } catch (const std::bad_alloc &) {
         set_error("out of host memory");
         return VF_ENOMEM;
