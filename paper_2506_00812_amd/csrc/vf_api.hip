@@ -34,6 +34,12 @@ void set_error(const std::string &msg) { g_err = msg; }
         }                                     \
     } while (0)
 
+static int env_int_early(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return (e && *e) ? atoi(e) : dflt;
+}
+
 struct DevBuf {
     void *p = nullptr;
     size_t cap = 0;
@@ -183,12 +189,17 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     const int32_t *map = ix->d_M_HS.as<int32_t>() + base;
     launch_interleave(ix->dtype, ix->X, ix->dim, map, nullptr, nullptr, nl, n_groups, ix->ncp, ix->tmp_blk.as<uint4>(),
                       ix->tmp_norm.p, s);
-    std::vector<ScanItem> items((size_t)n_groups);
-    for (int64_t t = 0; t < n_groups; ++t) {
+    // float32: 16-row tiles on the 16x16x4 MFMA (their smaller LDS footprint more than doubles the resident
+    // waves); uint8: 32-row tiles
+    static const int build16 = env_int_early("VF_BUILD16", 1);
+    const int32_t TR = (build16 && scan16_supported(ix->dtype, ix->dim, 16)) ? 16 : 32;
+    const int64_t n_tiles = (nl + TR - 1) / TR;
+    std::vector<ScanItem> items((size_t)n_tiles);
+    for (int64_t t = 0; t < n_tiles; ++t) {
         ScanItem &it = items[(size_t)t];
         it.group0 = 0; it.map_off = 0; it.entry0 = 0; it.n = nl;
-        it.q_begin = (int32_t)(t * 32);
-        it.q_count = (int32_t)std::min<int64_t>(32, nl - t * 32);
+        it.q_begin = (int32_t)(t * TR);
+        it.q_count = (int32_t)std::min<int64_t>(TR, nl - t * TR);
         it.self_base = it.q_begin;
         it.part_row = it.q_begin;
     }
@@ -198,10 +209,11 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     ScanParams p{};
     p.xblk = ix->tmp_blk.as<uint4>(); p.xnorm = ix->tmp_norm.p; p.map = map;
     p.qsrc = ix->X; p.qrow = map; p.items = d_items.as<ScanItem>();
-    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.tile_rows = 32;
+    p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.tile_rows = TR;
     p.res_idx = cand_idx.as<int32_t>(); p.res_bits = cand_dist.as<uint32_t>();
     p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
-    launch_scan(ix->dtype, p, (int)n_groups, s);
+    if (TR == 16) launch_scan16(p, (int)n_tiles, s);
+    else launch_scan(ix->dtype, p, (int)n_tiles, s);
     launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
                       ix->d_G.as<int32_t>() + base * ix->R, s);
     launch_graph_global_ids(ix->d_G.as<int32_t>() + base * ix->R, map, (int64_t)nl * ix->R,

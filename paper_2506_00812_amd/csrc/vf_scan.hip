@@ -513,6 +513,8 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
     };
 
     const int n_groups = (it.n + kGroup - 1) / kGroup;
+    // segment-relative index of the entry that equals this lane's row 4 kq (graph build), else never matched
+    const int self0 = it.self_base >= 0 ? it.self_base + 4 * kq - it.entry0 : -0x40000000;
     // B registers of both column blocks; each block is refilled with the next group's chunks right
     // after its own MFMAs have been issued
     uint4 breg[2][NS];
@@ -572,7 +574,9 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
                 const float d = (qn[i] + xn[cb]) - 2.0f * acc[cb][i];
                 bitsv[cb * 4 + i] = __float_as_uint(fmaxf(d, 0.0f));
                 const uint32_t below = bitsv[cb * 4 + i] <= thr[i] ? 1u : 0u;
-                pm |= (below & (col_ok >> i) & 1u) << (cb * 4 + i);
+                // graph build: the list entry that is the query row itself is skipped
+                const uint32_t not_self = grp * kGroup + cb * 16 + c16 != self0 + i ? 1u : 0u;
+                pm |= (below & not_self & (col_ok >> i) & 1u) << (cb * 4 + i);
             }
         }
         if (any_and && pm != 0) {
@@ -808,7 +812,7 @@ bool scan16_supported(int dtype, int dim, int tile_rows)
     return dtype == 1 && (dim == 128 || dim == 96) && tile_rows <= 16;
 }
 
-// float32 search tiles of <= 16 queries (no self exclusion): see scan_topk16_kernel
+// float32 tiles of <= 16 queries: see scan_topk16_kernel
 void launch_scan16(const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
