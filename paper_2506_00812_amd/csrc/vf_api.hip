@@ -212,8 +212,23 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     p.dim = ix->dim; p.ncp = ix->ncp; p.K = K; p.tile_rows = TR;
     p.res_idx = cand_idx.as<int32_t>(); p.res_bits = cand_dist.as<uint32_t>();
     p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
-    if (TR == 16) launch_scan16(p, (int)n_tiles, s);
-    else launch_scan(ix->dtype, p, (int)n_tiles, s);
+    if (TR == 16) {
+        // long lists go panel by panel (about 1 MiB of list each) so that the resident waves share L2
+        // (VF_BUILD_PANEL_KB: panel size, 1024 by default; lists of up to 16 panels are not cut)
+        static const int64_t panel_bytes = (int64_t)std::max(1, env_int_early("VF_BUILD_PANEL_KB", 1024)) << 10;
+        const int64_t list_bytes = n_groups * (int64_t)ix->group_bytes();
+        if (list_bytes <= 16 * panel_bytes) {
+            launch_scan16(p, (int)n_tiles, s);
+        } else {
+            const int32_t panel = (int32_t)std::max<int64_t>(32, panel_bytes / ((int64_t)ix->group_bytes() / 32) / 32 * 32);
+            for (int64_t e0 = 0; e0 < nl; e0 += panel) {
+                p.panel_entry0 = (int32_t)e0; p.panel_n = panel; p.carry = e0 > 0;
+                launch_scan16(p, (int)n_tiles, s);
+            }
+        }
+    } else {
+        launch_scan(ix->dtype, p, (int)n_tiles, s);
+    }
     launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
                       ix->d_G.as<int32_t>() + base * ix->R, s);
     launch_graph_global_ids(ix->d_G.as<int32_t>() + base * ix->R, map, (int64_t)nl * ix->R,

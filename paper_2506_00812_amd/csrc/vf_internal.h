@@ -61,6 +61,12 @@ struct ScanParams {
     const ScanItem *items;
     int32_t dim, ncp, K;
     int32_t tile_rows;      // rows of the largest tile (LDS buffers are sized for it), <= 32
+    // Panel mode (scan_topk16_kernel, panel_n > 0): every item of the launch covers only list entries
+    // [panel_entry0, panel_entry0 + panel_n) of its list (multiples of 32); with carry != 0 a row's K best
+    // start from the partial row a previous launch left in res_idx / res_bits.  Launching the panels of a
+    // long list one after the other keeps all resident waves on the same megabyte, which every XCD's L2
+    // then serves: the kNN self-join of a 400,000-vector list is otherwise bound by HBM bandwidth.
+    int32_t panel_entry0, panel_n, carry;
     int64_t *out_ids;       // final output [*][K] (items with part_row < 0): row = qrow value
     float *out_dists;
     int32_t *res_idx;       // partial output [*][K]: list-relative entry index, -1 = none

@@ -447,7 +447,14 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
     typedef float v4f __attribute__((ext_vector_type(4)));
     constexpr int NCH = 2 * NCP, NS = NCH / 4, row_bytes = NCH * kChunkBytes, PC = 64;
     static_assert(NCH % 4 == 0, "the chunk count must be a multiple of four");
-    const ScanItem it = p.items[blockIdx.x];
+    ScanItem it = p.items[blockIdx.x];
+    if (p.panel_n > 0) {
+        const int rem = it.n - p.panel_entry0;
+        if (rem <= 0) return;   // the item's list ends before this panel (the whole workgroup leaves)
+        it.group0 += p.panel_entry0 / kGroup;
+        it.entry0 += p.panel_entry0;
+        it.n = rem < p.panel_n ? rem : p.panel_n;
+    }
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5, c16 = lane & 15, kq = lane >> 4;
     const int K = p.K, KS = K | 1, TR = p.tile_rows;   // TR <= 16
 
@@ -461,6 +468,16 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
     if (lane < 32) { qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1; pcnt[lane] = 0; }
     for (int i = lane; i < TR * KS; i += 64) best[i] = KEY_MAX;
     __syncthreads();
+    const bool carry = p.carry != 0 && it.part_row >= 0;
+    if (carry) {   // the K best so far of every row, left by the launch over the previous panel
+        for (int r = 0; r < it.q_count; ++r) {
+            if (lane < K) {
+                const int64_t o = (int64_t)(it.part_row + r) * K + lane;
+                const int32_t idx = p.res_idx[o];
+                if (idx >= 0) best[r * KS + lane] = ((uint64_t)p.res_bits[o] << 32) | (uint32_t)idx;
+            }
+        }
+    }
     {
         // lane (r = n32, h) copies chunks h, h+2, ... of query row r and sums their squares
         const int qr = n32 < TR ? qrow_s[n32] : -1;
@@ -501,6 +518,12 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
     const bool any_and = __any(and_rows != 0);
     int pcv = 0;                  // state of tile row r, held by lane r
     uint64_t row_kth = KEY_MAX;
+    if (carry) {
+        if (lane < it.q_count) row_kth = best[lane * KS + K - 1];
+        const uint32_t t = (uint32_t)(row_kth >> 32);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) thr[i] = __shfl(t, 4 * kq + i);
+    }
 
     auto drain = [&]() {
         wave_lds_sync();

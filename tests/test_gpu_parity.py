@@ -2,6 +2,8 @@
 same seeded inputs.  Integer (uint8) results and every graph-path result must be
 bit-exact; float scan-path results must agree within 1e-4 relative with id sets
 equal up to ties inside that tolerance."""
+import os
+
 import numpy as np
 import pytest
 
@@ -447,3 +449,30 @@ def test_float_multi_search(vf, mode_name):
     assert_exact(ig[all_graph], dg[all_graph], io[all_graph], do[all_graph], f"float {mode_name}, graph lists only")
     assert_close_with_ties(ig[~all_graph], dg[~all_graph], io[~all_graph], do[~all_graph], RTOL,
                            f"float {mode_name}, scan lists involved")
+
+
+def test_float_graph_build_in_panels():
+    """Long float32 lists are self-joined panel by panel with the rows' best-so-far carried between
+    launches.  With the panel forced down to one 32-vector group every list of this workload takes
+    that route (hundreds of launches per list): the graph rows must still be the oracle's."""
+    import subprocess
+    import sys
+    code = r'''
+import os, sys, numpy as np, torch
+sys.path.insert(0, os.environ["VF_TEST_ROOT"])
+from oracle import OracleIndex
+from paper_2506_00812_amd import binding as vf
+from paper_2506_00812_amd.workloads import make_workload
+w = make_workload("c2", n=12_000, nq=10, n_labels=12, n_clusters=16, T=600, graph_degree=32)
+s = w.spec
+ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+G = ix.export("G_HS").reshape(-1, s.graph_degree)
+assert ix.stats()["n_graph_labels"] >= 6 and len(G) > 10_000
+bad = np.flatnonzero((G != ixo.G_HS).any(axis=1))
+assert len(bad) == 0, (len(bad), bad[:5])
+print("panel build ok", len(G))
+'''
+    env = dict(os.environ, VF_BUILD_PANEL_KB="16", VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
+    assert out.returncode == 0 and "panel build ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
