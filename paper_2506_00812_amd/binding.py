@@ -112,13 +112,14 @@ class Index:
     def __init__(self, handle, vectors):
         self._h = handle
         self.vectors = vectors
+        self._free = load_library().vf_index_free  # bound here: module globals may be gone at interpreter exit
 
     def __del__(self):
         self.free()
 
     def free(self):
         if getattr(self, "_h", None):
-            load_library().vf_index_free(self._h)
+            self._free(self._h)
             self._h = None
 
     def stats(self) -> dict:

@@ -213,11 +213,12 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     p.res_idx = cand_idx.as<int32_t>(); p.res_bits = cand_dist.as<uint32_t>();
     p.others_off = nullptr; p.others = nullptr; p.meta = ix->meta();
     if (TR == 16) {
-        // long lists go panel by panel (about 1 MiB of list each) so that the resident waves share L2
-        // (VF_BUILD_PANEL_KB: panel size, 1024 by default; lists of up to 16 panels are not cut)
-        static const int64_t panel_bytes = (int64_t)std::max(1, env_int_early("VF_BUILD_PANEL_KB", 1024)) << 10;
+        // long lists go panel by panel so that the resident waves share L2
+        // (VF_BUILD_PANEL_KB: panel size, 4096 by default -- the measured optimum, one XCD's L2; lists of
+        // up to 4 panels are not cut)
+        static const int64_t panel_bytes = (int64_t)std::max(1, env_int_early("VF_BUILD_PANEL_KB", 4096)) << 10;
         const int64_t list_bytes = n_groups * (int64_t)ix->group_bytes();
-        if (list_bytes <= 16 * panel_bytes) {
+        if (list_bytes <= 4 * panel_bytes) {
             launch_scan16(p, (int)n_tiles, s);
         } else {
             const int32_t panel = (int32_t)std::max<int64_t>(32, panel_bytes / ((int64_t)ix->group_bytes() / 32) / 32 * 32);

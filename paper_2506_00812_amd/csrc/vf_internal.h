@@ -64,7 +64,7 @@ struct ScanParams {
     // Panel mode (scan_topk16_kernel, panel_n > 0): every item of the launch covers only list entries
     // [panel_entry0, panel_entry0 + panel_n) of its list (multiples of 32); with carry != 0 a row's K best
     // start from the partial row a previous launch left in res_idx / res_bits.  Launching the panels of a
-    // long list one after the other keeps all resident waves on the same megabyte, which every XCD's L2
+    // long list one after the other keeps all resident waves on the same few megabytes, which every XCD's L2
     // then serves: the kNN self-join of a 400,000-vector list is otherwise bound by HBM bandwidth.
     int32_t panel_entry0, panel_n, carry;
     int64_t *out_ids;       // final output [*][K] (items with part_row < 0): row = qrow value

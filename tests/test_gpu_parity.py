@@ -453,7 +453,7 @@ def test_float_multi_search(vf, mode_name):
 
 def test_float_graph_build_in_panels():
     """Long float32 lists are self-joined panel by panel with the rows' best-so-far carried between
-    launches.  With the panel forced down to one 32-vector group every list of this workload takes
+    launches.  With the panel forced down to one 32-vector group every list of more than 128 vectors takes
     that route (hundreds of launches per list): the graph rows must still be the oracle's."""
     import subprocess
     import sys
