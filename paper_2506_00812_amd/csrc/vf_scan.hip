@@ -38,6 +38,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 #ifndef VF_SCAN_WAVES
 #define VF_SCAN_WAVES 2
 #endif
+#ifndef VF_SCAN16_WAVES
+#define VF_SCAN16_WAVES 2
+#endif
 #ifndef VF_DRAIN_ROWS
 #define VF_DRAIN_ROWS 4
 #endif
@@ -435,13 +438,15 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
 
 // float32 search tiles of <= 16 queries: the same selection around v_mfma_f32_16x16x4_f32, which
 // spends half the matrix-core time of a 32-row tile on them.  Lane (c = lane % 16, kq = lane / 16):
-//   A operand  row c of the query tile, the 16-byte chunks 4 s + kq (s = 0 .. chunks / 4 - 1);
+//   A operand  row c of the query tile, the 16-byte chunks 4 s + kq (s = 0 .. chunks / 4 - 1), read
+//              from global memory once and kept in registers for the whole item (two waves per SIMD
+//              leave room for it without spills; the workgroup's LDS holds only queues and lists);
 //   B operand  list entries c (column block 0) and 16 + c (block 1) of the group, the same chunks;
 //              the four components of a chunk feed four consecutive MFMAs, so the contraction
 //              index runs over (s, kq, component) on both operands alike;
 //   D          rows 4 kq + i (i = 0..3) x entry c of each column block.
 template <int NCP>
-__global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
+__global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
     typedef float v4f __attribute__((ext_vector_type(4)));
@@ -458,8 +463,7 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5, c16 = lane & 15, kq = lane >> 4;
     const int K = p.K, KS = K | 1, TR = p.tile_rows;   // TR <= 16
 
-    uint4 *qtile = smem;                                         // [NCH][TR]
-    uint64_t *pend = (uint64_t *)(smem + NCH * TR);              // [TR][PC]
+    uint64_t *pend = (uint64_t *)smem;                           // [TR][PC]
     uint64_t *best = pend + TR * PC;                             // [TR][KS]
     int32_t *qrow_s = (int32_t *)(best + TR * KS);               // [32]
     uint32_t *qnorm_s = (uint32_t *)(qrow_s + 32);               // [32]
@@ -478,23 +482,26 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
             }
         }
     }
+    // A operand, resident in registers for the whole item: lane (c16, kq) holds chunks 4 sq + kq of
+    // query row c16 (zeros for a row the tile does not have); the row's squared norm is summed over
+    // the four lanes that share it
+    uint4 areg[NS];
     {
-        // lane (r = n32, h) copies chunks h, h+2, ... of query row r and sums their squares
-        const int qr = n32 < TR ? qrow_s[n32] : -1;
+        const int qr = c16 < it.q_count ? qrow_s[c16] : -1;
         const char *qp = (const char *)p.qsrc + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
         float acc = 0.f;
 #pragma unroll
-        for (int c0 = 0; c0 < NCP; ++c0) {
-            const int c = 2 * c0 + h;
+        for (int sq = 0; sq < NS; ++sq) {
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (qr >= 0) v = *(const uint4 *)(qp + c * kChunkBytes);
-            if (n32 < TR) qtile[c * TR + n32] = v;
+            if (qr >= 0) v = *(const uint4 *)(qp + (4 * sq + kq) * kChunkBytes);
+            areg[sq] = v;
             const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc += f[i] * f[i];
         }
+        acc += __shfl_xor(acc, 16);
         acc += __shfl_xor(acc, 32);
-        if (h == 0) qnorm_s[n32] = __float_as_uint(acc);
+        if (kq == 0) qnorm_s[c16] = __float_as_uint(acc);
     }
     __syncthreads();
 
@@ -559,12 +566,6 @@ __global__ __launch_bounds__(64, 3) void scan_topk16_kernel(ScanParams p)
         v4f acc[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) acc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-        uint4 areg[NS];
-#pragma unroll
-        for (int sq = 0; sq < NS; ++sq) {
-            areg[sq] = make_uint4(0, 0, 0, 0);
-            if (c16 < TR) areg[sq] = qtile[(4 * sq + kq) * TR + c16];
-        }
         const float xn[2] = {xn_next[0], xn_next[1]};
         const int32_t gid[2] = {gid_next[0], gid_next[1]};
 #pragma unroll
@@ -839,7 +840,7 @@ bool scan16_supported(int dtype, int dim, int tile_rows)
 void launch_scan16(const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
-    const size_t lds = scan_lds_bytes(p);
+    const size_t lds = (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;   // no query tile: it lives in registers
     if (p.dim == 128) hipLaunchKernelGGL((scan_topk16_kernel<16>), dim3(n_items), dim3(64), lds, s, p);
     else hipLaunchKernelGGL((scan_topk16_kernel<12>), dim3(n_items), dim3(64), lds, s, p);
 }
