@@ -185,6 +185,53 @@ __device__ __forceinline__ void wave_drain_rows(uint64_t *pend, int PC, uint64_t
     pcv = 0;
 }
 
+// The rows whose queue holds at most SEG keys (K <= SEG), 64 / SEG of them at a time: one row per
+// aligned segment of SEG lanes, the sort and merge networks confined to the segment.  After the
+// first drain of an item almost every row is of this kind (a handful of keys passed the row's
+// threshold), and a 16-lane network has 10 + 4 stages for four rows where the 64-lane one has
+// 21 + 6 for each.  Rows it has merged leave with pcv = 0.
+template <int SEG>
+__device__ __forceinline__ void wave_drain_rows_packed(const uint64_t *pend, int PC, uint64_t *best, int KS, int K,
+                                                       int &pcv, uint64_t &row_kth, int lane)
+{
+    constexpr int NSEG = 64 / SEG;
+    const int seg = lane / SEG, ls = lane % SEG;
+    uint32_t todo = (uint32_t)__ballot(lane < 32 && pcv > 0 && pcv <= SEG);
+    const uint32_t merged = todo;
+    while (todo != 0) {
+        int r = -1;   // the row of this lane's segment
+#pragma unroll
+        for (int u = 0; u < NSEG; ++u) {
+            const int ru = todo != 0 ? __builtin_ctz(todo) : -1;
+            if (u == seg) r = ru;
+            todo &= todo - 1;
+        }
+        const int rs = r >= 0 ? r : 0;
+        const int pc_rs = __shfl(pcv, rs);   // outside any condition: a cross-lane read needs its source lane active
+        const int pc = r >= 0 ? pc_rs : 0;
+        const uint32_t klo = __shfl((uint32_t)row_kth, rs), khi = __shfl((uint32_t)(row_kth >> 32), rs);
+        const uint64_t kth = ((uint64_t)khi << 32) | klo;
+        uint64_t x = ls < pc ? pend[rs * PC + ls] : KEY_MAX;
+        x = x < kth ? x : KEY_MAX;
+        x = wave_sort_segments<SEG>(x, lane);
+        const int bi = SEG - 1 - ls;   // the row's best list, reversed
+        const uint64_t w = (r >= 0 && bi < K) ? best[rs * KS + bi] : KEY_MAX;
+        x = w < x ? w : x;             // ascending min descending: the SEG smallest, bitonic
+#pragma unroll
+        for (int j = SEG / 2; j > 0; j >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)x, j), hi = __shfl_xor((uint32_t)(x >> 32), j);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            const uint64_t mn = x < o ? x : o, mx = x < o ? o : x;
+            x = (lane & j) == 0 ? mn : mx;
+        }
+        if (r >= 0 && ls < K) best[rs * KS + ls] = x;
+    }
+    if (merged != 0) {
+        wave_lds_sync();
+        if (lane < 32 && ((merged >> lane) & 1u)) { row_kth = best[lane * KS + K - 1]; pcv = 0; }
+    }
+}
+
 template <int DT, int NCP>
 __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams p)
 {
@@ -294,6 +341,8 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
     // belongs to row 8*(j/4) + 4*h + (j%4)).
     auto drain = [&]() {
         wave_lds_sync();
+        if (K <= 16) wave_drain_rows_packed<16>(pend, PC, best, KS, K, pcv, row_kth, lane);
+        if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv, row_kth, lane);
         wave_drain_rows<VF_DRAIN_ROWS>(pend, PC, best, KS, K, pcv, row_kth, lane);
         if (lane < 32) pcnt[lane] = 0;
         wave_lds_sync();
@@ -534,6 +583,8 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
 
     auto drain = [&]() {
         wave_lds_sync();
+        if (K <= 16) wave_drain_rows_packed<16>(pend, PC, best, KS, K, pcv, row_kth, lane);
+        if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv, row_kth, lane);
         wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
         if (lane < 32) pcnt[lane] = 0;
         wave_lds_sync();
@@ -751,6 +802,8 @@ __global__ __launch_bounds__(64) void scan_valu_kernel(ScanParams p)
         }
         if (__any(pcv > PC - 64) || (step + 1 == n_steps && __any(pcv != 0))) {
             wave_lds_sync();
+            if (K <= 16) wave_drain_rows_packed<16>(pend, PC, best, KS, K, pcv, row_kth, lane);
+            if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv, row_kth, lane);
             wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
             wave_lds_sync();
         }
