@@ -27,6 +27,8 @@
 // both types the kNN self-joins of the index build and the ground truth).  scan_topk16_kernel:
 // float32 search tiles, which hold at most 16 queries, on the 16x16x4 MFMA.  scan_valu_kernel:
 // float32 tiles of small batches on plain FMAs.
+#include <type_traits>
+
 #include "vf_device.h"
 
 namespace vf {
@@ -494,7 +496,7 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
 //              the four components of a chunk feed four consecutive MFMAs, so the contraction
 //              index runs over (s, kq, component) on both operands alike;
 //   D          rows 4 kq + i (i = 0..3) x entry c of each column block.
-template <int NCP>
+template <int NCP, bool AND>
 __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
@@ -565,13 +567,12 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
         thr[i] = 0xFFFFFFFFu;
         if (row < it.q_count) {
             live |= 1u << i;
-            if (p.others_off != nullptr) {
+            if (AND) {
                 const int qr = qrow_s[row];
                 if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << i;
             }
         }
     }
-    const bool any_and = __any(and_rows != 0);
     int pcv = 0;                  // state of tile row r, held by lane r
     uint64_t row_kth = KEY_MAX;
     if (carry) {
@@ -596,47 +597,74 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
     const int n_groups = (it.n + kGroup - 1) / kGroup;
     // segment-relative index of the entry that equals this lane's row 4 kq (graph build), else never matched
     const int self0 = it.self_base >= 0 ? it.self_base + 4 * kq - it.entry0 : -0x40000000;
-    // B registers of both column blocks; each block is refilled with the next group's chunks right
-    // after its own MFMAs have been issued
-    uint4 breg[2][NS];
-    float xn_next[2];
-    int32_t gid_next[2] = {-1, -1};
-    {
-        const uint4 *blk0 = p.xblk + it.group0 * (int64_t)(NCH * 32);
+    // B registers: two groups (slots 0 and 1, even and odd groups), each of two column blocks.  A slot is
+    // refilled with the chunks of the group after next right after its own MFMAs have been issued, so a
+    // wave keeps up to two groups (32 KiB at dim 128) of list in flight (kNN self-joins of the index
+    // build: 12 % faster than with one group of distance; search tiles: unchanged).
+    // Nothing else is prefetched: a scalar carried from one step to the next gets copied at the top of the
+    // loop, and that copy would wait for every load issued before it.  The entries' norms are summed from
+    // the B registers (in the shadow of the MFMAs) and the AND predicate fetches global ids on demand.
+    uint4 breg[2][2][NS];
+    auto fetch_block = [&](int slot, int g, int cb) {   // group g (exists), column block cb -> slot
+        const uint4 *blk = p.xblk + (it.group0 + g) * (int64_t)(NCH * 32);
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
+        for (int sq = 0; sq < NS; ++sq) breg[slot][cb][sq] = blk[(4 * sq + kq) * 32 + cb * 16 + c16];
+    };
+    // Every fetch is unconditional (past the end the last group is fetched again, from L2): with a fetch
+    // under a condition the compiler cannot tell which loads are outstanding where the paths meet, and
+    // its waits then cover all of them, the block just requested included.
+    const int last_group = n_groups - 1;
 #pragma unroll
-            for (int sq = 0; sq < NS; ++sq) breg[cb][sq] = blk0[(4 * sq + kq) * 32 + cb * 16 + c16];
-            xn_next[cb] = ((const float *)p.xnorm)[it.group0 * kGroup + cb * 16 + c16];
-            if (any_and && cb * 16 + c16 < it.n) gid_next[cb] = p.map[it.map_off + it.entry0 + cb * 16 + c16];
-        }
+    for (int slot = 0; slot < 2; ++slot) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) fetch_block(slot, slot < last_group ? slot : last_group, cb);
+        __builtin_amdgcn_sched_barrier(0);   // the loads stay in this order, here and in the loop
     }
-    for (int grp = 0; grp < n_groups; ++grp) {
-        const bool more = grp + 1 < n_groups;
-        const uint4 *nblk = p.xblk + (it.group0 + grp + 1) * (int64_t)(NCH * 32);
+    for (int grp0 = 0; grp0 < n_groups; grp0 += 2) {
+#pragma unroll
+      for (int slot = 0; slot < 2; ++slot) {
+        // (an odd number of groups ends with a phantom step on the re-fetched last group, every column
+        // masked: a way out between the two steps would be one more path into the loop's end, one on
+        // which slot 0 holds the newest loads, and the waits at the top would cover slot 1's as well)
+        const int grp = grp0 + slot;
+        const int refill = grp + 2 < last_group ? grp + 2 : last_group;
         v4f acc[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) acc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
-        const float xn[2] = {xn_next[0], xn_next[1]};
-        const int32_t gid[2] = {gid_next[0], gid_next[1]};
+        // the two column blocks are two independent accumulation chains: issued alternately they keep the
+        // matrix core busy (one chain alone issues every 52 cycles, two every 32)
+#pragma unroll
+        for (int sq = 0; sq < NS; ++sq) {
+            const uint4 a = areg[sq], b0 = breg[slot][0][sq], b1 = breg[slot][1][sq];
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b0.x), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b1.x), acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b0.y), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b1.y), acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b0.z), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b1.z), acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b0.w), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b1.w), acc[1], 0, 0, 0);
+        }
+        // |x|^2 of this lane's two entries: its own chunks, then the four lanes that share an entry
+        float xn[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
+            float s0 = 0.f, s1 = 0.f;
 #pragma unroll
             for (int sq = 0; sq < NS; ++sq) {
-                const uint4 a = areg[sq], b = breg[cb][sq];
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc[cb], 0, 0, 0);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc[cb], 0, 0, 0);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc[cb], 0, 0, 0);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc[cb], 0, 0, 0);
+                const uint4 b = breg[slot][cb][sq];
+                const float f[4] = {__uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w)};
+                s0 += f[0] * f[0]; s1 += f[1] * f[1]; s0 += f[2] * f[2]; s1 += f[3] * f[3];
             }
-            if (more) {
-#pragma unroll
-                for (int sq = 0; sq < NS; ++sq) breg[cb][sq] = nblk[(4 * sq + kq) * 32 + cb * 16 + c16];
-                xn_next[cb] = ((const float *)p.xnorm)[(it.group0 + grp + 1) * kGroup + cb * 16 + c16];
-                if (any_and && (grp + 1) * kGroup + cb * 16 + c16 < it.n)
-                    gid_next[cb] = p.map[it.map_off + it.entry0 + (grp + 1) * kGroup + cb * 16 + c16];
-            }
+            float t = s0 + s1;
+            t += __shfl_xor(t, 16);
+            t += __shfl_xor(t, 32);
+            xn[cb] = t;
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) fetch_block(slot, refill, cb);
+        __builtin_amdgcn_sched_barrier(0);
 
         // phase 1 (branch-free): distances and threshold tests of this lane's 4 rows x 2 entries
         uint32_t bitsv[8];
@@ -654,14 +682,15 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
                 pm |= (below & not_self & (col_ok >> i) & 1u) << (cb * 4 + i);
             }
         }
-        if (any_and && pm != 0) {
+        if (AND && pm != 0) {
 #pragma unroll
             for (int b = 0; b < 8; ++b) {
                 if (((pm >> b) & 1u) && ((and_rows >> (b & 3)) & 1u)) {
                     const int qr = qrow_s[4 * kq + (b & 3)];
                     const int o_begin = p.others_off[qr], o_end = p.others_off[qr + 1];
                     bool ok = true;
-                    for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(p.meta, p.others[o], gid[b >> 2]);
+                    const int32_t gid = p.map[it.map_off + it.entry0 + grp * kGroup + (b >> 2) * 16 + c16];
+                    for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(p.meta, p.others[o], gid);
                     if (!ok) pm &= ~(1u << b);
                 }
             }
@@ -683,6 +712,7 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
             pcv = lane < 32 ? (int)pcnt[lane] : 0;
         }
         if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
+      }
     }
     __syncthreads();
 
@@ -894,8 +924,16 @@ void launch_scan16(const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
     const size_t lds = (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;   // no query tile: it lives in registers
-    if (p.dim == 128) hipLaunchKernelGGL((scan_topk16_kernel<16>), dim3(n_items), dim3(64), lds, s, p);
-    else hipLaunchKernelGGL((scan_topk16_kernel<12>), dim3(n_items), dim3(64), lds, s, p);
+    // two instantiations: with loads of the AND predicate inside the loop the compiler can no longer count
+    // which outstanding loads a wait must cover, and every wait becomes a wait for all of them
+    const bool with_and = p.others_off != nullptr;
+    if (p.dim == 128) {
+        if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<16, true>), dim3(n_items), dim3(64), lds, s, p);
+        else hipLaunchKernelGGL((scan_topk16_kernel<16, false>), dim3(n_items), dim3(64), lds, s, p);
+    } else {
+        if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<12, true>), dim3(n_items), dim3(64), lds, s, p);
+        else hipLaunchKernelGGL((scan_topk16_kernel<12, false>), dim3(n_items), dim3(64), lds, s, p);
+    }
 }
 
 bool scan_valu_supported(int dtype, int dim, int tile_rows)
