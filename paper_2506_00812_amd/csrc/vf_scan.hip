@@ -711,7 +711,7 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
             wave_lds_sync();
             pcv = lane < 32 ? (int)pcnt[lane] : 0;
         }
-        if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
+        if (__any(pcv >= PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
       }
     }
     __syncthreads();
