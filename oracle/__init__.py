@@ -50,6 +50,10 @@ def lib():
             getattr(L, name).argtypes = [p]
         L.vfo_graph_row.restype = C.c_int
         L.vfo_graph_row.argtypes = [p, i32, i64, p]
+        L.vfo_build_pruned.restype = p
+        L.vfo_build_pruned.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, i32, C.c_int]
+        L.vfo_pruned_row.restype = C.c_int
+        L.vfo_pruned_row.argtypes = [p, i32, i64, i32, p]
         L.vfo_dist_f32_ordered.restype = C.c_float
         L.vfo_dist_f32_ordered.argtypes = [p, p, i32]
         L.vfo_dist_u8.restype = i32
@@ -77,7 +81,10 @@ def _view(addr, n, dtype):
 class OracleIndex:
     """Dual-structured label-centric index (Alg. 1) built on the CPU."""
 
-    def __init__(self, vectors, label_offsets, label_ids, n_labels, T, graph_degree, lazy_graph=False, n_threads=0):
+    def __init__(self, vectors, label_offsets, label_ids, n_labels, T, graph_degree, lazy_graph=False, n_threads=0,
+                 knn_degree=0):
+        """knn_degree = D > 0: the graphs are built with degree D and reduced to graph_degree by rank-based
+        pruning and reverse edges (vfo_build_pruned); 0: the exact graph_degree-nearest-neighbour graphs."""
         self.vectors = np.ascontiguousarray(vectors)
         self.dtype = str(self.vectors.dtype)
         self.n, self.dim = self.vectors.shape
@@ -85,9 +92,17 @@ class OracleIndex:
         self.label_ids = np.ascontiguousarray(label_ids, dtype=np.int32)
         self.n_labels, self.T, self.R = int(n_labels), int(T), int(graph_degree)
         self.n_threads = n_threads or (os.cpu_count() or 1)
-        self._h = lib().vfo_build(_ptr(self.vectors), _DT[self.dtype], self.n, self.dim, _ptr(self.label_offsets),
-                                  _ptr(self.label_ids), self.n_labels, self.T, self.R, int(lazy_graph),
-                                  self.n_threads)
+        self.knn_degree = int(knn_degree)
+        if self.knn_degree > 0:
+            if lazy_graph:
+                raise ValueError("a pruned graph cannot be built row by row (reverse edges need every row)")
+            self._h = lib().vfo_build_pruned(_ptr(self.vectors), _DT[self.dtype], self.n, self.dim,
+                                             _ptr(self.label_offsets), _ptr(self.label_ids), self.n_labels, self.T,
+                                             self.R, self.knn_degree, self.n_threads)
+        else:
+            self._h = lib().vfo_build(_ptr(self.vectors), _DT[self.dtype], self.n, self.dim, _ptr(self.label_offsets),
+                                      _ptr(self.label_ids), self.n_labels, self.T, self.R, int(lazy_graph),
+                                      self.n_threads)
         if not self._h:
             raise ValueError("vfo_build rejected its arguments")
         self.lazy = bool(lazy_graph)
@@ -131,6 +146,13 @@ class OracleIndex:
         if self.lazy:
             raise RuntimeError("lazy index: use graph_row()")
         return _view(lib().vfo_G_HS(self._h), self.n_HS * self.R, np.int32).reshape(-1, self.R)
+
+    def pruned_row(self, label, j, knn_degree):
+        """Forward row (pruning step only) of one vertex, from brute-force degree-D rows of it and its neighbours."""
+        row = np.empty(self.R, dtype=np.int32)
+        if lib().vfo_pruned_row(self._h, int(label), int(j), int(knn_degree), _ptr(row)) != 0:
+            raise IndexError((label, j))
+        return row
 
     def graph_row(self, label, j):
         row = np.empty(self.R, dtype=np.int32)

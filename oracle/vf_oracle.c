@@ -22,8 +22,12 @@
  *   - distance = squared Euclidean, no square root;
  *   - C_l is kept in ascending global id, so local order == global order;
  *   - the per-list graph is the exact R-nearest-neighbour graph, rows ordered by
- *     (distance, local id);  CAGRA's NN-descent + reordering is not specified by
- *     the paper and is not reproduced;
+ *     (distance, local id);  CAGRA's NN-descent is not specified by the paper and
+ *     is not reproduced.  Optionally (vfo_build_pruned) that graph is built with a
+ *     larger degree D and reduced to R the way the CAGRA paper (Ootomo et al. 2023,
+ *     Section 3.2 "graph optimization") describes: rank-based counting of
+ *     detourable routes, then reverse edges -- see optimize_list() for the exact
+ *     rules chosen where that description leaves freedom;
  *   - seeds are ns = min(n_seeds, n) stratified local ids floor(j*n/ns), the same
  *     for every query of a label (the paper: random sampling confined to the
  *     label's size);
@@ -211,9 +215,9 @@ static inline int less_di(float d1, int32_t i1, float d2, int32_t i2)
 
 /* Row j of label l's graph: the R nearest other members of X_l as local ids,
  * ordered by (distance, local id). */
-static void build_row(const vfo_index *ix, int64_t base, int64_t n, int64_t j, int32_t *row)
+static void build_row_deg(const vfo_index *ix, int64_t base, int64_t n, int64_t j, int32_t R, int32_t *row)
 {
-    int32_t R = ix->R, cnt = 0;
+    int32_t cnt = 0;
     dist_id *best = (dist_id *)malloc(sizeof(dist_id) * (R + 1));
     size_t es = ix->dtype == VFO_U8 ? 1 : 4;
     const void *xj = (const char *)ix->X + (int64_t)ix->M_HS[base + j] * ix->dim * es;
@@ -228,6 +232,11 @@ static void build_row(const vfo_index *ix, int64_t base, int64_t n, int64_t j, i
     }
     for (int32_t e = 0; e < R; ++e) row[e] = e < cnt ? best[e].id : -1;
     free(best);
+}
+
+static void build_row(const vfo_index *ix, int64_t base, int64_t n, int64_t j, int32_t *row)
+{
+    build_row_deg(ix, base, n, j, ix->R, row);
 }
 
 static const int32_t *graph_row(vfo_index *ix, int64_t base, int64_t n, int64_t j)
@@ -323,6 +332,152 @@ vfo_index *vfo_build(const void *X, int dtype, int64_t n, int32_t dim, const int
         }
     }
     return ix;
+}
+
+/* ------------------------------------------------------------------ graph optimisation (optional)
+ *
+ * knn: [n][D] rows of one list, local ids ordered by (distance, id): position = rank.
+ * Step 1, pruning.  The edge x -> y_j (rank j in x's row) can be detoured through y_i when
+ *   i < j and y_j stands in y_i's row at a rank r < j: both hops are then "shorter" (in rank)
+ *   than the direct edge.  c_j counts such (i, r) pairs.  The R edges with the smallest
+ *   (c_j, j) are kept, in that order: the forward row F[x].
+ * Step 2, reverse edges.  Every forward edge x -> y at position p of F[x] proposes x as a
+ *   neighbour of y; y's proposals are ordered by (p, x) and the first R form B[y].
+ * Step 3, merge.  Row of y = the first floor(R/2) entries of F[y] (always kept), then the
+ *   first R - floor(R/2) entries of B[y] that are not among those, then the remaining
+ *   entries of F[y], in order, that are not yet in the row, until it holds R entries.
+ * Everything is integer work on ranks and ids: no distance is evaluated. */
+
+typedef struct { int32_t c, j; } cnt_rank;
+static int cmp_cnt_rank(const void *a, const void *b)
+{
+    const cnt_rank *x = (const cnt_rank *)a, *y = (const cnt_rank *)b;
+    if (x->c != y->c) return (x->c > y->c) - (x->c < y->c);
+    return (x->j > y->j) - (x->j < y->j);
+}
+typedef struct { int32_t p, x; } pos_src;
+static int cmp_pos_src(const void *a, const void *b)
+{
+    const pos_src *u = (const pos_src *)a, *v = (const pos_src *)b;
+    if (u->p != v->p) return (u->p > v->p) - (u->p < v->p);
+    return (u->x > v->x) - (u->x < v->x);
+}
+
+static void prune_row(const int32_t *knn, int32_t D, int32_t R, int64_t x, int32_t *frow)
+{
+    const int32_t *row = knn + x * D;
+    cnt_rank *cr = (cnt_rank *)malloc(sizeof(cnt_rank) * D);
+    int32_t valid = 0;
+    for (int32_t j = 0; j < D; ++j) {
+        if (row[j] < 0) continue;
+        int32_t c = 0;
+        for (int32_t i = 0; i < j; ++i) {
+            if (row[i] < 0) continue;
+            const int32_t *via = knn + (int64_t)row[i] * D;
+            for (int32_t r = 0; r < j && r < D; ++r)
+                if (via[r] == row[j]) ++c;
+        }
+        cr[valid].c = c; cr[valid].j = j; ++valid;
+    }
+    qsort(cr, valid, sizeof(cnt_rank), cmp_cnt_rank);
+    for (int32_t p = 0; p < R; ++p) frow[p] = p < valid ? row[cr[p].j] : -1;
+    free(cr);
+}
+
+static void optimize_list(const int32_t *knn, int64_t n, int32_t D, int32_t R, int32_t *G, int n_threads)
+{
+    int32_t *F = (int32_t *)malloc(sizeof(int32_t) * n * R);
+#pragma omp parallel for schedule(dynamic, 64) num_threads(n_threads > 0 ? n_threads : 1)
+    for (int64_t x = 0; x < n; ++x) prune_row(knn, D, R, x, F + x * R);
+
+    /* proposals (p, x) grouped by target y */
+    int64_t *off = (int64_t *)calloc(n + 1, sizeof(int64_t));
+    for (int64_t e = 0; e < n * R; ++e)
+        if (F[e] >= 0) off[F[e] + 1]++;
+    for (int64_t y = 0; y < n; ++y) off[y + 1] += off[y];
+    pos_src *prop = (pos_src *)malloc(sizeof(pos_src) * (off[n] > 0 ? off[n] : 1));
+    int64_t *cur = (int64_t *)malloc(sizeof(int64_t) * (n > 0 ? n : 1));
+    memcpy(cur, off, sizeof(int64_t) * n);
+    for (int64_t x = 0; x < n; ++x)
+        for (int32_t p = 0; p < R; ++p) {
+            int32_t y = F[x * R + p];
+            if (y >= 0) { prop[cur[y]].p = p; prop[cur[y]].x = (int32_t)x; cur[y]++; }
+        }
+    free(cur);
+
+    const int32_t half = R / 2;
+#pragma omp parallel for schedule(dynamic, 64) num_threads(n_threads > 0 ? n_threads : 1)
+    for (int64_t y = 0; y < n; ++y) {
+        pos_src *py = prop + off[y];
+        int64_t np = off[y + 1] - off[y];
+        qsort(py, np, sizeof(pos_src), cmp_pos_src);
+        int32_t *out = G + y * R;
+        const int32_t *f = F + y * R;
+        int32_t cnt = 0;
+        for (int32_t p = 0; p < half; ++p) out[cnt++] = f[p];
+        int32_t nb = 0;
+        for (int64_t t = 0; t < np && t < R && nb < R - half; ++t) {
+            int32_t x = py[t].x, dup = 0;
+            for (int32_t p = 0; p < half; ++p) dup |= f[p] == x;
+            if (!dup) { out[cnt++] = x; ++nb; }
+        }
+        for (int32_t p = half; p < R && cnt < R; ++p) {
+            int32_t dup = f[p] < 0;
+            for (int32_t t = 0; t < cnt; ++t) dup |= out[t] == f[p];
+            if (!dup) out[cnt++] = f[p];
+        }
+        while (cnt < R) out[cnt++] = -1;
+    }
+    free(prop); free(off); free(F);
+}
+
+/* The index of vfo_build, its graphs built with degree D >= R and reduced to R by
+ * optimize_list().  Needs T >= D + 1.  Returns NULL on invalid arguments. */
+vfo_index *vfo_build_pruned(const void *X, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                            const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t R, int32_t D,
+                            int n_threads)
+{
+    if (D < R || T < D + 1) return NULL;
+    vfo_index *ix = vfo_build(X, dtype, n, dim, label_offsets, label_ids, n_labels, T, R, 1, n_threads);
+    if (!ix) return NULL;
+    for (int32_t l = 0; l < n_labels; ++l) {
+        if (ix->O_HS[l] < 0) continue;
+        int64_t base = ix->O_HS[l], nl = ix->S[l];
+        int32_t *knn = (int32_t *)malloc(sizeof(int32_t) * nl * D);
+#pragma omp parallel for schedule(dynamic, 8) num_threads(n_threads > 0 ? n_threads : 1)
+        for (int64_t j = 0; j < nl; ++j) build_row_deg(ix, base, nl, j, D, knn + j * D);
+        optimize_list(knn, nl, D, R, ix->G_HS + base * R, n_threads);
+        free(knn);
+        memset(ix->G_built + base, 1, nl);
+    }
+    ix->lazy = 0;
+    return ix;
+}
+
+/* Forward row F[j] (step 1 only) of one vertex of label's list: needs the degree-D rows of j and
+ * of its D neighbours, computed here by brute force, so single rows of lists of any size can be
+ * checked.  Returns 0 on success. */
+int vfo_pruned_row(const vfo_index *ix, int32_t label, int64_t j, int32_t D, int32_t *row_out)
+{
+    if (label < 0 || label >= ix->n_labels || ix->O_HS[label] < 0) return -1;
+    int64_t base = ix->O_HS[label], nl = ix->S[label];
+    if (j < 0 || j >= nl || D < ix->R || nl < D + 1) return -1;
+    int32_t *own = (int32_t *)malloc(sizeof(int32_t) * D);
+    build_row_deg(ix, base, nl, j, D, own);
+    cnt_rank *cr = (cnt_rank *)malloc(sizeof(cnt_rank) * D);
+    int32_t *via = (int32_t *)malloc(sizeof(int32_t) * D * D);
+    for (int32_t i = 0; i < D; ++i) build_row_deg(ix, base, nl, own[i], D, via + (int64_t)i * D);
+    for (int32_t t = 0; t < D; ++t) {
+        int32_t c = 0;
+        for (int32_t i = 0; i < t; ++i)
+            for (int32_t r = 0; r < t; ++r)
+                if (via[(int64_t)i * D + r] == own[t]) ++c;
+        cr[t].c = c; cr[t].j = t;
+    }
+    qsort(cr, D, sizeof(cnt_rank), cmp_cnt_rank);
+    for (int32_t p = 0; p < ix->R; ++p) row_out[p] = own[cr[p].j];
+    free(via); free(cr); free(own);
+    return 0;
 }
 
 /* ------------------------------------------------------------------ export */

@@ -517,3 +517,102 @@ def test_multi_search_rejects_bad_arguments(tiny, tiny_oracle):
         tiny_oracle.search_multi(tiny.queries[:4], np.arange(5), np.zeros(4, dtype=np.int32), 7, 10)
     with pytest.raises(ValueError):
         tiny_oracle.search_multi(tiny.queries[:4], np.arange(5), np.full(4, 10 ** 6, dtype=np.int32), oracle.OR, 10)
+
+
+# ------------------------------------------------------------------ pruned graphs (rank-based pruning + reverse edges)
+
+def _one_label_index(X, R, D, dtype):
+    """All points carry label 0 (one graph list, local id == global id)."""
+    n = len(X)
+    off = np.arange(n + 1, dtype=np.int64)
+    ids = np.zeros(n, dtype=np.int32)
+    return OracleIndex(np.ascontiguousarray(X.astype(dtype)), off, ids, 1, D + 1, R, knn_degree=D)
+
+
+def _rules_in_python(X, R, D):
+    """The three steps written out a second time with Python sets and tuple sorts (uint8 data: exact distances)."""
+    n = len(X)
+    Xi = X.astype(np.int64)
+    d = ((Xi[:, None, :] - Xi[None, :, :]) ** 2).sum(-1)
+    np.fill_diagonal(d, np.iinfo(np.int64).max)
+    knn = [sorted(range(n), key=lambda c: (d[x, c], c))[:D] for x in range(n)]
+    F = []
+    for x in range(n):
+        keyed = []
+        for j, y in enumerate(knn[x]):
+            c = sum(1 for i in range(j) for r in range(j) if knn[knn[x][i]][r] == y)
+            keyed.append((c, j, y))
+        F.append([y for _, _, y in sorted(keyed)[:R]])
+    proposals = {y: [] for y in range(n)}
+    for x in range(n):
+        for p, y in enumerate(F[x]):
+            proposals[y].append((p, x))
+    G = []
+    for y in range(n):
+        row = list(F[y][:R // 2])
+        back = [x for _, x in sorted(proposals[y])[:R]]
+        row += [x for x in back if x not in row][:R - R // 2]
+        row += [v for v in F[y][R // 2:] if v not in row][:R - len(row)]
+        G.append(row)
+    return np.array(knn), np.array(F), np.array(G)
+
+
+def test_pruned_graph_equals_the_rules_written_out_in_python():
+    rng = np.random.default_rng(5)
+    X = rng.integers(0, 256, size=(150, 16)).astype(np.uint8)
+    for R, D in ((4, 8), (6, 9), (5, 5)):
+        ix = _one_label_index(X, R, D, np.uint8)
+        _, F, G = _rules_in_python(X, R, D)
+        assert np.array_equal(ix.G_HS, G), (R, D)
+        for j in (0, 17, 149):
+            assert np.array_equal(ix.pruned_row(0, j, D), F[j])
+
+
+def test_pruned_graph_of_points_on_a_line_is_the_chain():
+    # positions 0, 1, 2, ...: the degree-4 row of an interior x is [x-1, x+1, x-2, x+2] (ties to the
+    # lower id); x-2 is reached through x-1 and x+2 through x+1, so pruning to R = 2 leaves
+    # [x-1, x+1]; x-1 proposes x at position 1 and x+1 proposes x at position 0, hence B[x] = [x+1, x-1]
+    # and the merged row is [x-1, x+1]: worked by hand from the three steps.
+    n = 40
+    X = np.zeros((n, 16), dtype=np.float32)
+    X[:, 0] = np.arange(n)
+    ix = _one_label_index(X, 2, 4, np.float32)
+    G = ix.G_HS
+    for x in range(4, n - 4):
+        assert G[x].tolist() == [x - 1, x + 1], x
+
+
+def test_pruned_graph_invariants(tiny):
+    s = tiny.spec
+    R, D = s.graph_degree, 2 * s.graph_degree
+    pruned = OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, R, knn_degree=D)
+    wide = OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, D)   # exact degree-D rows
+    G, KNN = pruned.G_HS, wide.G_HS
+    S, O = pruned.S, pruned.O_HS
+    for l in np.flatnonzero(O >= 0)[:6]:
+        base, nl = int(O[l]), int(S[l])
+        g, knn = G[base:base + nl], KNN[base:base + nl]
+        assert g.min() >= 0 and g.max() < nl
+        assert not (g == np.arange(nl)[:, None]).any()                      # no self loops
+        assert all(len(set(r.tolist())) == R for r in g)                    # R distinct neighbours
+        assert np.array_equal(g[:, 0], knn[:, 0])                           # the nearest neighbour has no detour
+        fwd = [set(r.tolist()) for r in knn]
+        for y in range(nl):
+            assert set(g[y, :R // 2].tolist()) <= fwd[y]                    # kept forward edges come from the kNN row
+            for x in g[y, R // 2:]:
+                assert int(x) in fwd[y] or y in fwd[int(x)]                 # the rest: forward, or reverse of a kNN edge
+        # the single-row routine agrees with the whole-graph build on the part that is always kept
+        for j in (0, nl // 2, nl - 1):
+            assert np.array_equal(pruned.pruned_row(l, j, D)[:R // 2], g[j, :R // 2])
+
+
+def test_pruned_build_rejects_bad_arguments(tiny):
+    s = tiny.spec
+    with pytest.raises(ValueError):
+        OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, s.graph_degree,
+                    knn_degree=s.graph_degree - 1)
+    with pytest.raises(ValueError):
+        OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, 20, 16, knn_degree=32)   # T < D + 1
+    with pytest.raises(ValueError):
+        OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True,
+                    knn_degree=2 * s.graph_degree)
