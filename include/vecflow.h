@@ -70,6 +70,31 @@ int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const
                    void *hip_stream, vf_index **out);
 
 /*
+ * The same index with the per-list graphs the paper's BuildCAGRAGraph (Alg. 1) stands for in its second
+ * half: graph optimisation as in the CAGRA paper (Ootomo et al. 2023, Section 3.2).  Every graph list gets
+ * an exact kNN graph of degree knn_degree = D, which is then reduced to graph_degree = R using ranks only:
+ *   1. the edge x -> y_j (rank j in x's row) is detourable through y_i, i < j, when y_j stands at a rank
+ *      r < j in y_i's row; the R edges with the fewest such (i, r) pairs (ties: lower rank) are kept, in
+ *      that order;
+ *   2. every kept edge x -> y at position p proposes the reverse edge y -> x; a vertex keeps the R
+ *      proposals with the smallest (p, x);
+ *   3. row = the first R/2 kept edges, then up to R - R/2 reverse edges not among them, then the
+ *      remaining kept edges, in order, until the row holds R entries.
+ *
+ *   graph_kind   VF_GRAPH_KNN: exactly vf_build_index (knn_degree must be 0);
+ *                VF_GRAPH_PRUNED: as described above
+ *   knn_degree   D; 0 = min(2 R, 64) for uint8, min(2 R, 48) for float32, which are also the largest
+ *                values accepted (the self-join keeps 64 candidates per vertex and float32 rows are
+ *                re-ranked out of 16 more candidates than they keep).  Needs R <= D and T >= D + 1.
+ * All other arguments, ownership and errors as for vf_build_index.  Searches do not depend on graph_kind.
+ */
+#define VF_GRAPH_KNN 0
+#define VF_GRAPH_PRUNED 1
+int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                       const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                       int32_t graph_kind, int32_t knn_degree, void *hip_stream, vf_index **out);
+
+/*
  * Batched label-filtered top-k search (Alg. 2; AND semantics of Section 4.3.2).
  *
  *   queries         device, row-major [nq][dim], same dtype as the index

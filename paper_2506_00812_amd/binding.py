@@ -20,7 +20,8 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
                   GO_LS=np.int64, X_LS=np.uint8, BITSET=np.uint32)
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
-                    "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi")
+                    "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi",
+                    "vf_build_index_opt")
 
 
 class VfStats(C.Structure):
@@ -59,6 +60,8 @@ def load_library():
         p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         L.vf_build_index.restype = C.c_int
         L.vf_build_index.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, p, C.POINTER(p)]
+        L.vf_build_index_opt.restype = C.c_int
+        L.vf_build_index_opt.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, i32, i32, p, C.POINTER(p)]
         L.vf_search.restype = C.c_int
         L.vf_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
         L.vf_search_exact.restype = C.c_int
@@ -157,8 +160,14 @@ class Index:
         return out
 
 
-def build_index(vectors, label_offsets, label_ids, n_labels, T, graph_degree, stream=None) -> Index:
-    """vectors: CUDA tensor [n, dim] uint8/float32 (contiguous); labels: host CSR arrays."""
+GRAPH_KNN, GRAPH_PRUNED = 0, 1
+
+
+def build_index(vectors, label_offsets, label_ids, n_labels, T, graph_degree, stream=None, graph_kind=GRAPH_KNN,
+                knn_degree=0) -> Index:
+    """vectors: CUDA tensor [n, dim] uint8/float32 (contiguous); labels: host CSR arrays.
+    graph_kind=GRAPH_PRUNED: graphs of degree knn_degree (0 = the default) reduced to graph_degree by
+    rank-based pruning and reverse edges (vf_build_index_opt)."""
     L = load_library()
     if not vectors.is_cuda or not vectors.is_contiguous() or vectors.dim() != 2:
         raise VecflowError("vectors must be a contiguous 2-D CUDA tensor")
@@ -167,9 +176,15 @@ def build_index(vectors, label_offsets, label_ids, n_labels, T, graph_degree, st
     if off.shape[0] != vectors.shape[0] + 1:
         raise VecflowError("label_offsets must have n + 1 entries")
     h = C.c_void_p()
-    _check(L.vf_build_index(C.c_void_p(vectors.data_ptr()), _dtype_code(vectors), vectors.shape[0], vectors.shape[1],
-                            _np_ptr(off), _np_ptr(ids), int(n_labels), int(T), int(graph_degree),
-                            _stream_handle(stream), C.byref(h)))
+    if graph_kind == GRAPH_KNN and knn_degree == 0:
+        _check(L.vf_build_index(C.c_void_p(vectors.data_ptr()), _dtype_code(vectors), vectors.shape[0],
+                                vectors.shape[1], _np_ptr(off), _np_ptr(ids), int(n_labels), int(T), int(graph_degree),
+                                _stream_handle(stream), C.byref(h)))
+    else:
+        _check(L.vf_build_index_opt(C.c_void_p(vectors.data_ptr()), _dtype_code(vectors), vectors.shape[0],
+                                    vectors.shape[1], _np_ptr(off), _np_ptr(ids), int(n_labels), int(T),
+                                    int(graph_degree), int(graph_kind), int(knn_degree), _stream_handle(stream),
+                                    C.byref(h)))
     return Index(h, vectors)
 
 

@@ -88,6 +88,7 @@ struct vf_index {
     int dtype = 0;
     int64_t n = 0;
     int32_t dim = 0, n_labels = 0, T = 0, R = 0, ncp = 0;
+    int32_t graph_kind = 0, knn_degree = 0;
     const void *X = nullptr;
     // host metadata
     std::vector<int32_t> S, hs_slot;
@@ -178,10 +179,11 @@ template <class T> static int upload(DevBuf &b, const std::vector<T> &v, hipStre
     return VF_OK;
 }
 
-// Exact kNN rows of one graph list: interleave the list, contract it against itself,
-// keep K candidates per vertex, order them into rows.
-static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &cand_idx, DevBuf &cand_dist, DevBuf &d_items,
-                                 hipStream_t s)
+// Exact kNN rows of label l's list: interleave the list, contract it against itself, keep K candidates per
+// vertex, order `deg` of them into rows_out ([|C_l|][deg] local ids); with global_ids the same rows also go
+// to the index's global-id table (deg == R).
+static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, int32_t deg, int32_t *rows_out, bool global_ids,
+                                 DevBuf &cand_idx, DevBuf &cand_dist, DevBuf &d_items, hipStream_t s)
 {
     const int64_t base = ix->O_HS[l];
     const int32_t nl = ix->S[l];
@@ -230,17 +232,76 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, DevBuf &can
     } else {
         launch_scan(ix->dtype, p, (int)n_tiles, s);
     }
-    launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, ix->R,
-                      ix->d_G.as<int32_t>() + base * ix->R, s);
-    launch_graph_global_ids(ix->d_G.as<int32_t>() + base * ix->R, map, (int64_t)nl * ix->R,
-                            ix->d_Gg.as<int32_t>() + base * ix->R, s);
+    launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, deg, rows_out, s);
+    if (global_ids)
+        launch_graph_global_ids(rows_out, map, (int64_t)nl * deg, ix->d_Gg.as<int32_t>() + base * ix->R, s);
     VF_HIP(hipGetLastError());
     return VF_OK;
 }
 
+// Reduces the degree-D rows of all lists (knn, [n_HS][D]) to the index's degree-R rows: rank-based pruning,
+// reverse edges, merge (vf_graphopt.hip).  d_Gg serves as the forward rows' storage until the end.
+static int optimize_graphs(vf_index *ix, const int32_t *d_knn, int32_t D, hipStream_t s)
+{
+    const int64_t nn = ix->n_HS;
+    const int32_t R = ix->R;
+    int rc;
+    DevBuf d_base, d_deg, d_off, d_seg;
+    struct Rel { DevBuf &a, &b, &c, &d; ~Rel() { a.release(); b.release(); c.release(); d.release(); } } rel{d_base, d_deg, d_off, d_seg};
+    std::vector<int32_t> base((size_t)nn);
+    for (int32_t l : ix->graph_labels)
+        std::fill(base.begin() + ix->O_HS[(size_t)l], base.begin() + ix->O_HS[(size_t)l] + ix->S[(size_t)l],
+                  (int32_t)ix->O_HS[(size_t)l]);
+    if ((rc = upload(d_base, base, s)) != VF_OK) return rc;
+    if ((rc = d_deg.reserve((size_t)nn * 4)) != VF_OK) return rc;
+    if ((rc = d_off.reserve((size_t)(nn + 1) * 8)) != VF_OK) return rc;
+    int32_t *F = ix->d_Gg.as<int32_t>();
+    launch_graph_prune(d_knn, d_base.as<int32_t>(), nn, D, R, F, s);
+    VF_HIP(hipMemsetAsync(d_deg.p, 0, (size_t)nn * 4, s));
+    launch_graph_indegree(F, d_base.as<int32_t>(), nn, R, d_deg.as<int32_t>(), s);
+    std::vector<int32_t> deg((size_t)nn);
+    VF_HIP(hipMemcpyAsync(deg.data(), d_deg.p, (size_t)nn * 4, hipMemcpyDeviceToHost, s));
+    VF_HIP(hipStreamSynchronize(s));   // also: `base` is pageable host memory
+    std::vector<int64_t> off((size_t)nn + 1);
+    off[0] = 0;
+    for (int64_t g = 0; g < nn; ++g) off[(size_t)g + 1] = off[(size_t)g] + deg[(size_t)g];
+    VF_REQUIRE(off[(size_t)nn] <= nn * (int64_t)R, "internal: more proposals than forward edges");
+    if ((rc = upload(d_off, off, s)) != VF_OK) return rc;
+    if ((rc = d_seg.reserve((size_t)std::max<int64_t>(1, off[(size_t)nn]) * 8)) != VF_OK) return rc;
+    VF_HIP(hipMemsetAsync(d_deg.p, 0, (size_t)nn * 4, s));   // now the per-target cursors
+    launch_graph_reverse_fill(F, d_base.as<int32_t>(), nn, R, d_off.as<int64_t>(), d_deg.as<int32_t>(),
+                              d_seg.as<uint64_t>(), s);
+    launch_graph_reverse_merge(F, d_off.as<int64_t>(), d_seg.as<uint64_t>(), nn, R, ix->d_G.as<int32_t>(), s);
+    launch_graph_global_ids_based(ix->d_G.as<int32_t>(), d_base.as<int32_t>(), ix->d_M_HS.as<int32_t>(), nn, R,
+                                  ix->d_Gg.as<int32_t>(), s);
+    VF_HIP(hipGetLastError());
+    VF_HIP(hipStreamSynchronize(s));   // `off` is pageable host memory; the temporaries are freed on return
+    return VF_OK;
+}
+
+static int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                            const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                            int32_t graph_kind, int32_t knn_degree, void *hip_stream, vf_index **out);
+
 extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
                               const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
                               void *hip_stream, vf_index **out)
+{
+    return build_index_impl(vectors, dtype, n, dim, label_offsets, label_ids, n_labels, T, graph_degree, VF_GRAPH_KNN, 0,
+                            hip_stream, out);
+}
+
+extern "C" int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                                  const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                                  int32_t graph_kind, int32_t knn_degree, void *hip_stream, vf_index **out)
+{
+    return build_index_impl(vectors, dtype, n, dim, label_offsets, label_ids, n_labels, T, graph_degree, graph_kind,
+                            knn_degree, hip_stream, out);
+}
+
+static int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
+                            const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
+                            int32_t graph_kind, int32_t knn_degree, void *hip_stream, vf_index **out)
 {
     VF_REQUIRE(out != nullptr, "out is NULL");
     *out = nullptr;
@@ -254,6 +315,19 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
     VF_REQUIRE(n_labels > 0, "n_labels must be positive");
     VF_REQUIRE(graph_degree >= 1 && graph_degree <= 64, "graph_degree must be in [1, 64]");
     VF_REQUIRE(T >= graph_degree + 1, "T must be at least graph_degree + 1");
+    VF_REQUIRE(graph_kind == VF_GRAPH_KNN || graph_kind == VF_GRAPH_PRUNED, "graph_kind must be VF_GRAPH_KNN or VF_GRAPH_PRUNED");
+    // degree of the kNN graph a pruned graph starts from: 2 R, as far as the self-join's 64 candidates per
+    // row reach (float32 rows are re-ranked out of 16 candidates more than they keep)
+    const int32_t knn_max = dtype == VF_U8 ? 64 : 48;
+    int32_t D = graph_degree;
+    if (graph_kind == VF_GRAPH_PRUNED) {
+        D = knn_degree > 0 ? knn_degree : std::min(2 * graph_degree, knn_max);
+        VF_REQUIRE(D >= graph_degree && D <= knn_max,
+                   "knn_degree must lie in [graph_degree, 64] (uint8) or [graph_degree, 48] (float32)");
+        VF_REQUIRE(T >= D + 1, "T must be at least knn_degree + 1");
+    } else {
+        VF_REQUIRE(knn_degree == 0, "knn_degree is only used with VF_GRAPH_PRUNED");
+    }
     VF_REQUIRE(label_offsets[0] == 0, "label_offsets[0] must be 0");
     for (int64_t i = 0; i < n; ++i) VF_REQUIRE(label_offsets[i + 1] >= label_offsets[i], "label_offsets must not decrease");
     const int64_t n_raw = label_offsets[n];
@@ -355,7 +429,11 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
             if ((rc = ix->d_Gg.reserve((size_t)ix->n_HS * ix->R * 4)) != VF_OK) return rc;
             int32_t max_list = 0;
             for (int32_t l : ix->graph_labels) max_list = std::max(max_list, ix->S[(size_t)l]);
-            const int32_t K = dtype == VF_U8 ? ix->R : std::min(64, ix->R + 16);
+            const bool pruned = graph_kind == VF_GRAPH_PRUNED;
+            const int32_t K = dtype == VF_U8 ? D : std::min(64, D + 16);
+            DevBuf d_knn;
+            struct RK { DevBuf &a; ~RK() { a.release(); } } rk{d_knn};
+            if (pruned && (rc = d_knn.reserve((size_t)ix->n_HS * D * 4)) != VF_OK) return rc;
             DevBuf cand_idx, cand_dist, d_items;
             struct R3 { DevBuf &a, &b, &c; ~R3() { a.release(); b.release(); c.release(); } } r3{cand_idx, cand_dist, d_items};
             const int64_t max_groups = (max_list + 31) / 32;
@@ -378,9 +456,17 @@ extern "C" int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t
                 ++done;
                 launch_bitset_fill(ix->d_M_HS.as<int32_t>() + ix->O_HS[(size_t)l], ix->S[(size_t)l],
                                    ix->d_bitsets.as<uint32_t>() + (int64_t)ix->hs_slot[(size_t)l] * ix->bitset_words, s);
-                if ((rc = build_graph_for_label(ix, l, K, cand_idx, cand_dist, d_items, s)) != VF_OK) return rc;
+                const int64_t base = ix->O_HS[(size_t)l];
+                int32_t *rows = pruned ? d_knn.as<int32_t>() + base * D : ix->d_G.as<int32_t>() + base * ix->R;
+                if ((rc = build_graph_for_label(ix, l, K, D, rows, !pruned, cand_idx, cand_dist, d_items, s)) != VF_OK)
+                    return rc;
             }
             VF_HIP(hipStreamSynchronize(s));
+            if (pruned) {
+                cand_idx.release(); cand_dist.release();
+                if ((rc = optimize_graphs(ix, d_knn.as<int32_t>(), D, s)) != VF_OK) return rc;
+            }
+            ix->graph_kind = graph_kind; ix->knn_degree = pruned ? D : 0;
             ix->tmp_blk.release();
             ix->tmp_norm.release();
             if (seed_mfma_supported(ix->dtype, ix->dim)) {

@@ -170,6 +170,21 @@ void launch_fill_out(int64_t *ids, float *dists, int64_t count, hipStream_t s);
 // rows[i] of the [*][k] outputs := (-1, +inf)
 void launch_fill_rows(int64_t *ids, float *dists, const int32_t *rows, int64_t n_rows, int32_t k, hipStream_t s);
 
+// ---------------------------------------------------------------- graph optimisation (vf_graphopt.hip)
+
+// Vertices are positions g in the compacted graph partition; node_base[g] = position of the first vertex of
+// g's list.  knn: [n_nodes][D] local ids in rank order; F, G: [n_nodes][R] local ids.
+void launch_graph_prune(const int32_t *knn, const int32_t *node_base, int64_t n_nodes, int32_t D, int32_t R, int32_t *F,
+                        hipStream_t s);
+void launch_graph_indegree(const int32_t *F, const int32_t *node_base, int64_t n_nodes, int32_t R, int32_t *deg,
+                           hipStream_t s);
+void launch_graph_reverse_fill(const int32_t *F, const int32_t *node_base, int64_t n_nodes, int32_t R, const int64_t *off,
+                               int32_t *cursor, uint64_t *seg, hipStream_t s);
+void launch_graph_reverse_merge(const int32_t *F, const int64_t *off, const uint64_t *seg, int64_t n_nodes, int32_t R,
+                                int32_t *G, hipStream_t s);
+void launch_graph_global_ids_based(const int32_t *rows, const int32_t *node_base, const int32_t *M, int64_t n_nodes,
+                                   int32_t R, int32_t *out, hipStream_t s);
+
 // ---------------------------------------------------------------- multi-label queries (OR, parallel AND)
 
 // out[i] = row parent[i] of a row-major table (rows of row_bytes, a multiple of 16)
