@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--T", type=int, default=None)
     ap.add_argument("--sweep", action="store_true", help="print recall/QPS of every candidate setting to stderr")
+    ap.add_argument("--graph", choices=("knn", "pruned"), default="knn",
+                    help="per-list graphs: exact kNN (the configuration the oracle baseline can follow at full size) "
+                         "or degree-2R kNN reduced by rank-based pruning and reverse edges (implies --no-cpu)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=64)
     ap.add_argument("--params", default=None,
@@ -122,6 +125,8 @@ def main():
     ap.add_argument("--gt-sample", type=int, default=0,
                     help="measure recall on this many randomly chosen queries (ground truth of the full set "
                          "of a 10M-vector workload would take many minutes)")
+    ap.add_argument("--compare-graphs", action="store_true",
+                    help="also build the index with exact kNN and with pruned graphs and report recall by list size")
     ap.add_argument("--multi", action="store_true",
                     help="also measure two-label AND (greedy and parallel policy) and OR queries on the same index")
     ap.add_argument("--latency", action="store_true",
@@ -151,7 +156,11 @@ def main():
     Q = torch.from_numpy(w.queries).cuda()
     t0 = time.time()
     log("[bench] building the index ...")
-    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    pruned = args.graph == "pruned"
+    if pruned:
+        args.no_cpu = True   # the oracle cannot build whole pruned graphs of this size in bounded time
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree,
+                        graph_kind=vf.GRAPH_PRUNED if pruned else vf.GRAPH_KNN)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     st = ix.stats()
@@ -209,6 +218,13 @@ def main():
     if s.n > 2_000_000:   # long lists need more seeds: a coarser grid reaching further
         cands = sorted({(itopk, 1, iters, ns) for itopk in (32, 64) for iters in (8, 16, 32)
                         for ns in (2048, 4096, 8192, 16384, 32768)}, key=lambda c: c[3] + c[2] * 32)
+    if pruned:   # pruned graphs are connected far better: a fraction of the seeds suffices
+        cands = sorted({(32, wd, iters, ns) for wd in (1, 2) for iters in (3, 4, 6, 8, 12, 16, 24)
+                        for ns in (64, 128, 256, 384, 512, 768, 1024, 1536, 2048, 4096)},
+                       key=lambda c: c[3] + c[2] * c[1] * 32)
+        if s.n > 2_000_000:
+            cands = sorted({(itopk, 1, iters, ns) for itopk in (32, 64) for iters in (8, 16, 32)
+                            for ns in (256, 512, 1024, 2048, 4096, 8192)}, key=lambda c: c[3] + c[2] * 32)
     for params in cands:
         if params[1] * s.graph_degree > 128:
             continue
@@ -427,6 +443,36 @@ def main():
             res[name] = row
         extra["two_label_queries"] = res
 
+    # ---- exact kNN graphs against pruned graphs (rank-based pruning + reverse edges): recall of the graph-routed
+    # queries by list size at fixed search parameters, and the build time of either kind
+    if args.compare_graphs:
+        S_host = ix.export("S")
+        first_label = w.qlabel_ids[w.qlabel_offsets[:-1]]
+        single = np.diff(w.qlabel_offsets) == 1
+        rows_all = np.arange(s.nq) if gt_rows is None else gt_rows
+        gt_full = {int(r): gt[t] for t, r in enumerate(rows_all)}
+        settings = [(32, 1, 8, 256), (32, 1, 8, 1024), tuple(headline[0]), tuple((p99 or headline)[0])]
+        buckets = [(s.T, 2 * s.T), (2 * s.T, 5 * s.T), (5 * s.T, 15 * s.T), (15 * s.T, 1 << 62)]
+        cmp_out = {"settings": [list(p) for p in settings], "index_build_s": {}, "recall_at_10": {}}
+        for kind_name, kind in (("knn", vf.GRAPH_KNN), ("pruned", vf.GRAPH_PRUNED)):
+            torch.cuda.synchronize()
+            tb = time.time()
+            ix2 = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, graph_kind=kind)
+            torch.cuda.synchronize()
+            cmp_out["index_build_s"][kind_name] = round(time.time() - tb, 3)
+            for prm in settings:
+                vf.search(ix2, Q, w.qlabel_offsets, w.qlabel_ids, k, *prm, out_ids, out_dists)
+                found = out_ids.cpu().numpy()
+                for lo, hi in buckets:
+                    sel = [r for r in rows_all if single[r] and lo <= S_host[first_label[r]] < hi]
+                    if not sel:
+                        continue
+                    rec = recall_at_k(found[sel], np.stack([gt_full[int(r)] for r in sel]))
+                    key = f"list size [{lo}, {hi if hi < (1 << 61) else 'inf'})"
+                    cmp_out["recall_at_10"].setdefault(key, {"queries": len(sel)}).setdefault(kind_name, []).append(round(rec, 4))
+            del ix2
+        extra["graph_comparison"] = cmp_out
+
     # ---- small-batch latency on the same index (batches of 1, 8, 64; labels half graph lists, half scan lists)
     if args.latency:
         S_host = ix.export("S")
@@ -497,6 +543,7 @@ def main():
         "config": {"workload": f"{s.name}: N={s.n} dim={s.dim} {s.dtype}, {s.n_clusters} Gaussian clusters, "
                                f"{s.n_labels} Zipf({s.zipf_alpha}) labels, T={s.T}, R={s.graph_degree}, "
                                f"{s.nq} queries ({s.query_mode}), k={k}, seed {s.seed}",
+                   "graphs": "pruned (degree-2R kNN, rank-based pruning, reverse edges)" if pruned else "exact kNN",
                    "params": dict(zip(("itopk", "width", "iters", "n_seeds"), headline[0])),
                    "recall_at_10": round(recall_head, 4), "reached_0.90": p90 is not None,
                    "recall_by_stratum": strata,
