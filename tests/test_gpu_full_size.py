@@ -47,6 +47,37 @@ def test_full_size_layout_and_sampled_graph_rows(c2):
             assert np.array_equal(G[O[l] + j], ixo.graph_row(l, j)), (l, j)
 
 
+def test_full_size_pruned_graph_sampled_rows_and_properties(c2):
+    """VF_GRAPH_PRUNED at the benchmark's size.  The oracle cannot build whole pruned graphs of 400,000-vertex
+    lists, but a vertex's forward row needs only the degree-D rows of the vertex and of its D neighbours, which
+    it computes by brute force: the part of a row that is always kept (the first R/2 entries) is compared for
+    sampled vertices, every other entry of those rows must be a forward edge or the reverse of a kept edge, and
+    all rows are checked for range, self loops and duplicates."""
+    import torch
+    vf, w, _, _, ixo = c2
+    s = w.spec
+    R, D = s.graph_degree, 48
+    X = torch.from_numpy(w.vectors).cuda()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, R, graph_kind=vf.GRAPH_PRUNED)
+    G = ix.export("G_HS").reshape(-1, R)
+    S, O = ixo.S, ixo.O_HS
+    graph_labels = np.flatnonzero(S >= s.T)
+    rng = np.random.default_rng(11)
+    for l in graph_labels:
+        g = G[O[l]:O[l] + S[l]]
+        assert g.min() >= 0 and g.max() < S[l]
+        assert not (g == np.arange(S[l])[:, None]).any()
+        srt = np.sort(g, axis=1)
+        assert (srt[:, 1:] != srt[:, :-1]).all()
+    for l in graph_labels[[0, 7, 35]]:
+        for j in rng.integers(0, S[l], size=4):
+            f = ixo.pruned_row(l, int(j), D)
+            row = G[O[l] + j]
+            assert np.array_equal(row[:R // 2], f[:R // 2]), (l, j)
+            for x in row[R // 2:][:4]:
+                assert x in f or j in ixo.pruned_row(l, int(x), D), (l, j, x)
+
+
 @pytest.mark.parametrize("params", [PARAMS, PARAMS_99, PARAMS_WIDE])
 def test_full_size_search_sampled_against_oracle(c2, params):
     import torch
