@@ -665,6 +665,8 @@ static int env_int(const char *name, int dflt, int lo, int hi)
 }
 // tuning knobs (the environment overrides exist for experiments)
 static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
+static const int kSegGroupsHeavy = env_int("VF_SEG_GROUPS_HEAVY", 32, 1, 4096);  // the same for tiles of >= kHeavyRows queries
+static const int kHeavyRows = env_int("VF_SEG_HEAVY_ROWS", 9, 1, 33);
 static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
 static const int kScanValu = env_int("VF_SCAN_VALU", 1, 0, 2);      // float32 FMA scan kernel: 0 never, 1 for small batches, 2 always
 static const int kScan16 = env_int("VF_SCAN16", 1, 0, 1);          // 0: float32 search tiles keep the 32-row matrix-core kernel
@@ -682,12 +684,15 @@ struct ItemBuilder {
     void add_label(const std::vector<uint64_t> &pairs, size_t lo, size_t hi, int64_t group0, int64_t map_off, int32_t n)
     {
         const int32_t n_groups = (n + 31) / 32;
-        const int32_t seg_groups = std::max(kSegGroups, (n_groups + kMaxSegs - 1) / kMaxSegs);
-        const int32_t nseg = (n_groups + seg_groups - 1) / seg_groups;
-        max_nseg = std::max(max_nseg, nseg);
         for (size_t t = lo; t < hi; t += (size_t)tile_rows) {
             const int32_t q_begin = (int32_t)qrow.size();
             const int32_t q_count = (int32_t)std::min<size_t>((size_t)tile_rows, hi - t);
+            // a tile's work item is a serial chain whose cost per group grows with its queries (selection):
+            // tiles with many queries get shorter segments, so that the items of a launch end together
+            const int32_t want = q_count >= kHeavyRows ? kSegGroupsHeavy : kSegGroups;
+            const int32_t seg_groups = std::max(want, (n_groups + kMaxSegs - 1) / kMaxSegs);
+            const int32_t nseg = (n_groups + seg_groups - 1) / seg_groups;
+            max_nseg = std::max(max_nseg, nseg);
             for (size_t u = t; u < t + (size_t)q_count; ++u) qrow.push_back((int32_t)(uint32_t)pairs[u]);
             for (int32_t sg = 0; sg < nseg; ++sg) {
                 ScanItem it{};

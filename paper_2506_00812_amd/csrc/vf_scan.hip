@@ -496,7 +496,7 @@ __global__ __launch_bounds__(64, VF_SCAN_WAVES) void scan_topk_kernel(ScanParams
 //              the four components of a chunk feed four consecutive MFMAs, so the contraction
 //              index runs over (s, kq, component) on both operands alike;
 //   D          rows 4 kq + i (i = 0..3) x entry c of each column block.
-template <int NCP, bool AND>
+template <int NCP, bool AND, int SLOTS>
 __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanParams p)
 {
     extern __shared__ uint4 smem[];
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
     // Nothing else is prefetched: a scalar carried from one step to the next gets copied at the top of the
     // loop, and that copy would wait for every load issued before it.  The entries' norms are summed from
     // the B registers (in the shadow of the MFMAs) and the AND predicate fetches global ids on demand.
-    uint4 breg[2][2][NS];
+    uint4 breg[SLOTS][2][NS];
     auto fetch_block = [&](int slot, int g, int cb) {   // group g (exists), column block cb -> slot
         const uint4 *blk = p.xblk + (it.group0 + g) * (int64_t)(NCH * 32);
 #pragma unroll
@@ -615,19 +615,19 @@ __global__ __launch_bounds__(64, VF_SCAN16_WAVES) void scan_topk16_kernel(ScanPa
     // its waits then cover all of them, the block just requested included.
     const int last_group = n_groups - 1;
 #pragma unroll
-    for (int slot = 0; slot < 2; ++slot) {
+    for (int slot = 0; slot < SLOTS; ++slot) {
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) fetch_block(slot, slot < last_group ? slot : last_group, cb);
         __builtin_amdgcn_sched_barrier(0);   // the loads stay in this order, here and in the loop
     }
-    for (int grp0 = 0; grp0 < n_groups; grp0 += 2) {
+    for (int grp0 = 0; grp0 < n_groups; grp0 += SLOTS) {
 #pragma unroll
-      for (int slot = 0; slot < 2; ++slot) {
+      for (int slot = 0; slot < SLOTS; ++slot) {
         // (an odd number of groups ends with a phantom step on the re-fetched last group, every column
         // masked: a way out between the two steps would be one more path into the loop's end, one on
         // which slot 0 holds the newest loads, and the waits at the top would cover slot 1's as well)
         const int grp = grp0 + slot;
-        const int refill = grp + 2 < last_group ? grp + 2 : last_group;
+        const int refill = grp + SLOTS < last_group ? grp + SLOTS : last_group;
         v4f acc[2];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) acc[cb] = (v4f){0.f, 0.f, 0.f, 0.f};
@@ -924,16 +924,27 @@ void launch_scan16(const ScanParams &p, int n_items, hipStream_t s)
 {
     if (n_items <= 0) return;
     const size_t lds = (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;   // no query tile: it lives in registers
-    // two instantiations: with loads of the AND predicate inside the loop the compiler can no longer count
-    // which outstanding loads a wait must cover, and every wait becomes a wait for all of them
+    // Instantiations.  AND: with loads of the AND predicate inside the loop the compiler can no longer count
+    // which outstanding loads a wait must cover, and every wait becomes a wait for all of them.  SLOTS: the
+    // kNN self-joins of the index build (alone on the chip) prefetch two groups ahead; search
+    // tiles one group, with 70 registers less per wave, which leaves room for the waves of the graph kernels
+    // that run beside them.
     const bool with_and = p.others_off != nullptr;
-    if (p.dim == 128) {
-        if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<16, true>), dim3(n_items), dim3(64), lds, s, p);
-        else hipLaunchKernelGGL((scan_topk16_kernel<16, false>), dim3(n_items), dim3(64), lds, s, p);
-    } else {
-        if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<12, true>), dim3(n_items), dim3(64), lds, s, p);
-        else hipLaunchKernelGGL((scan_topk16_kernel<12, false>), dim3(n_items), dim3(64), lds, s, p);
-    }
+    const bool deep = p.K > 16;   // the self-joins keep 48 or 64 candidates per row, searches k
+    const dim3 grid(n_items), block(64);
+#define VF_LAUNCH16(NCP_) \
+    do { \
+        if (deep) { \
+            if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<NCP_, true, 2>), grid, block, lds, s, p); \
+            else hipLaunchKernelGGL((scan_topk16_kernel<NCP_, false, 2>), grid, block, lds, s, p); \
+        } else { \
+            if (with_and) hipLaunchKernelGGL((scan_topk16_kernel<NCP_, true, 1>), grid, block, lds, s, p); \
+            else hipLaunchKernelGGL((scan_topk16_kernel<NCP_, false, 1>), grid, block, lds, s, p); \
+        } \
+    } while (0)
+    if (p.dim == 128) VF_LAUNCH16(16);
+    else VF_LAUNCH16(12);
+#undef VF_LAUNCH16
 }
 
 bool scan_valu_supported(int dtype, int dim, int tile_rows)
