@@ -200,7 +200,8 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  *               seeds re-scored with the ordered distance after matrix-core scoring
  */
 typedef struct vf_profile {
-    float scan_ms, seed_ms, beam_ms;   /* durations of the last call: IVF-BFS kernels, dense seed scoring, beam search */
+    float scan_ms, seed_ms, beam_ms;   /* durations of the last call: the IVF-BFS scan kernel (vf_search_exact: all its
+                                          scan and merge launches), dense seed scoring, beam search */
     double scan_ms_sum, seed_ms_sum, beam_ms_sum; /* sums over all calls since profiling was enabled */
     int64_t calls;                     /* number of calls in those sums                */
     int64_t nq, n_scan_queries, n_graph_queries, n_scan_items;

@@ -961,6 +961,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 } else {
                     launch_scan(ix->dtype, sp, (int)n_ls_items, ss);
                 }
+                // a search times its scan kernel by itself (the merge of the segments' candidates follows it)
+                if (prof && hs_runs.empty()) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
                 launch_scan_merge(ix->dtype, d_merges, (int)n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
                                   ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
             }
@@ -979,12 +981,12 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                 launch_scan_merge(ix->dtype, d_merges + n_ls_merges, (int)(ib.merges.size() - n_ls_merges), sp.res_idx,
                                   sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
             }
-            if (prof) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
+            if (prof && !(hs_runs.empty() && n_ls_items)) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
             if (forked) VF_HIP(hipEventRecord(ix->ev_join, ss));
             return VF_OK;
         };
         // the scan goes first: its longest work items decide when it ends (measured: forking it
-        // after the seed kernel costs 20 % of the step)
+        // after the seed kernel costs 6 to 20 % of the step)
         if ((rc = run_scan()) != VF_OK) return rc;
         if ((rc = run_seeds()) != VF_OK) return rc;
         if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
