@@ -261,10 +261,11 @@ def main():
     gc.disable()
     ix.profile_enable(True)
     itopk, width, iters, n_seeds = headline[0]
-    # untimed, like the burst after the index build: the first time a dozen calls with timing events are in
-    # flight the HIP runtime stalls once more for about 5 ms (seen in one run out of four when only the W
-    # warm-up steps preceded the timed region: 20 steps then took 12.8 ms instead of 7.8 ms)
-    for _ in range(12):
+    # untimed, like the burst after the index build: one pass over the library's ring of 64 timing-event sets.
+    # While events are recorded for the first time the HIP runtime stalls once more for about 5 ms at some
+    # point (seen in one run out of four when only the W warm-up steps preceded the timed region: 20 steps
+    # then took 12.8 ms instead of 7.8 ms)
+    for _ in range(72):
         vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, k, itopk, width, iters, n_seeds, out_ids, out_dists)
     torch.cuda.synchronize()
     for _ in range(args.warmup):
@@ -408,7 +409,7 @@ def main():
     # second operating point, timed the plain way
     extra = {}
     if p99 is not None:
-        ms99 = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, p99[0], args.steps, args.warmup, out_ids,
+        ms99 = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, p99[0], args.steps, args.warmup + 12, out_ids,
                            out_dists)
         extra = {"qps_at_recall_0.99": round(s.nq / ms99 * 1e3, 1), "recall_0.99_measured": round(p99[1], 4),
                  "params_0.99": dict(zip(("itopk", "width", "iters", "n_seeds"), p99[0]))}
@@ -435,7 +436,7 @@ def main():
             gtm = gi.cpu().numpy()
             row = {}
             for tag, prm in (("p90", headline[0]), ("p99", (p99 or headline)[0])):
-                for _ in range(args.warmup):
+                for _ in range(args.warmup + 12):   # a new call shape: the runtime's one-time stall again (see above)
                     vf.search_multi(ix, Q, qoff2, qids2, mode, k, *prm, out_ids, out_dists)
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
