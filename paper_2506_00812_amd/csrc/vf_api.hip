@@ -107,6 +107,11 @@ struct vf_index {
     bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
     // search workspace
     DevBuf ws_blob, ws_blob_b, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
+    // the seeds of every graph list for the last n_seeds used, interleaved like a scan list, so that the
+    // matrix-core seed kernel reads its B operand with coalesced loads (rebuilt when n_seeds changes)
+    DevBuf seed_blk, seed_norm, seed_goff;
+    int32_t seed_cache_ns = -1;      // n_seeds the copy was built for
+    bool seed_cache_ok = false;      // false: it did not fit, the kernel gathers rows from the vector table
     // vf_search_multi: gathered query rows, results of the sub-searches, their parents
     DevBuf multi_q, multi_ids, multi_dists, multi_meta;
     std::vector<int32_t> multi_host;      // [n_sub parents | nq + 1 first sub-search of each query], alive until the next call
@@ -152,7 +157,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G, &ix->d_Gg,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->seed_blk, &ix->seed_norm, &ix->seed_goff, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
     for (auto &set : ix->prof_ring)
         for (hipEvent_t e : set)
@@ -713,6 +718,61 @@ struct ItemBuilder {
     }
 };
 
+// Interleaved copy of the seeds (local ids floor(j n / ns), j < ns = min(n_seeds, n)) of every graph list.
+// Depends on the index and on n_seeds only; rebuilt on the caller's stream when n_seeds changes, skipped
+// (seed_cache_ok = false) when it would need more than half of the free device memory.
+static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
+{
+    static const int enabled = env_int_early("VF_SEED_CACHE", 1);
+    if (ix->seed_cache_ns == n_seeds) return VF_OK;
+    ix->seed_cache_ns = n_seeds;
+    ix->seed_cache_ok = false;
+    if (!enabled) return VF_OK;
+    const size_t n_gl = ix->graph_labels.size();
+    std::vector<int64_t> goff(n_gl), slot_base(n_gl);
+    std::vector<int32_t> slot_n(n_gl), grp_slot, grp_j0, grp_cnt;
+    std::vector<int64_t> grp_src;
+    int64_t n_groups = 0;
+    for (size_t t = 0; t < n_gl; ++t) {
+        const int32_t l = ix->graph_labels[t];
+        const int32_t n = ix->S[(size_t)l], ns = std::min(n_seeds, n);
+        goff[t] = n_groups; slot_base[t] = ix->O_HS[(size_t)l]; slot_n[t] = n;
+        for (int32_t j0 = 0; j0 < ns; j0 += 32) {
+            grp_slot.push_back((int32_t)t); grp_j0.push_back(j0);
+            grp_src.push_back(n_groups * 32); grp_cnt.push_back(std::min(32, ns - j0));
+            ++n_groups;
+        }
+    }
+    if (n_groups == 0) return VF_OK;
+    const size_t need = (size_t)n_groups * (ix->group_bytes() + 32 * 4 + 32 * 4 + 32);
+    if (need > ix->seed_blk.cap) {
+        size_t free_b = 0, total_b = 0;
+        VF_HIP(hipMemGetInfo(&free_b, &total_b));
+        if (need + need / 4 > (free_b + ix->seed_blk.cap) / 2) return VF_OK;
+    }
+    int rc;
+    DevBuf d_map, d_base, d_n, d_slot, d_j0, d_src, d_cnt;
+    struct Rel { DevBuf *b[7]; ~Rel() { for (DevBuf *x : b) x->release(); } } rel{{&d_map, &d_base, &d_n, &d_slot, &d_j0, &d_src, &d_cnt}};
+    if ((rc = ix->seed_blk.reserve((size_t)n_groups * ix->group_bytes())) != VF_OK) return rc;
+    if ((rc = ix->seed_norm.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
+    if ((rc = d_map.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
+    if ((rc = upload(ix->seed_goff, goff, s)) != VF_OK) return rc;
+    if ((rc = upload(d_base, slot_base, s)) != VF_OK) return rc;
+    if ((rc = upload(d_n, slot_n, s)) != VF_OK) return rc;
+    if ((rc = upload(d_slot, grp_slot, s)) != VF_OK) return rc;
+    if ((rc = upload(d_j0, grp_j0, s)) != VF_OK) return rc;
+    if ((rc = upload(d_src, grp_src, s)) != VF_OK) return rc;
+    if ((rc = upload(d_cnt, grp_cnt, s)) != VF_OK) return rc;
+    launch_seed_map(ix->d_M_HS.as<int32_t>(), d_base.as<int64_t>(), d_n.as<int32_t>(), n_seeds, d_slot.as<int32_t>(),
+                    d_j0.as<int32_t>(), n_groups, d_map.as<int32_t>(), s);
+    launch_interleave(ix->dtype, ix->X, ix->dim, d_map.as<int32_t>(), d_src.as<int64_t>(), d_cnt.as<int32_t>(),
+                      n_groups * 32, n_groups, ix->ncp, ix->seed_blk.as<uint4>(), ix->seed_norm.p, s);
+    VF_HIP(hipGetLastError());
+    VF_HIP(hipStreamSynchronize(s));   // the tables above are pageable host memory and temporaries
+    ix->seed_cache_ok = true;
+    return VF_OK;
+}
+
 // first_is_searched: every query searches the list of its first label (the others are the
 // predicate) instead of its smallest list -- the sub-searches of vf_search_multi.
 static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
@@ -914,8 +974,20 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                     sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
                     sd.dseed = ix->dseed.as<uint32_t>();
                     if (seeds_mfma) {
+                        sd.chunk_seeds = kSeedMfmaChunk;
                         sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
                         sd.xnorm_all = ix->d_xnorm_all.as<uint32_t>();
+                        if ((rc = ensure_seed_cache(ix, n_seeds, s)) != VF_OK) return rc;
+                        if (ix->seed_cache_ok) {
+                            sd.seed_blk = ix->seed_blk.as<uint4>(); sd.seed_norm = ix->seed_norm.as<uint32_t>();
+                            sd.seed_goff = ix->seed_goff.as<int64_t>();
+                            // seeds per wave: few long waves share the chip better with the scan (512 seeds:
+                            // step 0.374 -> 0.340 ms on 10,000-query batches), small batches need many short ones
+                            sd.chunk_seeds = 4 * kSeedMfmaChunk;
+                            if ((int64_t)tiles.size() * ((ns_stride + sd.chunk_seeds - 1) / sd.chunk_seeds) < 512)
+                                sd.chunk_seeds = kSeedMfmaChunk;
+                            sd.max_chunks = (ns_stride + sd.chunk_seeds - 1) / sd.chunk_seeds;
+                        }
                         launch_seed_mfma(ix->dtype, sd, (int)tiles.size(), s);
                         if (ix->dtype == VF_F32) {
                             bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;

@@ -132,9 +132,20 @@ struct SeedParams {
     int32_t dim, n_seeds, ns_stride, max_chunks;  // max_chunks = seed chunks per tile (kSeedChunk or kSeedMfmaChunk seeds each)
     uint32_t *dseed;
     const uint32_t *xnorm_all;  // [n] squared norms of the rows of X, float bits / int32 of the -128 shifted bytes (seed_mfma_kernel only)
+    // seed_mfma_kernel, optional: the seeds of every graph list for this n_seeds as an interleaved copy
+    // ([group][chunk][32] 16-byte chunks like a scan list, 32 seeds per group in seed order, zero padded)
+    const uint4 *seed_blk;
+    const uint32_t *seed_norm;  // [group * 32 + v] squared norms as in xnorm_all
+    const int64_t *seed_goff;   // [n_graph_labels] first group of each graph list, by rank among graph labels
+    int32_t chunk_seeds;        // seeds per wave: kSeedMfmaChunk, or four times that (interleaved copy only); max_chunks matches it
 };
 
-constexpr int kSeedMfmaChunk = 128;  // seeds per wave of the MFMA seed kernel (four 32-seed groups)
+// seed_map[g * 32 + v] = global id of seed j = grp_j0[g] + v of graph list grp_slot[g] (local id floor(j n / ns)),
+// 0 for v beyond the list's seeds
+void launch_seed_map(const int32_t *M_HS, const int64_t *slot_base, const int32_t *slot_n, int32_t n_seeds,
+                     const int32_t *grp_slot, const int32_t *grp_j0, int64_t n_groups, int32_t *seed_map, hipStream_t s);
+
+constexpr int kSeedMfmaChunk = 128;  // seeds per wave of the MFMA seed kernel when it gathers rows (four 32-seed groups)
 
 bool seed_dist_supported(int dtype, int dim);
 void launch_seed_dist(int dtype, const SeedParams &p, int n_tiles, hipStream_t s);

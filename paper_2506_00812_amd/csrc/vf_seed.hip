@@ -115,10 +115,15 @@ typedef float v16f_seed __attribute__((ext_vector_type(16)));
 typedef int v16i_seed __attribute__((ext_vector_type(16)));
 typedef int v4i_seed __attribute__((ext_vector_type(4)));
 
-template <int DT, int NCP>
+// CACHED: the B operand comes from the interleaved copy of the seeds (coalesced 1-KiB loads, lane (v, h)
+// taking chunk 2 c + h of seed v of the group); otherwise every lane pair gathers its seed's row from X
+// (32 rows of 32 bytes per load instruction).  NG = 32-seed groups per wave (fully unrolled: a loop with a
+// run-time trip count needs both operand buffers live at once and spills): few long waves for large
+// batches, many short ones for small batches.
+template <int DT, int NCP, bool CACHED, int NG>
 __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 {
-    constexpr int NCH = 2 * NCP, row_bytes = NCH * kChunkBytes, NG = kSeedMfmaChunk / 32;
+    constexpr int NCH = 2 * NCP, row_bytes = NCH * kChunkBytes;
     __shared__ uint4 qtile[NCH * 32];
     __shared__ uint32_t qnorm_s[32];   // float bits / int
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
@@ -127,20 +132,30 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
     const int n = p.meta.S[t.label];
     const int64_t base = p.meta.O_HS[t.label];
     const int ns = p.n_seeds < n ? p.n_seeds : n;
-    const int j0 = chunk * kSeedMfmaChunk;
+    const int j0 = chunk * (NG * 32);
     if (j0 >= ns) return;
 
+    constexpr bool cached = CACHED;
+    const int64_t grp0 = cached ? p.seed_goff[p.meta.hs_slot[t.label]] + j0 / 32 : 0;
     // global ids and norms of this lane's seed in each group (issued first: the longest dependent chain)
     int gid[NG];
     uint32_t xn[NG];
+    if (cached) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int j = j0 + g * 32 + n32;
-        const int c = j < ns ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
-        gid[g] = p.meta.M_HS[base + c];
+        for (int g = 0; g < NG; ++g) {
+            gid[g] = 0;
+            xn[g] = j0 + g * 32 < ns ? p.seed_norm[(grp0 + g) * 32 + n32] : 0u;
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int j = j0 + g * 32 + n32;
+            const int c = j < ns ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
+            gid[g] = p.meta.M_HS[base + c];
+        }
+#pragma unroll
+        for (int g = 0; g < NG; ++g) xn[g] = p.xnorm_all[gid[g]];
     }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) xn[g] = p.xnorm_all[gid[g]];
 
     // query tile, chunk-major; rows without a query are zero
     {
@@ -185,22 +200,25 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
     for (int jj = 0; jj < 16; ++jj) qn[jj] = qnorm_s[8 * (jj >> 2) + 4 * h + (jj & 3)];
 
     uint4 bnext[NCP];
-    {
-        const char *xrow = (const char *)p.X + (int64_t)gid[0] * row_bytes;
+    auto fetch_group = [&](int g) {   // group g of this wave's seeds (exists)
+        if (cached) {
+            const uint4 *blk = p.seed_blk + (grp0 + g) * (int64_t)(NCH * 32);
 #pragma unroll
-        for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
-    }
+            for (int cp = 0; cp < NCP; ++cp) bnext[cp] = blk[(2 * cp + h) * 32 + n32];
+        } else {
+            const char *xrow = (const char *)p.X + (int64_t)gid[g] * row_bytes;
+#pragma unroll
+            for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
+        }
+    };
+    fetch_group(0);
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         if (j0 + g * 32 >= ns) break;   // wave uniform
         uint4 b[NCP];
 #pragma unroll
         for (int cp = 0; cp < NCP; ++cp) b[cp] = bnext[cp];
-        if (g + 1 < NG && j0 + (g + 1) * 32 < ns) {
-            const char *xrow = (const char *)p.X + (int64_t)gid[g + 1 < NG ? g + 1 : g] * row_bytes;
-#pragma unroll
-            for (int cp = 0; cp < NCP; ++cp) bnext[cp] = *(const uint4 *)(xrow + (2 * cp + h) * kChunkBytes);
-        }
+        if (g + 1 < NG && j0 + (g + 1) * 32 < ns) fetch_group(g + 1 < NG ? g + 1 : g);
         uint32_t bits[16];
         if constexpr (DT == 0) {
             v16i_seed acc;
@@ -255,10 +273,43 @@ void launch_seed_mfma(int dtype, const SeedParams &p, int n_tiles, hipStream_t s
 {
     if (n_tiles <= 0) return;
     const dim3 grid((unsigned)n_tiles * (unsigned)p.max_chunks), block(64);
-    if (dtype == 1 && p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<1, 16>), grid, block, 0, s, p);
-    else if (dtype == 1 && p.dim == 96) hipLaunchKernelGGL((seed_mfma_kernel<1, 12>), grid, block, 0, s, p);
-    else if (dtype == 0 && p.dim == 128) hipLaunchKernelGGL((seed_mfma_kernel<0, 4>), grid, block, 0, s, p);
-    else if (dtype == 0 && p.dim == 192) hipLaunchKernelGGL((seed_mfma_kernel<0, 6>), grid, block, 0, s, p);
+    // separate instantiations for the two operand sources (one kernel holding both paths needs so many
+    // registers that a SIMD takes a single wave of it) and for the seeds per wave (p.chunk_seeds: 128,
+    // or 512 with the interleaved copy)
+    const bool cached = p.seed_blk != nullptr;
+    const bool wide = cached && p.chunk_seeds == 4 * kSeedMfmaChunk;
+#define VF_LAUNCH_SEED(DT_, NCP_) \
+    do { \
+        if (wide) hipLaunchKernelGGL((seed_mfma_kernel<DT_, NCP_, true, 16>), grid, block, 0, s, p); \
+        else if (cached) hipLaunchKernelGGL((seed_mfma_kernel<DT_, NCP_, true, 4>), grid, block, 0, s, p); \
+        else hipLaunchKernelGGL((seed_mfma_kernel<DT_, NCP_, false, 4>), grid, block, 0, s, p); \
+    } while (0)
+    if (dtype == 1 && p.dim == 128) VF_LAUNCH_SEED(1, 16);
+    else if (dtype == 1 && p.dim == 96) VF_LAUNCH_SEED(1, 12);
+    else if (dtype == 0 && p.dim == 128) VF_LAUNCH_SEED(0, 4);
+    else if (dtype == 0 && p.dim == 192) VF_LAUNCH_SEED(0, 6);
+#undef VF_LAUNCH_SEED
+}
+
+__global__ void seed_map_kernel(const int32_t *M_HS, const int64_t *slot_base, const int32_t *slot_n, int32_t n_seeds,
+                                const int32_t *grp_slot, const int32_t *grp_j0, int64_t n_groups, int32_t *seed_map)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_groups * 32) return;
+    const int64_t g = t >> 5;
+    const int slot = grp_slot[g];
+    const int n = slot_n[slot];
+    const int ns = n_seeds < n ? n_seeds : n;
+    const int j = grp_j0[g] + (int)(t & 31);
+    seed_map[t] = j < ns ? M_HS[slot_base[slot] + (int64_t)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns)] : 0;
+}
+
+void launch_seed_map(const int32_t *M_HS, const int64_t *slot_base, const int32_t *slot_n, int32_t n_seeds,
+                     const int32_t *grp_slot, const int32_t *grp_j0, int64_t n_groups, int32_t *seed_map, hipStream_t s)
+{
+    if (n_groups <= 0) return;
+    hipLaunchKernelGGL(seed_map_kernel, dim3((unsigned)((n_groups * 32 + 255) / 256)), dim3(256), 0, s, M_HS, slot_base,
+                       slot_n, n_seeds, grp_slot, grp_j0, n_groups, seed_map);
 }
 
 // One thread per row, elements in ascending order.  float32: sum of squares (float bits);
