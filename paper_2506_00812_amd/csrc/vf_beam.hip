@@ -114,6 +114,23 @@ template <int E> struct TopM {
     }
 };
 
+// A batch of up to 64 keys, one per lane (KEY_MAX = none), none of them in the list yet, into a list of at
+// most 64 entries: sort the batch, take the 64 smallest of batch and list (element-wise minimum against
+// the reversed batch), sort that bitonic sequence.  The same list as inserting the keys one by one, in
+// about 330 wave instructions whatever the batch holds (one insertion: about 30).
+__device__ __forceinline__ void merge_batch(TopM<1> &list, uint64_t key, int lane)
+{
+    uint64_t v = key < list.worst ? key : KEY_MAX;
+    if (!__any(v != KEY_MAX)) return;
+    v = wave_sort64(v, lane);
+    const uint64_t vr = shfl64(v, 63 - lane);
+    uint64_t m = list.cur[0] < vr ? list.cur[0] : vr;
+    m = wave_merge64(m, lane);
+    if (lane >= list.itopk) m = KEY_MAX;
+    list.cur[0] = m;
+    list.worst = readlane64(m, list.itopk - 1);
+}
+
 template <int DT, int E>
 __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 {
@@ -160,9 +177,15 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         }
     };
     auto offer = [&](bool valid, uint32_t bits, int c) { offer_to(top, valid, bits, c); };
+    // Seeds are distinct and offered once, so many of them can enter a list in one merge.
+    auto offer_seeds_to = [&](TopM<1> &list, bool valid, uint32_t bits, int c) {
+        const bool in = valid && bits <= (uint32_t)(list.worst >> 32);
+        if (__popcll(__ballot(in)) < 10) { offer_to(list, valid, bits, c); return; }
+        merge_batch(list, in ? ((uint64_t)bits << 32) | ((uint64_t)(uint32_t)c << 1) | 1ull : KEY_MAX, lane);
+    };
 
     // Distances of cand[0..cnt) (eight at a time, one per team) into cand_d.
-    auto score = [&](int cnt) {
+    auto score = [&](int cnt, bool distinct_new = false) {   // distinct_new: seeds (see offer_seeds_to)
         n_scored += cnt;
         n_gathered += cnt;
 #pragma unroll 2
@@ -179,6 +202,9 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         for (int i0 = 0; i0 < cnt; i0 += 64) {
             const int i = i0 + lane;
             const bool valid = i < cnt;
+            if constexpr (E == 1) {
+                if (distinct_new) { offer_seeds_to(top, valid, valid ? cand_d[i] : 0u, valid ? cand_c[i] : 0); continue; }
+            }
             offer(valid, valid ? cand_d[i] : 0u, valid ? cand_c[i] : 0);
         }
     };
@@ -291,7 +317,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 const bool valid = i < cnt;
                 int c = valid ? cand_c[i] : 0;
                 if (!as_index) c = (int)(((uint64_t)c * (uint64_t)n) / (uint64_t)ns);
-                offer_to(list, valid, valid ? cand_d[i] : 0u, c);
+                offer_seeds_to(list, valid, valid ? cand_d[i] : 0u, c);
             }
             done_to = jc + 64 * NBLK < ns ? jc + 64 * NBLK : ns;
         }
@@ -318,7 +344,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 const int cnt = __popcll(__ballot(valid));
                 if (valid) { cand_c[lane] = c; cand_g[lane] = p.meta.M_HS[base + c]; }
                 __syncthreads();
-                score(cnt);
+                score(cnt, true);
                 float qn = 0.f;
                 for (int i = lane; i < nchunks; i += 64) {
                     const uint4 v = qv[i];

@@ -164,6 +164,36 @@ __device__ __forceinline__ uint32_t wave_merge_u32(uint32_t v, int lane)
     return v;
 }
 
+// The same two networks for 64-bit keys.
+__device__ __forceinline__ uint64_t wave_sort64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)v, j), hi = __shfl_xor((uint32_t)(v >> 32), j);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            const bool up = k == 64 ? true : (lane & k) == 0;
+            const bool take_min = ((lane & j) == 0) == up;
+            const uint64_t mn = v < o ? v : o, mx = v < o ? o : v;
+            v = take_min ? mn : mx;
+        }
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_merge64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, j), hi = __shfl_xor((uint32_t)(v >> 32), j);
+        const uint64_t o = ((uint64_t)hi << 32) | lo;
+        const uint64_t mn = v < o ? v : o, mx = v < o ? o : v;
+        v = (lane & j) == 0 ? mn : mx;
+    }
+    return v;
+}
+
 // Bitonic sort of keys[0..n) ascending in LDS by one wave; n a power of two.
 __device__ __forceinline__ void wave_bitonic_sort(uint64_t *keys, int n, int lane)
 {
