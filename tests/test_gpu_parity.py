@@ -476,3 +476,38 @@ print("panel build ok", len(G))
     env = dict(os.environ, VF_BUILD_PANEL_KB="16", VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
     assert out.returncode == 0 and "panel build ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+
+
+def test_matrix_core_seeds_without_the_seed_copy():
+    """The matrix-core seed kernel normally reads an interleaved copy of the seeds; when that copy does not fit
+    (or VF_SEED_CACHE=0) it gathers the seeds' rows from the vector table instead.  Same results either way:
+    bit-exact graph-path answers on uint8 and float32 data."""
+    import subprocess
+    import sys
+    code = r'''
+import os, sys, numpy as np, torch
+sys.path.insert(0, os.environ["VF_TEST_ROOT"])
+from oracle import OracleIndex
+from paper_2506_00812_amd import binding as vf
+from paper_2506_00812_amd.workloads import make_workload
+for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32)):
+    s = w.spec
+    ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    Q = torch.from_numpy(w.queries).cuda()
+    for params in (dict(itopk=32, width=1, iters=6, n_seeds=200), dict(itopk=32, width=2, iters=10, n_seeds=700)):
+        ids, d = vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+        torch.cuda.synchronize()
+        io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+        g = info["method"] == 2
+        assert g.sum() > 100
+        assert np.array_equal(ids.cpu().numpy()[g], io[g]), (s.name, params)
+        assert np.array_equal(d.cpu().numpy()[g].view(np.uint32), do[g].astype(np.float32).view(np.uint32)), (s.name, params)
+    ix.profile_enable(True)
+    vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, 32, 1, 6, 200)
+    assert ix.profile_read()["seeds_on_matrix_cores"] == 1
+print("gather path ok")
+'''
+    env = dict(os.environ, VF_SEED_CACHE="0", VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
+    assert out.returncode == 0 and "gather path ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
