@@ -672,6 +672,7 @@ static int env_int(const char *name, int dflt, int lo, int hi)
 static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
 static const int kSegGroupsHeavy = env_int("VF_SEG_GROUPS_HEAVY", 32, 1, 4096);  // the same for tiles of >= kHeavyRows queries
 static const int kHeavyRows = env_int("VF_SEG_HEAVY_ROWS", 9, 1, 33);
+static const int kZeroCopyBytes = env_int("VF_ZERO_COPY_BYTES", 8192, 0, 1 << 20);  // blobs up to this size are read in place
 static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
 static const int kScanValu = env_int("VF_SCAN_VALU", 1, 0, 2);      // float32 FMA scan kernel: 0 never, 1 for small batches, 2 always
 static const int kScan16 = env_int("VF_SCAN16", 1, 0, 1);          // 0: float32 search tiles keep the 32-row matrix-core kernel
@@ -906,19 +907,30 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         // Two device blobs alternate.  When the call forks, its blob is uploaded on the side stream: there it
         // follows the previous call's scan, not the previous call's beam search, so the upload is off the
         // critical path.  The buffer was last read two calls ago; the upload waits for that call's end.
+        // A small blob (small batches) is not copied at all: the kernels read the few hundred bytes they need
+        // straight from the pinned staging buffer, which saves the copy's submission and its latency; the
+        // staging buffer then stays untouched until the call's last kernel has ended.
+        const bool zero_copy = kZeroCopyBytes > 0 && L.total <= (size_t)kZeroCopyBytes;
         const int bsel = ix->blob_next;
         DevBuf &blob = bsel ? ix->ws_blob_b : ix->ws_blob;
-        ix->blob_next ^= 1;
-        if ((rc = blob.reserve(L.total)) != VF_OK) return rc;
-        char *dp = blob.as<char>();
-        hipStream_t cs = forked ? ix->side : s;
-        if (forked && ix->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, ix->ev_blob_done[bsel], 0));
-        VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, cs));
-        VF_HIP(hipEventRecord(st->done, cs));
-        st->pending = true;
-        if (forked) {
-            VF_HIP(hipEventRecord(ix->ev_copy, cs));
-            VF_HIP(hipStreamWaitEvent(s, ix->ev_copy, 0));
+        char *dp = nullptr;
+        if (zero_copy) {
+            void *dev_view = nullptr;
+            VF_HIP(hipHostGetDevicePointer(&dev_view, st->p, 0));
+            dp = (char *)dev_view;
+        } else {
+            ix->blob_next ^= 1;
+            if ((rc = blob.reserve(L.total)) != VF_OK) return rc;
+            dp = blob.as<char>();
+            hipStream_t cs = forked ? ix->side : s;
+            if (forked && ix->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, ix->ev_blob_done[bsel], 0));
+            VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, cs));
+            VF_HIP(hipEventRecord(st->done, cs));
+            st->pending = true;
+            if (forked) {
+                VF_HIP(hipEventRecord(ix->ev_copy, cs));
+                VF_HIP(hipStreamWaitEvent(s, ix->ev_copy, 0));
+            }
         }
 
         // every routed query's kernel writes all k entries of its row; only queries without any match are padded here
@@ -1070,8 +1082,13 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             ++ix->prof_unfolded;
         }
         if (forked) VF_HIP(hipStreamWaitEvent(s, ix->ev_join, 0));
-        VF_HIP(hipEventRecord(ix->ev_blob_done[bsel], s));
-        ix->blob_used[bsel] = true;
+        if (zero_copy) {
+            VF_HIP(hipEventRecord(st->done, s));
+            st->pending = true;
+        } else {
+            VF_HIP(hipEventRecord(ix->ev_blob_done[bsel], s));
+            ix->blob_used[bsel] = true;
+        }
         VF_HIP(hipGetLastError());
         if (exact) {
             VF_HIP(hipStreamSynchronize(s));
