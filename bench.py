@@ -353,11 +353,14 @@ def main():
             "flops": 3 * gathered * s.dim},
         seed_kernel: {
             "ms": seed_avg_ms, "bound": "mfma" if pf["seeds_on_matrix_cores"] else "alu",
-            "peak": (FP32_VECTOR_PEAK_TFLOPS if s.dtype == "float32" else 5000.0) if pf["seeds_on_matrix_cores"]
-                    else FP32_VECTOR_PEAK_TFLOPS,
-            "bytes": pf["seed_tile_seeds"] * (vec_bytes + 4) + n_gq * vec_bytes + pf["seed_pairs"] * 4,
+            # 2: float32 data scored from the bfloat16 copy of the seeds (two bfloat16 products per component:
+            # the query's high and low part)
+            "peak": ((2500.0 if pf["seeds_on_matrix_cores"] == 2 else FP32_VECTOR_PEAK_TFLOPS)
+                     if s.dtype == "float32" else 5000.0) if pf["seeds_on_matrix_cores"] else FP32_VECTOR_PEAK_TFLOPS,
+            "bytes": pf["seed_tile_seeds"] * ((vec_bytes // 2 if pf["seeds_on_matrix_cores"] == 2 else vec_bytes) + 4)
+                     + n_gq * vec_bytes + pf["seed_pairs"] * 4,
             # matrix cores: one multiply-add per element of q.x; vector ALU: one subtract + one fused multiply-add
-            "flops": (2 if pf["seeds_on_matrix_cores"] else 3) * pf["seed_pairs"] * s.dim},
+            "flops": ({0: 3, 1: 2, 2: 4}[int(pf["seeds_on_matrix_cores"])]) * pf["seed_pairs"] * s.dim},
         scan_kernel: {
             "ms": scan_avg_ms, "bound": "hbm",
             "bytes": pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),

@@ -211,7 +211,8 @@ typedef struct vf_profile {
     int64_t n_seed_tiles;              /* tiles of <= 64 same-label graph queries scored densely (0: seeds were gathered) */
     int64_t seed_pairs;                /* sum over graph queries of the seeds scored for them                            */
     int64_t seed_tile_seeds;           /* sum over seed tiles of the seeds they read                                     */
-    int64_t seeds_on_matrix_cores;     /* 1: float32 seeds were scored on MFMA (approximate) and re-ranked by the beam kernel */
+    int64_t seeds_on_matrix_cores;     /* 1: the seeds were scored on MFMA (float32: approximations, re-ranked by the beam
+                                          kernel); 2: the same from the bfloat16 copy of the seeds (float32 data)         */
     int64_t seed_rescored;             /* ordered distances computed for that re-ranking                                 */
     int64_t seed_fallbacks;            /* queries whose proof failed and that scored every seed themselves               */
     int64_t beam_gathered;             /* distances whose vector the beam kernel fetched itself (children, re-ranked seeds, seeds when not scored densely) */

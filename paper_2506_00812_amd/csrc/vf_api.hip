@@ -110,6 +110,8 @@ struct vf_index {
     // the seeds of every graph list for the last n_seeds used, interleaved like a scan list, so that the
     // matrix-core seed kernel reads its B operand with coalesced loads (rebuilt when n_seeds changes)
     DevBuf seed_blk, seed_norm, seed_goff;
+    bool seed_bf16 = false;      // seed_blk holds bfloat16 (float32 data only)
+    float seed_bf16_delta = 0.f; // upper bound of |x - bf16(x)| over the seeds of the copy
     int32_t seed_cache_ns = -1;      // n_seeds the copy was built for
     bool seed_cache_ok = false;      // false: it did not fit, the kernel gathers rows from the vector table
     // vf_search_multi: gathered query rows, results of the sub-searches, their parents
@@ -770,6 +772,28 @@ static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
                       n_groups * 32, n_groups, ix->ncp, ix->seed_blk.as<uint4>(), ix->seed_norm.p, s);
     VF_HIP(hipGetLastError());
     VF_HIP(hipStreamSynchronize(s));   // the tables above are pageable host memory and temporaries
+    ix->seed_bf16 = false;
+    static const int want_bf16 = env_int_early("VF_SEED_BF16", 1);
+    if (ix->dtype == VF_F32 && want_bf16) {
+        // float32 data: the copy is kept in bfloat16; the largest rounding error of a seed goes into the
+        // beam kernel's proof (zero for integer-valued data up to 256, SIFT's kind)
+        DevBuf d_blk16, d_err2;
+        struct Rel2 { DevBuf *b[2]; ~Rel2() { for (DevBuf *x : b) x->release(); } } rel2{{&d_blk16, &d_err2}};
+        if ((rc = d_blk16.reserve((size_t)n_groups * ix->group_bytes() / 2)) != VF_OK) return rc;
+        if ((rc = d_err2.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
+        launch_seed_pack_bf16(ix->seed_blk.as<uint4>(), n_groups, ix->ncp, d_blk16.as<uint4>(), d_err2.as<float>(), s);
+        std::vector<float> e2((size_t)n_groups * 32);
+        VF_HIP(hipMemcpyAsync(e2.data(), d_err2.p, e2.size() * 4, hipMemcpyDeviceToHost, s));
+        VF_HIP(hipStreamSynchronize(s));
+        double mx = 0.0;
+        bool finite = true;
+        for (float v : e2) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+        if (finite) {
+            std::swap(ix->seed_blk, d_blk16);   // the float32 copy is released on return
+            ix->seed_bf16 = true;
+            ix->seed_bf16_delta = (float)(std::sqrt(mx) * 1.001);
+        }
+    }
     ix->seed_cache_ok = true;
     return VF_OK;
 }
@@ -994,6 +1018,8 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                         if (ix->seed_cache_ok) {
                             sd.seed_blk = ix->seed_blk.as<uint4>(); sd.seed_norm = ix->seed_norm.as<uint32_t>();
                             sd.seed_goff = ix->seed_goff.as<int64_t>();
+                            sd.seed_bf16 = ix->seed_bf16 ? 1 : 0;
+                            if (prof && sd.seed_bf16) ix->prof.seeds_on_matrix_cores = 2;
                             // seeds per wave: few long waves share the chip better with the scan (512 seeds:
                             // step 0.374 -> 0.340 ms on 10,000-query batches), small batches need many short ones
                             sd.chunk_seeds = 4 * kSeedMfmaChunk;
@@ -1005,6 +1031,17 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                         if (ix->dtype == VF_F32) {
                             bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound; bp.xn_max = ix->xn_max;
                             bp.seed_keep = std::min(64, itopk + kSeedMargin);
+                            if (sd.seed_bf16) {
+                                // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the
+                                // query's split (2^-16 = 256 u), norms and final additions (< 200 u): 2048 u
+                                // = 2^-13 relative to |q|^2 + xn_max, and 2 |q| max |x - bf16(x)|
+                                bp.err_bound = ix->seed_err_bound * 8.0f;
+                                bp.err_q = 2.0f * ix->seed_bf16_delta;
+                                // the wider bound needs a wider gap: more approximations are kept for re-ranking
+                                // (a failed proof costs the query a gather of every seed)
+                                static const int margin16 = env_int_early("VF_SEED_MARGIN_BF16", 24);
+                                bp.seed_keep = std::min(64, itopk + std::max(margin16, kSeedMargin));
+                            }
                         }
                     } else {
                         sd.max_chunks = ns_stride / kSeedChunk;

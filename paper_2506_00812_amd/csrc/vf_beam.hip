@@ -353,7 +353,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 }
 #pragma unroll
                 for (int o = 32; o > 0; o >>= 1) qn += __shfl_xor(qn, o);
-                const float B = p.err_bound * (qn + p.xn_max);
+                const float B = p.err_bound * (qn + p.xn_max) + p.err_q * sqrtf(qn);
                 const bool all_kept = tmp.worst == KEY_MAX;
                 const bool proven = top.worst != KEY_MAX &&
                                     __uint_as_float((uint32_t)(top.worst >> 32)) < __uint_as_float((uint32_t)(tmp.worst >> 32)) - B;

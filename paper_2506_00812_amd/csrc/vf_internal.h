@@ -109,10 +109,11 @@ struct BeamParams {
     const uint32_t *dseed; // optional [n_gq][ns_stride]: seed distance bits from seed_dist_kernel / seed_mfma_kernel
     int32_t ns_stride;
     // dseed holds MFMA approximations (float32 only): the kernel re-scores the best of them with the
-    // ordered distance and proves, with err_bound * (|q|^2 + xn_max), that no other seed can matter
+    // ordered distance and proves, with B = err_bound * (|q|^2 + xn_max) + err_q * |q|, that no other seed can matter
     int32_t seed_approx;
     int32_t seed_keep;  // approximations kept for re-ranking (itopk < seed_keep <= 64)
     float err_bound, xn_max;
+    float err_q;        // 0 unless the seeds were scored from their bfloat16 copy: 2 * max |x - bf16(x)| over the seeds
 };
 
 // ---------------------------------------------------------------- dense seed distances
@@ -135,6 +136,7 @@ struct SeedParams {
     // seed_mfma_kernel, optional: the seeds of every graph list for this n_seeds as an interleaved copy
     // ([group][chunk][32] 16-byte chunks like a scan list, 32 seeds per group in seed order, zero padded)
     const uint4 *seed_blk;
+    int32_t seed_bf16;          // float32 data: seed_blk holds the seeds rounded to bfloat16 (chunks of 8 components)
     const uint32_t *seed_norm;  // [group * 32 + v] squared norms as in xnorm_all
     const int64_t *seed_goff;   // [n_graph_labels] first group of each graph list, by rank among graph labels
     int32_t chunk_seeds;        // seeds per wave: kSeedMfmaChunk, or four times that (interleaved copy only); max_chunks matches it
@@ -143,6 +145,7 @@ struct SeedParams {
 
 // seed_map[g * 32 + v] = global id of seed j = grp_j0[g] + v of graph list grp_slot[g] (local id floor(j n / ns)),
 // 0 for v beyond the list's seeds
+void launch_seed_pack_bf16(const uint4 *blk32, int64_t n_groups, int32_t nch16, uint4 *blk16, float *err2, hipStream_t s);
 void launch_seed_map(const int32_t *M_HS, const int64_t *slot_base, const int32_t *slot_n, int32_t n_seeds,
                      const int32_t *grp_slot, const int32_t *grp_j0, int64_t n_groups, int32_t *seed_map, hipStream_t s);
 

@@ -114,17 +114,32 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 typedef float v16f_seed __attribute__((ext_vector_type(16)));
 typedef int v16i_seed __attribute__((ext_vector_type(16)));
 typedef int v4i_seed __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf_seed __attribute__((ext_vector_type(8)));
+
+// float -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_rn_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
 
 // CACHED: the B operand comes from the interleaved copy of the seeds (coalesced 1-KiB loads, lane (v, h)
 // taking chunk 2 c + h of seed v of the group); otherwise every lane pair gathers its seed's row from X
 // (32 rows of 32 bytes per load instruction).  NG = 32-seed groups per wave (fully unrolled: a loop with a
 // run-time trip count needs both operand buffers live at once and spills): few long waves for large
 // batches, many short ones for small batches.
+// DT = 2: float32 data whose interleaved seed copy holds bfloat16 (16-byte chunks of 8 components, NCH of
+// them per seed, CACHED only).  The queries are split into a bfloat16 high part and the bfloat16 rounding
+// of the rest (|q - hi - lo| <= 2^-16 |q| per component), both multiplied with the seeds by
+// v_mfma_f32_32x32x16_bf16 into one float32 accumulator: half the operand bytes and an eighth of the
+// matrix-core time of the float32 form.  The norms stay those of the unrounded vectors, so the only new
+// error is 2 q.(x - bf16(x)), which the beam kernel's bound carries as err_q * |q|.
 template <int DT, int NCP, bool CACHED, int NG>
 __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 {
-    constexpr int NCH = 2 * NCP, row_bytes = NCH * kChunkBytes;
-    __shared__ uint4 qtile[NCH * 32];
+    static_assert(DT != 2 || CACHED, "bfloat16 seeds exist only as the interleaved copy");
+    constexpr int NCH = 2 * NCP, row_bytes = (DT == 2 ? 2 : 1) * NCH * kChunkBytes;   // row_bytes: of a query
+    __shared__ uint4 qtile[(DT == 2 ? 2 : 1) * NCH * 32];   // DT 2: high parts, then low parts
     __shared__ uint32_t qnorm_s[32];   // float bits / int
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
     const int tile = blockIdx.x / p.max_chunks, chunk = blockIdx.x % p.max_chunks;
@@ -166,6 +181,26 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
 #pragma unroll
         for (int c0 = 0; c0 < NCP; ++c0) {
             const int c = 2 * c0 + h;
+            if constexpr (DT == 2) {   // components 8 c .. 8 c + 7
+                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+                if (qr >= 0) {
+                    v0 = *(const uint4 *)(qp + (2 * c) * kChunkBytes);
+                    v1 = *(const uint4 *)(qp + (2 * c + 1) * kChunkBytes);
+                }
+                const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                uint32_t hi[8], lo[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float f = __uint_as_float(w[i]);
+                    facc += f * f;
+                    hi[i] = bf16_rn_bits(f);
+                    lo[i] = bf16_rn_bits(f - __uint_as_float(hi[i] << 16));
+                }
+                qtile[c * 32 + n32] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+                qtile[NCH * 32 + c * 32 + n32] =
+                    make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+                continue;
+            }
             uint4 v = make_uint4(0, 0, 0, 0);
             if (qr >= 0) {
                 v = *(const uint4 *)(qp + c * kChunkBytes);
@@ -235,6 +270,22 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
             }
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) bits[jj] = (uint32_t)((int)qn[jj] + (int)xn[g] - 2 * acc[jj]);
+        } else if constexpr (DT == 2) {
+            v16f_seed acc;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) acc[jj] = 0.f;
+#pragma unroll
+            for (int cp = 0; cp < NCP; ++cp) {
+                const v8bf_seed bv = __builtin_bit_cast(v8bf_seed, b[cp]);
+                const uint4 ah = qtile[(2 * cp + h) * 32 + n32], al = qtile[NCH * 32 + (2 * cp + h) * 32 + n32];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_seed, ah), bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_seed, al), bv, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const float d = (__uint_as_float(qn[jj]) + __uint_as_float(xn[g])) - 2.0f * acc[jj];
+                bits[jj] = __float_as_uint(fmaxf(d, 0.0f));
+            }
         } else {
             v16f_seed acc;
 #pragma unroll
@@ -287,11 +338,51 @@ void launch_seed_mfma(int dtype, const SeedParams &p, int n_tiles, hipStream_t s
         else if (cached) hipLaunchKernelGGL((seed_mfma_kernel<DT_, NCP_, true, 4>), grid, block, 0, s, p); \
         else hipLaunchKernelGGL((seed_mfma_kernel<DT_, NCP_, false, 4>), grid, block, 0, s, p); \
     } while (0)
-    if (dtype == 1 && p.dim == 128) VF_LAUNCH_SEED(1, 16);
+    if (dtype == 1 && p.seed_bf16 && cached) {
+        if (p.dim == 128) {
+            if (wide) hipLaunchKernelGGL((seed_mfma_kernel<2, 8, true, 16>), grid, block, 0, s, p);
+            else hipLaunchKernelGGL((seed_mfma_kernel<2, 8, true, 4>), grid, block, 0, s, p);
+        } else if (p.dim == 96) {
+            if (wide) hipLaunchKernelGGL((seed_mfma_kernel<2, 6, true, 16>), grid, block, 0, s, p);
+            else hipLaunchKernelGGL((seed_mfma_kernel<2, 6, true, 4>), grid, block, 0, s, p);
+        }
+    } else if (dtype == 1 && p.dim == 128) VF_LAUNCH_SEED(1, 16);
     else if (dtype == 1 && p.dim == 96) VF_LAUNCH_SEED(1, 12);
     else if (dtype == 0 && p.dim == 128) VF_LAUNCH_SEED(0, 4);
     else if (dtype == 0 && p.dim == 192) VF_LAUNCH_SEED(0, 6);
 #undef VF_LAUNCH_SEED
+}
+
+// The interleaved float32 copy of the seeds (groups of 32, 2 * nch16 chunks of 4 components) rounded to
+// bfloat16 (nch16 chunks of 8 components); err2[group * 32 + v] = |x - bf16(x)|^2.  One thread per seed.
+__global__ void seed_pack_bf16_kernel(const uint4 *blk32, int64_t n_vec, int32_t nch16, uint4 *blk16, float *err2)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_vec) return;
+    const int64_t g = t >> 5;
+    const int v = (int)(t & 31);
+    float e2 = 0.f;
+    for (int c = 0; c < nch16; ++c) {
+        const uint4 a = blk32[(g * (2 * nch16) + 2 * c) * 32 + v], b = blk32[(g * (2 * nch16) + 2 * c + 1) * 32 + v];
+        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float f = __uint_as_float(w[i]);
+            r[i] = bf16_rn_bits(f);
+            const float d = f - __uint_as_float(r[i] << 16);
+            e2 += d * d;
+        }
+        blk16[(g * nch16 + c) * 32 + v] = make_uint4(r[0] | (r[1] << 16), r[2] | (r[3] << 16), r[4] | (r[5] << 16), r[6] | (r[7] << 16));
+    }
+    err2[t] = e2;
+}
+
+void launch_seed_pack_bf16(const uint4 *blk32, int64_t n_groups, int32_t nch16, uint4 *blk16, float *err2, hipStream_t s)
+{
+    if (n_groups <= 0) return;
+    hipLaunchKernelGGL(seed_pack_bf16_kernel, dim3((unsigned)((n_groups * 32 + 255) / 256)), dim3(256), 0, s, blk32,
+                       n_groups * 32, nch16, blk16, err2);
 }
 
 __global__ void seed_map_kernel(const int32_t *M_HS, const int64_t *slot_base, const int32_t *slot_n, int32_t n_seeds,

@@ -337,7 +337,7 @@ def test_float_seed_scoring_variants(vf, env, name):
         assert_exact(ig[g], dg[g], io[g], do[g], f"{name} {env} {params}")
         assert pf["beam_scored"] == info["counters"][g, 0].sum()
         on_mfma = "VF_SEED_EXACT" not in env and params["n_seeds"] > 64
-        assert pf["seeds_on_matrix_cores"] == int(on_mfma)
+        assert pf["seeds_on_matrix_cores"] == (2 if on_mfma else 0)     # 2: from the bfloat16 copy of the seeds
         if "VF_SEED_SLACK" in env and on_mfma:          # lists with <= 64 seeds keep every seed: nothing to prove
             assert pf["seed_fallbacks"] > 0.5 * g.sum()
         elif on_mfma:
@@ -478,10 +478,14 @@ print("panel build ok", len(G))
     assert out.returncode == 0 and "panel build ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
 
 
-def test_matrix_core_seeds_without_the_seed_copy():
-    """The matrix-core seed kernel normally reads an interleaved copy of the seeds; when that copy does not fit
-    (or VF_SEED_CACHE=0) it gathers the seeds' rows from the vector table instead.  Same results either way:
-    bit-exact graph-path answers on uint8 and float32 data."""
+@pytest.mark.parametrize("knob,expect", [({"VF_SEED_CACHE": "0"}, 1), ({"VF_SEED_BF16": "0"}, 1), ({}, 2)],
+                         ids=["row gathers", "float32 seed copy", "bfloat16 seed copy"])
+def test_matrix_core_seed_operand_sources(knob, expect):
+    """The matrix-core seed kernel normally reads an interleaved copy of the seeds, held in bfloat16 for
+    float32 data; with VF_SEED_BF16=0 the copy stays float32, and when it does not fit (or VF_SEED_CACHE=0)
+    the kernel gathers the seeds' rows from the vector table.  Same results every way: bit-exact graph-path
+    answers on uint8 and float32 data (dim 128 and 96).  Each form runs in a process of its own because the
+    library reads these knobs once."""
     import subprocess
     import sys
     code = r'''
@@ -490,24 +494,30 @@ sys.path.insert(0, os.environ["VF_TEST_ROOT"])
 from oracle import OracleIndex
 from paper_2506_00812_amd import binding as vf
 from paper_2506_00812_amd.workloads import make_workload
-for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32)):
+for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32),
+          make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)):
     s = w.spec
     ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
     ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
     Q = torch.from_numpy(w.queries).cuda()
+    qoff = np.arange(s.nq + 1, dtype=np.int64)                     # single-label queries: first label of each
+    qids = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[:-1]])
     for params in (dict(itopk=32, width=1, iters=6, n_seeds=200), dict(itopk=32, width=2, iters=10, n_seeds=700)):
-        ids, d = vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+        ids, d = vf.search(ix, Q, qoff, qids, 10, **params)
         torch.cuda.synchronize()
-        io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+        io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
         g = info["method"] == 2
         assert g.sum() > 100
         assert np.array_equal(ids.cpu().numpy()[g], io[g]), (s.name, params)
         assert np.array_equal(d.cpu().numpy()[g].view(np.uint32), do[g].astype(np.float32).view(np.uint32)), (s.name, params)
     ix.profile_enable(True)
-    vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, 32, 1, 6, 200)
-    assert ix.profile_read()["seeds_on_matrix_cores"] == 1
-print("gather path ok")
+    vf.search(ix, Q, qoff, qids, 10, 32, 1, 6, 200)
+    pf = ix.profile_read()
+    assert pf["seeds_on_matrix_cores"] == (int(os.environ["VF_TEST_EXPECT"]) if s.dtype == "float32" else 1), pf
+    assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf
+print("seed operand ok")
 '''
-    env = dict(os.environ, VF_SEED_CACHE="0", VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    env = dict(os.environ, VF_TEST_EXPECT=str(expect), VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    env.update(knob)
     out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
-    assert out.returncode == 0 and "gather path ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+    assert out.returncode == 0 and "seed operand ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
