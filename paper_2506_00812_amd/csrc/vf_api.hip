@@ -111,6 +111,16 @@ struct vf_index {
     // matrix-core seed kernel reads its B operand with coalesced loads (rebuilt when n_seeds changes)
     DevBuf seed_blk, seed_norm, seed_goff;
     bool seed_bf16 = false;      // seed_blk holds bfloat16 (float32 data only)
+    // Watch on the bfloat16 form: queries whose proof failed are counted on the device; the count is fetched
+    // every kFallbackWindow graph queries and read at a later call, and a window with more than 1/64 failures
+    // switches this index back to the float32 copy (a failed proof costs its query a gather of every seed).
+    bool seed_bf16_off = false;
+    DevBuf d_fb_count;
+    uint32_t *h_fb = nullptr;    // pinned
+    hipEvent_t ev_fb = nullptr;
+    bool fb_pending = false;
+    uint32_t fb_last = 0;
+    int64_t fb_window_q = 0, fb_sent_q = 0;
     float seed_bf16_delta = 0.f; // upper bound of |x - bf16(x)| over the seeds of the copy
     int32_t seed_cache_ns = -1;      // n_seeds the copy was built for
     bool seed_cache_ok = false;      // false: it did not fit, the kernel gathers rows from the vector table
@@ -164,6 +174,9 @@ static void free_index(vf_index *ix)
     for (auto &set : ix->prof_ring)
         for (hipEvent_t e : set)
             if (e) (void)hipEventDestroy(e);
+    if (ix->ev_fb) (void)hipEventDestroy(ix->ev_fb);
+    if (ix->h_fb) (void)hipHostFree(ix->h_fb);
+    ix->d_fb_count.release();
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
     if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
     if (ix->ev_copy) (void)hipEventDestroy(ix->ev_copy);
@@ -675,6 +688,7 @@ static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vect
 static const int kSegGroupsHeavy = env_int("VF_SEG_GROUPS_HEAVY", 32, 1, 4096);  // the same for tiles of >= kHeavyRows queries
 static const int kHeavyRows = env_int("VF_SEG_HEAVY_ROWS", 9, 1, 33);
 static const int kZeroCopyBytes = env_int("VF_ZERO_COPY_BYTES", 8192, 0, 1 << 20);  // blobs up to this size are read in place
+static const int kFallbackWindow = env_int("VF_SEED_FB_WINDOW", 131072, 1, 1 << 30);  // graph queries between two looks at the failed proofs
 static const int kSeedMargin = env_int("VF_SEED_MARGIN", 8, 1, 32);  // matrix-core seed scores kept beyond itopk for re-ranking
 static const int kScanValu = env_int("VF_SCAN_VALU", 1, 0, 2);      // float32 FMA scan kernel: 0 never, 1 for small batches, 2 always
 static const int kScan16 = env_int("VF_SCAN16", 1, 0, 1);          // 0: float32 search tiles keep the 32-row matrix-core kernel
@@ -774,7 +788,7 @@ static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
     VF_HIP(hipStreamSynchronize(s));   // the tables above are pageable host memory and temporaries
     ix->seed_bf16 = false;
     static const int want_bf16 = env_int_early("VF_SEED_BF16", 1);
-    if (ix->dtype == VF_F32 && want_bf16) {
+    if (ix->dtype == VF_F32 && want_bf16 && !ix->seed_bf16_off) {
         // float32 data: the copy is kept in bfloat16; the largest rounding error of a seed goes into the
         // beam kernel's proof (zero for integer-valued data up to 256, SIFT's kind)
         DevBuf d_blk16, d_err2;
@@ -792,6 +806,14 @@ static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
             std::swap(ix->seed_blk, d_blk16);   // the float32 copy is released on return
             ix->seed_bf16 = true;
             ix->seed_bf16_delta = (float)(std::sqrt(mx) * 1.001);
+            if (!ix->h_fb) {
+                if ((rc = ix->d_fb_count.reserve(4)) != VF_OK) return rc;
+                VF_HIP(hipMemsetAsync(ix->d_fb_count.p, 0, 4, s));
+                VF_HIP(hipStreamSynchronize(s));
+                VF_HIP(hipHostMalloc((void **)&ix->h_fb, 4, hipHostMallocDefault));
+                *ix->h_fb = 0;
+                VF_HIP(hipEventCreateWithFlags(&ix->ev_fb, hipEventDisableTiming));
+            }
         }
     }
     ix->seed_cache_ok = true;
@@ -1014,6 +1036,17 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                         sd.chunk_seeds = kSeedMfmaChunk;
                         sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
                         sd.xnorm_all = ix->d_xnorm_all.as<uint32_t>();
+                        if (ix->fb_pending && hipEventQuery(ix->ev_fb) == hipSuccess) {
+                            const uint32_t now = *ix->h_fb, failed = now - ix->fb_last;
+                            ix->fb_last = now;
+                            ix->fb_pending = false;
+                            if ((int64_t)failed * 64 > ix->fb_sent_q) {
+                                ix->seed_bf16_off = true;
+                                ix->seed_cache_ns = -1;   // the copy is rebuilt in float32 below
+                            }
+                        } else if (ix->fb_pending) {
+                            (void)hipGetLastError();      // "not ready" is no error
+                        }
                         if ((rc = ensure_seed_cache(ix, n_seeds, s)) != VF_OK) return rc;
                         if (ix->seed_cache_ok) {
                             sd.seed_blk = ix->seed_blk.as<uint4>(); sd.seed_norm = ix->seed_norm.as<uint32_t>();
@@ -1037,6 +1070,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                                 // = 2^-13 relative to |q|^2 + xn_max, and 2 |q| max |x - bf16(x)|
                                 bp.err_bound = ix->seed_err_bound * 8.0f;
                                 bp.err_q = 2.0f * ix->seed_bf16_delta;
+                                bp.fallback_count = ix->d_fb_count.as<uint32_t>();
                                 // the wider bound needs a wider gap: more approximations are kept for re-ranking
                                 // (a failed proof costs the query a gather of every seed)
                                 static const int margin16 = env_int_early("VF_SEED_MARGIN_BF16", 24);
@@ -1112,6 +1146,16 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if ((rc = run_scan()) != VF_OK) return rc;
         if ((rc = run_seeds()) != VF_OK) return rc;
         if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
+        if (bp.fallback_count != nullptr) {
+            ix->fb_window_q += (int64_t)n_gq;
+            if (!ix->fb_pending && ix->fb_window_q >= kFallbackWindow) {
+                VF_HIP(hipMemcpyAsync(ix->h_fb, bp.fallback_count, 4, hipMemcpyDeviceToHost, s));
+                VF_HIP(hipEventRecord(ix->ev_fb, s));
+                ix->fb_pending = true;
+                ix->fb_sent_q = ix->fb_window_q;
+                ix->fb_window_q = 0;
+            }
+        }
         if (prof) {
             VF_HIP(hipEventRecord(ix->prof_ev[4], s));
             ix->prof_valid = true;

@@ -368,6 +368,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
                 n_scored = 0;
                 n_tested = 0;
                 seed_fallback = 1;
+                if (p.fallback_count != nullptr && lane == 0) atomicAdd(p.fallback_count, 1u);
             }
         }
     }

@@ -113,6 +113,7 @@ struct BeamParams {
     int32_t seed_approx;
     int32_t seed_keep;  // approximations kept for re-ranking (itopk < seed_keep <= 64)
     float err_bound, xn_max;
+    uint32_t *fallback_count;  // optional: incremented once per query whose proof failed
     float err_q;        // 0 unless the seeds were scored from their bfloat16 copy: 2 * max |x - bf16(x)| over the seeds
 };
 
