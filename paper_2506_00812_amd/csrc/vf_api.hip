@@ -1066,8 +1066,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                             bp.seed_keep = std::min(64, itopk + kSeedMargin);
                             if (sd.seed_bf16) {
                                 // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the
-                                // query's split (2^-16 = 256 u), norms and final additions (< 200 u): 2048 u
-                                // = 2^-13 relative to |q|^2 + xn_max, and 2 |q| max |x - bf16(x)|
+                                // query's split (2^-16 = 256 u), norms and final additions (< 200 u): under
+                                // 1024 u; 4096 u = 2^-12 relative to |q|^2 + xn_max is used, plus
+                                // 2 |q| max |x - bf16(x)|
                                 bp.err_bound = ix->seed_err_bound * 8.0f;
                                 bp.err_q = 2.0f * ix->seed_bf16_delta;
                                 bp.fallback_count = ix->d_fb_count.as<uint32_t>();
