@@ -68,6 +68,19 @@ __device__ __forceinline__ bool is_seed(uint32_t c, uint32_t n, uint32_t ns, dou
     return r == 0 || r > (int64_t)(n - ns);
 }
 
+// floor(j * n / ns) for j < ns <= n: quotient estimated in double precision (exact product below 2^52, the
+// estimate off by at most one), corrected with the exact remainder.
+__device__ __forceinline__ int seed_local_id(uint32_t j, uint32_t n, uint32_t ns)
+{
+    const uint64_t prod = (uint64_t)j * n;
+    if (((uint64_t)n * ns) >> 52) return (int)(prod / ns);
+    uint32_t q = (uint32_t)((double)j * (double)n / (double)ns);
+    int64_t r = (int64_t)prod - (int64_t)((uint64_t)q * ns);
+    if (r < 0) { r += ns; --q; }
+    if (r >= (int64_t)ns) { r -= ns; ++q; }
+    return (int)q;
+}
+
 // The sorted top-M list: element i sits in register i / 64 of lane i % 64.
 template <int E> struct TopM {
     uint64_t cur[E];
@@ -277,41 +290,40 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             // the two smallest values of every lane; the M-th smallest of those 128 bounds the M-th
             // smallest of the chunk: sort both sets across the wave, take the 64 smallest of their
             // union (element-wise minimum against the reversed other set), sort those
-            uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
+            // (a full list bounds the chunk as well as that, or better from the third chunk on: its worst
+            // entry is the M-th smallest of everything before)
+            uint32_t tau = (uint32_t)(list.worst >> 32);
+            if (list.worst == KEY_MAX) {
+                uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
 #pragma unroll
-            for (int i = 1; i < NBLK; ++i) {
-                const uint32_t hi = v[i] > m1 ? v[i] : m1;
-                m2 = hi < m2 ? hi : m2;
-                m1 = v[i] < m1 ? v[i] : m1;
+                for (int i = 1; i < NBLK; ++i) {
+                    const uint32_t hi = v[i] > m1 ? v[i] : m1;
+                    m2 = hi < m2 ? hi : m2;
+                    m1 = v[i] < m1 ? v[i] : m1;
+                }
+                const uint32_t s1 = wave_sort_u32(m1, lane), s2 = wave_sort_u32(m2, lane);
+                const uint32_t s2r = (uint32_t)__shfl((int)s2, 63 - lane);
+                const uint32_t sorted = wave_merge_u32(s1 < s2r ? s1 : s2r, lane);
+                tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, list.itopk - 1);
             }
-            const uint32_t s1 = wave_sort_u32(m1, lane), s2 = wave_sort_u32(m2, lane);
-            const uint32_t s2r = (uint32_t)__shfl((int)s2, 63 - lane);
-            const uint32_t sorted = wave_merge_u32(s1 < s2r ? s1 : s2r, lane);
-            uint32_t tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, list.itopk - 1);
-            const uint32_t wb = (uint32_t)(list.worst >> 32);
-            tau = tau < wb ? tau : wb;
-            int total = 0;
-#pragma unroll
-            for (int i = 0; i < NBLK; ++i)
-                total += __popcll(__ballot(v[i] <= tau && v[i] != 0xFFFFFFFFu && jc + i * 64 + lane < ns));
-            if (total > 128) break;
-            n_scored += chunk_scored;
-            n_tested += chunk_tested;
             __syncthreads();
-            int cnt = 0;
+            int cnt = 0;   // seeds at or below the bound, compacted into cand[] (those beyond its 128 slots only counted)
 #pragma unroll
             for (int i = 0; i < NBLK; ++i) {
                 const int j = jc + i * 64 + lane;
                 const bool pass = v[i] <= tau && v[i] != 0xFFFFFFFFu && j < ns;
                 const uint64_t m = __ballot(pass);
-                if (pass) {
-                    const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
+                const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
+                if (pass && at < 128) {
                     cand_d[at] = v[i];
                     cand_c[at] = j;
                 }
                 cnt += __popcll(m);
             }
             __syncthreads();
+            if (cnt > 128) break;
+            n_scored += chunk_scored;
+            n_tested += chunk_tested;
             for (int i0 = 0; i0 < cnt; i0 += 64) {
                 const int i = i0 + lane;
                 const bool valid = i < cnt;
@@ -338,7 +350,7 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             if (got == ns) {
                 const uint64_t key = tmp.cur[0];
                 const bool valid = key != KEY_MAX;
-                const int c = valid ? (int)(((uint64_t)((uint32_t)(key >> 1) & 0x7FFFFFFFu) * (uint64_t)n) / (uint64_t)ns) : 0;
+                const int c = valid ? seed_local_id((uint32_t)(key >> 1) & 0x7FFFFFFFu, (uint32_t)n, (uint32_t)ns) : 0;
                 // the kept seeds sit in lanes 0 .. cnt - 1 (sorted list) and have passed the predicate already
                 __syncthreads();
                 const int cnt = __popcll(__ballot(valid));
@@ -413,6 +425,8 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
     }
 
     // ---- iterations: expand the best unexpanded entries, score their unvisited children, merge
+    // child slot j = j0 + lane (j0 = 0 or 64, width * R <= 128) is edge j % R of parent j / R
+    const int jq0 = lane / R, jr0 = lane - jq0 * R, jq1 = (lane + 64) / R, jr1 = lane + 64 - jq1 * R;
     for (int it = 0; it < p.iters; ++it) {
         int np = 0;
 #pragma unroll
@@ -446,9 +460,10 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
             if (valid) {
                 // the row as local ids (list bookkeeping) and as global ids (where the vector is): two
                 // independent coalesced loads instead of a lookup in M that depends on the first
-                const int pa = parents[j / R];
-                c = p.G[(base + pa) * R + (j % R)];
-                g = p.Gg[(base + pa) * R + (j % R)];
+                const int pa = parents[j0 == 0 ? jq0 : jq1];
+                const int64_t at = (base + pa) * R + (j0 == 0 ? jr0 : jr1);
+                c = p.G[at];
+                g = p.Gg[at];
                 valid = c >= 0 && !is_seed((uint32_t)c, (uint32_t)n, (uint32_t)ns, inv_n) &&
                         visit(hash, p.hash_bits, (uint32_t)c);
             }
