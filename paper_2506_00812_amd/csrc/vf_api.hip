@@ -110,7 +110,9 @@ struct vf_index {
     // the seeds of every graph list for the last n_seeds used, interleaved like a scan list, so that the
     // matrix-core seed kernel reads its B operand with coalesced loads (rebuilt when n_seeds changes)
     DevBuf seed_blk, seed_norm, seed_goff;
-    bool seed_bf16 = false;      // seed_blk holds bfloat16 (float32 data only)
+    DevBuf seed_blk16;           // the same seeds rounded to bfloat16 (float32 data only)
+    bool seed_bf16 = false;      // seed_blk16 is valid
+    bool seed_f32 = false;       // float32 data: seed_blk was kept beside seed_blk16 (small copies only)
     // Watch on the bfloat16 form: queries whose proof failed are counted on the device; the count is fetched
     // every kFallbackWindow graph queries and read at a later call, and a window with more than 1/64 failures
     // switches this index back to the float32 copy (a failed proof costs its query a gather of every seed).
@@ -169,7 +171,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G, &ix->d_Gg,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->seed_blk, &ix->seed_norm, &ix->seed_goff, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->seed_blk, &ix->seed_blk16, &ix->seed_norm, &ix->seed_goff, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
     for (DevBuf *b : bufs) b->release();
     for (auto &set : ix->prof_ring)
         for (hipEvent_t e : set)
@@ -502,7 +504,11 @@ static int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t d
                         VF_HIP(hipStreamSynchronize(s));
                         for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
                     }
-                    if (finite) {   // a table with NaN or overflowing norms keeps the exact kernel
+                    // a table with NaN or overflowing norms keeps the exact kernel, and so does one whose largest
+                    // squared norm is outside [1e-24, 1e30]: the bound below is relative to that norm and assumes
+                    // that what the matrix cores flush (products under 1.2e-38) is negligible beside it
+                    if (ix->dtype == VF_F32 && !(mx >= 1e-24f && mx <= 1e30f)) finite = false;
+                    if (finite) {
                         ix->xn_max = mx;
                         // |approximation - ordered distance| <= 300 u (|q|^2 + |x|^2), u = 2^-24 (dot product of
                         // <= 512 terms in any order, two norms, the final additions, the ordered sum's own
@@ -761,7 +767,7 @@ static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
         }
     }
     if (n_groups == 0) return VF_OK;
-    const size_t need = (size_t)n_groups * (ix->group_bytes() + 32 * 4 + 32 * 4 + 32);
+    const size_t need = (size_t)n_groups * (ix->group_bytes() * 3 / 2 + 32 * 4 + 32 * 4 + 32 * 4 + 32);
     if (need > ix->seed_blk.cap) {
         size_t free_b = 0, total_b = 0;
         VF_HIP(hipMemGetInfo(&free_b, &total_b));
@@ -787,23 +793,31 @@ static int ensure_seed_cache(vf_index *ix, int32_t n_seeds, hipStream_t s)
     VF_HIP(hipGetLastError());
     VF_HIP(hipStreamSynchronize(s));   // the tables above are pageable host memory and temporaries
     ix->seed_bf16 = false;
+    ix->seed_f32 = true;
+    ix->seed_blk16.release();
     static const int want_bf16 = env_int_early("VF_SEED_BF16", 1);
     if (ix->dtype == VF_F32 && want_bf16 && !ix->seed_bf16_off) {
-        // float32 data: the copy is kept in bfloat16; the largest rounding error of a seed goes into the
+        // float32 data: a second copy in bfloat16; the largest rounding error of a seed goes into the
         // beam kernel's proof (zero for integer-valued data up to 256, SIFT's kind)
-        DevBuf d_blk16, d_err2;
-        struct Rel2 { DevBuf *b[2]; ~Rel2() { for (DevBuf *x : b) x->release(); } } rel2{{&d_blk16, &d_err2}};
-        if ((rc = d_blk16.reserve((size_t)n_groups * ix->group_bytes() / 2)) != VF_OK) return rc;
+        DevBuf d_err2;
+        struct Rel2 { DevBuf *b[1]; ~Rel2() { for (DevBuf *x : b) x->release(); } } rel2{{&d_err2}};
+        if ((rc = ix->seed_blk16.reserve((size_t)n_groups * ix->group_bytes() / 2)) != VF_OK) return rc;
         if ((rc = d_err2.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
-        launch_seed_pack_bf16(ix->seed_blk.as<uint4>(), n_groups, ix->ncp, d_blk16.as<uint4>(), d_err2.as<float>(), s);
+        launch_seed_pack_bf16(ix->seed_blk.as<uint4>(), n_groups, ix->ncp, ix->seed_blk16.as<uint4>(), d_err2.as<float>(), s);
         std::vector<float> e2((size_t)n_groups * 32);
         VF_HIP(hipMemcpyAsync(e2.data(), d_err2.p, e2.size() * 4, hipMemcpyDeviceToHost, s));
         VF_HIP(hipStreamSynchronize(s));
         double mx = 0.0;
         bool finite = true;
         for (float v : e2) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+        if (!finite) ix->seed_blk16.release();
         if (finite) {
-            std::swap(ix->seed_blk, d_blk16);   // the float32 copy is released on return
+            // small batches are served from the float32 copy (its proofs need fewer re-scored seeds, which
+            // is what a latency-bound call notices), so a copy of up to 128 MiB stays
+            if ((size_t)n_groups * ix->group_bytes() > ((size_t)128 << 20)) {
+                ix->seed_blk.release();
+                ix->seed_f32 = false;
+            }
             ix->seed_bf16 = true;
             ix->seed_bf16_delta = (float)(std::sqrt(mx) * 1.001);
             if (!ix->h_fb) {
@@ -1049,9 +1063,12 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                         }
                         if ((rc = ensure_seed_cache(ix, n_seeds, s)) != VF_OK) return rc;
                         if (ix->seed_cache_ok) {
-                            sd.seed_blk = ix->seed_blk.as<uint4>(); sd.seed_norm = ix->seed_norm.as<uint32_t>();
+                            static const int min16 = env_int_early("VF_SEED_BF16_MIN_BATCH", 512);
+                            const bool use16 = ix->seed_bf16 && (!ix->seed_f32 || (int64_t)n_gq >= min16);
+                            sd.seed_blk = use16 ? ix->seed_blk16.as<uint4>() : ix->seed_blk.as<uint4>();
+                            sd.seed_norm = ix->seed_norm.as<uint32_t>();
                             sd.seed_goff = ix->seed_goff.as<int64_t>();
-                            sd.seed_bf16 = ix->seed_bf16 ? 1 : 0;
+                            sd.seed_bf16 = use16 ? 1 : 0;
                             if (prof && sd.seed_bf16) ix->prof.seeds_on_matrix_cores = 2;
                             // seeds per wave: few long waves share the chip better with the scan (512 seeds:
                             // step 0.374 -> 0.340 ms on 10,000-query batches), small batches need many short ones
