@@ -956,7 +956,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (!ib.merges.empty()) memcpy(hp + L.off_merges, ib.merges.data(), ib.merges.size() * sizeof(MergeItem));
         if (!tiles.empty()) memcpy(hp + L.off_tiles, tiles.data(), tiles.size() * sizeof(SeedTile));
         if (!r.empty_q.empty()) memcpy(hp + L.off_empty, r.empty_q.data(), r.empty_q.size() * 4);
-        if (dense_seeds && (rc = ix->dseed.reserve(((size_t)n_gq * ns_stride + 64) * 4)) != VF_OK) return rc;
+        if (dense_seeds && (rc = ix->dseed.reserve(((size_t)n_gq * ns_stride + 64 * 1024) * 4)) != VF_OK) return rc;
         if (ib.part_rows > 0) {
             VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
             if ((rc = ix->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
@@ -1046,6 +1046,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                     sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
                     sd.dseed = ix->dseed.as<uint32_t>();
                     sd.dump_off = (int64_t)n_gq * ns_stride;
+                    sd.dump_mask = 1023;
                     if (seeds_mfma) {
                         sd.chunk_seeds = kSeedMfmaChunk;
                         sd.max_chunks = (ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;

@@ -141,7 +141,8 @@ struct SeedParams {
     const uint32_t *seed_norm;  // [group * 32 + v] squared norms as in xnorm_all
     const int64_t *seed_goff;   // [n_graph_labels] first group of each graph list, by rank among graph labels
     int32_t chunk_seeds;        // seeds per wave: kSeedMfmaChunk, or four times that (interleaved copy only); max_chunks matches it
-    int64_t dump_off;           // seed_mfma_kernel: dseed[dump_off .. dump_off + 64) takes the stores of lanes without a pair
+    int64_t dump_off;           // seed_mfma_kernel: dseed[dump_off .. dump_off + 64 * (dump_mask + 1)) takes the stores of
+    int32_t dump_mask;          // lanes without a pair, 64 entries per workgroup index & dump_mask (2^k - 1)
 };
 
 // seed_map[g * 32 + v] = global id of seed j = grp_j0[g] + v of graph list grp_slot[g] (local id floor(j n / ns)),

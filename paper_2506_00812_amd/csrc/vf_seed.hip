@@ -306,13 +306,16 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
         }
         // Every lane stores every value, those without a (query, seed) pair into a dump area behind the
         // matrix: with the stores under conditions the compiler cannot count them, and its wait for the next
-        // group's operand loads becomes a wait for these stores to be acknowledged as well.
+        // group's operand loads becomes a wait for these stores to be acknowledged as well.  The dump area has
+        // a slot per workgroup index (mod 1024): one shared slot is a single hot cache line when many tiles
+        // are partly filled.
         const int j = j0 + g * 32 + n32;
+        uint32_t *dump = p.dseed + p.dump_off + (((int64_t)(blockIdx.x & (unsigned)p.dump_mask)) << 6) + lane;
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
             const int row = 8 * (jj >> 2) + 4 * h + (jj & 3);
             const bool ok = j < ns && row < t.q_count;
-            uint32_t *dst = ok ? p.dseed + (int64_t)(t.gq_begin + row) * p.ns_stride + j : p.dseed + p.dump_off + lane;
+            uint32_t *dst = ok ? p.dseed + (int64_t)(t.gq_begin + row) * p.ns_stride + j : dump;
             *dst = bits[jj];
         }
     }
