@@ -240,13 +240,13 @@ def main():
         return max(ok, key=lambda t: t[2]) if ok else None
 
     p90, p99 = best(0.90), best(0.99)
-    # several settings are within measurement noise of one another; among those within 6 % of the
-    # fastest, the one the committed rocprofv3 counters were taken at is preferred, so that the
-    # `traffic` figure applies to the run
+    # several settings are within measurement noise of one another (three timed steps each); among those
+    # within 10 % of the fastest, the one the committed rocprofv3 counters were taken at is preferred, so
+    # that the `traffic` figure applies to the run
     pref = committed_params(s.name)
     if p90 is not None and pref is not None:
         for t in table:
-            if t[0] == pref and t[1] >= 0.90 and t[2] >= 0.94 * p90[2]:
+            if t[0] == pref and t[1] >= 0.90 and t[2] >= 0.90 * p90[2]:
                 p90 = t
     if args.params:
         forced = tuple(int(v) for v in args.params.split(","))
@@ -510,6 +510,32 @@ def main():
             t = np.sort(np.array(times[200:]))      # first 200 batches are warm-up
             lat[f"batch_{bs}"] = {"p50_ms": round(float(t[len(t) // 2]), 4), "p99_ms": round(float(t[int(len(t) * 0.99)]), 4),
                                   "qps": round(bs / float(np.mean(t)) * 1e3, 1)}
+        # throughput of small batches that arrive faster than one call completes: the same calls issued
+        # round-robin on 1 and on 4 streams without waiting in between (every stream has a workspace of its
+        # own inside the index, so calls on different streams overlap on the GPU)
+        streams = [torch.cuda.Stream() for _ in range(4)]
+        for bs in (1, 8, 64):
+            batches = []
+            for b in range(64):
+                ng = bs // 2 if bs > 1 else (b % 2)
+                pick = np.concatenate([rng.choice(gq_idx, size=ng, replace=False),
+                                       rng.choice(sq_idx, size=bs - ng, replace=False)])
+                batches.append((Q[torch.from_numpy(pick).cuda()].contiguous(), np.arange(bs + 1, dtype=np.int64),
+                                np.ascontiguousarray(lab[pick]),
+                                torch.empty((bs, k), dtype=torch.int64, device="cuda"),
+                                torch.empty((bs, k), dtype=torch.float32, device="cuda")))
+            torch.cuda.synchronize()
+            for n_streams in (1, 4):
+                rates = []
+                for rep in range(6):
+                    t0 = time.perf_counter()
+                    for r in range(8):
+                        for i, (Qb, qo, ql, oi, od) in enumerate(batches):
+                            with torch.cuda.stream(streams[i % n_streams]):
+                                vf.search(ix, Qb, qo, ql, k, *p_lat, oi, od)
+                    torch.cuda.synchronize()
+                    rates.append(8 * len(batches) * bs / (time.perf_counter() - t0))
+                lat[f"batch_{bs}"][f"pipelined_qps_{n_streams}_stream{'s' if n_streams > 1 else ''}"] = round(float(np.median(rates[1:])), 1)
         extra["latency"] = {"params": dict(zip(("itopk", "width", "iters", "n_seeds"), p_lat)), **lat}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same queries

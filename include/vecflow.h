@@ -113,8 +113,17 @@ int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, c
  *   out_dists       device [nq][k] squared distances; +inf where out_ids is -1
  *   hip_stream      the search is enqueued on this stream and the call returns
  *                   without waiting; outputs are valid once the stream has been
- *                   synchronised.  The index holds one workspace: calls on the same
- *                   index must be issued on one stream at a time.
+ *                   synchronised.  Calls on one stream run in order.  Calls on
+ *                   different streams may be issued without waiting for one another,
+ *                   from one host thread or several (the host side of a call is
+ *                   serialised inside the library), and overlap on the GPU: the index
+ *                   keeps a workspace per calling stream, four of them; a fifth stream
+ *                   takes over the workspace of the stream that has held one longest
+ *                   and waits on the host until that stream has drained.  This is how
+ *                   small batches that arrive faster than one call completes are
+ *                   served (the case of the paper's persistent kernel, Section 4.2.3,
+ *                   which is not built).  vf_search_multi follows the same rule; profiled calls
+ *                   and vf_search_exact must not overlap with other calls on the index.
  *
  * A query whose label (any of its labels) has an empty posting list, or whose
  * labels have an empty intersection, yields a row of (-1, +inf); that is not an

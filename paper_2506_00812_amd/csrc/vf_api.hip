@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <ctime>
+#include <mutex>
 #include <new>
 #include <numeric>
 
@@ -84,6 +85,30 @@ struct Routed {
 
 using namespace vf;
 
+// Everything a call writes besides its outputs.  An index has kWorkspaces of them and hands one to each
+// stream that calls it, so that calls on different streams can overlap on the GPU (small batches leave most
+// of the chip idle); calls on one stream share one workspace and run in order as before.
+struct Workspace {
+    DevBuf ws_blob, ws_blob_b, part_idx, part_bits, dseed;
+    // vf_search_multi: gathered query rows, results of the sub-searches, their parents
+    DevBuf multi_q, multi_ids, multi_dists, multi_meta;
+    std::vector<int32_t> multi_host;      // [n_sub parents | nq + 1 first sub-search of each query], alive until the next call
+    std::vector<int64_t> multi_qoff;
+    std::vector<int32_t> multi_qids;
+    // the scan path runs beside the graph path on a second stream of the same (default) priority
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_copy = nullptr;
+    hipEvent_t ev_blob_done[2] = {nullptr, nullptr};   // recorded on the caller's stream when a call that read blob b ends
+    bool blob_used[2] = {false, false};
+    int blob_next = 0;   // the device blob alternates between two buffers
+    Staging stage[2];
+    int stage_next = 0;
+    Routed routed;
+    bool ready = false;          // stream and events exist
+    bool owned = false;
+    hipStream_t owner = nullptr; // the stream whose calls use this workspace
+};
+
 struct vf_index {
     int dtype = 0;
     int64_t n = 0;
@@ -105,8 +130,12 @@ struct vf_index {
     float xn_max = 0.f;
     float seed_err_bound = 0.f;  // relative to |q|^2 + xn_max; VF_SEED_SLACK in the environment scales it (tests)
     bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
-    // search workspace
-    DevBuf ws_blob, ws_blob_b, tmp_blk, tmp_norm, counters, part_idx, part_bits, dseed;
+    // search workspaces (see Workspace); profiled calls and vf_search_exact must not overlap with other calls
+    static constexpr int kWorkspaces = 4;
+    Workspace ws[kWorkspaces];
+    int ws_steal = 0;
+    std::recursive_mutex mu;     // host side of every call
+    DevBuf tmp_blk, tmp_norm, counters;
     // the seeds of every graph list for the last n_seeds used, interleaved like a scan list, so that the
     // matrix-core seed kernel reads its B operand with coalesced loads (rebuilt when n_seeds changes)
     DevBuf seed_blk, seed_norm, seed_goff;
@@ -126,11 +155,6 @@ struct vf_index {
     float seed_bf16_delta = 0.f; // upper bound of |x - bf16(x)| over the seeds of the copy
     int32_t seed_cache_ns = -1;      // n_seeds the copy was built for
     bool seed_cache_ok = false;      // false: it did not fit, the kernel gathers rows from the vector table
-    // vf_search_multi: gathered query rows, results of the sub-searches, their parents
-    DevBuf multi_q, multi_ids, multi_dists, multi_meta;
-    std::vector<int32_t> multi_host;      // [n_sub parents | nq + 1 first sub-search of each query], alive until the next call
-    std::vector<int64_t> multi_qoff;
-    std::vector<int32_t> multi_qids;
     // profiling
     bool profiling = false, prof_valid = false;
     // a ring of event sets (scan begin/end, graph begin, seeds end, beam end), one set per profiled call:
@@ -139,22 +163,12 @@ struct vf_index {
     hipEvent_t prof_ring[kProfRing][5] = {};
     hipEvent_t *prof_ev = prof_ring[0];   // the set of the call being issued
     int prof_next = 0, prof_unfolded = 0; // next ring slot; recorded sets whose durations are not in the sums yet
-    // the scan path runs beside the graph path on a second stream of the same (default) priority
-    hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_copy = nullptr;
-    hipEvent_t ev_blob_done[2] = {nullptr, nullptr};   // recorded on the caller's stream when a call that read blob b ends
-    bool blob_used[2] = {false, false};
-    int blob_next = 0;   // the device blob alternates between two buffers
     bool overlap = true;  // VF_NO_OVERLAP=1 in the environment serialises the two paths (for per-kernel timing)
     bool prof_serial = false;  // vf_profile_enable(index, 2): same, switched at run time
     vf_profile prof{};
     std::vector<int32_t> prof_graph_queries;   // graph-routed queries of the last profiled call
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
     int64_t prof_calls = 0;
-    Staging stage[2];
-    int stage_next = 0;
-    Routed routed;
-
     LabelMeta meta() const
     {
         LabelMeta m;
@@ -171,7 +185,7 @@ static void free_index(vf_index *ix)
 {
     if (!ix) return;
     DevBuf *bufs[] = {&ix->d_S, &ix->d_O_HS, &ix->d_O_LS, &ix->d_hs_slot, &ix->d_M_HS, &ix->d_M_LS, &ix->d_G, &ix->d_Gg,
-                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->ws_blob, &ix->ws_blob_b, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->part_idx, &ix->part_bits, &ix->dseed, &ix->seed_blk, &ix->seed_blk16, &ix->seed_norm, &ix->seed_goff, &ix->multi_q, &ix->multi_ids, &ix->multi_dists, &ix->multi_meta};
+                      &ix->d_X_LS, &ix->d_xnorm_LS, &ix->d_bitsets, &ix->d_xnorm_all, &ix->tmp_blk, &ix->tmp_norm, &ix->counters, &ix->seed_blk, &ix->seed_blk16, &ix->seed_norm, &ix->seed_goff};
     for (DevBuf *b : bufs) b->release();
     for (auto &set : ix->prof_ring)
         for (hipEvent_t e : set)
@@ -179,16 +193,20 @@ static void free_index(vf_index *ix)
     if (ix->ev_fb) (void)hipEventDestroy(ix->ev_fb);
     if (ix->h_fb) (void)hipHostFree(ix->h_fb);
     ix->d_fb_count.release();
-    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
-    if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
-    if (ix->ev_copy) (void)hipEventDestroy(ix->ev_copy);
-    for (hipEvent_t e : ix->ev_blob_done)
-        if (e) (void)hipEventDestroy(e);
-    if (ix->side) { (void)hipStreamSynchronize(ix->side); (void)hipStreamDestroy(ix->side); }
-    for (Staging &s : ix->stage) {
-        if (s.pending) (void)hipEventSynchronize(s.done);
-        if (s.done) (void)hipEventDestroy(s.done);
-        if (s.p) (void)hipHostFree(s.p);
+    for (Workspace &w : ix->ws) {
+        DevBuf *wb[] = {&w.ws_blob, &w.ws_blob_b, &w.part_idx, &w.part_bits, &w.dseed, &w.multi_q, &w.multi_ids, &w.multi_dists, &w.multi_meta};
+        for (DevBuf *b : wb) b->release();
+        if (w.ev_fork) (void)hipEventDestroy(w.ev_fork);
+        if (w.ev_join) (void)hipEventDestroy(w.ev_join);
+        if (w.ev_copy) (void)hipEventDestroy(w.ev_copy);
+        for (hipEvent_t e : w.ev_blob_done)
+            if (e) (void)hipEventDestroy(e);
+        if (w.side) { (void)hipStreamSynchronize(w.side); (void)hipStreamDestroy(w.side); }
+        for (Staging &s : w.stage) {
+            if (s.pending) (void)hipEventSynchronize(s.done);
+            if (s.done) (void)hipEventDestroy(s.done);
+            if (s.p) (void)hipHostFree(s.p);
+        }
     }
     delete ix;
 }
@@ -530,11 +548,6 @@ static int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t d
         const char *e = getenv("VF_NO_OVERLAP");
         ix->overlap = !(e && e[0] == '1');
     }
-    VF_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
-    VF_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
-    VF_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
-    VF_HIP(hipEventCreateWithFlags(&ix->ev_copy, hipEventDisableTiming));
-    for (hipEvent_t &e : ix->ev_blob_done) VF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     guard.ix = nullptr;
     *out = ix;
     return VF_OK;
@@ -650,10 +663,41 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
 
-static int get_staging(vf_index *ix, size_t bytes, Staging **out)
+// The workspace of the calls on stream s: the one the stream has used before, else a free one, else one taken
+// from another stream once that stream has drained.
+static int workspace_for(vf_index *ix, hipStream_t s, Workspace **out)
 {
-    Staging &st = ix->stage[ix->stage_next];
-    ix->stage_next ^= 1;
+    Workspace *w = nullptr;
+    for (Workspace &c : ix->ws)
+        if (c.owned && c.owner == s) { w = &c; break; }
+    if (!w)
+        for (Workspace &c : ix->ws)
+            if (!c.owned) { w = &c; break; }
+    if (!w) {
+        w = &ix->ws[ix->ws_steal];
+        ix->ws_steal = (ix->ws_steal + 1) % vf_index::kWorkspaces;
+        // (a stream its owner has destroyed meanwhile has drained; the error that reports it is dropped)
+        if (hipStreamSynchronize(w->owner) != hipSuccess) (void)hipGetLastError();
+        VF_HIP(hipStreamSynchronize(w->side));
+    }
+    w->owned = true;
+    w->owner = s;
+    if (!w->ready) {
+        VF_HIP(hipStreamCreateWithFlags(&w->side, hipStreamNonBlocking));
+        VF_HIP(hipEventCreateWithFlags(&w->ev_fork, hipEventDisableTiming));
+        VF_HIP(hipEventCreateWithFlags(&w->ev_join, hipEventDisableTiming));
+        VF_HIP(hipEventCreateWithFlags(&w->ev_copy, hipEventDisableTiming));
+        for (hipEvent_t &e : w->ev_blob_done) VF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        w->ready = true;
+    }
+    *out = w;
+    return VF_OK;
+}
+
+static int get_staging(Workspace *W, size_t bytes, Staging **out)
+{
+    Staging &st = W->stage[W->stage_next];
+    W->stage_next ^= 1;
     if (st.pending) { VF_HIP(hipEventSynchronize(st.done)); st.pending = false; }
     if (!st.done) VF_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
     if (bytes > st.cap) {
@@ -842,6 +886,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
 {
     int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
     if (rc != VF_OK) return rc;
+    std::lock_guard<std::recursive_mutex> lock(ix->mu);
+    Workspace *W = nullptr;
+    if ((rc = workspace_for(ix, s, &W)) != VF_OK) return rc;
     if (!exact) {
         VF_REQUIRE(itopk >= k && itopk >= 1 && itopk <= 256, "itopk must be in [k, 256]");
         VF_REQUIRE(width >= 1 && width <= 8 && width * ix->R <= 128, "width must be >= 1 with width * R <= 128");
@@ -861,7 +908,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
     }
     if (nq == 0) return VF_OK;
     try {
-        Routed &r = ix->routed;
+        Routed &r = W->routed;
         if ((rc = route_queries(ix, nq, qoff, qids, exact, first_is_searched, r)) != VF_OK) return rc;
 
         // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
@@ -908,10 +955,10 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         bool dseed_fits = true;
         {
             const uint64_t need = (uint64_t)n_gq * (uint64_t)ns_stride * 4;
-            if (need > ix->dseed.cap) {
+            if (need > W->dseed.cap) {
                 size_t free_b = 0, total_b = 0;
                 VF_HIP(hipMemGetInfo(&free_b, &total_b));
-                dseed_fits = need + need / 4 + 256 <= (free_b + ix->dseed.cap) / 2;
+                dseed_fits = need + need / 4 + 256 <= (free_b + W->dseed.cap) / 2;
             }
         }
         const bool dense_seeds = !exact && n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) && dseed_fits;
@@ -943,7 +990,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         L.total = o;
 
         Staging *st = nullptr;
-        if ((rc = get_staging(ix, L.total, &st)) != VF_OK) return rc;
+        if ((rc = get_staging(W, L.total, &st)) != VF_OK) return rc;
         char *hp = (char *)st->p;
         if (n_gq) {
             memcpy(hp + L.off_gq_query, r.gq_query.data(), n_gq * 4);
@@ -956,11 +1003,11 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         if (!ib.merges.empty()) memcpy(hp + L.off_merges, ib.merges.data(), ib.merges.size() * sizeof(MergeItem));
         if (!tiles.empty()) memcpy(hp + L.off_tiles, tiles.data(), tiles.size() * sizeof(SeedTile));
         if (!r.empty_q.empty()) memcpy(hp + L.off_empty, r.empty_q.data(), r.empty_q.size() * 4);
-        if (dense_seeds && (rc = ix->dseed.reserve(((size_t)n_gq * ns_stride + 64 * 1024) * 4)) != VF_OK) return rc;
+        if (dense_seeds && (rc = W->dseed.reserve(((size_t)n_gq * ns_stride + 64 * 1024) * 4)) != VF_OK) return rc;
         if (ib.part_rows > 0) {
             VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
-            if ((rc = ix->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
-            if ((rc = ix->part_bits.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
+            if ((rc = W->part_idx.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
+            if ((rc = W->part_bits.reserve((size_t)ib.part_rows * k * 4)) != VF_OK) return rc;
         }
         // The scan path runs on the side stream beside the graph path on the caller's stream.
         const bool forked = ix->overlap && !ix->prof_serial && !exact && n_gq > 0 && !items.empty();
@@ -971,25 +1018,25 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         // straight from the pinned staging buffer, which saves the copy's submission and its latency; the
         // staging buffer then stays untouched until the call's last kernel has ended.
         const bool zero_copy = kZeroCopyBytes > 0 && L.total <= (size_t)kZeroCopyBytes;
-        const int bsel = ix->blob_next;
-        DevBuf &blob = bsel ? ix->ws_blob_b : ix->ws_blob;
+        const int bsel = W->blob_next;
+        DevBuf &blob = bsel ? W->ws_blob_b : W->ws_blob;
         char *dp = nullptr;
         if (zero_copy) {
             void *dev_view = nullptr;
             VF_HIP(hipHostGetDevicePointer(&dev_view, st->p, 0));
             dp = (char *)dev_view;
         } else {
-            ix->blob_next ^= 1;
+            W->blob_next ^= 1;
             if ((rc = blob.reserve(L.total)) != VF_OK) return rc;
             dp = blob.as<char>();
-            hipStream_t cs = forked ? ix->side : s;
-            if (forked && ix->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, ix->ev_blob_done[bsel], 0));
+            hipStream_t cs = forked ? W->side : s;
+            if (forked && W->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, W->ev_blob_done[bsel], 0));
             VF_HIP(hipMemcpyAsync(dp, hp, L.total, hipMemcpyHostToDevice, cs));
             VF_HIP(hipEventRecord(st->done, cs));
             st->pending = true;
             if (forked) {
-                VF_HIP(hipEventRecord(ix->ev_copy, cs));
-                VF_HIP(hipStreamWaitEvent(s, ix->ev_copy, 0));
+                VF_HIP(hipEventRecord(W->ev_copy, cs));
+                VF_HIP(hipStreamWaitEvent(s, W->ev_copy, 0));
             }
         }
 
@@ -1044,7 +1091,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                     sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
                     sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
                     sd.dim = ix->dim; sd.n_seeds = n_seeds; sd.ns_stride = ns_stride;
-                    sd.dseed = ix->dseed.as<uint32_t>();
+                    sd.dseed = W->dseed.as<uint32_t>();
                     sd.dump_off = (int64_t)n_gq * ns_stride;
                     sd.dump_mask = 1023;
                     if (seeds_mfma) {
@@ -1108,9 +1155,9 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
         };
         auto run_scan = [&]() -> int {
             if (forked) {
-                VF_HIP(hipEventRecord(ix->ev_fork, s));
-                VF_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
-                ss = ix->side;
+                VF_HIP(hipEventRecord(W->ev_fork, s));
+                VF_HIP(hipStreamWaitEvent(W->side, W->ev_fork, 0));
+                ss = W->side;
             }
             if (prof) VF_HIP(hipEventRecord(ix->prof_ev[0], ss));
 
@@ -1118,7 +1165,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             sp.qsrc = queries; sp.qrow = (const int32_t *)(dp + L.off_qrow);
             sp.dim = ix->dim; sp.ncp = ix->ncp; sp.K = k; sp.tile_rows = ib.tile_rows;
             sp.out_ids = out_ids; sp.out_dists = out_dists;
-            sp.res_idx = ix->part_idx.as<int32_t>(); sp.res_bits = ix->part_bits.as<uint32_t>();
+            sp.res_idx = W->part_idx.as<int32_t>(); sp.res_bits = W->part_bits.as<uint32_t>();
             const MergeItem *d_merges = (const MergeItem *)(dp + L.off_merges);
             sp.others_off = d_others_off; sp.others = d_others; sp.meta = ix->meta();
             if (n_ls_items) {
@@ -1157,7 +1204,7 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
                                   sp.res_bits, k, ib.max_nseg * k, ix->d_M_HS.as<int32_t>(), out_ids, out_dists, s);
             }
             if (prof && !(hs_runs.empty() && n_ls_items)) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
-            if (forked) VF_HIP(hipEventRecord(ix->ev_join, ss));
+            if (forked) VF_HIP(hipEventRecord(W->ev_join, ss));
             return VF_OK;
         };
         // the scan goes first: its longest work items decide when it ends (measured: forking it
@@ -1181,13 +1228,13 @@ static int search_impl(vf_index *ix, const void *queries, int64_t nq, const int6
             ix->prof_next = (ix->prof_next + 1) % vf_index::kProfRing;
             ++ix->prof_unfolded;
         }
-        if (forked) VF_HIP(hipStreamWaitEvent(s, ix->ev_join, 0));
+        if (forked) VF_HIP(hipStreamWaitEvent(s, W->ev_join, 0));
         if (zero_copy) {
             VF_HIP(hipEventRecord(st->done, s));
             st->pending = true;
         } else {
-            VF_HIP(hipEventRecord(ix->ev_blob_done[bsel], s));
-            ix->blob_used[bsel] = true;
+            VF_HIP(hipEventRecord(W->ev_blob_done[bsel], s));
+            W->blob_used[bsel] = true;
         }
         VF_HIP(hipGetLastError());
         if (exact) {
@@ -1233,10 +1280,13 @@ extern "C" int vf_search_multi(vf_index *ix, const void *queries, int64_t nq, co
     if (rc != VF_OK) return rc;
     VF_REQUIRE(qoff && qids, "NULL query label arrays");
     if (nq == 0) return VF_OK;
+    std::lock_guard<std::recursive_mutex> lock(ix->mu);
+    Workspace *W = nullptr;
+    if ((rc = workspace_for(ix, s, &W)) != VF_OK) return rc;
     try {
-        std::vector<int32_t> &host = ix->multi_host;
-        std::vector<int64_t> &sqoff = ix->multi_qoff;
-        std::vector<int32_t> &sqids = ix->multi_qids;
+        std::vector<int32_t> &host = W->multi_host;
+        std::vector<int64_t> &sqoff = W->multi_qoff;
+        std::vector<int32_t> &sqids = W->multi_qids;
         host.clear(); sqoff.assign(1, 0); sqids.clear();
         std::vector<int32_t> first((size_t)nq + 1, 0);
         int32_t labs[kMaxOthers + 1];
@@ -1287,18 +1337,18 @@ extern "C" int vf_search_multi(vf_index *ix, const void *queries, int64_t nq, co
         }
         host.insert(host.end(), first.begin(), first.end());
         const size_t row_bytes = (size_t)ix->dim * ix->elem();
-        if ((rc = ix->multi_meta.reserve(host.size() * 4)) != VF_OK) return rc;
-        if ((rc = ix->multi_q.reserve((size_t)n_sub * row_bytes)) != VF_OK) return rc;
-        if ((rc = ix->multi_ids.reserve((size_t)n_sub * k * 8)) != VF_OK) return rc;
-        if ((rc = ix->multi_dists.reserve((size_t)n_sub * k * 4)) != VF_OK) return rc;
-        VF_HIP(hipMemcpyAsync(ix->multi_meta.p, host.data(), host.size() * 4, hipMemcpyHostToDevice, s));
-        const int32_t *d_parent = ix->multi_meta.as<int32_t>();
+        if ((rc = W->multi_meta.reserve(host.size() * 4)) != VF_OK) return rc;
+        if ((rc = W->multi_q.reserve((size_t)n_sub * row_bytes)) != VF_OK) return rc;
+        if ((rc = W->multi_ids.reserve((size_t)n_sub * k * 8)) != VF_OK) return rc;
+        if ((rc = W->multi_dists.reserve((size_t)n_sub * k * 4)) != VF_OK) return rc;
+        VF_HIP(hipMemcpyAsync(W->multi_meta.p, host.data(), host.size() * 4, hipMemcpyHostToDevice, s));
+        const int32_t *d_parent = W->multi_meta.as<int32_t>();
         const int32_t *d_first = d_parent + n_sub;
-        launch_gather_rows(queries, (int32_t)row_bytes, d_parent, n_sub, ix->multi_q.p, s);
-        rc = search_impl(ix, ix->multi_q.p, n_sub, sqoff.data(), sqids.data(), k, itopk, width, iters, n_seeds, exact,
-                         ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), s, true);
+        launch_gather_rows(queries, (int32_t)row_bytes, d_parent, n_sub, W->multi_q.p, s);
+        rc = search_impl(ix, W->multi_q.p, n_sub, sqoff.data(), sqids.data(), k, itopk, width, iters, n_seeds, exact,
+                         W->multi_ids.as<int64_t>(), W->multi_dists.as<float>(), s, true);
         if (rc != VF_OK) return rc;
-        launch_multi_merge(d_first, nq, ix->multi_ids.as<int64_t>(), ix->multi_dists.as<float>(), k, out_ids, out_dists, s);
+        launch_multi_merge(d_first, nq, W->multi_ids.as<int64_t>(), W->multi_dists.as<float>(), k, out_ids, out_dists, s);
         VF_HIP(hipGetLastError());
     } catch (const std::bad_alloc &) {
         set_error("out of host memory");
@@ -1357,6 +1407,7 @@ extern "C" int vf_index_stats(const vf_index *ix, vf_stats *out)
 extern "C" int vf_profile_enable(vf_index *ix, int on)
 {
     VF_REQUIRE(ix != nullptr, "index is NULL");
+    std::lock_guard<std::recursive_mutex> lock(ix->mu);
     if (on)
         for (auto &set : ix->prof_ring)
             for (hipEvent_t &e : set)
@@ -1373,6 +1424,7 @@ extern "C" int vf_profile_enable(vf_index *ix, int on)
 extern "C" int vf_profile_read(vf_index *ix, vf_profile *out, int32_t *per_query)
 {
     VF_REQUIRE(ix && out, "NULL argument");
+    std::lock_guard<std::recursive_mutex> lock(ix->mu);
     VF_REQUIRE(ix->prof_valid, "no profiled vf_search call to report");
     int rc = fold_profile(ix, vf_index::kProfRing);
     if (rc != VF_OK) return rc;

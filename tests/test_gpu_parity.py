@@ -573,3 +573,55 @@ print("watch ok", seen)
                VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
     out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
     assert out.returncode == 0 and "watch ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+
+
+def test_calls_on_several_streams_overlap_safely(vf):
+    """Every stream that calls an index gets a workspace of its own (four per index, a fifth stream takes over
+    the oldest one once that has drained), so small batches issued on different streams may run at the same
+    time.  Interleaved calls on six streams, no synchronisation in between, each with its own outputs: every
+    call must return exactly what the same call returns alone."""
+    import torch
+    w = _float_small()
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    Q = torch.from_numpy(w.queries).cuda()
+    params = dict(itopk=32, width=2, iters=8, n_seeds=700)
+    sizes = (1, 8, 64, 200)
+    chunks = []
+    pos = 0
+    for rep in range(6):
+        for b in sizes:
+            lo, hi = pos % (s.nq - 200), pos % (s.nq - 200) + b
+            pos += 37
+            qo = (w.qlabel_offsets[lo:hi + 1] - w.qlabel_offsets[lo]).astype(np.int64)
+            qi = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[lo]:w.qlabel_offsets[hi]])
+            chunks.append((lo, hi, qo, qi))
+    alone = []
+    for lo, hi, qo, qi in chunks:
+        ids, d = vf.search(ix, Q[lo:hi], qo, qi, 10, **params)
+        torch.cuda.synchronize()
+        alone.append((ids.cpu().numpy(), d.cpu().numpy()))
+    streams = [torch.cuda.Stream() for _ in range(6)]
+    outs = []
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        outs.clear()
+        for i, (lo, hi, qo, qi) in enumerate(chunks):
+            with torch.cuda.stream(streams[(i + rnd) % len(streams)]):
+                outs.append(vf.search(ix, Q[lo:hi], qo, qi, 10, **params))
+        torch.cuda.synchronize()
+        for i, (ids, d) in enumerate(outs):
+            assert np.array_equal(ids.cpu().numpy(), alone[i][0]), (rnd, i)
+            assert np.array_equal(d.cpu().numpy().view(np.uint32), alone[i][1].view(np.uint32)), (rnd, i)
+    # the multi-label entry point keeps its buffers in the workspace as well
+    qo2, qi2 = _and_queries(64, s.n_labels, 5, hi_a=8, hi_b=30)
+    ref = vf.search_multi(ix, Q[:64], qo2, qi2, vf.OR, 10, **params)
+    torch.cuda.synchronize()
+    got = []
+    for i in range(8):
+        with torch.cuda.stream(streams[i % len(streams)]):
+            got.append(vf.search_multi(ix, Q[:64], qo2, qi2, vf.OR, 10, **params))
+    torch.cuda.synchronize()
+    for ids, d in got:
+        assert np.array_equal(ids.cpu().numpy(), ref[0].cpu().numpy())
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), ref[1].cpu().numpy().view(np.uint32))
