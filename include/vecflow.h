@@ -117,9 +117,9 @@ int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, c
  *                   different streams may be issued without waiting for one another,
  *                   from one host thread or several (the host side of a call is
  *                   serialised inside the library), and overlap on the GPU: the index
- *                   keeps a workspace per calling stream, four of them; a fifth stream
- *                   takes over the workspace of the stream that has held one longest
- *                   and waits on the host until that stream has drained.  This is how
+ *                   keeps a workspace per calling stream, eight of them; a ninth stream
+ *                   takes over the workspace of a stream that is idle, else it waits on
+ *                   the host until one has drained.  This is how
  *                   small batches that arrive faster than one call completes are
  *                   served (the case of the paper's persistent kernel, Section 4.2.3,
  *                   which is not built).  vf_search_multi follows the same rule; profiled calls

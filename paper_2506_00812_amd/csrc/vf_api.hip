@@ -131,7 +131,7 @@ struct vf_index {
     float seed_err_bound = 0.f;  // relative to |q|^2 + xn_max; VF_SEED_SLACK in the environment scales it (tests)
     bool seed_mfma = false;      // VF_SEED_EXACT=1 in the environment keeps the exact VALU seed kernel
     // search workspaces (see Workspace); profiled calls and vf_search_exact must not overlap with other calls
-    static constexpr int kWorkspaces = 4;
+    static constexpr int kWorkspaces = 8;
     Workspace ws[kWorkspaces];
     int ws_steal = 0;
     std::recursive_mutex mu;     // host side of every call
@@ -674,11 +674,19 @@ static int workspace_for(vf_index *ix, hipStream_t s, Workspace **out)
         for (Workspace &c : ix->ws)
             if (!c.owned) { w = &c; break; }
     if (!w) {
-        w = &ix->ws[ix->ws_steal];
-        ix->ws_steal = (ix->ws_steal + 1) % vf_index::kWorkspaces;
-        // (a stream its owner has destroyed meanwhile has drained; the error that reports it is dropped)
-        if (hipStreamSynchronize(w->owner) != hipSuccess) (void)hipGetLastError();
-        VF_HIP(hipStreamSynchronize(w->side));
+        // every workspace has an owner: take one whose streams are idle, else the next in turn once its streams
+        // have drained (a stream its owner has destroyed meanwhile has drained; the error that reports it is dropped)
+        for (Workspace &c : ix->ws) {
+            const hipError_t qo = hipStreamQuery(c.owner), qs = hipStreamQuery(c.side);
+            if (qo != hipSuccess || qs != hipSuccess) (void)hipGetLastError();
+            if (qo != hipErrorNotReady && qs == hipSuccess) { w = &c; break; }
+        }
+        if (!w) {
+            w = &ix->ws[ix->ws_steal];
+            ix->ws_steal = (ix->ws_steal + 1) % vf_index::kWorkspaces;
+            if (hipStreamSynchronize(w->owner) != hipSuccess) (void)hipGetLastError();
+            VF_HIP(hipStreamSynchronize(w->side));
+        }
     }
     w->owned = true;
     w->owner = s;

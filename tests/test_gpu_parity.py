@@ -576,9 +576,9 @@ print("watch ok", seen)
 
 
 def test_calls_on_several_streams_overlap_safely(vf):
-    """Every stream that calls an index gets a workspace of its own (four per index, a fifth stream takes over
-    the oldest one once that has drained), so small batches issued on different streams may run at the same
-    time.  Interleaved calls on six streams, no synchronisation in between, each with its own outputs: every
+    """Every stream that calls an index gets a workspace of its own (eight per index, a ninth stream takes over
+    one whose stream is idle or has drained), so small batches issued on different streams may run at the same
+    time.  Interleaved calls on eleven streams, no synchronisation in between, each with its own outputs: every
     call must return exactly what the same call returns alone."""
     import torch
     w = _float_small()
@@ -601,7 +601,7 @@ def test_calls_on_several_streams_overlap_safely(vf):
         ids, d = vf.search(ix, Q[lo:hi], qo, qi, 10, **params)
         torch.cuda.synchronize()
         alone.append((ids.cpu().numpy(), d.cpu().numpy()))
-    streams = [torch.cuda.Stream() for _ in range(6)]
+    streams = [torch.cuda.Stream() for _ in range(11)]
     outs = []
     torch.cuda.synchronize()
     for rnd in range(3):
