@@ -11,7 +11,7 @@ queries, k = 10 (a seeded synthetic stand-in for the paper's dataset).
 Prints ONE JSON line.  `value` is queries/s at the fastest setting of a grid of
 (itopk, width, iters, n_seeds) whose recall@10, measured in this run against exact
 filtered ground truth, is >= 0.90; the >= 0.99 operating point is reported beside it.
-`roofline` prices the kernel that takes longest when it has the chip to itself against
+`roofline` prices the kernel with the longest launches in the timed region against
 the roof that bounds it, from the algorithmic bytes / flops its work counters imply and
 its duration from HIP events; `cpu_baseline` times the CPU oracle on a bounded sample
 of the same queries.  --latency, --multi, --sweep, --workload c3|c5 add further

@@ -79,3 +79,21 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(binding.VecflowError):
         binding.load_library()
+
+
+def test_bench_reads_the_committed_counter_summary():
+    """bench.py takes `roofline.traffic` from the rocprofv3 counter summary under profiles/ and prefers the
+    parameters that summary was taken at: the summary must parse, and it must cover the three search kernels."""
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("vf_bench", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    params = bench.committed_params("c2")
+    assert params is not None and len(params) == 4 and params in bench.CANDIDATES
+    for kernel in ("beam_kernel", "seed_mfma_kernel", "scan_topk16_kernel"):
+        t = bench.committed_traffic(kernel, "c2", params)
+        assert t is not None and 10_000_000 < t < 5_000_000_000, (kernel, t)
+    assert bench.committed_traffic("beam_kernel", "c2", (1, 1, 1, 1)) is None      # other parameters: no figure
+    assert bench.committed_params("no such workload") is None
