@@ -742,8 +742,8 @@ static int env_int(const char *name, int dflt, int lo, int hi)
     return v < lo ? lo : (v > hi ? hi : v);
 }
 // tuning knobs (the environment overrides exist for experiments)
-static const int kSegGroups = env_int("VF_SEG_GROUPS", 32, 1, 4096);  // 32-vector groups per list segment
-static const int kSegGroupsHeavy = env_int("VF_SEG_GROUPS_HEAVY", 32, 1, 4096);  // the same for tiles of >= kHeavyRows queries
+static const int kSegGroups = env_int("VF_SEG_GROUPS", 16, 1, 4096);  // 32-vector groups per list segment
+static const int kSegGroupsHeavy = env_int("VF_SEG_GROUPS_HEAVY", 16, 1, 4096);  // the same for tiles of >= kHeavyRows queries
 static const int kHeavyRows = env_int("VF_SEG_HEAVY_ROWS", 9, 1, 33);
 static const int kZeroCopyBytes = env_int("VF_ZERO_COPY_BYTES", 8192, 0, 1 << 20);  // blobs up to this size are read in place
 static const int kFallbackWindow = env_int("VF_SEED_FB_WINDOW", 131072, 1, 1 << 30);  // graph queries between two looks at the failed proofs
