@@ -19,7 +19,8 @@
  *   - dtype VF_U8: uint8 vectors, integer-exact distances (exactly representable in
  *     the float output for dim <= 258).  dtype VF_F32: float32 vectors.
  *   - Supported shapes: VF_U8 needs dim % 16 == 0, VF_F32 needs dim % 4 == 0;
- *     16 <= dim*sizeof(elem) <= 2048; n < 2^31.
+ *     16 <= dim*sizeof(elem) <= 992 (a 32-row tile of the contraction kernel, its query rows and its
+ *     candidate queues, must fit the 64 KiB of LDS a workgroup may use); n < 2^31.
  */
 #ifndef VECFLOW_H
 #define VECFLOW_H
@@ -35,11 +36,31 @@ extern "C" {
 #define VF_EINVAL (-1) /* bad shape / dtype / parameter / label id            */
 #define VF_ENOMEM (-2) /* host or device allocation failed                     */
 #define VF_EHIP (-3)   /* a HIP runtime call failed; text in vf_last_error()   */
+#define VF_EINTERNAL (-4) /* an unexpected failure inside the library (a C++ exception caught at the boundary) */
 
 #define VF_U8 0
 #define VF_F32 1
 
 typedef struct vf_index vf_index; /* opaque; owned by the library */
+
+/*
+ * Device allocator supplied by the caller (for instance PyTorch's caching allocator), so that the index and
+ * its workspaces live in memory the caller's framework accounts for.
+ *   alloc   returns `bytes` of device memory on the current device, aligned to at least 256 bytes, or NULL
+ *           when it has none (the call in progress then fails with VF_ENOMEM); must not throw
+ *   free    takes back a pointer alloc returned; the library calls it only after all work that used the
+ *           memory has completed on the device
+ *   ctx     passed through to both
+ * The struct is copied by vf_build_index; the functions and ctx must stay valid until vf_index_free returns.
+ * Every device allocation of the index goes through it: the arrays of Alg. 1 at build time, and the
+ * per-stream workspaces and seed copies that searches create or grow on demand.  Pinned host staging buffers
+ * are the library's own (hipHostMalloc).
+ */
+typedef struct vf_allocator {
+    void *(*alloc)(size_t bytes, void *ctx);
+    void (*free)(void *ptr, void *ctx);
+    void *ctx;
+} vf_allocator;
 
 /*
  * Index construction (Alg. 1; layout of Section 4.2.1 "redundancy bypassing" and
@@ -55,6 +76,8 @@ typedef struct vf_index vf_index; /* opaque; owned by the library */
  *                  graph list, 0 < |C_l| < T -> scan list (Section 4.1.1-4.1.2)
  *   graph_degree   R, out-degree of each per-label graph; needs 1 <= R <= 64 and
  *                  T >= R + 1
+ *   allocator      device allocator for everything the index holds (see vf_allocator);
+ *                  NULL = hipMalloc / hipFree
  *   hip_stream     hipStream_t (NULL = default stream); the call returns after the
  *                  build has completed on it
  *   out            receives the index
@@ -67,7 +90,7 @@ typedef struct vf_index vf_index; /* opaque; owned by the library */
  */
 int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
                    const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
-                   void *hip_stream, vf_index **out);
+                   const vf_allocator *allocator, void *hip_stream, vf_index **out);
 
 /*
  * The same index with the per-list graphs the paper's BuildCAGRAGraph (Alg. 1) stands for in its second
@@ -92,7 +115,8 @@ int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const
 #define VF_GRAPH_PRUNED 1
 int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
                        const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,
-                       int32_t graph_kind, int32_t knn_degree, void *hip_stream, vf_index **out);
+                       int32_t graph_kind, int32_t knn_degree, const vf_allocator *allocator, void *hip_stream,
+                       vf_index **out);
 
 /*
  * Batched label-filtered top-k search (Alg. 2; AND semantics of Section 4.3.2).
@@ -181,6 +205,23 @@ int vf_search_exact(vf_index *index, const void *queries, int64_t nq, const int6
  */
 int vf_index_export(const vf_index *index, int which, void *host_dst, size_t *bytes);
 
+/*
+ * Sizes of an index, in the terms of the memory model of Section 4.2.4 (N points, F_HS / F_LS average number
+ * of graph / scan labels per point, so that n_HS = N F_HS and n_LS = N F_LS, out-degree R, b bytes per
+ * element, D elements per vector).  The base table X (N D b) is the caller's and is not counted.
+ *   bytes_graph    neighbour lists of the HS partition, the model's N F_HS R b with b = 4 (ids are int32),
+ *                  stored twice: as local ids (G_HS of Alg. 1) and once more as global ids (a copy the search
+ *                  reads instead of a lookup in M_HS)
+ *   bytes_x_ls     vectors of the LS partition, the model's N D F_LS b, in the interleaved layout of Section
+ *                  4.2.2: every list is padded to whole groups of 32 vectors (n_groups_LS groups in all) and to
+ *                  an even number of 16-byte chunks per vector (chunks_per_vector), plus one 4-byte squared
+ *                  norm per slot
+ *   bytes_maps     local -> global index mappings M_HS and M_LS, the model's N F b with b = 4
+ *   bytes_bitsets  membership bitsets of the graph labels (the AND predicate of Section 4.3.2 as this library
+ *                  stores it): n_graph_labels ceil(N / 32) 4
+ *   bytes_meta     per-label sizes and offsets ("label metadata" of Section 4.2.4): 24 bytes per label
+ *   bytes_total    the sum of the five
+ */
 typedef struct vf_stats {
     int64_t n, n_HS, n_LS, n_groups_LS;
     int32_t dim, dtype, n_labels, T, graph_degree, n_graph_labels, n_scan_labels, chunks_per_vector;
@@ -188,6 +229,19 @@ typedef struct vf_stats {
 } vf_stats;
 
 int vf_index_stats(const vf_index *index, vf_stats *out);
+
+/*
+ * Experiment and test switches (not part of the paper's method): launch geometry, which kernels serve which
+ * batch sizes, the error-bound scale of the float32 seed proofs.  With index == NULL the process-wide
+ * defaults change, which indexes built afterwards start from (the build-time switches "build16",
+ * "build_panel_kb" and "build_progress" only act that way); with an index, that index's own copy changes, and
+ * no call on it may be in flight.  Names: "seg_groups", "seg_groups_heavy", "heavy_rows", "tile_rows",
+ * "zero_copy_bytes", "scan_valu", "scan16", "overlap", "seed_exact", "seed_slack", "seed_margin",
+ * "seed_margin_bf16", "seed_cache", "seed_bf16", "seed_bf16_min_batch", "seed_fb_window", "build16",
+ * "build_panel_kb", "build_progress".  Returns VF_EINVAL for an unknown name or a value out of range.
+ * Results never depend on any of them.
+ */
+int vf_tune(vf_index *index, const char *name, double value);
 
 /*
  * Measurement support (not part of the paper's method).  While profiling is on,
@@ -230,6 +284,25 @@ typedef struct vf_profile {
 
 int vf_profile_enable(vf_index *index, int on);
 int vf_profile_read(vf_index *index, vf_profile *out, int32_t *per_query);
+
+/*
+ * Test support, host only (no device call): routes a batch the way vf_search does -- per query the searched label
+ * (the smallest of its lists, ties to the lower label id, Section 4.3.2; -1 when one of its lists is empty),
+ * the method (0 = empty result, 1 = scan, |C_l| < T, 2 = graph, Section 4.1.2) and the number of predicate
+ * labels -- and builds the work list of the scan path for posting-list sizes S alone (scan lists laid out in
+ * ascending label id, as vf_build_index does).
+ *   items_out   [items_cap][8] int64: first 32-vector group, start in M_LS, first entry, entries, first tile row,
+ *               tile rows, -1, partial row of tile row 0 (-1: the item writes final results)
+ *   merges_out  [merges_cap][5] int64: start in M_LS, query, partial row of segment 0, stride, segments
+ *   qrow_out    [nq] int32: the query of every scan tile row, then the graph queries grouped by label
+ *   counts      [6] int64: graph queries, scan tile rows, items, merges, partial rows, largest segment count
+ * Output arrays may be NULL except searched, method, n_others and counts (a first call with NULL arrays gives the
+ * sizes).
+ */
+int vf_debug_route(const int32_t *S, int32_t n_labels, int32_t T, int64_t nq, const int64_t *qlabel_offsets,
+                   const int32_t *qlabel_ids, int32_t tile_rows, int32_t seg_groups, int32_t *searched, int32_t *method,
+                   int32_t *n_others, int64_t *items_out, int64_t items_cap, int64_t *merges_out, int64_t merges_cap,
+                   int32_t *qrow_out, int64_t *counts);
 
 /* Releases the index and its workspace.  NULL is allowed. */
 void vf_index_free(vf_index *index);

@@ -21,7 +21,14 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
                     "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi",
-                    "vf_build_index_opt")
+                    "vf_build_index_opt", "vf_tune", "vf_debug_route")
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class VfAllocator(C.Structure):
+    _fields_ = [("alloc", ALLOC_FN), ("free", FREE_FN), ("ctx", C.c_void_p)]
 
 
 class VfStats(C.Structure):
@@ -59,9 +66,14 @@ def load_library():
         L = C.CDLL(LIB_PATH)
         p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         L.vf_build_index.restype = C.c_int
-        L.vf_build_index.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, p, C.POINTER(p)]
+        L.vf_build_index.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, C.POINTER(VfAllocator), p, C.POINTER(p)]
         L.vf_build_index_opt.restype = C.c_int
-        L.vf_build_index_opt.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, i32, i32, p, C.POINTER(p)]
+        L.vf_build_index_opt.argtypes = [p, C.c_int, i64, i32, p, p, i32, i32, i32, i32, i32, C.POINTER(VfAllocator), p,
+                                         C.POINTER(p)]
+        L.vf_tune.restype = C.c_int
+        L.vf_tune.argtypes = [p, C.c_char_p, C.c_double]
+        L.vf_debug_route.restype = C.c_int
+        L.vf_debug_route.argtypes = [p, i32, i32, i64, p, p, i32, i32, p, p, p, p, i64, p, i64, p, p]
         L.vf_search.restype = C.c_int
         L.vf_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
         L.vf_search_exact.restype = C.c_int
@@ -109,13 +121,63 @@ def _dtype_code(t):
     raise VecflowError(f"unsupported dtype {t.dtype}")
 
 
+class TorchAllocator:
+    """vf_allocator backed by PyTorch's caching allocator: the index and its workspaces then live in memory that
+    torch accounts for and reuses.  Blocks are requested on the stream of the call in progress (the binding sets
+    it before every library call); the library frees a block only after the work that used it has completed."""
+
+    def __init__(self, device):
+        import torch
+        self._torch = torch
+        self.device = device
+        self.stream = 0
+        self.live = {}            # address -> bytes
+        self.n_alloc = self.n_free = 0
+
+        def _alloc(nbytes, _ctx):
+            try:
+                ptr = torch.cuda.caching_allocator_alloc(int(nbytes), device=self.device, stream=self.stream)
+            except Exception:      # out of memory: the library reports VF_ENOMEM
+                return None
+            self.live[ptr] = int(nbytes)
+            self.n_alloc += 1
+            return ptr
+
+        def _free(ptr, _ctx):
+            try:
+                if self.live.pop(ptr, None) is not None:
+                    self.n_free += 1
+                    torch.cuda.caching_allocator_delete(ptr)
+            except Exception:      # interpreter shutdown: torch may be gone, the process is ending anyway
+                pass
+
+        self._alloc_cb, self._free_cb = ALLOC_FN(_alloc), FREE_FN(_free)   # kept alive with this object
+        self.struct = VfAllocator(self._alloc_cb, self._free_cb, None)
+
+    def live_bytes(self):
+        return sum(self.live.values())
+
+
 class Index:
     """Handle of a built index.  Keeps the vector tensor alive (the library references it)."""
 
-    def __init__(self, handle, vectors):
+    def __init__(self, handle, vectors, allocator=None):
         self._h = handle
         self.vectors = vectors
+        self.allocator = allocator   # keeps the callbacks alive as long as the library may call them
         self._free = load_library().vf_index_free  # bound here: module globals may be gone at interpreter exit
+
+    def _enter(self, stream=None):
+        """Before a library call that may allocate: blocks come from the pool of the call's stream."""
+        if self.allocator is not None:
+            import torch
+            s = stream if stream is not None else torch.cuda.current_stream()
+            self.allocator.stream = s.cuda_stream
+
+    def tune(self, name: str, value):
+        """Experiment / test switch of this index (vf_tune)."""
+        self._enter()
+        _check(load_library().vf_tune(self._h, name.encode(), float(value)))
 
     def __del__(self):
         self.free()
@@ -160,14 +222,42 @@ class Index:
         return out
 
 
+def debug_route(S, T, qlabel_offsets, qlabel_ids, tile_rows=16, seg_groups=16):
+    """Host-only routing and scan work list for posting-list sizes S (vf_debug_route); no device is touched."""
+    L = load_library()
+    S = np.ascontiguousarray(S, dtype=np.int32)
+    off = np.ascontiguousarray(qlabel_offsets, dtype=np.int64)
+    ids = np.ascontiguousarray(qlabel_ids, dtype=np.int32)
+    nq = len(off) - 1
+    searched, method, n_others = (np.empty(nq, dtype=np.int32) for _ in range(3))
+    counts = np.zeros(6, dtype=np.int64)
+    args = [_np_ptr(S), len(S), int(T), nq, _np_ptr(off), _np_ptr(ids), int(tile_rows), int(seg_groups),
+            _np_ptr(searched), _np_ptr(method), _np_ptr(n_others)]
+    _check(L.vf_debug_route(*args, None, 0, None, 0, None, _np_ptr(counts)))      # sizes only
+    items = np.zeros((max(int(counts[2]), 1), 8), dtype=np.int64)
+    merges = np.zeros((max(int(counts[3]), 1), 5), dtype=np.int64)
+    qrow = np.zeros(max(nq, 1), dtype=np.int32)
+    _check(L.vf_debug_route(*args, _np_ptr(items), len(items), _np_ptr(merges), len(merges), _np_ptr(qrow),
+                            _np_ptr(counts)))
+    n_g, n_s, n_items, n_merges, part_rows, max_nseg = (int(c) for c in counts)
+    return dict(searched=searched, method=method, n_others=n_others, items=items[:n_items], merges=merges[:n_merges],
+                scan_rows=qrow[:n_s], graph_queries=qrow[n_s:n_s + n_g], part_rows=part_rows, max_nseg=max_nseg)
+
+
 GRAPH_KNN, GRAPH_PRUNED = 0, 1
 
 
+def tune_defaults(name: str, value):
+    """Process-wide default of an experiment / test switch: indexes built afterwards start from it."""
+    _check(load_library().vf_tune(None, name.encode(), float(value)))
+
+
 def build_index(vectors, label_offsets, label_ids, n_labels, T, graph_degree, stream=None, graph_kind=GRAPH_KNN,
-                knn_degree=0) -> Index:
+                knn_degree=0, torch_allocator=True) -> Index:
     """vectors: CUDA tensor [n, dim] uint8/float32 (contiguous); labels: host CSR arrays.
     graph_kind=GRAPH_PRUNED: graphs of degree knn_degree (0 = the default) reduced to graph_degree by
-    rank-based pruning and reverse edges (vf_build_index_opt)."""
+    rank-based pruning and reverse edges (vf_build_index_opt).
+    torch_allocator: the index takes its device memory from PyTorch's caching allocator (False: hipMalloc)."""
     L = load_library()
     if not vectors.is_cuda or not vectors.is_contiguous() or vectors.dim() != 2:
         raise VecflowError("vectors must be a contiguous 2-D CUDA tensor")
@@ -176,16 +266,22 @@ def build_index(vectors, label_offsets, label_ids, n_labels, T, graph_degree, st
     if off.shape[0] != vectors.shape[0] + 1:
         raise VecflowError("label_offsets must have n + 1 entries")
     h = C.c_void_p()
+    al = None
+    if torch_allocator:
+        import torch
+        al = TorchAllocator(vectors.device)
+        al.stream = (stream if stream is not None else torch.cuda.current_stream()).cuda_stream
+    al_ref = C.byref(al.struct) if al is not None else None
     if graph_kind == GRAPH_KNN and knn_degree == 0:
         _check(L.vf_build_index(C.c_void_p(vectors.data_ptr()), _dtype_code(vectors), vectors.shape[0],
                                 vectors.shape[1], _np_ptr(off), _np_ptr(ids), int(n_labels), int(T), int(graph_degree),
-                                _stream_handle(stream), C.byref(h)))
+                                al_ref, _stream_handle(stream), C.byref(h)))
     else:
         _check(L.vf_build_index_opt(C.c_void_p(vectors.data_ptr()), _dtype_code(vectors), vectors.shape[0],
                                     vectors.shape[1], _np_ptr(off), _np_ptr(ids), int(n_labels), int(T),
-                                    int(graph_degree), int(graph_kind), int(knn_degree), _stream_handle(stream),
+                                    int(graph_degree), int(graph_kind), int(knn_degree), al_ref, _stream_handle(stream),
                                     C.byref(h)))
-    return Index(h, vectors)
+    return Index(h, vectors, al)
 
 
 def _prep_queries(index, queries, qlabel_offsets, qlabel_ids):
@@ -210,6 +306,7 @@ def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width
         out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
     if out_dists is None:
         out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    index._enter(stream)
     _check(load_library().vf_search(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids), int(k),
                                     int(itopk), int(width), int(iters), int(n_seeds),
                                     C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
@@ -231,6 +328,7 @@ def search_multi(index: Index, queries, qlabel_offsets, qlabel_ids, mode, k, ito
         out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
     if out_dists is None:
         out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    index._enter(stream)
     _check(load_library().vf_search_multi(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids),
                                           int(mode), int(k), int(itopk), int(width), int(iters), int(n_seeds),
                                           C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
@@ -245,6 +343,7 @@ def search_exact(index: Index, queries, qlabel_offsets, qlabel_ids, k, stream=No
     nq = queries.shape[0]
     out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
     out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    index._enter(stream)
     _check(load_library().vf_search_exact(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids),
                                           int(k), C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
                                           _stream_handle(stream)))

@@ -214,5 +214,6 @@ void launch_multi_merge(const int32_t *first, int64_t nq, const int64_t *sub_ids
 // ---------------------------------------------------------------- errors
 
 void set_error(const std::string &msg);
+const char *last_error();
 
 }  // namespace vf

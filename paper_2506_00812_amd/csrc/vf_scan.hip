@@ -890,14 +890,15 @@ __global__ __launch_bounds__(64) void scan_merge_kernel(const MergeItem *items, 
     }
 }
 
-static size_t scan_lds_bytes(const ScanParams &p)
+// LDS of the 32-row form: the query tile (chunk-major), per row a 64-slot queue and the sorted best list
+size_t scan_lds_bytes(int32_t ncp, int32_t tile_rows, int32_t K)
 {
-    return (size_t)2 * p.ncp * p.tile_rows * 16 + (size_t)p.tile_rows * (64 + (p.K | 1)) * 8 + 3 * 32 * 4;
+    return (size_t)2 * ncp * tile_rows * 16 + (size_t)tile_rows * (64 + (K | 1)) * 8 + 3 * 32 * 4;
 }
 
 template <int DT> static void launch_scan_dt(const ScanParams &p, int n_items, hipStream_t s)
 {
-    const size_t lds = scan_lds_bytes(p);
+    const size_t lds = scan_lds_bytes(p.ncp, p.tile_rows, p.K);
     const dim3 grid(n_items), block(64);
     if (DT == 0) {
         switch (p.ncp) {

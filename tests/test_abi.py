@@ -65,13 +65,42 @@ def test_build_rejects_bad_arguments_without_gpu(lib):
         dict(dtype=0, dim=16, n_labels=4, T=40, R=8),        # label id 5 outside the vocabulary
     ]
     for c in cases:
-        rc = lib.vf_build_index(fake, c["dtype"], 2, c["dim"], p(off), p(ids), c["n_labels"], c["T"], c["R"], None,
+        rc = lib.vf_build_index(fake, c["dtype"], 2, c["dim"], p(off), p(ids), c["n_labels"], c["T"], c["R"], None, None,
                                 C.byref(h))
         assert rc == -1, c
         assert lib.vf_last_error()
         assert not h.value
-    assert lib.vf_build_index(None, 0, 2, 16, p(off), p(ids), 8, 40, 8, None, C.byref(h)) == -1
+    assert lib.vf_build_index(None, 0, 2, 16, p(off), p(ids), 8, 40, 8, None, None, C.byref(h)) == -1
+    # vectors longer than the contraction kernel's LDS tile allows; an allocator with a missing function
+    assert lib.vf_build_index(fake, 1, 2, 256, p(off), p(ids), 8, 40, 8, None, None, C.byref(h)) == -1
+    assert b"992" in lib.vf_last_error()
+    half = binding.VfAllocator(binding.ALLOC_FN(lambda n, c: None), binding.FREE_FN(0), None)
+    assert lib.vf_build_index(fake, 0, 2, 16, p(off), p(ids), 8, 40, 8, C.byref(half), None, C.byref(h)) == -1
+    assert b"allocator" in lib.vf_last_error()
     lib.vf_index_free(None)    # allowed
+
+
+def test_tuning_names_and_ranges_without_gpu(lib):
+    """vf_tune with a NULL index changes the process-wide defaults: every documented name is accepted, unknown
+    names and values out of range are rejected with VF_EINVAL, and nothing throws across the ABI."""
+    hdr = open(os.path.join(ROOT, "include", "vecflow.h")).read()
+    doc = re.search(r"Names: (.*?)\.  Returns VF_EINVAL", hdr, re.S).group(1)
+    names = re.findall(r'"([a-z_0-9]+)"', doc)
+    assert len(names) == 19
+    defaults = dict(seg_groups=16, seg_groups_heavy=16, heavy_rows=9, tile_rows=16, zero_copy_bytes=8192, scan_valu=1,
+                    scan16=1, overlap=1, seed_exact=0, seed_slack=1.0, seed_margin=8, seed_margin_bf16=24, seed_cache=1,
+                    seed_bf16=1, seed_bf16_min_batch=512, seed_fb_window=131072, build16=1, build_panel_kb=4096,
+                    build_progress=0)
+    assert sorted(names) == sorted(defaults)
+    for n in names:
+        assert lib.vf_tune(None, n.encode(), float(defaults[n])) == 0, n
+    assert lib.vf_tune(None, b"no_such_knob", 1.0) == -1
+    assert b"no_such_knob" in lib.vf_last_error()
+    assert lib.vf_tune(None, b"tile_rows", 33.0) == -1
+    assert lib.vf_tune(None, b"tile_rows", 7.5) == -1
+    assert lib.vf_tune(None, b"seed_slack", -1.0) == -1
+    assert lib.vf_tune(None, b"seed_slack", float("nan")) == -1
+    assert lib.vf_tune(None, None, 1.0) == -1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -215,3 +215,38 @@ def test_c5_like_midscale_and_queries_sampled_against_oracle():
             lst = M_HS[O_HS[l]:O_HS[l] + S[l]] if O_HS[l] >= 0 else M_LS[O_LS[l]:O_LS[l] + S[l]]
             for res in (ids[j], idp[j]):
                 assert np.isin(res[res >= 0], lst).all()
+
+
+@pytest.mark.parametrize("bs,n_batches", [(1, 8), (8, 4), (64, 2)])
+def test_small_batches_on_the_full_index_against_oracle(c2, bs, n_batches):
+    """The small-batch configuration: batches of 1, 8 and 64 single-label queries on the full-size index, half
+    of each batch on graph lists and half on scan lists (drawn the way bench.py --latency draws them), at the
+    parameters bench.py uses there.  Small batches take the FMA scan kernel over multi-segment lists of up to
+    T - 1 vectors and read their routing tables in place from pinned host memory."""
+    import torch
+    vf, w, ix, Q, ixo = c2
+    s = w.spec
+    S = ixo.S
+    lab = w.qlabel_ids[w.qlabel_offsets[:-1]]
+    gq_idx = np.flatnonzero(S[lab] >= s.T)
+    sq_idx = np.flatnonzero((S[lab] < s.T) & (S[lab] > 0))
+    long_scan = sq_idx[S[lab[sq_idx]] > 5000]          # scan lists of several segments
+    assert len(long_scan) >= 8
+    rng = np.random.default_rng(4321 + bs)
+    for b in range(n_batches):
+        ng = bs // 2 if bs > 1 else (b % 2)
+        pick_s = rng.choice(sq_idx, size=bs - ng, replace=False)
+        if len(pick_s):
+            pick_s[0] = rng.choice(long_scan)
+        pick = np.concatenate([rng.choice(gq_idx, size=ng, replace=False), pick_s]).astype(np.int64)
+        Qb = Q[torch.from_numpy(pick).cuda()].contiguous()
+        qo = np.arange(bs + 1, dtype=np.int64)
+        ql = np.ascontiguousarray(lab[pick])
+        ids, dists = vf.search(ix, Qb, qo, ql, s.k, **PARAMS_99)
+        torch.cuda.synchronize()
+        ids, dists = to_np(ids), to_np(dists)
+        io, do, info = ixo.search(w.queries[pick], qo, ql, s.k, with_info=True, **PARAMS_99)
+        g = info["method"] == 2
+        assert g.sum() == ng
+        assert_exact(ids[g], dists[g], io[g], do[g], f"batch of {bs}, graph path")
+        assert_close_with_ties(ids[~g], dists[~g], io[~g], do[~g], 1e-4, f"batch of {bs}, scan path")

@@ -295,31 +295,23 @@ def test_dims_without_dense_seed_kernel(vf, name, dim):
             assert_close_with_ties(ig[~g], dg[~g], io[~g], do[~g], RTOL, f"{name} dim {dim} scan")
 
 
-@pytest.mark.parametrize("env", [{}, {"VF_SEED_SLACK": "1e30"}, {"VF_SEED_EXACT": "1"}],
+@pytest.mark.parametrize("knob", [{}, {"seed_slack": 1e30}, {"seed_exact": 1}],
                          ids=["matrix-core seeds", "proof always fails", "exact seed kernel"])
 @pytest.mark.parametrize("name", ["c2", "c5"])
-def test_float_seed_scoring_variants(vf, env, name):
+def test_float_seed_scoring_variants(vf, knob, name):
     """float32 seeds are scored on the matrix cores and re-ranked with the ordered distance;
     the beam kernel accepts that only with a proof and otherwise scores every seed itself.
     All three routes (proof holds; proof forced to fail; exact seed kernel) must give the
     oracle's bits, for dim 128 and dim 96, also when a list is shorter than the seed count."""
-    import os
     import torch
     if name == "c2":
         w = _float_small()
     else:
         w = make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)
     s = w.spec
-    old = {k: os.environ.get(k) for k in env}
-    os.environ.update(env)
-    try:
-        ix = _gpu_index(vf, w)
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
+    ix = _gpu_index(vf, w)
+    for key, value in knob.items():
+        ix.tune(key, value)
     ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
     Q = torch.from_numpy(w.queries).cuda()
     qoff = np.arange(s.nq + 1, dtype=np.int64)                     # single-label queries: first label of each
@@ -334,12 +326,12 @@ def test_float_seed_scoring_variants(vf, env, name):
         io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
         g = info["method"] == 2
         assert g.sum() > 100
-        assert_exact(ig[g], dg[g], io[g], do[g], f"{name} {env} {params}")
+        assert_exact(ig[g], dg[g], io[g], do[g], f"{name} {knob} {params}")
         assert pf["beam_scored"] == info["counters"][g, 0].sum()
-        on_mfma = "VF_SEED_EXACT" not in env and params["n_seeds"] > 64
+        on_mfma = "seed_exact" not in knob and params["n_seeds"] > 64
         # 2: from the bfloat16 copy of the seeds (calls with >= 512 graph queries), 1: from the float32 copy
         assert pf["seeds_on_matrix_cores"] == ((2 if g.sum() >= 512 else 1) if on_mfma else 0)
-        if "VF_SEED_SLACK" in env and on_mfma:          # lists with <= 64 seeds keep every seed: nothing to prove
+        if "seed_slack" in knob and on_mfma:            # lists with <= 64 seeds keep every seed: nothing to prove
             assert pf["seed_fallbacks"] > 0.5 * g.sum()
         elif on_mfma:
             assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf["seed_fallbacks"]
@@ -452,127 +444,93 @@ def test_float_multi_search(vf, mode_name):
                            f"float {mode_name}, scan lists involved")
 
 
-def test_float_graph_build_in_panels():
+def test_float_graph_build_in_panels(vf):
     """Long float32 lists are self-joined panel by panel with the rows' best-so-far carried between
     launches.  With the panel forced down to one 32-vector group every list of more than 128 vectors takes
     that route (hundreds of launches per list): the graph rows must still be the oracle's."""
-    import subprocess
-    import sys
-    code = r'''
-import os, sys, numpy as np, torch
-sys.path.insert(0, os.environ["VF_TEST_ROOT"])
-from oracle import OracleIndex
-from paper_2506_00812_amd import binding as vf
-from paper_2506_00812_amd.workloads import make_workload
-w = make_workload("c2", n=12_000, nq=10, n_labels=12, n_clusters=16, T=600, graph_degree=32)
-s = w.spec
-ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
-ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
-G = ix.export("G_HS").reshape(-1, s.graph_degree)
-assert ix.stats()["n_graph_labels"] >= 6 and len(G) > 10_000
-bad = np.flatnonzero((G != ixo.G_HS).any(axis=1))
-assert len(bad) == 0, (len(bad), bad[:5])
-print("panel build ok", len(G))
-'''
-    env = dict(os.environ, VF_BUILD_PANEL_KB="16", VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
-    assert out.returncode == 0 and "panel build ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+    import torch
+    w = make_workload("c2", n=12_000, nq=10, n_labels=12, n_clusters=16, T=600, graph_degree=32)
+    s = w.spec
+    vf.tune_defaults("build_panel_kb", 16)
+    try:
+        ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T,
+                            s.graph_degree)
+    finally:
+        vf.tune_defaults("build_panel_kb", 4096)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    G = ix.export("G_HS").reshape(-1, s.graph_degree)
+    assert ix.stats()["n_graph_labels"] >= 6 and len(G) > 10_000
+    bad = np.flatnonzero((G != ixo.G_HS).any(axis=1))
+    assert len(bad) == 0, (len(bad), bad[:5])
 
 
-@pytest.mark.parametrize("knob,expect", [({"VF_SEED_CACHE": "0"}, 1), ({"VF_SEED_BF16": "0"}, 1), ({}, 2)],
+@pytest.mark.parametrize("knob,expect", [({"seed_cache": 0}, 1), ({"seed_bf16": 0}, 1), ({}, 2)],
                          ids=["row gathers", "float32 seed copy", "bfloat16 seed copy"])
-def test_matrix_core_seed_operand_sources(knob, expect):
+def test_matrix_core_seed_operand_sources(vf, knob, expect):
     """The matrix-core seed kernel normally reads an interleaved copy of the seeds, held in bfloat16 for
     float32 data (calls with fewer than 512 graph queries use a float32 copy kept beside it); with
-    VF_SEED_BF16=0 there is only the float32 copy, and when the copy does not fit (or VF_SEED_CACHE=0)
+    seed_bf16 = 0 there is only the float32 copy, and when the copy does not fit (or seed_cache = 0)
     the kernel gathers the seeds' rows from the vector table.  Same results every way: bit-exact graph-path
-    answers on uint8 and float32 data (dim 128 and 96).  Each form runs in a process of its own because the
-    library reads these knobs once."""
-    import subprocess
-    import sys
-    code = r'''
-import os, sys, numpy as np, torch
-sys.path.insert(0, os.environ["VF_TEST_ROOT"])
-from oracle import OracleIndex
-from paper_2506_00812_amd import binding as vf
-from paper_2506_00812_amd.workloads import make_workload
-for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32),
-          make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)):
+    answers on uint8 and float32 data (dim 128 and 96)."""
+    import torch
+    for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32),
+              make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)):
+        s = w.spec
+        ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+        for key, value in knob.items():
+            ix.tune(key, value)
+        ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+        Q = torch.from_numpy(w.queries).cuda()
+        qoff = np.arange(s.nq + 1, dtype=np.int64)                     # single-label queries: first label of each
+        qids = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[:-1]])
+        for params in (dict(itopk=32, width=1, iters=6, n_seeds=200), dict(itopk=32, width=2, iters=10, n_seeds=700)):
+            ids, d = _search(vf, ix, Q, qoff, qids, 10, **params)
+            io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
+            g = info["method"] == 2
+            assert g.sum() > 100
+            assert_exact(ids[g], d[g], io[g], do[g].astype(np.float32), f"{s.name} {knob} {params}")
+        ix.profile_enable(True)
+        vf.search(ix, Q, qoff, qids, 10, 32, 1, 6, 200)
+        pf = ix.profile_read()
+        want = expect
+        if want == 2 and g.sum() < 512:      # small calls are served from the float32 copy
+            want = 1
+        assert pf["seeds_on_matrix_cores"] == (want if s.dtype == "float32" else 1), pf
+        assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf
+        if s.dtype == "float32":               # and a call of 64 queries always is
+            vf.search(ix, Q[:64], qoff[:65], qids[:64], 10, 32, 1, 6, 200)
+            small = ix.profile_read()
+            assert small["seeds_on_matrix_cores"] == 1, small
+
+
+def test_bfloat16_seed_copy_is_given_up_when_proofs_fail(vf):
+    """Failed proofs are counted on the device; a window of graph queries with more than 1/64 of them switches
+    the index back to the float32 seed copy.  Forced here with a bound that never holds and a short window:
+    the first call scores from the bfloat16 copy, a later one from the float32 copy, and every call returns
+    the oracle's bits."""
+    import torch
+    w = make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32)
     s = w.spec
     ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    for key, value in (("seed_slack", 1e30), ("seed_fb_window", 64), ("seed_bf16_min_batch", 1)):
+        ix.tune(key, value)
     ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
     Q = torch.from_numpy(w.queries).cuda()
-    qoff = np.arange(s.nq + 1, dtype=np.int64)                     # single-label queries: first label of each
+    qoff = np.arange(s.nq + 1, dtype=np.int64)
     qids = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[:-1]])
-    for params in (dict(itopk=32, width=1, iters=6, n_seeds=200), dict(itopk=32, width=2, iters=10, n_seeds=700)):
-        ids, d = vf.search(ix, Q, qoff, qids, 10, **params)
-        torch.cuda.synchronize()
-        io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
-        g = info["method"] == 2
-        assert g.sum() > 100
-        assert np.array_equal(ids.cpu().numpy()[g], io[g]), (s.name, params)
-        assert np.array_equal(d.cpu().numpy()[g].view(np.uint32), do[g].astype(np.float32).view(np.uint32)), (s.name, params)
-    ix.profile_enable(True)
-    vf.search(ix, Q, qoff, qids, 10, 32, 1, 6, 200)
-    pf = ix.profile_read()
-    expect = int(os.environ["VF_TEST_EXPECT"])
-    if expect == 2 and g.sum() < 512:      # small calls are served from the float32 copy
-        expect = 1
-    assert pf["seeds_on_matrix_cores"] == (expect if s.dtype == "float32" else 1), pf
-    assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf
-    if s.dtype == "float32":               # and a call of 64 queries always is
-        vf.search(ix, Q[:64], qoff[:65], qids[:64], 10, 32, 1, 6, 200)
-        small = ix.profile_read()
-        assert small["seeds_on_matrix_cores"] == 1, small
-print("seed operand ok")
-'''
-    env = dict(os.environ, VF_TEST_EXPECT=str(expect), VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-    env.update(knob)
-    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
-    assert out.returncode == 0 and "seed operand ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
-
-
-def test_bfloat16_seed_copy_is_given_up_when_proofs_fail():
-    """Failed proofs are counted on the device; a window of graph queries with more than 1/64 of them switches
-    the index back to the float32 seed copy.  Forced here with a bound that never holds (VF_SEED_SLACK) and a
-    short window: the first call scores from the bfloat16 copy, a later one from the float32 copy, and every
-    call returns the oracle's bits."""
-    import subprocess
-    import sys
-    code = r'''
-import os, sys, numpy as np, torch
-sys.path.insert(0, os.environ["VF_TEST_ROOT"])
-from oracle import OracleIndex
-from paper_2506_00812_amd import binding as vf
-from paper_2506_00812_amd.workloads import make_workload
-w = make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32)
-s = w.spec
-ix = vf.build_index(torch.from_numpy(w.vectors).cuda(), w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
-ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
-Q = torch.from_numpy(w.queries).cuda()
-qoff = np.arange(s.nq + 1, dtype=np.int64)
-qids = np.ascontiguousarray(w.qlabel_ids[w.qlabel_offsets[:-1]])
-params = dict(itopk=32, width=1, iters=6, n_seeds=700)
-io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
-g = info["method"] == 2
-assert g.sum() > 100
-seen = []
-for call in range(4):
-    ix.profile_enable(True)
-    ids, d = vf.search(ix, Q, qoff, qids, 10, **params)
-    torch.cuda.synchronize()
-    pf = ix.profile_read()
-    ix.profile_enable(False)
-    seen.append(int(pf["seeds_on_matrix_cores"]))
-    assert np.array_equal(ids.cpu().numpy()[g], io[g]), call
-    assert np.array_equal(d.cpu().numpy()[g].view(np.uint32), do[g].astype(np.float32).view(np.uint32)), call
-assert seen[0] == 2 and seen[-1] == 1, seen
-print("watch ok", seen)
-'''
-    env = dict(os.environ, VF_SEED_SLACK="1e30", VF_SEED_FB_WINDOW="64", VF_SEED_BF16_MIN_BATCH="1",
-               VF_TEST_ROOT=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=280)
-    assert out.returncode == 0 and "watch ok" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]
+    params = dict(itopk=32, width=1, iters=6, n_seeds=700)
+    io, do, info = ixo.search(w.queries, qoff, qids, 10, with_info=True, **params)
+    g = info["method"] == 2
+    assert g.sum() > 100
+    seen = []
+    for call in range(4):
+        ix.profile_enable(True)
+        ids, d = _search(vf, ix, Q, qoff, qids, 10, **params)
+        pf = ix.profile_read()
+        ix.profile_enable(False)
+        seen.append(int(pf["seeds_on_matrix_cores"]))
+        assert_exact(ids[g], d[g], io[g], do[g].astype(np.float32), f"call {call}")
+    assert seen[0] == 2 and seen[-1] == 1, seen
 
 
 def test_calls_on_several_streams_overlap_safely(vf):
