@@ -237,7 +237,8 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * "build_panel_kb" and "build_progress" only act that way); with an index, that index's own copy changes, and
  * no call on it may be in flight.  Names: "seg_groups", "seg_groups_heavy", "heavy_rows", "tile_rows",
  * "zero_copy_bytes", "scan_valu", "scan16", "overlap", "seed_exact", "seed_slack", "seed_margin",
- * "seed_margin_bf16", "seed_cache", "seed_bf16", "seed_bf16_min_batch", "seed_fb_window", "build16",
+ * "seed_margin_bf16", "seed_cache", "seed_bf16", "seed_bf16_min_batch", "seed_fb_window", "seed_select",
+ * "seed_seg_seeds", "build16",
  * "build_panel_kb", "build_progress".  Returns VF_EINVAL for an unknown name or a value out of range.
  * Results never depend on any of them.
  */
@@ -280,6 +281,8 @@ typedef struct vf_profile {
     int64_t seed_fallbacks;            /* queries whose proof failed and that scored every seed themselves               */
     int64_t beam_gathered;             /* distances whose vector the beam kernel fetched itself (children, re-ranked seeds, seeds when not scored densely) */
     int64_t scan_kernel;               /* IVF-BFS kernel of the call: 0 = 32-row matrix-core tiles, 1 = 16-row matrix-core tiles, 2 = FMA */
+    int64_t seed_selected;             /* 1: the seed kernel also selected (a few keys per query and seed segment instead of every distance) */
+    int64_t seed_run_keys;             /* 8-byte keys that kernel left for the beam kernel (sum over graph queries of segments x keys per run) */
 } vf_profile;
 
 int vf_profile_enable(vf_index *index, int on);

@@ -30,6 +30,17 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def default_threads() -> int:
+    """Threads the oracle runs its query loop on: the machine's own limit (OMP_NUM_THREADS) when it sets one,
+    else every core the interpreter sees."""
+    seen = os.cpu_count() or 1
+    try:
+        limit = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    except ValueError:
+        limit = 0
+    return min(seen, limit) if limit > 0 else seen
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -91,7 +102,7 @@ class OracleIndex:
         self.label_offsets = np.ascontiguousarray(label_offsets, dtype=np.int64)
         self.label_ids = np.ascontiguousarray(label_ids, dtype=np.int32)
         self.n_labels, self.T, self.R = int(n_labels), int(T), int(graph_degree)
-        self.n_threads = n_threads or (os.cpu_count() or 1)
+        self.n_threads = n_threads or default_threads()
         self.knn_degree = int(knn_degree)
         if self.knn_degree > 0:
             if lazy_graph:

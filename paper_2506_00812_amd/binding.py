@@ -46,7 +46,7 @@ class VfProfile(C.Structure):
                                          "scan_list_entries", "scan_pairs", "beam_scored", "beam_expanded",
                                          "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds",
                                          "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "beam_gathered",
-                                         "scan_kernel")]
+                                         "scan_kernel", "seed_selected", "seed_run_keys")]
 
 
 class VecflowError(RuntimeError):

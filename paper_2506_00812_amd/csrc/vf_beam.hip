@@ -144,6 +144,20 @@ __device__ __forceinline__ void merge_batch(TopM<1> &list, uint64_t key, int lan
     list.worst = readlane64(m, list.itopk - 1);
 }
 
+// The same for a batch that arrives sorted (ascending by lane, KEY_MAX at the end): the keys at or above the
+// list's worst entry are a suffix, so the batch stays sorted after they are dropped and needs no sort.
+__device__ __forceinline__ void merge_sorted_run(TopM<1> &list, uint64_t key, int lane)
+{
+    const uint64_t v = key < list.worst ? key : KEY_MAX;
+    if (!__any(v != KEY_MAX)) return;
+    const uint64_t vr = shfl64(v, 63 - lane);
+    uint64_t m = list.cur[0] < vr ? list.cur[0] : vr;
+    m = wave_merge64(m, lane);
+    if (lane >= list.itopk) m = KEY_MAX;
+    list.cur[0] = m;
+    list.worst = readlane64(m, list.itopk - 1);
+}
+
 template <int DT, int E>
 __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 {
@@ -338,15 +352,38 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
 
     bool seeds_done = false;
     int n_rescored = 0, seed_fallback = 0;   // profiling only
+    // The runs the selection kernel left for this query: one per seed segment, sorted, keys
+    // (value bits << 32 | seed index).  as_index as in select_seeds.
+    auto merge_runs = [&](TopM<1> &list, bool as_index) {
+        const int nseg = (ns + p.seg_seeds - 1) / p.seg_seeds;
+        const uint64_t *runs = p.seed_runs + (int64_t)gq * p.run_segs * p.run_K;
+        uint64_t next = lane < p.run_K ? runs[lane] : KEY_MAX;
+        for (int sg = 0; sg < nseg; ++sg) {
+            const uint64_t raw = next;
+            if (sg + 1 < nseg) next = lane < p.run_K ? runs[(sg + 1) * p.run_K + lane] : KEY_MAX;
+            uint64_t key = KEY_MAX;
+            if (raw != KEY_MAX) {
+                const uint32_t j = (uint32_t)raw;
+                const uint32_t c = as_index ? j : (uint32_t)seed_local_id(j, (uint32_t)n, (uint32_t)ns);
+                key = (raw & 0xFFFFFFFF00000000ull) | ((uint64_t)c << 1) | 1ull;
+            }
+            merge_sorted_run(list, key, lane);
+        }
+        n_tested += o_cnt > 0 ? ns : 0;
+        n_scored += (o_cnt > 0 && p.seed_pass != nullptr) ? p.seed_pass[gq] : ns;
+    };
+
     if constexpr (E == 1 && DT == 1) {
-        if (p.dseed != nullptr && p.seed_approx != 0) {
-            // dseed holds matrix-core approximations.  Keep the seed_keep best of them, re-score those
-            // with the ordered distance, and accept the result only if every other seed is provably
+        if ((p.dseed != nullptr || p.seed_runs != nullptr) && p.seed_approx != 0) {
+            // The seeds were scored approximately on the matrix cores.  Keep the seed_keep best of them, re-score
+            // those with the ordered distance, and accept the result only if every other seed is provably
             // worse than the list's worst entry: its approximation is at least T (the last one kept),
             // its ordered distance therefore at least T - B.
             TopM<1> tmp;
             tmp.init(p.seed_keep);
-            const int got = select_seeds(tmp, p.dseed + (int64_t)gq * p.ns_stride, true);
+            int got = ns;
+            if (p.seed_runs != nullptr) merge_runs(tmp, true);
+            else got = select_seeds(tmp, p.dseed + (int64_t)gq * p.ns_stride, true);
             if (got == ns) {
                 const uint64_t key = tmp.cur[0];
                 const bool valid = key != KEY_MAX;
@@ -385,6 +422,10 @@ __global__ __launch_bounds__(64) void beam_kernel(BeamParams p)
         }
     }
     if constexpr (E == 1) {
+        if (!seeds_done && p.seed_runs != nullptr && p.seed_approx == 0) {   // exact distances (uint8)
+            merge_runs(top, false);
+            seeds_done = true;
+        }
         if (!seeds_done && p.dseed != nullptr && p.seed_approx == 0)
             j_begin = select_seeds(top, p.dseed + (int64_t)gq * p.ns_stride, false);
     }

@@ -101,6 +101,8 @@ struct Tuning {
     int seed_bf16 = 1;            // 0: float32 data keep only the float32 copy of the seeds
     int seed_bf16_min_batch = 512;   // calls with fewer graph queries use the float32 copy when it is resident
     int seed_fb_window = 131072;  // graph queries between two looks at the failed-proof counter
+    int seed_select = 1;          // 0: the seed kernel writes every distance, the beam kernel selects (itopk <= 64 only differs)
+    int seed_seg_seeds = 0;       // seeds per wave of the selecting seed kernel; 0: chosen per call (512 .. 4096)
     int build16 = 1;              // float32 kNN self-joins on 16-row tiles
     int build_panel_kb = 4096;    // self-joins of long lists go panel by panel, this much of the list per launch
     int build_progress = 0;       // 1: a line on stderr every ten seconds while graphs are built
@@ -198,7 +200,8 @@ struct SeedCopy {
     float bf16_delta = 0.f;      // upper bound of |x - bf16(x)| over the seeds of the copy
     uint64_t last_use = 0;
     DevBuf blk, blk16, norm, goff;
-    std::vector<DevBuf *> bufs() { return {&blk, &blk16, &norm, &goff}; }
+    DevBuf map;                  // [group * 32 + v] global id of the seed (AND predicate inside the seed kernel)
+    std::vector<DevBuf *> bufs() { return {&blk, &blk16, &norm, &goff, &map}; }
 };
 
 }  // namespace vf
@@ -310,6 +313,9 @@ struct CallPlan {
     std::vector<SeedTile> tiles;          // dense seed scoring: tiles of <= 64 (32) graph queries of one label
     size_t n_gq = 0;
     bool dense_seeds = false, seeds_mfma = false;
+    // seeds_mfma with the selection fused into the seed kernel: runs of sel_K keys per (query, segment)
+    bool seed_select = false, sel_bf16 = false;
+    int32_t sel_K = 0, seg_seeds = 0, max_segs = 0;
     BlobLayout L{};
     size_t dseed_words = 0;               // seed distance matrix + the dump area behind it
     size_t part_words = 0;                // partial result rows x k
@@ -331,11 +337,15 @@ int check_search_params(const vf_index *ix, bool exact, int32_t k, int32_t &itop
                         int32_t &n_seeds);
 int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, const int32_t *qids, bool exact,
               bool first_is_searched, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
-              uint64_t dseed_budget_words, CallPlan &P);
+              uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P);
+// May this call's seeds be scored on the matrix cores (so that an interleaved seed copy is worth having)?
+bool wants_seed_copy(const vf_index *ix, bool exact, int32_t itopk, int32_t n_seeds);
+// The resident copy for n_seeds, or (build = true) a new one; *out stays null when there is none.
+int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, bool build, SeedCopy **out);
 void fill_blob(const CallPlan &P, const Routed &r, char *hp);
-int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem &M, const void *queries, int64_t *out_ids,
-                float *out_dists, hipStream_t s, hipStream_t side, hipEvent_t ev_fork, hipEvent_t ev_join,
-                bool may_allocate);
+int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem &M, const SeedCopy *sc, const void *queries,
+                int64_t *out_ids, float *out_dists, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
+                hipEvent_t ev_join, bool may_allocate);
 
 // vf_index_build.hip
 int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,

@@ -115,6 +115,12 @@ struct BeamParams {
     float err_bound, xn_max;
     uint32_t *fallback_count;  // optional: incremented once per query whose proof failed
     float err_q;        // 0 unless the seeds were scored from their bfloat16 copy: 2 * max |x - bf16(x)| over the seeds
+    // seeds scored with the selection fused in (seed_select_kernel; itopk <= 64): per query run_segs runs of run_K
+    // keys, of which the first ceil(min(n_seeds, |C_l|) / seg_seeds) exist.  uint8: exact distances; float32:
+    // approximations (seed_approx != 0, run_K == seed_keep)
+    const uint64_t *seed_runs;
+    int32_t run_K, run_segs, seg_seeds;
+    const int32_t *seed_pass;  // optional (profiling, AND batches): seeds of the query that pass its predicate
 };
 
 // ---------------------------------------------------------------- dense seed distances
@@ -144,6 +150,30 @@ struct SeedParams {
     int64_t dump_off;           // seed_mfma_kernel: dseed[dump_off .. dump_off + 64 * (dump_mask + 1)) takes the stores of
     int32_t dump_mask;          // lanes without a pair, 64 entries per workgroup index & dump_mask (2^k - 1)
 };
+
+// Seed scoring with fused selection (seed_select_kernel): one run of K keys per (graph query, seed segment)
+struct SeedSelParams {
+    const void *Q;
+    const int32_t *gq_query;
+    const SeedTile *tiles;      // tiles of <= 32 graph queries of one label
+    LabelMeta meta;
+    int32_t dim, n_seeds;
+    int32_t K;                  // keys kept per (query, segment), <= 64
+    int32_t seg_seeds;          // seeds per segment, a multiple of 32
+    int32_t max_segs;           // segments per tile in the grid: ceil(min(n_seeds, longest list of the batch) / seg_seeds)
+    const uint4 *seed_blk;      // interleaved copy of the seeds: uint8, or bfloat16 for float32 data
+    const uint32_t *seed_norm;  // [group * 32 + v] squared norms (int32 of the -128 shifted bytes / float bits)
+    const int64_t *seed_goff;   // [n_graph_labels] first group of each graph list
+    const int32_t *seed_map;    // [group * 32 + v] global id of the seed (AND predicate)
+    const int32_t *others_off;  // AND partner labels per query; null when the batch has none
+    const int32_t *others;
+    uint64_t *runs;             // [n_gq][max_segs][K]: (value bits << 32 | seed index), ascending, KEY_MAX = none
+};
+bool seed_select_supported(int dtype, int dim, bool bf16_copy);
+size_t seed_select_lds_bytes(int32_t K);
+void launch_seed_select(int dtype, const SeedSelParams &p, int n_tiles, hipStream_t s);
+void launch_seed_pass_count(const int32_t *gq_query, const int32_t *gq_label, const LabelMeta &meta, int32_t n_seeds,
+                            const int32_t *others_off, const int32_t *others, int32_t *pass_count, int n_gq, hipStream_t s);
 
 // seed_map[g * 32 + v] = global id of seed j = grp_j0[g] + v of graph list grp_slot[g] (local id floor(j n / ns)),
 // 0 for v beyond the list's seeds

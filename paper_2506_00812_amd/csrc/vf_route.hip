@@ -51,6 +51,8 @@ bool Tuning::set(const char *name, double value)
         {"seed_bf16", &Tuning::seed_bf16, 0, 1},
         {"seed_bf16_min_batch", &Tuning::seed_bf16_min_batch, 0, 1 << 30},
         {"seed_fb_window", &Tuning::seed_fb_window, 1, 1 << 30},
+        {"seed_select", &Tuning::seed_select, 0, 1},
+        {"seed_seg_seeds", &Tuning::seed_seg_seeds, 0, 1 << 20},
         {"build16", &Tuning::build16, 0, 1},
         {"build_panel_kb", &Tuning::build_panel_kb, 1, 1 << 22},
         {"build_progress", &Tuning::build_progress, 0, 1},

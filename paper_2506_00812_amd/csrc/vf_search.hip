@@ -109,9 +109,16 @@ int drop_seed_copies(vf_index *ix)
 // read it).  The index keeps kSeedCopies of them; the least recently used one makes room, after the device
 // has drained, since calls on other streams may still be reading it.  (*out)->ok is false when a copy would need
 // more than half of the free device memory: the seed kernel then gathers rows from the vector table.
-static int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, SeedCopy **out)
+bool wants_seed_copy(const vf_index *ix, bool exact, int32_t itopk, int32_t n_seeds)
+{
+    return !exact && !ix->graph_labels.empty() && ix->seed_mfma_ok && !ix->tune.seed_exact && n_seeds > 64 &&
+           (ix->dtype == VF_U8 || itopk <= 48);
+}
+
+int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, bool build, SeedCopy **out)
 {
     SeedCopy *c = nullptr;
+    *out = nullptr;
     for (SeedCopy &x : ix->seed_copies)
         if (x.n_seeds == n_seeds) c = &x;
     if (c != nullptr) {
@@ -119,6 +126,7 @@ static int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, SeedCopy 
         *out = c;
         return VF_OK;
     }
+    if (!build) return VF_OK;
     for (SeedCopy &x : ix->seed_copies)
         if (x.n_seeds < 0) { c = &x; break; }
     if (c == nullptr) {
@@ -151,15 +159,16 @@ static int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, SeedCopy 
     }
     if (n_groups == 0) return VF_OK;
     {
-        const size_t need = (size_t)n_groups * (ix->group_bytes() * 3 / 2 + 32 * 4 + 32 * 4 + 32 * 4 + 32);
+        const size_t need = (size_t)n_groups * (ix->group_bytes() * 3 / 2 + 32 * 4 + 32 * 4 + 32 * 4 + 32 * 4 + 32);
         size_t free_b = 0, total_b = 0;
         VF_HIP(hipMemGetInfo(&free_b, &total_b));
         if (need + need / 4 > free_b / 2) return VF_OK;
     }
     int rc;
-    DevBuf d_map(&ix->alloc), d_base(&ix->alloc), d_n(&ix->alloc), d_slot(&ix->alloc), d_j0(&ix->alloc), d_src(&ix->alloc),
-        d_cnt(&ix->alloc), d_err2(&ix->alloc);
-    DevBufGuard rel{&d_map, &d_base, &d_n, &d_slot, &d_j0, &d_src, &d_cnt, &d_err2};
+    DevBuf d_base(&ix->alloc), d_n(&ix->alloc), d_slot(&ix->alloc), d_j0(&ix->alloc), d_src(&ix->alloc), d_cnt(&ix->alloc),
+        d_err2(&ix->alloc);
+    DevBufGuard rel{&d_base, &d_n, &d_slot, &d_j0, &d_src, &d_cnt, &d_err2};
+    DevBuf &d_map = c->map;
     if ((rc = c->blk.reserve((size_t)n_groups * ix->group_bytes())) != VF_OK) return rc;
     if ((rc = c->norm.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
     if ((rc = d_map.reserve((size_t)n_groups * 32 * 4)) != VF_OK) return rc;
@@ -231,7 +240,7 @@ int check_search_params(const vf_index *ix, bool exact, int32_t k, int32_t &itop
 // beam kernel gathers the seeds itself).
 int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, const int32_t *qids, bool exact,
                      bool first_is_searched, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
-                     uint64_t dseed_budget_words, CallPlan &P)
+                     uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P)
 {
     int rc;
     P.nq = nq; P.k = k; P.itopk = itopk; P.width = width; P.iters = iters; P.n_seeds = n_seeds; P.exact = exact;
@@ -282,15 +291,53 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
 
     P.n_gq = r.gq_query.size();
     P.ns_stride = (n_seeds + 31) & ~31;
-    // dense seed scoring needs the seed distance matrix to fit
-    const uint64_t need = (uint64_t)P.n_gq * (uint64_t)P.ns_stride + 64 * 1024;
-    P.dense_seeds = !exact && P.n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) && need <= dseed_budget_words;
-    // uint8: the matrix cores give the exact integer distances, nothing else changes.
+    // Seeds on the matrix cores.  uint8: they give the exact integer distances, nothing else changes.
     // float32: approximations, re-ranked by the beam kernel (its proof needs a list of at most 48 entries).
-    P.seeds_mfma = P.dense_seeds && ix->seed_mfma_ok && !ix->tune.seed_exact && n_seeds > 64 &&
-                   (ix->dtype == VF_U8 || itopk <= 48);
+    const bool mfma_ok = wants_seed_copy(ix, exact, itopk, n_seeds) && P.n_gq > 0;
+    // With an interleaved seed copy the seed kernel also selects (itopk <= 64: the beam kernel's one-register
+    // list): it leaves sel_K keys per (query, seed segment) instead of every distance.  float32 data: from the
+    // bfloat16 copy; calls with few graph queries keep the float32 copy and the unfused kernel (their proofs
+    // need fewer re-scored seeds, which a latency-bound call notices).
+    const Tuning &tune = ix->tune;
+    if (mfma_ok && sc != nullptr && sc->ok && tune.seed_select && itopk <= 64 &&
+        seed_select_supported(ix->dtype, ix->dim, sc->has_bf16) &&
+        (ix->dtype == VF_U8 || !sc->has_f32 || (int64_t)P.n_gq >= tune.seed_bf16_min_batch)) {
+        P.sel_bf16 = ix->dtype == VF_F32;
+        P.sel_K = ix->dtype == VF_U8 ? itopk : std::min(64, itopk + std::max(tune.seed_margin_bf16, tune.seed_margin));
+        int32_t longest = 0;
+        size_t n_tiles = 0;
+        for (size_t i = 0; i < P.n_gq;) {
+            size_t e = i;
+            while (e < P.n_gq && r.gq_label[e] == r.gq_label[i]) ++e;
+            longest = std::max(longest, std::min(n_seeds, ix->S[(size_t)r.gq_label[i]]));
+            n_tiles += (e - i + 31) / 32;
+            i = e;
+        }
+        // seeds per wave: long segments select better (a row's threshold tightens as the segment streams by) but
+        // the launch needs a few thousand waves
+        int32_t seg = tune.seed_seg_seeds;
+        if (seg <= 0) {
+            const int64_t want_segs = std::max<int64_t>(1, (2048 + (int64_t)n_tiles - 1) / (int64_t)n_tiles);
+            seg = (int32_t)std::min<int64_t>(4096, std::max<int64_t>(512, (longest / want_segs) / 32 * 32));
+        }
+        seg = std::max(32, seg / 32 * 32);
+        P.seg_seeds = seg;
+        P.max_segs = (longest + seg - 1) / seg;
+        const uint64_t need = (uint64_t)P.n_gq * (uint64_t)P.max_segs * (uint64_t)P.sel_K * 2;   // 8-byte keys
+        if (need <= dseed_budget_words) {
+            P.seed_select = true;
+            P.dense_seeds = P.seeds_mfma = true;
+            P.dseed_words = (size_t)need;
+        }
+    }
+    if (!P.seed_select) {
+        // every distance goes through the seed distance matrix, which must fit
+        const uint64_t need = (uint64_t)P.n_gq * (uint64_t)P.ns_stride + 64 * 1024;
+        P.dense_seeds = !exact && P.n_gq > 0 && seed_dist_supported(ix->dtype, ix->dim) && need <= dseed_budget_words;
+        P.seeds_mfma = P.dense_seeds && mfma_ok;
+        if (P.dense_seeds) P.dseed_words = (size_t)need;
+    }
     if (P.dense_seeds) {
-        P.dseed_words = (size_t)need;
         const size_t tile_q = P.seeds_mfma ? 32 : 64;
         for (size_t i = 0; i < P.n_gq;) {
             size_t e = i;
@@ -336,9 +383,9 @@ void fill_blob(const CallPlan &P, const Routed &r, char *hp)
 // The launches of one call.  s: the caller's stream; side: the stream the scan path runs on beside the graph path
 // (ev_fork / ev_join tie it to s), or nullptr: everything on s.  may_allocate = false (the entry point that
 // allocates nothing): no seed copy is built, no profiling, no failed-proof watch.
-int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem &M, const void *queries,
-                       int64_t *out_ids, float *out_dists, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
-                       hipEvent_t ev_join, bool may_allocate)
+int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem &M, const SeedCopy *sc, const void *queries,
+                int64_t *out_ids, float *out_dists, hipStream_t s, hipStream_t side, hipEvent_t ev_fork, hipEvent_t ev_join,
+                bool may_allocate)
 {
     int rc;
     const Tuning &tune = ix->tune;
@@ -359,7 +406,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         ix->prof_ev = ix->prof_ring[ix->prof_next];
         // [nq][4] counters, then [nq] gathered; written by the beam kernel for graph queries only (no clearing
         // pass: the rows of the other queries are never read)
-        if ((rc = ix->counters.reserve((size_t)P.nq * 20)) != VF_OK) return rc;
+        if ((rc = ix->counters.reserve((size_t)P.nq * 24)) != VF_OK) return rc;
         ix->prof_graph_queries = r.gq_query;
         vf_profile &pf = ix->prof;
         pf = vf_profile{};
@@ -395,7 +442,45 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
     }
     auto run_seeds = [&]() -> int {
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
-        if (n_gq && P.dense_seeds) {
+        if (n_gq && P.seed_select) {
+            // scoring and selection in one kernel: runs of sel_K keys per (query, seed segment)
+            SeedSelParams sl{};
+            sl.Q = queries; sl.gq_query = bp.gq_query;
+            sl.tiles = (const SeedTile *)(dp + L.off_tiles); sl.meta = bp.meta;
+            sl.dim = ix->dim; sl.n_seeds = P.n_seeds; sl.K = P.sel_K; sl.seg_seeds = P.seg_seeds; sl.max_segs = P.max_segs;
+            sl.seed_blk = P.sel_bf16 ? sc->blk16.as<uint4>() : sc->blk.as<uint4>();
+            sl.seed_norm = sc->norm.as<uint32_t>();
+            sl.seed_goff = sc->goff.as<int64_t>();
+            sl.seed_map = sc->map.as<int32_t>();
+            sl.others_off = d_others_off; sl.others = d_others;
+            sl.runs = (uint64_t *)M.dseed;
+            launch_seed_select(ix->dtype, sl, (int)P.tiles.size(), s);
+            bp.seed_runs = sl.runs; bp.run_K = P.sel_K; bp.run_segs = P.max_segs; bp.seg_seeds = P.seg_seeds;
+            if (prof) {
+                ix->prof.seeds_on_matrix_cores = P.sel_bf16 ? 2 : 1;
+                ix->prof.seed_selected = 1;
+                for (const SeedTile &t : P.tiles) {
+                    const int64_t ns_l = std::min<int64_t>(P.n_seeds, ix->S[(size_t)t.label]);
+                    ix->prof.seed_run_keys += (int64_t)t.q_count * ((ns_l + P.seg_seeds - 1) / P.seg_seeds) * P.sel_K;
+                }
+                if (r.any_and) {   // the counters report the seeds that pass the predicate as distances computed
+                    int32_t *pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;
+                    launch_seed_pass_count(bp.gq_query, bp.gq_label, bp.meta, P.n_seeds, d_others_off, d_others, pass,
+                                           (int)n_gq, s);
+                    bp.seed_pass = pass;
+                }
+            }
+            if (ix->dtype == VF_F32) {
+                // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the query's split
+                // (2^-16 = 256 u), norms and final additions (< 200 u): under 1024 u; 4096 u = 2^-12 relative to
+                // |q|^2 + xn_max is used, plus 2 |q| max |x - bf16(x)|
+                bp.seed_approx = 1; bp.xn_max = ix->xn_max;
+                bp.err_bound = ix->seed_err_bound() * 8.0f;
+                bp.err_q = 2.0f * sc->bf16_delta;
+                bp.seed_keep = P.sel_K;
+                if (may_allocate) bp.fallback_count = ix->d_fb_count.as<uint32_t>();
+            }
+        } else if (n_gq && P.dense_seeds) {
             SeedParams sd{};
             sd.X = ix->X; sd.Q = queries; sd.gq_query = bp.gq_query;
             sd.tiles = (const SeedTile *)(dp + L.off_tiles); sd.meta = bp.meta;
@@ -408,26 +493,9 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                 sd.max_chunks = (P.ns_stride + kSeedMfmaChunk - 1) / kSeedMfmaChunk;
                 sd.xnorm_all = ix->d_xnorm_all.as<uint32_t>();
                 float seed_bf16_delta = 0.f;
-                SeedCopy *sc = nullptr;
-                if (may_allocate) {
-                    if (ix->fb_pending && hipEventQuery(ix->ev_fb) == hipSuccess) {
-                        const uint32_t now = *ix->h_fb, failed = now - ix->fb_last;
-                        ix->fb_last = now;
-                        ix->fb_pending = false;
-                        if ((int64_t)failed * 64 > ix->fb_sent_q) {
-                            ix->seed_bf16_off = true;   // the copies are rebuilt in float32 below
-                            if ((rc = drop_seed_copies(ix)) != VF_OK) return rc;
-                        }
-                    } else if (ix->fb_pending) {
-                        (void)hipGetLastError();      // "not ready" is no error
-                    }
-                    if ((rc = seed_copy_for(ix, P.n_seeds, s, &sc)) != VF_OK) return rc;
-                } else {
-                    for (SeedCopy &x : ix->seed_copies)   // a copy is used when a regular call has left one
-                        if (x.n_seeds == P.n_seeds) sc = &x;
-                }
                 if (sc != nullptr && sc->ok) {
-                    // without the watch on failed proofs (it needs a pinned counter) the bfloat16 form stays unused
+                    // without the watch on failed proofs (it needs a pinned counter) the bfloat16 form is used only
+                    // where it is the only one
                     const bool use16 = sc->has_bf16 &&
                                        (!sc->has_f32 || (may_allocate && (int64_t)n_gq >= tune.seed_bf16_min_batch));
                     sd.seed_blk = use16 ? sc->blk16.as<uint4>() : sc->blk.as<uint4>();
@@ -448,15 +516,11 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                     bp.seed_approx = 1; bp.err_bound = ix->seed_err_bound(); bp.xn_max = ix->xn_max;
                     bp.seed_keep = std::min(64, P.itopk + tune.seed_margin);
                     if (sd.seed_bf16) {
-                        // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the
-                        // query's split (2^-16 = 256 u), norms and final additions (< 200 u): under
-                        // 1024 u; 4096 u = 2^-12 relative to |q|^2 + xn_max is used, plus
-                        // 2 |q| max |x - bf16(x)|
+                        // the bfloat16 bound (see above) and its wider margin: more approximations are kept for
+                        // re-ranking (a failed proof costs the query a gather of every seed)
                         bp.err_bound = ix->seed_err_bound() * 8.0f;
                         bp.err_q = 2.0f * seed_bf16_delta;
                         if (may_allocate) bp.fallback_count = ix->d_fb_count.as<uint32_t>();
-                        // the wider bound needs a wider gap: more approximations are kept for re-ranking
-                        // (a failed proof costs the query a gather of every seed)
                         bp.seed_keep = std::min(64, P.itopk + std::max(tune.seed_margin_bf16, tune.seed_margin));
                     }
                 }
@@ -569,9 +633,27 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
         VF_HIP(hipMemGetInfo(&free_b, &total_b));
         dseed_budget = std::max<uint64_t>(dseed_budget, (uint64_t)((free_b + W->dseed.cap) / 2) / 5);   // / 4 bytes, / 1.25 growth
     }
+    // the interleaved copy of the seeds for this seed count (built on first use), after a look at the watch
+    // on failed float32 proofs
+    SeedCopy *sc = nullptr;
+    if (wants_seed_copy(ix, exact, itopk, n_seeds)) {
+        if (ix->fb_pending && hipEventQuery(ix->ev_fb) == hipSuccess) {
+            const uint32_t now = *ix->h_fb, failed = now - ix->fb_last;
+            ix->fb_last = now;
+            ix->fb_pending = false;
+            if ((int64_t)failed * 64 > ix->fb_sent_q) {
+                ix->seed_bf16_off = true;   // the copies are rebuilt in float32
+                if ((rc = drop_seed_copies(ix)) != VF_OK) return rc;
+            }
+        } else if (ix->fb_pending) {
+            (void)hipGetLastError();      // "not ready" is no error
+        }
+        if ((rc = seed_copy_for(ix, n_seeds, s, true, &sc)) != VF_OK) return rc;
+    }
     CallPlan P(tune);
     Routed &r = W->routed;
-    if ((rc = plan_call(ix, r, nq, qoff, qids, exact, first_is_searched, k, itopk, width, iters, n_seeds, dseed_budget, P)) != VF_OK)
+    if ((rc = plan_call(ix, r, nq, qoff, qids, exact, first_is_searched, k, itopk, width, iters, n_seeds, dseed_budget, sc,
+                        P)) != VF_OK)
         return rc;
     const BlobLayout &L = P.L;
     Staging *st = nullptr;
@@ -616,8 +698,8 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     M.dseed = W->dseed.as<uint32_t>();
     M.part_idx = W->part_idx.as<int32_t>();
     M.part_bits = W->part_bits.as<uint32_t>();
-    if ((rc = launch_call(ix, P, r, M, queries, out_ids, out_dists, s, forked ? W->side : nullptr, W->ev_fork, W->ev_join,
-                          true)) != VF_OK)
+    if ((rc = launch_call(ix, P, r, M, sc, queries, out_ids, out_dists, s, forked ? W->side : nullptr, W->ev_fork,
+                          W->ev_join, true)) != VF_OK)
         return rc;
     if (zero_copy) {
         VF_HIP(hipEventRecord(st->done, s));

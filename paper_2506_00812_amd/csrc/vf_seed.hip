@@ -15,7 +15,7 @@
 //
 // Output: dseed[gq][j] = distance bits of graph query gq to seed j, consumed by the
 // beam kernel, which keeps the best itopk.
-#include "vf_device.h"
+#include "vf_select.h"
 
 namespace vf {
 
@@ -319,6 +319,305 @@ __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)
             *dst = bits[jj];
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Seed scoring with the selection fused in.  The beam search starts from the best `itopk` of a query's
+// seeds, a few dozen out of thousands, so nothing but those needs to leave the kernel that scores them.
+// One wave takes a tile of <= 32 same-label queries and a SEGMENT of the label's seeds (seg_seeds of them,
+// whole 32-seed groups of the interleaved copy), contracts them on the matrix cores group by group like
+// seed_mfma_kernel, and keeps per query row the K smallest (value, seed index) pairs with the queue-and-merge
+// selection of the scan kernels: a row's threshold tightens as the segment streams by, so after the first
+// groups only a few values per group reach a queue.  Output: one sorted run of K keys
+// (value bits << 32 | seed index) per (query, segment); the beam kernel merges a query's runs.
+// Why that is enough.  uint8 values are the exact distances, and the order of keys is the order of
+// (distance, local id) since the local id floor(j n / ns) grows with j: the K best of the union of the runs are
+// the K best seeds.  float32 values are approximations: the beam kernel keeps the K best of the union, re-scores
+// them with the ordered distance and needs a lower bound T on the approximation of every seed it did NOT keep.
+// A seed missing from the union was rejected in its segment by K values that all are in the union, so its
+// approximation is at least the union's K-th smallest value, which is T as before.
+// A operand (queries) in registers for the whole segment; LDS holds only the queues and the lists.
+// DT = 0: uint8 data (v_mfma_i32_32x32x32_i8 on the -128 shifted bytes).  DT = 2: float32 data, seeds from the
+// bfloat16 copy, queries split into a bfloat16 high and low part (see seed_mfma_kernel).
+template <int DT, int NCP>
+__global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
+{
+    static_assert(DT == 0 || DT == 2, "uint8, or float32 data with a bfloat16 seed copy");
+    extern __shared__ uint4 smem[];
+    constexpr int NCH = 2 * NCP, PC = 64;
+    constexpr int row_bytes = (DT == 2 ? 2 : 1) * NCH * kChunkBytes;   // of a query
+    const int K = p.K, KS = K | 1;
+    uint64_t *pend = (uint64_t *)smem;               // [32][PC] candidates not yet merged
+    uint64_t *best = pend + 32 * PC;                 // [32][KS] K best so far, ascending, KEY_MAX padded
+    uint32_t *qnorm_s = (uint32_t *)(best + 32 * KS); // [32] float bits / int
+    uint32_t *pcnt = qnorm_s + 32;                   // [32] keys waiting in pend[r]
+    int32_t *qrow_s = (int32_t *)(pcnt + 32);        // [32] query index of the row, -1: none
+
+    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int tile = blockIdx.x / p.max_segs, seg = blockIdx.x % p.max_segs;
+    const SeedTile t = p.tiles[tile];
+    const int n = p.meta.S[t.label];
+    const int ns = p.n_seeds < n ? p.n_seeds : n;
+    const int j0 = seg * p.seg_seeds;
+    if (j0 >= ns) return;   // the label has fewer segments than the grid allows for (the whole workgroup leaves)
+    const int nj = ns - j0 < p.seg_seeds ? ns - j0 : p.seg_seeds;
+    const int n_groups = (nj + 31) >> 5;
+    const int64_t grp0 = p.seed_goff[p.meta.hs_slot[t.label]] + (j0 >> 5);
+
+    if (lane < 32) { qrow_s[lane] = lane < t.q_count ? p.gq_query[t.gq_begin + lane] : -1; pcnt[lane] = 0; }
+    for (int i = lane; i < 32 * KS; i += 64) best[i] = KEY_MAX;
+    __syncthreads();
+
+    // ---- A operand: lane (n32, h) holds chunks 2 cp + h of query row n32 (zeros for a row without a query)
+    uint4 areg[NCP], alo[DT == 2 ? NCP : 1];
+    {
+        const int qr = qrow_s[n32];
+        const char *qp = (const char *)p.Q + (int64_t)(qr >= 0 ? qr : 0) * row_bytes;
+        float facc = 0.f;
+        int iacc = 0;
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) {
+            const int c = 2 * cp + h;
+            if constexpr (DT == 2) {   // components 8 c .. 8 c + 7
+                uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+                if (qr >= 0) {
+                    v0 = *(const uint4 *)(qp + (2 * c) * kChunkBytes);
+                    v1 = *(const uint4 *)(qp + (2 * c + 1) * kChunkBytes);
+                }
+                const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                uint32_t hi[8], lo[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float f = __uint_as_float(w[i]);
+                    facc += f * f;
+                    hi[i] = bf16_rn_bits(f);
+                    lo[i] = bf16_rn_bits(f - __uint_as_float(hi[i] << 16));
+                }
+                areg[cp] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+                alo[cp] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+            } else {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (qr >= 0) {
+                    v = *(const uint4 *)(qp + c * kChunkBytes);
+                    v.x ^= 0x80808080u; v.y ^= 0x80808080u; v.z ^= 0x80808080u; v.w ^= 0x80808080u;
+                }
+                areg[cp] = v;
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const int e = (int)(int8_t)(w[i] >> (8 * bb));
+                        iacc += e * e;
+                    }
+            }
+        }
+        if (DT == 0) {
+            iacc += __shfl_xor(iacc, 32);
+            if (h == 0) qnorm_s[n32] = (uint32_t)iacc;
+        } else {
+            facc += __shfl_xor(facc, 32);
+            if (h == 0) qnorm_s[n32] = __float_as_uint(facc);
+        }
+    }
+    __syncthreads();
+
+    // per-lane constants for its 16 accumulator rows: row(j) = 8 * (j / 4) + 4 * h + (j % 4)
+    uint32_t qn[16], thr[16];
+    uint32_t live_rows = 0, and_rows = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int row = 8 * (j >> 2) + 4 * h + (j & 3);
+        qn[j] = qnorm_s[row];
+        thr[j] = 0xFFFFFFFFu;
+        if (row < t.q_count) {
+            live_rows |= 1u << j;
+            if (p.others_off != nullptr) {
+                const int qr = qrow_s[row];
+                if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << j;
+            }
+        }
+    }
+    const bool any_and = __any(and_rows != 0);
+    int pcv = 0;                  // state of tile row r, held by lane r (r < 32)
+    uint64_t row_kth = KEY_MAX;
+
+    auto drain = [&]() {
+        wave_lds_sync();
+        if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv, row_kth, lane);
+        wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
+        if (lane < 32) pcnt[lane] = 0;
+        wave_lds_sync();
+        const uint32_t tk = (uint32_t)(row_kth >> 32);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) thr[j] = __shfl(tk, 8 * (j >> 2) + 4 * h + (j & 3));
+    };
+
+    // B operand: the whole group in registers, each half refilled with the next group's chunks right after its
+    // own MFMAs have been issued
+    constexpr int H0 = (NCP + 1) / 2;
+    uint4 breg[NCP];
+    {
+        const uint4 *blk0 = p.seed_blk + grp0 * (int64_t)(NCH * 32);
+#pragma unroll
+        for (int cp = 0; cp < NCP; ++cp) breg[cp] = blk0[(2 * cp + h) * 32 + n32];
+    }
+    uint32_t xn_next = p.seed_norm[grp0 * 32 + n32];
+    int32_t gid_next = -1;
+    if (any_and) gid_next = p.seed_map[grp0 * 32 + n32];
+    for (int grp = 0; grp < n_groups; ++grp) {
+        const uint4 *nblk = p.seed_blk + (grp0 + grp + 1) * (int64_t)(NCH * 32);
+        const bool more = grp + 1 < n_groups;
+        const uint32_t xn = xn_next;
+        const int32_t gid = gid_next;
+        if (more) {
+            xn_next = p.seed_norm[(grp0 + grp + 1) * 32 + n32];
+            if (any_and) gid_next = p.seed_map[(grp0 + grp + 1) * 32 + n32];
+        }
+        uint32_t bitsv[16];
+        if constexpr (DT == 0) {
+            v16i_seed acc;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = 0;
+            auto contract = [&](int cp) {
+                uint4 b = breg[cp];
+                b.x ^= 0x80808080u; b.y ^= 0x80808080u; b.z ^= 0x80808080u; b.w ^= 0x80808080u;
+                const uint4 a = areg[cp];
+                const v4i_seed av = {(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+                const v4i_seed bv = {(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, acc, 0, 0, 0);
+            };
+#pragma unroll
+            for (int cp = 0; cp < H0; ++cp) contract(cp);
+            if (more) {
+#pragma unroll
+                for (int cp = 0; cp < H0; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+#pragma unroll
+            for (int cp = H0; cp < NCP; ++cp) contract(cp);
+            if (more) {
+#pragma unroll
+                for (int cp = H0; cp < NCP; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) bitsv[j] = (uint32_t)((int)qn[j] + (int)xn - 2 * acc[j]);
+        } else {
+            v16f_seed acc;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+            auto contract = [&](int cp) {
+                const v8bf_seed bv = __builtin_bit_cast(v8bf_seed, breg[cp]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_seed, areg[cp]), bv, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_seed, alo[cp]), bv, acc, 0, 0, 0);
+            };
+#pragma unroll
+            for (int cp = 0; cp < H0; ++cp) contract(cp);
+            if (more) {
+#pragma unroll
+                for (int cp = 0; cp < H0; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+#pragma unroll
+            for (int cp = H0; cp < NCP; ++cp) contract(cp);
+            if (more) {
+#pragma unroll
+                for (int cp = H0; cp < NCP; ++cp) breg[cp] = nblk[(2 * cp + h) * 32 + n32];
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float d = (__uint_as_float(qn[j]) + __uint_as_float(xn)) - 2.0f * acc[j];
+                bitsv[j] = __float_as_uint(fmaxf(d, 0.0f));
+            }
+        }
+        // phase 1 (branch-free): threshold tests of this lane's 16 rows against its seed of the group
+        const int jrel = grp * 32 + n32;
+        uint32_t pm = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) pm |= (bitsv[j] <= thr[j] ? 1u : 0u) << j;
+        pm &= jrel < nj ? live_rows : 0u;
+        if (any_and && (pm & and_rows) != 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (((pm & and_rows) >> j) & 1u) {
+                    const int qr = qrow_s[8 * (j >> 2) + 4 * h + (j & 3)];
+                    const int o_begin = p.others_off[qr], o_end = p.others_off[qr + 1];
+                    bool ok = true;
+                    for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(p.meta, p.others[o], gid);
+                    if (!ok) pm &= ~(1u << j);
+                }
+            }
+        }
+        // phase 2: queue the candidates (slot from the row's LDS counter)
+        if (pm != 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if ((pm >> j) & 1u) {
+                    const int row = 8 * (j >> 2) + 4 * h + (j & 3);
+                    const uint32_t slot = atomicAdd(&pcnt[row], 1u);
+                    pend[row * PC + slot] = ((uint64_t)bitsv[j] << 32) | (uint32_t)(j0 + jrel);
+                }
+            }
+        }
+        if (__any(pm != 0)) {
+            wave_lds_sync();
+            pcv = lane < 32 ? (int)pcnt[lane] : 0;
+        }
+        if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
+    }
+    __syncthreads();
+
+    // ---- one sorted run of K keys per (query, segment)
+    for (int r = 0; r < t.q_count; ++r)
+        if (lane < K) p.runs[((int64_t)(t.gq_begin + r) * p.max_segs + seg) * K + lane] = best[r * KS + lane];
+}
+
+bool seed_select_supported(int dtype, int dim, bool bf16_copy)
+{
+    return dtype == 0 ? (dim == 128 || dim == 192) : (bf16_copy && (dim == 96 || dim == 128));
+}
+
+size_t seed_select_lds_bytes(int32_t K) { return (size_t)32 * 64 * 8 + (size_t)32 * (K | 1) * 8 + 3 * 32 * 4; }
+
+void launch_seed_select(int dtype, const SeedSelParams &p, int n_tiles, hipStream_t s)
+{
+    if (n_tiles <= 0) return;
+    const dim3 grid((unsigned)n_tiles * (unsigned)p.max_segs), block(64);
+    const size_t lds = seed_select_lds_bytes(p.K);
+    if (dtype == 0 && p.dim == 128) hipLaunchKernelGGL((seed_select_kernel<0, 4>), grid, block, lds, s, p);
+    else if (dtype == 0 && p.dim == 192) hipLaunchKernelGGL((seed_select_kernel<0, 6>), grid, block, lds, s, p);
+    else if (dtype == 1 && p.dim == 128) hipLaunchKernelGGL((seed_select_kernel<2, 8>), grid, block, lds, s, p);
+    else if (dtype == 1 && p.dim == 96) hipLaunchKernelGGL((seed_select_kernel<2, 6>), grid, block, lds, s, p);
+}
+
+// Profiling only: how many of a graph query's seeds pass its AND predicate (the "distances computed" figure the
+// search is accounted with counts them; the selection kernel tests only the seeds that reach a queue).
+__global__ __launch_bounds__(64) void seed_pass_count_kernel(const int32_t *gq_query, const int32_t *gq_label, LabelMeta meta,
+                                                             int32_t n_seeds, const int32_t *others_off,
+                                                             const int32_t *others, int32_t *pass_count)
+{
+    const int gq = blockIdx.x, lane = threadIdx.x;
+    const int qi = gq_query[gq], label = gq_label[gq];
+    const int n = meta.S[label];
+    const int ns = n_seeds < n ? n_seeds : n;
+    const int64_t base = meta.O_HS[label];
+    const int o_begin = others_off[qi], o_end = others_off[qi + 1];
+    int cnt = 0;
+    for (int j = lane; j < ns; j += 64) {
+        const int g = meta.M_HS[base + (int64_t)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns)];
+        bool ok = true;
+        for (int o = o_begin; o < o_end && ok; ++o) ok = has_label(meta, others[o], g);
+        cnt += ok ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    if (lane == 0) pass_count[gq] = cnt;
+}
+
+void launch_seed_pass_count(const int32_t *gq_query, const int32_t *gq_label, const LabelMeta &meta, int32_t n_seeds,
+                            const int32_t *others_off, const int32_t *others, int32_t *pass_count, int n_gq, hipStream_t s)
+{
+    if (n_gq <= 0) return;
+    hipLaunchKernelGGL(seed_pass_count_kernel, dim3(n_gq), dim3(64), 0, s, gq_query, gq_label, meta, n_seeds, others_off,
+                       others, pass_count);
 }
 
 bool seed_mfma_supported(int dtype, int dim)

@@ -464,14 +464,18 @@ def test_float_graph_build_in_panels(vf):
     assert len(bad) == 0, (len(bad), bad[:5])
 
 
-@pytest.mark.parametrize("knob,expect", [({"seed_cache": 0}, 1), ({"seed_bf16": 0}, 1), ({}, 2)],
-                         ids=["row gathers", "float32 seed copy", "bfloat16 seed copy"])
+@pytest.mark.parametrize("knob,expect", [({"seed_cache": 0}, 1), ({"seed_bf16": 0}, 1), ({}, 2), ({"seed_select": 0}, 2),
+                                         ({"seed_seg_seeds": 64}, 2)],
+                         ids=["row gathers", "float32 seed copy", "bfloat16 seed copy", "selection in the beam kernel",
+                              "short seed segments"])
 def test_matrix_core_seed_operand_sources(vf, knob, expect):
     """The matrix-core seed kernel normally reads an interleaved copy of the seeds, held in bfloat16 for
     float32 data (calls with fewer than 512 graph queries use a float32 copy kept beside it); with
     seed_bf16 = 0 there is only the float32 copy, and when the copy does not fit (or seed_cache = 0)
-    the kernel gathers the seeds' rows from the vector table.  Same results every way: bit-exact graph-path
-    answers on uint8 and float32 data (dim 128 and 96)."""
+    the kernel gathers the seeds' rows from the vector table.  With a copy the seed kernel also selects (for
+    float32 data from the bfloat16 copy, on calls with at least 512 graph queries) unless seed_select = 0, per
+    segment of seed_seg_seeds seeds.  Same results every way: bit-exact graph-path answers on uint8 and float32
+    data (dim 128 and 96)."""
     import torch
     for w in (make_workload("tiny"), make_workload("c2", n=30_000, nq=1500, n_labels=60, n_clusters=64, T=800, graph_degree=32),
               make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)):
@@ -496,6 +500,8 @@ def test_matrix_core_seed_operand_sources(vf, knob, expect):
         if want == 2 and g.sum() < 512:      # small calls are served from the float32 copy
             want = 1
         assert pf["seeds_on_matrix_cores"] == (want if s.dtype == "float32" else 1), pf
+        fused = knob.get("seed_select", 1) == 1 and knob.get("seed_cache", 1) == 1 and (s.dtype == "uint8" or want == 2)
+        assert pf["seed_selected"] == int(fused), pf
         assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf
         if s.dtype == "float32":               # and a call of 64 queries always is
             vf.search(ix, Q[:64], qoff[:65], qids[:64], 10, 32, 1, 6, 200)
