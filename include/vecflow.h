@@ -158,6 +158,26 @@ int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *q
               int64_t *out_ids, float *out_dists, void *hip_stream);
 
 /*
+ * vf_search for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Arguments, results and error behaviour are those of vf_search, and so are the kernels; the
+ * call creates nothing (no device or pinned memory, no stream, no event): its device-side temporaries (routing
+ * tables, partial results of segmented scan lists, seed distances) live in one fixed array of
+ * VF_NOALLOC_SCRATCH_BYTES of device memory per GPU, which the library holds from its first use on that GPU until
+ * the process ends, and the routing tables travel as kernel arguments.  Every launch goes to hip_stream, one
+ * after the other.  A call with more than VF_NOALLOC_MAX_QUERIES queries, or whose temporaries would not fit the
+ * array (the message says how many bytes it needs), fails with VF_EINVAL before anything is launched.  The
+ * interleaved seed copy of vf_search is used when an earlier vf_search call with the same n_seeds has left one;
+ * otherwise the seed kernel gathers the seeds' rows.  All calls on one GPU share the array, whatever their
+ * index or stream: two calls that overlap on the device race; the caller keeps them in stream order or waits
+ * in between.
+ */
+#define VF_NOALLOC_SCRATCH_BYTES (8u << 20)
+#define VF_NOALLOC_MAX_QUERIES 1024
+int vf_search_noalloc(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                      const int32_t *qlabel_ids, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
+                      int64_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
  * Multi-label queries through one search per label and a merge.
  *   mode VF_AND_GREEDY    the same as vf_search (smallest list + predicate, Section 4.3.2).
  *   mode VF_AND_PARALLEL  the parallel policy at the end of Section 4.3.2: when every query label

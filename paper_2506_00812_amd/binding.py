@@ -21,7 +21,7 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
                     "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi",
-                    "vf_build_index_opt", "vf_tune", "vf_debug_route")
+                    "vf_build_index_opt", "vf_tune", "vf_debug_route", "vf_search_noalloc")
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
 FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
@@ -76,6 +76,8 @@ def load_library():
         L.vf_debug_route.argtypes = [p, i32, i32, i64, p, p, i32, i32, p, p, p, p, i64, p, i64, p, p]
         L.vf_search.restype = C.c_int
         L.vf_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
+        L.vf_search_noalloc.restype = C.c_int
+        L.vf_search_noalloc.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
         L.vf_search_exact.restype = C.c_int
         L.vf_search_exact.argtypes = [p, p, i64, p, p, i32, p, p, p]
         L.vf_index_export.restype = C.c_int
@@ -314,6 +316,22 @@ def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width
     return out_ids, out_dists
 
 
+def search_noalloc(index: Index, queries, qlabel_offsets, qlabel_ids, k, out_ids, out_dists, itopk=64, width=1,
+                   iters=32, n_seeds=0, stream=None):
+    """vf_search_noalloc: the same search with every temporary in the library's fixed scratch array; the caller
+    passes the output tensors, nothing is allocated on the way.  Asynchronous on the (current) stream."""
+    off, ids = _prep_queries(index, queries, qlabel_offsets, qlabel_ids)
+    nq = queries.shape[0]
+    if tuple(out_ids.shape) != (nq, k) or tuple(out_dists.shape) != (nq, k):
+        raise VecflowError("out_ids / out_dists must be [nq, k]")
+    _check(load_library().vf_search_noalloc(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids),
+                                            int(k), int(itopk), int(width), int(iters), int(n_seeds),
+                                            C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
+                                            _stream_handle(stream)))
+    return out_ids, out_dists
+
+
+NOALLOC_SCRATCH_BYTES, NOALLOC_MAX_QUERIES = 8 << 20, 1024
 AND_GREEDY, AND_PARALLEL, OR = 0, 1, 2
 MULTI_EXACT = 0x100
 

@@ -233,6 +233,8 @@ struct vf_index {
     vf::Workspace ws[kWorkspaces];
     int ws_steal = 0;
     std::recursive_mutex mu;     // host side of every call
+    vf::Routed noalloc_routed;   // host-side scratch of vf_search_noalloc (kept between calls)
+    std::vector<char> noalloc_blob;
     vf::DevBuf tmp_blk, tmp_norm, counters;
     static constexpr int kSeedCopies = 4;
     vf::SeedCopy seed_copies[kSeedCopies];
