@@ -574,6 +574,38 @@ def main():
                     torch.cuda.synchronize()
                     rates.append(8 * len(batches) * bs / (time.perf_counter() - t0))
                 lat[f"batch_{bs}"][f"pipelined_qps_{n_streams}_stream{'s' if n_streams > 1 else ''}"] = round(float(np.median(rates[1:])), 1)
+        # the same kind of traffic through a serving session (one resident kernel, a job ring, one wave per query):
+        # single queries submitted from the host with 1, 8, 64 and 240 of them in flight.  A worker wave scores its
+        # query's seeds by itself, so sessions are measured at the operating point's parameters and at a moderate
+        # seed count
+        served = {}
+        n_serve = 4000
+        pick = np.concatenate([rng.choice(gq_idx, size=n_serve // 2, replace=True), rng.choice(sq_idx, size=n_serve // 2, replace=True)])
+        rng.shuffle(pick)
+        qs_host = np.ascontiguousarray(w.queries[pick])
+        qo_s = np.arange(n_serve + 1, dtype=np.int64)
+        ql_s = np.ascontiguousarray(lab[pick])
+        gt_s = gt if gt_rows is None else None
+        for tag, prm in (("operating_point", p_lat), ("512_seeds", (p_lat[0], p_lat[1], p_lat[2], 512))):
+            if prm[0] > 64:
+                continue
+            srv = vf.Server(ix, k, *prm, n_workers=240, ring_slots=1024)
+            try:
+                srv.run(qs_host[:512], qo_s[:513], ql_s[:512], in_flight=64)        # warm-up
+                row = {"params": list(prm)}
+                for fl in (1, 8, 64, 240):
+                    t0 = time.perf_counter()
+                    ids_s, _, lat_us = srv.run(qs_host, qo_s, ql_s, in_flight=fl)
+                    dt = time.perf_counter() - t0
+                    ls = np.sort(lat_us)
+                    row[f"in_flight_{fl}"] = {"qps": round(n_serve / dt, 1), "p50_ms": round(float(ls[len(ls) // 2]) / 1e3, 4),
+                                              "p99_ms": round(float(ls[int(len(ls) * 0.99)]) / 1e3, 4)}
+                if gt_s is not None:
+                    row["recall_at_10"] = round(recall_at_k(ids_s, gt_s[pick]), 4)
+            finally:
+                srv.end()
+            served[tag] = row
+        lat["served_session"] = served
         extra["latency"] = {"params": dict(zip(("itopk", "width", "iters", "n_seeds"), p_lat)), **lat}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same queries

@@ -37,6 +37,7 @@ extern "C" {
 #define VF_ENOMEM (-2) /* host or device allocation failed                     */
 #define VF_EHIP (-3)   /* a HIP runtime call failed; text in vf_last_error()   */
 #define VF_EINTERNAL (-4) /* an unexpected failure inside the library (a C++ exception caught at the boundary) */
+#define VF_EBUSY (-5)  /* vf_serve_submit: the job ring is full, try again                */
 
 #define VF_U8 0
 #define VF_F32 1
@@ -176,6 +177,56 @@ int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *q
 int vf_search_noalloc(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
                       const int32_t *qlabel_ids, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
                       int64_t *out_ids, float *out_dists, void *hip_stream);
+
+/*
+ * Queue-driven serving of single queries (the persistent kernel of Section 4.2.3).  vf_serve_begin launches ONE
+ * kernel that stays resident for the session: a dispatcher wave watches a job ring in pinned host memory and
+ * feeds a ring in device memory; worker waves (one per query, as many queries in flight as there are workers)
+ * claim jobs from it with an atomic compare-and-swap, route them (smallest list; graph search for |C_l| >= T,
+ * scan otherwise; the other labels as AND predicate) and write the k results and a done flag straight into a
+ * result ring in host memory.  A query costs no kernel launch and no HIP call: vf_serve_submit and
+ * vf_serve_poll only touch pinned memory.  Results are those of vf_search for the same query and parameters
+ * (uint8 and graph-searched float32 queries bit for bit).
+ *
+ *   k, itopk, width, iters, n_seeds   as in vf_search, fixed for the session; itopk <= 64.  A worker scores its
+ *                  query's seeds itself, one wave for all of them: sessions are meant for moderate seed counts
+ *   n_workers      worker waves, 0 = 240 (every workgroup of the kernel must fit on the chip at once)
+ *   ring_slots     jobs that may be in flight or unread, 0 = 1024
+ *   max_jobs       the kernel ends after this many jobs, 0 = no limit
+ *   idle_polls     the kernel ends after this many consecutive polls of the job ring without a new job
+ *                  (a poll takes about a microsecond), 0 = 2,000,000: every wave leaves on its own, the
+ *                  session need not be ended for the GPU to become free again
+ * The index must outlive the session and must not be freed before vf_serve_end.  One host thread at a time may
+ * submit; any thread may poll.
+ *
+ * vf_serve_submit  query: HOST pointer, dim elements of the index's dtype; labels: 1..8 label ids (AND).  *job
+ *                  receives the job's id (0, 1, 2, ... in submission order).  VF_EBUSY when ring_slots jobs
+ *                  before it are not finished yet; VF_EINVAL once the kernel has ended.
+ * vf_serve_poll    *done = 1 and the k (id, distance) pairs (host arrays; -1 / +inf padded) once the job has
+ *                  completed, else *done = 0.  A result stays readable until ring_slots further jobs have
+ *                  been submitted.
+ * vf_serve_end     asks the kernel to stop, waits for it (bounded: see idle_polls), reports how many jobs it
+ *                  completed and why it ended (1 asked to, 2 max_jobs, 3 idle), and releases the session.
+ */
+typedef struct vf_server vf_server;
+typedef struct vf_serve_params {
+    int32_t k, itopk, width, iters, n_seeds;
+    int32_t n_workers, ring_slots;
+    int32_t reserved;
+    int64_t max_jobs, idle_polls;
+} vf_serve_params;
+int vf_serve_begin(vf_index *index, const vf_serve_params *params, vf_server **out);
+int vf_serve_submit(vf_server *server, const void *query, const int32_t *labels, int32_t n_labels, int64_t *job);
+int vf_serve_poll(vf_server *server, int64_t job, int64_t *out_ids, float *out_dists, int32_t *done);
+int vf_serve_end(vf_server *server, int64_t *jobs_done, int32_t *exit_reason);
+/*
+ * A batch of host queries through a session, one job per query: submits them in order with at most in_flight
+ * (<= ring_slots) jobs outstanding and collects the results in order.  queries: HOST, row-major [nq][dim]; label
+ * arrays as in vf_search; out_ids / out_dists: HOST [nq][k]; latency_us: optional HOST [nq], microseconds from a
+ * job's submission until its result was seen.  Returns when every job is done (an error if the kernel ends first).
+ */
+int vf_serve_run(vf_server *server, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                 const int32_t *qlabel_ids, int32_t in_flight, int64_t *out_ids, float *out_dists, float *latency_us);
 
 /*
  * Multi-label queries through one search per label and a merge.

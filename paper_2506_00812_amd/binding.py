@@ -21,7 +21,8 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
 
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
                     "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi",
-                    "vf_build_index_opt", "vf_tune", "vf_debug_route", "vf_search_noalloc")
+                    "vf_build_index_opt", "vf_tune", "vf_debug_route", "vf_search_noalloc", "vf_serve_begin", "vf_serve_submit",
+                    "vf_serve_poll", "vf_serve_end", "vf_serve_run")
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
 FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
@@ -47,6 +48,11 @@ class VfProfile(C.Structure):
                                          "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds",
                                          "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "beam_gathered",
                                          "scan_kernel", "seed_selected", "seed_run_keys")]
+
+
+class VfServeParams(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("k", "itopk", "width", "iters", "n_seeds", "n_workers", "ring_slots", "reserved")] + \
+               [(n, C.c_int64) for n in ("max_jobs", "idle_polls")]
 
 
 class VecflowError(RuntimeError):
@@ -78,6 +84,16 @@ def load_library():
         L.vf_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
         L.vf_search_noalloc.restype = C.c_int
         L.vf_search_noalloc.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, p, p, p]
+        L.vf_serve_begin.restype = C.c_int
+        L.vf_serve_begin.argtypes = [p, C.POINTER(VfServeParams), C.POINTER(p)]
+        L.vf_serve_submit.restype = C.c_int
+        L.vf_serve_submit.argtypes = [p, p, p, i32, C.POINTER(i64)]
+        L.vf_serve_poll.restype = C.c_int
+        L.vf_serve_poll.argtypes = [p, i64, p, p, C.POINTER(i32)]
+        L.vf_serve_end.restype = C.c_int
+        L.vf_serve_end.argtypes = [p, C.POINTER(i64), C.POINTER(i32)]
+        L.vf_serve_run.restype = C.c_int
+        L.vf_serve_run.argtypes = [p, p, i64, p, p, i32, p, p, p]
         L.vf_search_exact.restype = C.c_int
         L.vf_search_exact.argtypes = [p, p, i64, p, p, i32, p, p, p]
         L.vf_index_export.restype = C.c_int
@@ -329,6 +345,74 @@ def search_noalloc(index: Index, queries, qlabel_offsets, qlabel_ids, k, out_ids
                                             C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
                                             _stream_handle(stream)))
     return out_ids, out_dists
+
+
+EBUSY = -5
+
+
+class Server:
+    """A serving session (vf_serve_*): a resident kernel that answers single queries from a job ring."""
+
+    def __init__(self, index: Index, k, itopk=32, width=1, iters=8, n_seeds=0, n_workers=0, ring_slots=0, max_jobs=0,
+                 idle_polls=0):
+        self.index, self.k = index, int(k)
+        prm = VfServeParams(int(k), int(itopk), int(width), int(iters), int(n_seeds), int(n_workers), int(ring_slots), 0,
+                            int(max_jobs), int(idle_polls))
+        h = C.c_void_p()
+        index._enter()
+        _check(load_library().vf_serve_begin(index._h, C.byref(prm), C.byref(h)))
+        self._h = h
+        self._np_dtype = np.uint8 if _dtype_code(index.vectors) == VF_U8 else np.float32
+        self.dim = index.vectors.shape[1]
+
+    def submit(self, query, labels):
+        """query: host array [dim]; labels: 1..8 ids.  Returns the job id, or None when the ring is full."""
+        q = np.ascontiguousarray(query, dtype=self._np_dtype)
+        if q.shape != (self.dim,):
+            raise VecflowError("query must have dim elements")
+        lab = np.ascontiguousarray(labels, dtype=np.int32).reshape(-1)
+        job = C.c_int64(-1)
+        rc = load_library().vf_serve_submit(self._h, _np_ptr(q), _np_ptr(lab), len(lab), C.byref(job))
+        if rc == EBUSY:
+            return None
+        _check(rc)
+        return job.value
+
+    def poll(self, job):
+        """(ids, dists) of a completed job, else None."""
+        ids = np.empty(self.k, dtype=np.int64)
+        d = np.empty(self.k, dtype=np.float32)
+        done = C.c_int32(0)
+        _check(load_library().vf_serve_poll(self._h, int(job), _np_ptr(ids), _np_ptr(d), C.byref(done)))
+        return (ids, d) if done.value else None
+
+    def run(self, queries, qlabel_offsets, qlabel_ids, in_flight=64):
+        """A host batch through the session, one job per query (vf_serve_run): (ids, dists, latency_us)."""
+        q = np.ascontiguousarray(queries, dtype=self._np_dtype)
+        off = np.ascontiguousarray(qlabel_offsets, dtype=np.int64)
+        lab = np.ascontiguousarray(qlabel_ids, dtype=np.int32)
+        nq = q.shape[0]
+        ids = np.empty((nq, self.k), dtype=np.int64)
+        d = np.empty((nq, self.k), dtype=np.float32)
+        lat = np.empty(nq, dtype=np.float32)
+        _check(load_library().vf_serve_run(self._h, _np_ptr(q), nq, _np_ptr(off), _np_ptr(lab), int(in_flight),
+                                           _np_ptr(ids), _np_ptr(d), _np_ptr(lat)))
+        return ids, d, lat
+
+    def end(self):
+        """Stops the kernel and releases the session; returns (jobs completed, exit reason)."""
+        if self._h is None:
+            return None
+        n, why = C.c_int64(0), C.c_int32(0)
+        h, self._h = self._h, None
+        _check(load_library().vf_serve_end(h, C.byref(n), C.byref(why)))
+        return n.value, why.value
+
+    def __del__(self):
+        try:
+            self.end()
+        except Exception:
+            pass
 
 
 NOALLOC_SCRATCH_BYTES, NOALLOC_MAX_QUERIES = 8 << 20, 1024

@@ -101,8 +101,8 @@ struct Tuning {
     int seed_bf16 = 1;            // 0: float32 data keep only the float32 copy of the seeds
     int seed_bf16_min_batch = 512;   // calls with fewer graph queries use the float32 copy when it is resident
     int seed_fb_window = 131072;  // graph queries between two looks at the failed-proof counter
-    int seed_select = 1;          // 0: the seed kernel writes every distance, the beam kernel selects (itopk <= 64 only differs)
-    int seed_seg_seeds = 0;       // seeds per wave of the selecting seed kernel; 0: chosen per call (512 .. 4096)
+    int seed_select = 0;          // 1: the seed kernel also selects (runs of keys instead of every distance; itopk <= 64)
+    int seed_seg_seeds = 0;       // seeds per wave of the selecting seed kernel; 0: chosen per call (512 .. 16384)
     int build16 = 1;              // float32 kNN self-joins on 16-row tiles
     int build_panel_kb = 4096;    // self-joins of long lists go panel by panel, this much of the list per launch
     int build_progress = 0;       // 1: a line on stderr every ten seconds while graphs are built

@@ -318,7 +318,7 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
         int32_t seg = tune.seed_seg_seeds;
         if (seg <= 0) {
             const int64_t want_segs = std::max<int64_t>(1, (2048 + (int64_t)n_tiles - 1) / (int64_t)n_tiles);
-            seg = (int32_t)std::min<int64_t>(4096, std::max<int64_t>(512, (longest / want_segs) / 32 * 32));
+            seg = (int32_t)std::min<int64_t>(16384, std::max<int64_t>(512, (longest / want_segs) / 32 * 32));
         }
         seg = std::max(32, seg / 32 * 32);
         P.seg_seeds = seg;
@@ -441,6 +441,12 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         bp.dseed = nullptr; bp.ns_stride = P.ns_stride;
     }
     auto run_seeds = [&]() -> int {
+        if (prof && n_gq && P.seed_select && r.any_and) {
+            // profiling only, outside the timed interval: the counters report the seeds that pass the predicate as
+            // distances computed, and the selecting kernel only tests the seeds that reach a queue
+            launch_seed_pass_count(bp.gq_query, bp.gq_label, bp.meta, P.n_seeds, d_others_off, d_others,
+                                   ix->counters.as<int32_t>() + (size_t)P.nq * 5, (int)n_gq, s);
+        }
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
         if (n_gq && P.seed_select) {
             // scoring and selection in one kernel: runs of sel_K keys per (query, seed segment)
@@ -463,12 +469,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                     const int64_t ns_l = std::min<int64_t>(P.n_seeds, ix->S[(size_t)t.label]);
                     ix->prof.seed_run_keys += (int64_t)t.q_count * ((ns_l + P.seg_seeds - 1) / P.seg_seeds) * P.sel_K;
                 }
-                if (r.any_and) {   // the counters report the seeds that pass the predicate as distances computed
-                    int32_t *pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;
-                    launch_seed_pass_count(bp.gq_query, bp.gq_label, bp.meta, P.n_seeds, d_others_off, d_others, pass,
-                                           (int)n_gq, s);
-                    bp.seed_pass = pass;
-                }
+                if (r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
             }
             if (ix->dtype == VF_F32) {
                 // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the query's split

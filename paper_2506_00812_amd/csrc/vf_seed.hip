@@ -352,6 +352,7 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
     uint32_t *qnorm_s = (uint32_t *)(best + 32 * KS); // [32] float bits / int
     uint32_t *pcnt = qnorm_s + 32;                   // [32] keys waiting in pend[r]
     int32_t *qrow_s = (int32_t *)(pcnt + 32);        // [32] query index of the row, -1: none
+    int32_t *pslot_s = qrow_s + 32;                  // [32] bitset row of the row's AND partner, see below
 
     const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
     const int tile = blockIdx.x / p.max_segs, seg = blockIdx.x % p.max_segs;
@@ -364,7 +365,18 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
     const int n_groups = (nj + 31) >> 5;
     const int64_t grp0 = p.seed_goff[p.meta.hs_slot[t.label]] + (j0 >> 5);
 
-    if (lane < 32) { qrow_s[lane] = lane < t.q_count ? p.gq_query[t.gq_begin + lane] : -1; pcnt[lane] = 0; }
+    if (lane < 32) {
+        const int qr = lane < t.q_count ? p.gq_query[t.gq_begin + lane] : -1;
+        qrow_s[lane] = qr;
+        pcnt[lane] = 0;
+        // the common AND query has one partner label, a graph label: its predicate is one bit of that label's
+        // bitset, which can be fetched for all of a lane's rows at once (pslot_s >= 0); other rows evaluate the
+        // general predicate pair by pair
+        int ps = -1;
+        if (qr >= 0 && p.others_off != nullptr && p.others_off[qr + 1] - p.others_off[qr] == 1)
+            ps = p.meta.hs_slot[p.others[p.others_off[qr]]];
+        pslot_s[lane] = ps;
+    }
     for (int i = lane; i < 32 * KS; i += 64) best[i] = KEY_MAX;
     __syncthreads();
 
@@ -424,7 +436,7 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
 
     // per-lane constants for its 16 accumulator rows: row(j) = 8 * (j / 4) + 4 * h + (j % 4)
     uint32_t qn[16], thr[16];
-    uint32_t live_rows = 0, and_rows = 0;
+    uint32_t live_rows = 0, and_rows = 0, fast_rows = 0;   // and_rows: general predicate; fast_rows: one bitset bit
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const int row = 8 * (j >> 2) + 4 * h + (j & 3);
@@ -434,19 +446,25 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
             live_rows |= 1u << j;
             if (p.others_off != nullptr) {
                 const int qr = qrow_s[row];
-                if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << j;
+                if (pslot_s[row] >= 0) fast_rows |= 1u << j;
+                else if (p.others_off[qr + 1] > p.others_off[qr]) and_rows |= 1u << j;
             }
         }
     }
-    const bool any_and = __any(and_rows != 0);
+    const bool any_and = __any((and_rows | fast_rows) != 0);
     int pcv = 0;                  // state of tile row r, held by lane r (r < 32)
     uint64_t row_kth = KEY_MAX;
 
-    auto drain = [&]() {
+    // Merge queues into lists: only the rows whose queue could overflow on the next group (more than PC - 32
+    // keys), or every row with a key at the end of the segment.  A drain costs a sort and a merge per row
+    // whatever the queue holds, so a row is left alone until its queue is worth it.
+    auto drain = [&](bool all) {
         wave_lds_sync();
-        if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv, row_kth, lane);
-        wave_drain_rows<4>(pend, PC, best, KS, K, pcv, row_kth, lane);
-        if (lane < 32) pcnt[lane] = 0;
+        const bool mine = lane < 32 && pcv > (all ? 0 : PC - 32);
+        int pcv_sel = mine ? pcv : 0;
+        if (K <= 32) wave_drain_rows_packed<32>(pend, PC, best, KS, K, pcv_sel, row_kth, lane);
+        wave_drain_rows<4>(pend, PC, best, KS, K, pcv_sel, row_kth, lane);
+        if (mine) { pcnt[lane] = 0; pcv = 0; }
         wave_lds_sync();
         const uint32_t tk = (uint32_t)(row_kth >> 32);
 #pragma unroll
@@ -534,6 +552,28 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
 #pragma unroll
         for (int j = 0; j < 16; ++j) pm |= (bitsv[j] <= thr[j] ? 1u : 0u) << j;
         pm &= jrel < nj ? live_rows : 0u;
+        if (any_and && __any((pm & fast_rows) != 0)) {
+            // one bitset word per candidate pair, all requested before the first is looked at (pairs that are
+            // no candidates read the table's first word: one cached address for the whole wave)
+            const uint32_t *bs = p.meta.bitsets;
+            const int64_t wi = gid >> 5;
+#pragma unroll
+            for (int j0 = 0; j0 < 16; j0 += 8) {
+                uint32_t wv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int j = j0 + u;
+                    const bool c = ((pm & fast_rows) >> j) & 1u;
+                    const int ps = pslot_s[8 * (j >> 2) + 4 * h + (j & 3)];
+                    wv[u] = bs[c ? (int64_t)ps * p.meta.bitset_words + wi : 0];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int j = j0 + u;
+                    if ((((pm & fast_rows) >> j) & 1u) && !((wv[u] >> (gid & 31)) & 1u)) pm &= ~(1u << j);
+                }
+            }
+        }
         if (any_and && (pm & and_rows) != 0) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -561,7 +601,8 @@ __global__ __launch_bounds__(64, 2) void seed_select_kernel(SeedSelParams p)
             wave_lds_sync();
             pcv = lane < 32 ? (int)pcnt[lane] : 0;
         }
-        if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
+        const bool last = grp + 1 == n_groups;
+        if (__any(pcv > PC - 32) || (last && __any(pcv != 0))) drain(last);
     }
     __syncthreads();
 
@@ -575,7 +616,7 @@ bool seed_select_supported(int dtype, int dim, bool bf16_copy)
     return dtype == 0 ? (dim == 128 || dim == 192) : (bf16_copy && (dim == 96 || dim == 128));
 }
 
-size_t seed_select_lds_bytes(int32_t K) { return (size_t)32 * 64 * 8 + (size_t)32 * (K | 1) * 8 + 3 * 32 * 4; }
+size_t seed_select_lds_bytes(int32_t K) { return (size_t)32 * 64 * 8 + (size_t)32 * (K | 1) * 8 + 4 * 32 * 4; }
 
 void launch_seed_select(int dtype, const SeedSelParams &p, int n_tiles, hipStream_t s)
 {

@@ -75,6 +75,15 @@ def test_c3_full_size_sampled_against_oracle(capsys):
     torch.cuda.synchronize()
     ids, dists = to_np(ids), to_np(dists)
     step("GPU search of the whole batch done")
+    # the same batch with the selection fused into the seed kernel (runs of keys instead of the 5.9 GB distance
+    # matrix): every row must come out the same
+    ix.tune("seed_select", 1)
+    ids2, dists2 = vf.search(ix, Q, w.qlabel_offsets, w.qlabel_ids, s.k, **C3_PARAMS)
+    torch.cuda.synchronize()
+    ix.tune("seed_select", 0)
+    assert np.array_equal(to_np(ids2), ids) and np.array_equal(to_np(dists2), dists)
+    del ids2, dists2
+    step("seed kernel with fused selection: same results")
 
     nlab = np.diff(w.qlabel_offsets)
     first = w.qlabel_ids[w.qlabel_offsets[:-1]]

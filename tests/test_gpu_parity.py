@@ -255,7 +255,9 @@ def test_work_counters_equal_oracle_counts(vf, tiny, tiny_oracle, tiny_gpu):
     ix.profile_enable(True)
     try:
         for (qo, qi, n) in ((tiny.qlabel_offsets, tiny.qlabel_ids, tiny.spec.nq), (qoff, qids, nq)):
-            for params in (dict(itopk=32, width=1, iters=20, n_seeds=0), dict(itopk=64, width=2, iters=24, n_seeds=700)):
+            for params, fused in ((dict(itopk=32, width=1, iters=20, n_seeds=0), 0), (dict(itopk=64, width=2, iters=24, n_seeds=700), 0),
+                                  (dict(itopk=64, width=2, iters=24, n_seeds=700), 1), (dict(itopk=32, width=1, iters=6, n_seeds=2000), 1)):
+                ix.tune("seed_select", fused)      # 1: the seed kernel selects (and applies the AND predicate to the seeds)
                 ig, dg = _search(vf, ix, Q[:n], qo, qi, 10, **params)
                 pf, cn = ix.profile_read(per_query=True)
                 io, do, info = tiny_oracle.search(tiny.queries[:n], qo, qi, 10, with_info=True, **params)
@@ -266,8 +268,10 @@ def test_work_counters_equal_oracle_counts(vf, tiny, tiny_oracle, tiny_gpu):
                 assert pf["beam_scored"] == info["counters"][g, 0].sum()
                 assert pf["n_graph_queries"] == g.sum() and pf["n_scan_queries"] == (info["method"] == 1).sum()
                 assert pf["beam_ms"] > 0
+                assert pf["seed_selected"] == fused
     finally:
         ix.profile_enable(False)
+        ix.tune("seed_select", 0)
 
 
 @pytest.mark.parametrize("name,dim", [("tiny", 48), ("c2", 40)])
@@ -464,16 +468,16 @@ def test_float_graph_build_in_panels(vf):
     assert len(bad) == 0, (len(bad), bad[:5])
 
 
-@pytest.mark.parametrize("knob,expect", [({"seed_cache": 0}, 1), ({"seed_bf16": 0}, 1), ({}, 2), ({"seed_select": 0}, 2),
-                                         ({"seed_seg_seeds": 64}, 2)],
-                         ids=["row gathers", "float32 seed copy", "bfloat16 seed copy", "selection in the beam kernel",
-                              "short seed segments"])
+@pytest.mark.parametrize("knob,expect", [({"seed_cache": 0}, 1), ({"seed_bf16": 0}, 1), ({}, 2), ({"seed_select": 1}, 2),
+                                         ({"seed_select": 1, "seed_seg_seeds": 64}, 2)],
+                         ids=["row gathers", "float32 seed copy", "bfloat16 seed copy", "selection in the seed kernel",
+                              "selection in the seed kernel, short segments"])
 def test_matrix_core_seed_operand_sources(vf, knob, expect):
     """The matrix-core seed kernel normally reads an interleaved copy of the seeds, held in bfloat16 for
     float32 data (calls with fewer than 512 graph queries use a float32 copy kept beside it); with
     seed_bf16 = 0 there is only the float32 copy, and when the copy does not fit (or seed_cache = 0)
     the kernel gathers the seeds' rows from the vector table.  With a copy the seed kernel also selects (for
-    float32 data from the bfloat16 copy, on calls with at least 512 graph queries) unless seed_select = 0, per
+    float32 data from the bfloat16 copy, on calls with at least 512 graph queries) when seed_select = 1, per
     segment of seed_seg_seeds seeds.  Same results every way: bit-exact graph-path answers on uint8 and float32
     data (dim 128 and 96)."""
     import torch
@@ -500,7 +504,7 @@ def test_matrix_core_seed_operand_sources(vf, knob, expect):
         if want == 2 and g.sum() < 512:      # small calls are served from the float32 copy
             want = 1
         assert pf["seeds_on_matrix_cores"] == (want if s.dtype == "float32" else 1), pf
-        fused = knob.get("seed_select", 1) == 1 and knob.get("seed_cache", 1) == 1 and (s.dtype == "uint8" or want == 2)
+        fused = knob.get("seed_select", 0) == 1 and knob.get("seed_cache", 1) == 1 and (s.dtype == "uint8" or want == 2)
         assert pf["seed_selected"] == int(fused), pf
         assert pf["seed_fallbacks"] <= 0.02 * g.sum(), pf
         if s.dtype == "float32":               # and a call of 64 queries always is

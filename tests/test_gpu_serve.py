@@ -1,0 +1,151 @@
+"""The queue-driven serving session (resident kernel, Section 4.2.3) against vf_search: every job's result equals
+the batched search of the same query; the kernel ends by itself when its bounded wait expires."""
+import time
+
+import numpy as np
+import pytest
+
+from paper_2506_00812_amd.workloads import make_workload
+from tests.gpu_util import assert_close_with_ties, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vf():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2506_00812_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _wait(server, jobs, timeout_s=60.0):
+    out, t0 = {}, time.time()
+    pending = list(jobs)
+    while pending:
+        assert time.time() - t0 < timeout_s, f"{len(pending)} jobs still pending"
+        rest = []
+        for j in pending:
+            r = server.poll(j)
+            if r is None:
+                rest.append(j)
+            else:
+                out[j] = r
+        pending = rest
+    return out
+
+
+def _labels_with_and(w, nq, rng):
+    first = w.qlabel_ids[w.qlabel_offsets[:-1]][:nq]
+    labs = []
+    for j in range(nq):
+        if j % 3 == 0:
+            labs.append([int(first[j]), int(rng.integers(0, min(8, w.spec.n_labels)))])
+        else:
+            labs.append([int(first[j])])
+    return labs
+
+
+@pytest.mark.parametrize("name", ["uint8", "float32", "float32 dim 96"])
+def test_served_queries_equal_batched_search(vf, name):
+    import torch
+    if name == "uint8":
+        w = make_workload("tiny", nq=600)
+    elif name == "float32":
+        w = make_workload("c2", n=30_000, nq=600, n_labels=60, n_clusters=64, T=800, graph_degree=32)
+    else:
+        w = make_workload("c5", n=20_000, nq=600, n_labels=80, n_clusters=32, T=600, graph_degree=16)
+    s = w.spec
+    X = torch.from_numpy(w.vectors).cuda()
+    Q = torch.from_numpy(w.queries).cuda()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    rng = np.random.default_rng(3)
+    nq = 600
+    labs = _labels_with_and(w, nq, rng)
+    off = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum([len(l) for l in labs], out=off[1:])
+    ids = np.concatenate(labs).astype(np.int32)
+    params = dict(itopk=32, width=2, iters=8, n_seeds=128)
+    ref_i, ref_d = vf.search(ix, Q[:nq], off, ids, 10, **params)
+    torch.cuda.synchronize()
+    ref_i, ref_d = to_np(ref_i), to_np(ref_d)
+    S = ix.export("S")
+    smallest = np.array([S[l].min() for l in labs])
+    graph = smallest >= s.T
+    assert graph.sum() > 100 and (~graph).sum() > 100
+
+    srv = vf.Server(ix, 10, n_workers=64, ring_slots=256, **params)
+    try:
+        pending, got = [], {}
+        for j in range(nq):                                  # more jobs than ring slots: the ring wraps
+            job = srv.submit(w.queries[j], labs[j])
+            while job is None:                               # ring full: the oldest jobs are still running
+                time.sleep(0.001)
+                job = srv.submit(w.queries[j], labs[j])
+            assert job == j
+            pending.append(job)
+            if len(pending) >= 192:                          # results must be read before the ring wraps over them
+                got.update(_wait(srv, pending[:64]))
+                pending = pending[64:]
+        got.update(_wait(srv, pending))
+        # the same queries once more as one host batch through the session
+        ri, rd, lat = srv.run(w.queries[:nq], off, ids, in_flight=48)
+        for j in range(nq):
+            assert np.array_equal(ri[j], got[j][0]) and np.array_equal(rd[j].view(np.uint32), got[j][1].view(np.uint32))
+        assert (lat > 0).all()
+    finally:
+        done, why = srv.end()
+    assert done == 2 * nq and why == 1
+    gi = np.stack([got[j][0] for j in range(nq)])
+    gd = np.stack([got[j][1] for j in range(nq)])
+    assert np.array_equal(gi[graph], ref_i[graph]), "graph-searched jobs"
+    assert np.array_equal(gd[graph].view(np.uint32), ref_d[graph].view(np.uint32))
+    if s.dtype == "uint8":
+        assert np.array_equal(gi[~graph], ref_i[~graph]) and np.array_equal(gd[~graph], ref_d[~graph])
+    else:
+        assert_close_with_ties(gi[~graph], gd[~graph], ref_i[~graph], ref_d[~graph], 1e-4, "scanned jobs")
+
+
+def test_serving_kernel_ends_by_itself(vf, tiny):
+    """Bounded waits: with a small idle bound the kernel leaves on its own, vf_serve_end returns at once and
+    reports why; submissions after that are refused; max_jobs ends a session as well."""
+    import torch
+    s = tiny.spec
+    X = torch.from_numpy(tiny.vectors).cuda()
+    ix = vf.build_index(X, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, s.graph_degree)
+    srv = vf.Server(ix, 10, itopk=32, width=1, iters=4, n_seeds=64, n_workers=8, ring_slots=16, idle_polls=2000)
+    job = srv.submit(tiny.queries[0], [int(tiny.qlabel_ids[0])])
+    r = _wait(srv, [job])
+    assert (r[job][0] >= 0).any()
+    t0 = time.time()
+    while time.time() - t0 < 20.0:                           # the idle bound expires within milliseconds
+        try:
+            if srv.submit(tiny.queries[1], [int(tiny.qlabel_ids[1])]) is None:
+                time.sleep(0.01)
+                continue
+            time.sleep(0.05)
+        except vf.VecflowError as e:
+            assert "ended" in str(e)
+            break
+    else:
+        pytest.fail("the kernel did not end by itself")
+    done, why = srv.end()
+    assert why == 3 and done >= 1
+    # max_jobs
+    srv = vf.Server(ix, 10, itopk=32, width=1, iters=4, n_seeds=64, n_workers=8, ring_slots=16, max_jobs=5)
+    jobs = [srv.submit(tiny.queries[j], [int(tiny.qlabel_ids[j])]) for j in range(5)]
+    _wait(srv, jobs)
+    with pytest.raises(vf.VecflowError):
+        srv.submit(tiny.queries[5], [int(tiny.qlabel_ids[5])])
+    done, why = srv.end()
+    assert done == 5 and why == 2
+    # bad arguments never reach the ring
+    srv = vf.Server(ix, 10, itopk=32, width=1, iters=4, n_seeds=64, n_workers=4, ring_slots=8, idle_polls=200000)
+    with pytest.raises(vf.VecflowError, match="outside"):
+        srv.submit(tiny.queries[0], [s.n_labels])
+    with pytest.raises(vf.VecflowError, match="1 to 8"):
+        srv.submit(tiny.queries[0], list(range(9)))
+    assert srv.end() == (0, 1)
+    with pytest.raises(vf.VecflowError, match="at most 64"):
+        vf.Server(ix, 10, itopk=128, width=1, iters=4, n_seeds=64)
