@@ -51,6 +51,8 @@ def lib():
         L.vfo_free.argtypes = [p]
         L.vfo_search.restype = C.c_int
         L.vfo_search.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, i64, C.c_int, p, p, p, p, p, C.c_int]
+        L.vfo_search_routed.restype = C.c_int
+        L.vfo_search_routed.argtypes = [p, p, i64, p, p, i32, i32, i32, i32, i32, i64, C.c_int, i64, p, p, p, p, p, C.c_int]
         L.vfo_search_multi.argtypes = [p, p, i64, p, p, C.c_int, i32, i32, i32, i32, i32, C.c_int, p, p, p, C.c_int]
         L.vfo_search_multi.restype = C.c_int
         for name in ("vfo_n_HS", "vfo_n_LS"):
@@ -172,7 +174,7 @@ class OracleIndex:
         return row
 
     def search(self, queries, qlabel_offsets, qlabel_ids, k, itopk=32, width=1, iters=20, n_seeds=0,
-               visited_cap=0, force_scan=False, n_threads=None, with_info=False):
+               visited_cap=0, force_scan=False, n_threads=None, with_info=False, and_scan_limit=0):
         queries = np.ascontiguousarray(queries)
         assert str(queries.dtype) == self.dtype and queries.shape[1] == self.dim
         nq = queries.shape[0]
@@ -183,9 +185,10 @@ class OracleIndex:
         method = np.empty(nq, dtype=np.int32)
         route = np.empty(nq, dtype=np.int32)
         counters = np.zeros((nq, 3), dtype=np.int64)
-        rc = lib().vfo_search(self._h, _ptr(queries), nq, _ptr(qoff), _ptr(qids), k, itopk, width, iters, n_seeds,
-                              visited_cap, int(force_scan), _ptr(ids), _ptr(dists), _ptr(method), _ptr(route),
-                              _ptr(counters), self.n_threads if n_threads is None else n_threads)
+        rc = lib().vfo_search_routed(self._h, _ptr(queries), nq, _ptr(qoff), _ptr(qids), k, itopk, width, iters, n_seeds,
+                                     visited_cap, int(force_scan), int(and_scan_limit), _ptr(ids), _ptr(dists),
+                                     _ptr(method), _ptr(route), _ptr(counters),
+                                     self.n_threads if n_threads is None else n_threads)
         if rc != 0:
             raise ValueError("vfo_search rejected its arguments")
         if with_info:

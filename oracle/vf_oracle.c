@@ -34,7 +34,14 @@
  *   - the loop runs a fixed number of iterations and stops early when the top-M
  *     list holds no unexpanded entry; ties are broken by lower id everywhere;
  *   - under AND, a scored point that fails the predicate never enters the top-M
- *     list and is never expanded.
+ *     list and is never expanded;
+ *   - optional selectivity-aware routing of AND queries (and_scan_limit > 0): an AND
+ *     query whose smallest list is a graph list of at most and_scan_limit points is
+ *     answered by the exact filtered scan of that list instead of the greedy graph
+ *     search (Section 4.3.2 chooses the smallest list and filters it with the predicate
+ *     function; Section 5.3 reports the recall ceiling of the greedy policy on such
+ *     queries; how large a list may be for the scan to stay the cheaper route is a
+ *     parameter here, 0 = never, the paper's behaviour).
  *
  * PARITY STATUS.  Scan path, posting lists, routing, predicate: pinned by the
  * definitions (exact filtered brute force in numpy, the paper's worked
@@ -641,11 +648,14 @@ static void scan_search(const vfo_index *ix, const void *q, int32_t l, const int
  * counters (optional, [nq][3]): distances computed, rows expanded, predicate tests.
  * force_scan != 0 answers every query by exact scan (ground truth).
  * visited_cap > 0 replaces the exact visited set by a forgetful table of that many slots.
+ * and_scan_limit > 0: AND queries (two or more distinct labels) whose smallest list is a graph
+ *   list of at most and_scan_limit points are answered by the exact filtered scan of that list
+ *   (method 3).
  * Returns 0, or -1 on invalid arguments. */
-int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
-               int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, int64_t visited_cap, int force_scan,
-               int64_t *out_ids, float *out_dists, int32_t *method_out, int32_t *route_label_out,
-               int64_t *counters, int n_threads)
+int vfo_search_routed(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
+                      int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, int64_t visited_cap, int force_scan,
+                      int64_t and_scan_limit, int64_t *out_ids, float *out_dists, int32_t *method_out,
+                      int32_t *route_label_out, int64_t *counters, int n_threads)
 {
     if (!ix || nq < 0 || k <= 0) return -1;
     if (!force_scan && (itopk < k || width <= 0 || iters < 0)) return -1;
@@ -695,6 +705,9 @@ int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, co
             } else if (force_scan || ix->S[best] < ix->T) {
                 scan_search(ix, q, best, ql, n_others, k, oi, od, cn);
                 method = 1;
+            } else if (n_others > 0 && and_scan_limit > 0 && ix->S[best] <= and_scan_limit) {
+                scan_search(ix, q, best, ql, n_others, k, oi, od, cn);
+                method = 3;
             } else {
                 vs.tick++;
                 if (vs.fcap > 0) for (int64_t s = 0; s < vs.fcap; ++s) vs.ftab[s] = -1;
@@ -708,6 +721,15 @@ int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, co
         free(vs.stamp); free(vs.ftab);
     }
     return 0;
+}
+
+int vfo_search(vfo_index *ix, const void *Q, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
+               int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, int64_t visited_cap, int force_scan,
+               int64_t *out_ids, float *out_dists, int32_t *method_out, int32_t *route_label_out,
+               int64_t *counters, int n_threads)
+{
+    return vfo_search_routed(ix, Q, nq, qoff, qids, k, itopk, width, iters, n_seeds, visited_cap, force_scan, 0, out_ids,
+                             out_dists, method_out, route_label_out, counters, n_threads);
 }
 
 /* ---------------------------------------------------------------------------

@@ -616,3 +616,44 @@ def test_pruned_build_rejects_bad_arguments(tiny):
     with pytest.raises(ValueError):
         OracleIndex(tiny.vectors, tiny.label_offsets, tiny.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True,
                     knn_degree=2 * s.graph_degree)
+
+
+def test_selectivity_aware_and_routing_is_exact_below_the_limit_and_unchanged_above(tiny, tiny_oracle):
+    """and_scan_limit (optional routing, Section 4.3.2 / the greedy policy's ceiling in Section 5.3): an AND query whose
+    smallest list is a graph list of at most that many points gets the exact filtered top-k of Def. 1 (written
+    separately in numpy); every other query -- single label, AND on a scan list, AND on a longer graph list -- is
+    answered exactly as without the limit."""
+    s = tiny.spec
+    mem = membership(tiny.label_offsets, tiny.label_ids, s.n_labels)
+    S = tiny_oracle.S
+    rng = np.random.default_rng(19)
+    nq = 240
+    a = rng.integers(0, 9, size=nq).astype(np.int32)            # the nine most frequent labels: graph lists and the first scan lists
+    b = rng.integers(0, 9, size=nq).astype(np.int32)
+    single = rng.random(nq) < 0.25
+    cnt = np.where(single, 1, 2)
+    qoff = np.zeros(nq + 1, dtype=np.int64)
+    np.cumsum(cnt, out=qoff[1:])
+    qids = np.empty(qoff[-1], dtype=np.int32)
+    qids[qoff[:-1]] = a
+    qids[qoff[:-1][~single] + 1] = b[~single]
+    params = dict(itopk=32, width=1, iters=6, n_seeds=32)
+    limit = 1000                                                 # graph lists hold 500 .. 3,427 points: some below, some above
+    base_i, base_d, base_info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, with_info=True, **params)
+    ids, dists, info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, s.k, with_info=True, and_scan_limit=limit, **params)
+    n_exact = 0
+    for j in range(nq):
+        labs = np.unique(qids[qoff[j]:qoff[j + 1]])
+        smallest = S[labs].min()
+        if len(labs) > 1 and s.T <= smallest <= limit:
+            assert info["method"][j] == 3 and base_info["method"][j] == 2
+            wi, wd = filtered_knn(tiny.vectors, mem, tiny.queries[j], list(labs), s.k)
+            assert np.array_equal(ids[j], wi) and np.array_equal(dists[j].astype(np.float64), wd)
+            n_exact += 1
+        else:
+            assert info["method"][j] == base_info["method"][j]
+            assert np.array_equal(ids[j], base_i[j]) and np.array_equal(dists[j], base_d[j])
+    assert n_exact > 20 and (info["method"] == 2).sum() > 20
+    # the greedy search misses some of what the exact route finds (the reason for the route)
+    changed = sum(not np.array_equal(ids[j], base_i[j]) for j in range(nq))
+    assert changed > 0
