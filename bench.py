@@ -131,6 +131,9 @@ def main():
                     help="also measure two-label AND (greedy and parallel policy) and OR queries on the same index")
     ap.add_argument("--latency", action="store_true",
                     help="also measure small-batch latency (batches of 1, 8 and 64 queries, half graph / half scan labels)")
+    ap.add_argument("--and-scan-limit", type=int, default=0,
+                    help="selectivity-aware routing (vf_search_ex): AND queries whose smallest list is a graph list of at "
+                         "most this many vectors are answered by the exact predicate scan of that list; 0 = the paper's routing")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (scale reference for HBM byte counters)")
     args = ap.parse_args()
@@ -145,6 +148,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     vf.load_library()
+    if args.and_scan_limit:
+        # every vf.search call of this run goes through vf_search_ex with the limit (single-label queries and AND
+        # queries on long lists are routed as before)
+        plain_search = vf.search
+        vf.search = lambda *a, **kw: plain_search(*a, and_scan_limit=args.and_scan_limit, **kw)
 
     t0 = time.time()
     log(f"[bench] generating workload {args.workload} ...")
@@ -627,7 +635,8 @@ def main():
         t0 = time.time()
         ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True,
                           n_threads=cores)
-        ids_o, d_o = ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds)       # untimed: builds the graph rows it touches
+        okw = dict(and_scan_limit=args.and_scan_limit)
+        ids_o, d_o = ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds, **okw)   # untimed: builds the graph rows it touches
         log(f"[bench] oracle index (lazy graph rows) + first pass over {len(sample)} queries on {cores} threads: "
             f"{time.time() - t0:.1f}s")
 
@@ -635,7 +644,7 @@ def main():
             reps, spent = 0, 0.0
             t0 = time.perf_counter()
             while spent < budget_s and reps < max_reps:
-                ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds, n_threads=n_threads)
+                ixo.search(qs, qo, ql, k, itopk, width, iters, n_seeds, n_threads=n_threads, **okw)
                 reps += 1
                 spent = time.perf_counter() - t0
             return reps * len(sample) / spent, reps
@@ -661,6 +670,7 @@ def main():
                                f"{s.n_labels} Zipf({s.zipf_alpha}) labels, T={s.T}, R={s.graph_degree}, "
                                f"{s.nq} queries ({s.query_mode}), k={k}, seed {s.seed}",
                    "graphs": "pruned (degree-2R kNN, rank-based pruning, reverse edges)" if pruned else "exact kNN",
+                   "and_scan_limit": args.and_scan_limit,
                    "params": dict(zip(("itopk", "width", "iters", "n_seeds"), headline[0])),
                    "recall_at_10": round(recall_head, 4), "reached_0.90": p90 is not None,
                    "recall_by_stratum": strata,

@@ -159,6 +159,24 @@ int vf_search(vf_index *index, const void *queries, int64_t nq, const int64_t *q
               int64_t *out_ids, float *out_dists, void *hip_stream);
 
 /*
+ * vf_search with its parameters in a struct, and one more routing option (selectivity-aware routing of AND queries,
+ * the remedy for the recall ceiling of the greedy policy that Section 5.3 reports):
+ *   and_scan_limit   > 0: an AND query (two or more distinct labels) whose smallest list is a graph list of at most
+ *                    this many vectors is answered exactly -- every member of that list is tested with the predicate
+ *                    (Section 4.3.2) and the members that pass are scored: the filtered scan of Section 4.3.2's LS
+ *                    case applied to a short HS list -- instead of by the greedy graph search.  0: vf_search's routing.
+ * Everything else as in vf_search (reserved must be zero).
+ */
+typedef struct vf_search_params {
+    int32_t k, itopk, width, iters, n_seeds;
+    int32_t and_scan_limit;
+    int32_t reserved[2];
+} vf_search_params;
+int vf_search_ex(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                 const int32_t *qlabel_ids, const vf_search_params *params, int64_t *out_ids, float *out_dists,
+                 void *hip_stream);
+
+/*
  * vf_search for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Arguments, results and error behaviour are those of vf_search, and so are the kernels; the
  * call creates nothing (no device or pinned memory, no stream, no event): its device-side temporaries (routing

@@ -22,7 +22,7 @@ _ARR_DTYPE = dict(S=np.int64, O_HS=np.int64, O_LS=np.int64, M_HS=np.int32, M_LS=
 EXPORTED_SYMBOLS = ("vf_build_index", "vf_search", "vf_search_exact", "vf_index_export", "vf_index_stats",
                     "vf_index_free", "vf_last_error", "vf_profile_enable", "vf_profile_read", "vf_search_multi",
                     "vf_build_index_opt", "vf_tune", "vf_debug_route", "vf_search_noalloc", "vf_serve_begin", "vf_serve_submit",
-                    "vf_serve_poll", "vf_serve_end", "vf_serve_run")
+                    "vf_serve_poll", "vf_serve_end", "vf_serve_run", "vf_search_ex")
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
 FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
@@ -48,6 +48,11 @@ class VfProfile(C.Structure):
                                          "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds",
                                          "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "beam_gathered",
                                          "scan_kernel", "seed_selected", "seed_run_keys")]
+
+
+class VfSearchParams(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("k", "itopk", "width", "iters", "n_seeds", "and_scan_limit")] + \
+               [("reserved", C.c_int32 * 2)]
 
 
 class VfServeParams(C.Structure):
@@ -94,6 +99,8 @@ def load_library():
         L.vf_serve_end.argtypes = [p, C.POINTER(i64), C.POINTER(i32)]
         L.vf_serve_run.restype = C.c_int
         L.vf_serve_run.argtypes = [p, p, i64, p, p, i32, p, p, p]
+        L.vf_search_ex.restype = C.c_int
+        L.vf_search_ex.argtypes = [p, p, i64, p, p, C.POINTER(VfSearchParams), p, p, p]
         L.vf_search_exact.restype = C.c_int
         L.vf_search_exact.argtypes = [p, p, i64, p, p, i32, p, p, p]
         L.vf_index_export.restype = C.c_int
@@ -315,8 +322,9 @@ def _prep_queries(index, queries, qlabel_offsets, qlabel_ids):
 
 
 def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width=1, iters=32, n_seeds=0,
-           out_ids=None, out_dists=None, stream=None):
-    """Asynchronous on the (current) stream; returns (ids int64 [nq,k], dists float32 [nq,k]) CUDA tensors."""
+           out_ids=None, out_dists=None, stream=None, and_scan_limit=0):
+    """Asynchronous on the (current) stream; returns (ids int64 [nq,k], dists float32 [nq,k]) CUDA tensors.
+    and_scan_limit > 0: vf_search_ex with selectivity-aware routing of AND queries."""
     import torch
     off, ids = _prep_queries(index, queries, qlabel_offsets, qlabel_ids)
     nq = queries.shape[0]
@@ -325,6 +333,12 @@ def search(index: Index, queries, qlabel_offsets, qlabel_ids, k, itopk=64, width
     if out_dists is None:
         out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
     index._enter(stream)
+    if and_scan_limit:
+        prm = VfSearchParams(int(k), int(itopk), int(width), int(iters), int(n_seeds), int(and_scan_limit))
+        _check(load_library().vf_search_ex(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids),
+                                           C.byref(prm), C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),
+                                           _stream_handle(stream)))
+        return out_ids, out_dists
     _check(load_library().vf_search(index._h, C.c_void_p(queries.data_ptr()), nq, _np_ptr(off), _np_ptr(ids), int(k),
                                     int(itopk), int(width), int(iters), int(n_seeds),
                                     C.c_void_p(out_ids.data_ptr()), C.c_void_p(out_dists.data_ptr()),

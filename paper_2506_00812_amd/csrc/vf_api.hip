@@ -36,6 +36,19 @@ extern "C" int vf_search(vf_index *index, const void *queries, int64_t nq, const
     });
 }
 
+extern "C" int vf_search_ex(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
+                            const int32_t *qlabel_ids, const vf_search_params *params, int64_t *out_ids, float *out_dists,
+                            void *hip_stream)
+{
+    return guarded([&]() -> int {
+        VF_REQUIRE(params != nullptr, "params is NULL");
+        VF_REQUIRE(params->reserved[0] == 0 && params->reserved[1] == 0, "params: reserved fields must be zero");
+        return search_impl(index, queries, nq, qlabel_offsets, qlabel_ids, params->k, params->itopk, params->width,
+                           params->iters, params->n_seeds, false, out_ids, out_dists, (hipStream_t)hip_stream, false,
+                           params->and_scan_limit);
+    });
+}
+
 extern "C" int vf_search_exact(vf_index *index, const void *queries, int64_t nq, const int64_t *qlabel_offsets,
                                const int32_t *qlabel_ids, int32_t k, int64_t *out_ids, float *out_dists, void *hip_stream)
 {

@@ -468,6 +468,84 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             }
             offer(pass, bits, c);
         }
+    } else if (p.sblk != nullptr) {
+        // The wave scores its seeds itself from the interleaved copy (a wave that serves one query at a time has
+        // no tile of queries to share a dense kernel with): one seed per lane, 64 seeds a step, every load a
+        // coalesced 16-byte chunk, the query a broadcast from LDS.  A lane walks its seed's chunks in the order
+        // of the 8-lane teams (partial sum t takes chunks t, t + 8, ...; fused multiply-add; the fixed tree), so
+        // the bits are those of a gathered evaluation.
+        const int64_t g0 = p.sgoff[p.meta.hs_slot[label]];
+        int qq_all = 0;
+        if (DT == 0) {
+            for (int ci = 0; ci < nchunks; ++ci) {
+                const uint4 q = qv[ci];
+                qq_all = (int)__builtin_amdgcn_udot4(q.x, q.x, (uint32_t)qq_all, false);
+                qq_all = (int)__builtin_amdgcn_udot4(q.y, q.y, (uint32_t)qq_all, false);
+                qq_all = (int)__builtin_amdgcn_udot4(q.z, q.z, (uint32_t)qq_all, false);
+                qq_all = (int)__builtin_amdgcn_udot4(q.w, q.w, (uint32_t)qq_all, false);
+            }
+        }
+        for (int j0 = 0; j0 < ns; j0 += 64) {
+            const int j = j0 + lane;
+            const bool valid = j < ns;
+            const int je = valid ? j : ns - 1;   // lanes past the end re-read the last seed (in bounds), masked below
+            const uint4 *col = p.sblk + (g0 + (je >> 5)) * (int64_t)(p.sblk_chunks * 32) + (je & 31);
+            uint32_t bits;
+            if (DT == 0) {
+                uint32_t xx = 0, qx = 0;
+                for (int c0 = 0; c0 < nchunks; c0 += 8) {
+                    uint4 x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (c0 + u < nchunks) {
+                            const uint4 q = qv[c0 + u];
+                            xx = __builtin_amdgcn_udot4(x[u].x, x[u].x, xx, false); qx = __builtin_amdgcn_udot4(q.x, x[u].x, qx, false);
+                            xx = __builtin_amdgcn_udot4(x[u].y, x[u].y, xx, false); qx = __builtin_amdgcn_udot4(q.y, x[u].y, qx, false);
+                            xx = __builtin_amdgcn_udot4(x[u].z, x[u].z, xx, false); qx = __builtin_amdgcn_udot4(q.z, x[u].z, qx, false);
+                            xx = __builtin_amdgcn_udot4(x[u].w, x[u].w, xx, false); qx = __builtin_amdgcn_udot4(q.w, x[u].w, qx, false);
+                        }
+                    }
+                }
+                bits = (uint32_t)(qq_all + (int)xx - 2 * (int)qx);
+            } else {
+                float a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a[u] = 0.0f;
+                for (int c0 = 0; c0 < nchunks; c0 += 8) {   // chunk c0 + u belongs to partial sum u
+                    uint4 x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (c0 + u < nchunks) {
+                            const uint4 q = qv[c0 + u];
+                            float d;
+                            d = __uint_as_float(q.x) - __uint_as_float(x[u].x); a[u] = __builtin_fmaf(d, d, a[u]);
+                            d = __uint_as_float(q.y) - __uint_as_float(x[u].y); a[u] = __builtin_fmaf(d, d, a[u]);
+                            d = __uint_as_float(q.z) - __uint_as_float(x[u].z); a[u] = __builtin_fmaf(d, d, a[u]);
+                            d = __uint_as_float(q.w) - __uint_as_float(x[u].w); a[u] = __builtin_fmaf(d, d, a[u]);
+                        }
+                    }
+                }
+                const float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];
+                const float c0s = b0 + b1, c1s = b2 + b3;
+                bits = __float_as_uint(c0s + c1s);
+            }
+            const int c = valid ? seed_local_id((uint32_t)j, (uint32_t)n, (uint32_t)ns) : 0;
+            bool pass = valid;
+            if (o_cnt > 0) {
+                n_tested += __popcll(__ballot(valid));
+                if (valid) {
+                    const int g = p.meta.M_HS[base + c];
+                    for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, bq.others[o], g);
+                }
+            }
+            n_scored += __popcll(__ballot(pass));
+            if constexpr (E == 1) offer_seeds_to(top, pass, bits, c);
+            else offer(pass, bits, c);
+        }
     } else {
         for (int j0 = 0; j0 < ns; j0 += 64) {
             const int j = j0 + lane;

@@ -124,6 +124,7 @@ struct Routed {
     std::vector<int32_t> gq_query, gq_label;          // graph queries, grouped by label (ascending), stable in query order
     std::vector<int32_t> others_off, others;          // [nq+1], AND partner labels per query
     std::vector<uint64_t> scan_pairs;                 // (label << 32 | query) of scan queries, ascending
+    std::vector<int32_t> xq_query, xq_label;          // AND queries on short graph lists that are answered exactly
     bool any_and = false;
     // scratch kept between calls
     std::vector<int32_t> q_best;                      // searched label of each query, -1: empty result
@@ -297,7 +298,7 @@ template <class T> int upload(DevBuf &b, const std::vector<T> &v, hipStream_t s)
 
 // vf_search.hip: the pieces of one search call
 struct BlobLayout {
-    size_t off_gq_query, off_gq_label, off_others_off, off_others, off_qrow, off_items, off_merges, off_tiles, off_empty, total;
+    size_t off_gq_query, off_gq_label, off_xq_query, off_xq_label, off_others_off, off_others, off_qrow, off_items, off_merges, off_tiles, off_empty, total;
 };
 
 // Everything the host decides about a call before anything is launched.
@@ -314,6 +315,7 @@ struct CallPlan {
     int32_t max_hs_list = 0;
     std::vector<SeedTile> tiles;          // dense seed scoring: tiles of <= 64 (32) graph queries of one label
     size_t n_gq = 0;
+    size_t n_xq = 0;                      // AND queries answered by the exact predicate scan of a short graph list
     bool dense_seeds = false, seeds_mfma = false;
     // seeds_mfma with the selection fused into the seed kernel: runs of sel_K keys per (query, segment)
     bool seed_select = false, sel_bf16 = false;
@@ -339,11 +341,12 @@ int check_search_params(const vf_index *ix, bool exact, int32_t k, int32_t &itop
                         int32_t &n_seeds);
 int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, const int32_t *qids, bool exact,
               bool first_is_searched, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
-              uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P);
+              int32_t and_scan_limit, uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P);
 // May this call's seeds be scored on the matrix cores (so that an interleaved seed copy is worth having)?
 bool wants_seed_copy(const vf_index *ix, bool exact, int32_t itopk, int32_t n_seeds);
 // The resident copy for n_seeds, or (build = true) a new one; *out stays null when there is none.
 int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, bool build, SeedCopy **out);
+int build_seed_copy(vf_index *ix, int32_t n_seeds, hipStream_t s, bool want_bf16, SeedCopy *c);
 void fill_blob(const CallPlan &P, const Routed &r, char *hp);
 int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem &M, const SeedCopy *sc, const void *queries,
                 int64_t *out_ids, float *out_dists, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
@@ -358,7 +361,7 @@ void free_index(vf_index *ix);
 // vf_search.hip
 int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
                 int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, bool exact, int64_t *out_ids,
-                float *out_dists, hipStream_t s, bool first_is_searched = false);
+                float *out_dists, hipStream_t s, bool first_is_searched = false, int32_t and_scan_limit = 0);
 int search_multi_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids,
                       int32_t mode, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
                       int64_t *out_ids, float *out_dists, hipStream_t s);

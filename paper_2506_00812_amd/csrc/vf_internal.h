@@ -121,6 +121,11 @@ struct BeamParams {
     const uint64_t *seed_runs;
     int32_t run_K, run_segs, seg_seeds;
     const int32_t *seed_pass;  // optional (profiling, AND batches): seeds of the query that pass its predicate
+    // optional: an interleaved copy of the seeds (uint8 or float32, never bfloat16) from which a wave scores its
+    // seeds itself when no dense seed kernel ran (the serving kernel); sgoff: first group of each graph list
+    const uint4 *sblk;
+    const int64_t *sgoff;
+    int32_t sblk_chunks;       // 16-byte chunks per vector in that copy (the even count of the interleaved layout)
 };
 
 // ---------------------------------------------------------------- dense seed distances

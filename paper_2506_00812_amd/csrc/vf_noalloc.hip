@@ -68,7 +68,7 @@ int search_noalloc_impl(vf_index *ix, const void *queries, int64_t nq, const int
     for (int attempt = 0; attempt < 2; ++attempt) {
         P = CallPlan(ix->tune);
         const uint64_t budget_words = attempt == 0 ? kScratchBytes / 4 : 0;
-        if ((rc = plan_call(ix, r, nq, qoff, qids, false, false, k, itopk, width, iters, n_seeds, budget_words, sc, P)) != VF_OK)
+        if ((rc = plan_call(ix, r, nq, qoff, qids, false, false, k, itopk, width, iters, n_seeds, 0, budget_words, sc, P)) != VF_OK)
             return rc;
         off_idx = up(P.L.total);
         off_bits = up(off_idx + P.part_words * 4);

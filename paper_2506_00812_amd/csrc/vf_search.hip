@@ -136,11 +136,18 @@ int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, bool build, Seed
         VF_HIP(hipDeviceSynchronize());
         for (DevBuf *b : c->bufs()) b->release();
     }
+    c->last_use = ++ix->seed_tick;
+    *out = c;
+    return build_seed_copy(ix, n_seeds, s, ix->dtype == VF_F32 && ix->tune.seed_bf16 && !ix->seed_bf16_off, c);
+}
+
+// Fills *c for n_seeds on stream s (complete when the call returns).  want_bf16: float32 data also get the
+// bfloat16 form (and lose the float32 one when it is larger than 128 MiB).
+int build_seed_copy(vf_index *ix, int32_t n_seeds, hipStream_t s, bool want_bf16, SeedCopy *c)
+{
     c->n_seeds = n_seeds;
     c->ok = c->has_f32 = c->has_bf16 = false;
     c->bf16_delta = 0.f;
-    c->last_use = ++ix->seed_tick;
-    *out = c;
     if (!ix->tune.seed_cache) return VF_OK;
     const size_t n_gl = ix->graph_labels.size();
     std::vector<int64_t> goff(n_gl), slot_base(n_gl);
@@ -186,7 +193,7 @@ int seed_copy_for(vf_index *ix, int32_t n_seeds, hipStream_t s, bool build, Seed
     VF_HIP(hipGetLastError());
     VF_HIP(hipStreamSynchronize(s));   // the tables above are pageable host memory and temporaries
     c->has_f32 = true;
-    if (ix->dtype == VF_F32 && ix->tune.seed_bf16 && !ix->seed_bf16_off) {
+    if (want_bf16) {
         // float32 data: a second copy in bfloat16; the largest rounding error of a seed goes into the
         // beam kernel's proof (zero for integer-valued data up to 256, SIFT's kind)
         if ((rc = c->blk16.reserve((size_t)n_groups * ix->group_bytes() / 2)) != VF_OK) return rc;
@@ -240,7 +247,7 @@ int check_search_params(const vf_index *ix, bool exact, int32_t k, int32_t &itop
 // beam kernel gathers the seeds itself).
 int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, const int32_t *qids, bool exact,
                      bool first_is_searched, int32_t k, int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds,
-                     uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P)
+                     int32_t and_scan_limit, uint64_t dseed_budget_words, const SeedCopy *sc, CallPlan &P)
 {
     int rc;
     P.nq = nq; P.k = k; P.itopk = itopk; P.width = width; P.iters = iters; P.n_seeds = n_seeds; P.exact = exact;
@@ -289,6 +296,21 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
     VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
     P.part_words = (size_t)ib.part_rows * k;
 
+    // selectivity-aware routing: AND queries whose (smallest) graph list is short leave the graph path
+    r.xq_query.clear(); r.xq_label.clear();
+    if (!exact && and_scan_limit > 0 && r.any_and) {
+        size_t w = 0;
+        for (size_t i = 0; i < r.gq_query.size(); ++i) {
+            const int32_t q = r.gq_query[i], l = r.gq_label[i];
+            if (r.others_off[(size_t)q + 1] > r.others_off[(size_t)q] && ix->S[(size_t)l] <= and_scan_limit) {
+                r.xq_query.push_back(q); r.xq_label.push_back(l);
+            } else {
+                r.gq_query[w] = q; r.gq_label[w] = l; ++w;
+            }
+        }
+        r.gq_query.resize(w); r.gq_label.resize(w);
+    }
+    P.n_xq = r.xq_query.size();
     P.n_gq = r.gq_query.size();
     P.ns_stride = (n_seeds + 31) & ~31;
     // Seeds on the matrix cores.  uint8: they give the exact integer distances, nothing else changes.
@@ -351,6 +373,8 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
     size_t o = 0;
     L.off_gq_query = o; o = align_up(o + P.n_gq * 4);
     L.off_gq_label = o; o = align_up(o + P.n_gq * 4);
+    L.off_xq_query = o; o = align_up(o + P.n_xq * 4);
+    L.off_xq_label = o; o = align_up(o + P.n_xq * 4);
     L.off_others_off = o; o = align_up(o + r.others_off.size() * 4);
     L.off_others = o; o = align_up(o + std::max<size_t>(r.others.size(), 1) * 4);
     L.off_qrow = o; o = align_up(o + std::max<size_t>(ib.qrow.size(), 1) * 4);
@@ -370,6 +394,10 @@ void fill_blob(const CallPlan &P, const Routed &r, char *hp)
     if (P.n_gq) {
         memcpy(hp + L.off_gq_query, r.gq_query.data(), P.n_gq * 4);
         memcpy(hp + L.off_gq_label, r.gq_label.data(), P.n_gq * 4);
+    }
+    if (P.n_xq) {
+        memcpy(hp + L.off_xq_query, r.xq_query.data(), P.n_xq * 4);
+        memcpy(hp + L.off_xq_label, r.xq_label.data(), P.n_xq * 4);
     }
     memcpy(hp + L.off_others_off, r.others_off.data(), r.others_off.size() * 4);
     if (!r.others.empty()) memcpy(hp + L.off_others, r.others.data(), r.others.size() * 4);
@@ -408,6 +436,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         // pass: the rows of the other queries are never read)
         if ((rc = ix->counters.reserve((size_t)P.nq * 24)) != VF_OK) return rc;
         ix->prof_graph_queries = r.gq_query;
+        ix->prof_graph_queries.insert(ix->prof_graph_queries.end(), r.xq_query.begin(), r.xq_query.end());
         vf_profile &pf = ix->prof;
         pf = vf_profile{};
         pf.nq = P.nq; pf.n_graph_queries = (int64_t)r.gq_query.size(); pf.n_scan_queries = (int64_t)ib.qrow.size();
@@ -426,7 +455,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
     const int32_t *d_others = (const int32_t *)(dp + L.off_others);
 
     BeamParams bp{};
-    if (n_gq) {
+    if (n_gq || P.n_xq) {
         bp.X = ix->X; bp.Q = queries; bp.G = ix->d_G.as<int32_t>(); bp.Gg = ix->d_Gg.as<int32_t>();
         bp.gq_query = (const int32_t *)(dp + L.off_gq_query);
         bp.gq_label = (const int32_t *)(dp + L.off_gq_label);
@@ -593,6 +622,17 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
     if ((rc = run_scan()) != VF_OK) return rc;
     if ((rc = run_seeds()) != VF_OK) return rc;
     if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
+    if (P.n_xq) {
+        // the exact route of short AND queries: the beam kernel with every member of the list as a seed, no
+        // iteration and a list of k entries -- each member is tested with the predicate, the members that pass
+        // are gathered and scored, the k best stay
+        BeamParams bx = bp;
+        bx.gq_query = (const int32_t *)(dp + L.off_xq_query);
+        bx.gq_label = (const int32_t *)(dp + L.off_xq_label);
+        bx.n_seeds = 0x7FFFFFFF; bx.iters = 0; bx.itopk = k; bx.LP = 128; bx.hash_bits = 9;
+        bx.dseed = nullptr; bx.seed_runs = nullptr; bx.seed_pass = nullptr; bx.seed_approx = 0; bx.fallback_count = nullptr;
+        launch_beam(ix->dtype, bx, (int)P.n_xq, s);
+    }
     if (bp.fallback_count != nullptr) {
         ix->fb_window_q += (int64_t)n_gq;
         if (!ix->fb_pending && ix->fb_window_q >= tune.seed_fb_window) {
@@ -617,7 +657,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
 // predicate) instead of its smallest list -- the sub-searches of vf_search_multi.
 int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qoff, const int32_t *qids, int32_t k,
                 int32_t itopk, int32_t width, int32_t iters, int32_t n_seeds, bool exact, int64_t *out_ids,
-                float *out_dists, hipStream_t s, bool first_is_searched)
+                float *out_dists, hipStream_t s, bool first_is_searched, int32_t and_scan_limit)
 {
     int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
     if (rc != VF_OK) return rc;
@@ -653,8 +693,9 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     }
     CallPlan P(tune);
     Routed &r = W->routed;
-    if ((rc = plan_call(ix, r, nq, qoff, qids, exact, first_is_searched, k, itopk, width, iters, n_seeds, dseed_budget, sc,
-                        P)) != VF_OK)
+    VF_REQUIRE(and_scan_limit >= 0, "and_scan_limit must be >= 0");
+    if ((rc = plan_call(ix, r, nq, qoff, qids, exact, first_is_searched, k, itopk, width, iters, n_seeds, and_scan_limit,
+                        dseed_budget, sc, P)) != VF_OK)
         return rc;
     const BlobLayout &L = P.L;
     Staging *st = nullptr;

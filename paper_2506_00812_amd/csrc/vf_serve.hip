@@ -238,6 +238,7 @@ struct vf_server {
     ServeResult *h_results = nullptr;     // pinned
     ServeHostCtrl *h_ctrl = nullptr;      // pinned
     DevBuf d_ring, d_ctrl, d_GO_LS;
+    SeedCopy seeds;                       // the session's own interleaved copy of the seeds (workers score from it)
     int32_t ring_slots = 0, slot_stride = 0, row_bytes = 0, k = 0;
     int64_t max_jobs = 0;
     uint64_t next_job = 0;
@@ -250,6 +251,7 @@ static void free_server(vf_server *sv)
     if (!sv) return;
     if (sv->stream) { (void)hipStreamSynchronize(sv->stream); (void)hipStreamDestroy(sv->stream); }
     sv->d_ring.release(); sv->d_ctrl.release(); sv->d_GO_LS.release();
+    for (DevBuf *b : sv->seeds.bufs()) b->release();
     if (sv->h_ring) (void)hipHostFree(sv->h_ring);
     if (sv->h_results) (void)hipHostFree(sv->h_results);
     if (sv->h_ctrl) (void)hipHostFree(sv->h_ctrl);
@@ -287,6 +289,7 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     sv->row_bytes = (int32_t)((size_t)ix->dim * ix->elem());
     sv->slot_stride = kServeHdr + ((sv->row_bytes + 63) & ~63);
     sv->d_ring.al = sv->d_ctrl.al = sv->d_GO_LS.al = &ix->alloc;
+    for (DevBuf *b : sv->seeds.bufs()) b->al = &ix->alloc;
     const size_t ring_bytes = (size_t)ring_slots * sv->slot_stride;
     const unsigned flags = hipHostMallocMapped | hipHostMallocCoherent;
     VF_HIP(hipHostMalloc((void **)&sv->h_ring, ring_bytes, flags));
@@ -301,6 +304,10 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     if ((rc = upload(sv->d_GO_LS, ix->GO_LS, sv->stream)) != VF_OK) return rc;
     VF_HIP(hipMemsetAsync(sv->d_ctrl.p, 0, sizeof(ServeDevCtrl), sv->stream));
     VF_HIP(hipStreamSynchronize(sv->stream));
+    // the seeds of every graph list, interleaved, in the data's own type (exact distances): a worker streams its
+    // query's seeds from it, one seed per lane.  The session owns the copy (the index's copies may be dropped
+    // while the kernel runs).  When it does not fit, workers gather the seeds' rows from the vector table.
+    if (!ix->graph_labels.empty() && (rc = build_seed_copy(ix, n_seeds, sv->stream, false, &sv->seeds)) != VF_OK) return rc;
 
     ServeParams p{};
     // beam search: geometry as vf_search computes it
@@ -311,6 +318,9 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     p.bp.X = ix->X; p.bp.G = ix->d_G.as<int32_t>(); p.bp.Gg = ix->d_Gg.as<int32_t>(); p.bp.meta = ix->meta();
     p.bp.dim = ix->dim; p.bp.R = ix->R; p.bp.k = k; p.bp.itopk = itopk; p.bp.width = width; p.bp.iters = iters;
     p.bp.n_seeds = n_seeds; p.bp.LP = LP; p.bp.hash_bits = hb;
+    if (sv->seeds.ok && sv->seeds.has_f32) {
+        p.bp.sblk = sv->seeds.blk.as<uint4>(); p.bp.sgoff = sv->seeds.goff.as<int64_t>(); p.bp.sblk_chunks = 2 * ix->ncp;
+    }
     const size_t beam_lds = beam_lds_bytes(p.bp, ix->dtype);
     // scan: one query against a whole list
     p.sp.xblk = ix->d_X_LS.as<uint4>(); p.sp.xnorm = ix->d_xnorm_LS.p; p.sp.map = ix->d_M_LS.as<int32_t>();

@@ -593,3 +593,43 @@ def test_calls_on_several_streams_overlap_safely(vf):
     for ids, d in got:
         assert np.array_equal(ids.cpu().numpy(), ref[0].cpu().numpy())
         assert np.array_equal(d.cpu().numpy().view(np.uint32), ref[1].cpu().numpy().view(np.uint32))
+
+
+@pytest.mark.parametrize("name", ["uint8", "float32"])
+def test_selectivity_aware_and_routing(vf, name):
+    """vf_search_ex with and_scan_limit: AND queries whose smallest list is a graph list of at most that many vectors
+    are answered by the exact predicate scan of that list (oracle method 3: bit-exact on uint8, scan tolerance on
+    float32); every other query of the batch is answered as by vf_search."""
+    import torch
+    if name == "uint8":
+        w = make_workload("tiny")
+        limit = 1000
+    else:
+        w = _float_small()
+        limit = 3000
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    Q = torch.from_numpy(w.queries).cuda()
+    nq = 600
+    qoff, qids = _and_queries(nq, s.n_labels, 29, hi_a=9, hi_b=12) if name == "uint8" else \
+        _and_queries(nq, s.n_labels, 29, hi_a=12, hi_b=40)
+    qids[qoff[:-1][::4] + 1] = qids[qoff[:-1][::4]]              # every fourth query: the same label twice = single label
+    params = dict(itopk=32, width=1, iters=8, n_seeds=128)
+    ig, dg = _search(vf, ix, Q[:nq], qoff, qids, 10, and_scan_limit=limit, **params)
+    io, do, info = ixo.search(w.queries[:nq], qoff, qids, 10, with_info=True, and_scan_limit=limit, **params)
+    m = info["method"]
+    assert (m == 3).sum() > 40 and (m == 2).sum() > 40 and (m == 1).sum() > 20
+    g = m == 2
+    assert_exact(ig[g], dg[g], io[g], do[g], f"{name}: graph-searched queries beside the exact route")
+    x = m == 3
+    if s.dtype == "uint8":
+        assert_exact(ig[x], dg[x], io[x], do[x], "uint8: exact route")
+        assert_exact(ig[m == 1], dg[m == 1], io[m == 1], do[m == 1], "uint8: scan lists")
+    else:
+        assert_close_with_ties(ig[x], dg[x], io[x], do[x], RTOL, "float32: exact route")
+        assert_close_with_ties(ig[m == 1], dg[m == 1], io[m == 1], do[m == 1], RTOL, "float32: scan lists")
+    # limit 0 is vf_search
+    i0, d0 = _search(vf, ix, Q[:nq], qoff, qids, 10, **params)
+    i1, d1 = _search(vf, ix, Q[:nq], qoff, qids, 10, and_scan_limit=0, **params)
+    assert np.array_equal(i0, i1) and np.array_equal(d0.view(np.uint32), d1.view(np.uint32))
