@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
+SCAN_KERNELS = ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel", "scan_bf16_kernel")   # vf_profile.scan_kernel
 
 # (itopk, width, iters, n_seeds) settings tried, cheapest first within each group.  Recall on this
 # workload is governed by the number of seeds (per-list graphs over separated clusters are
@@ -134,6 +135,8 @@ def main():
     ap.add_argument("--and-scan-limit", type=int, default=0,
                     help="selectivity-aware routing (vf_search_ex): AND queries whose smallest list is a graph list of at "
                          "most this many vectors are answered by the exact predicate scan of that list; 0 = the paper's routing")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="set an experiment switch of the library (vf_tune) before the index is built; repeatable")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (scale reference for HBM byte counters)")
     args = ap.parse_args()
@@ -162,6 +165,10 @@ def main():
         f"nq={s.nq} generated in {time.time() - t0:.1f}s")
     X = torch.from_numpy(w.vectors).cuda()
     Q = torch.from_numpy(w.queries).cuda()
+    for kv in args.tune:
+        name, _, value = kv.partition("=")
+        vf.tune_defaults(name.strip(), float(value))
+        log(f"[bench] switch {name.strip()} = {float(value):g}")
     t0 = time.time()
     log("[bench] building the index ...")
     pruned = args.graph == "pruned"
@@ -355,7 +362,7 @@ def main():
         return "seed_select_kernel" if p["seed_selected"] else ("seed_mfma_kernel" if p["seeds_on_matrix_cores"] else "seed_dist_kernel")
     alone_ms = {"beam_kernel": pfs["beam_ms_sum"] / pfs["calls"],
                 seed_kernel_name(pfs): pfs["seed_ms_sum"] / pfs["calls"],
-                ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel")[pfs["scan_kernel"]]: pfs["scan_ms_sum"] / pfs["calls"]}
+                SCAN_KERNELS[pfs["scan_kernel"]]: pfs["scan_ms_sum"] / pfs["calls"]}
     ix.profile_enable(False)
 
     eb = 1 if s.dtype == "uint8" else 4
@@ -369,7 +376,10 @@ def main():
     # what passes from the seed kernel to the beam kernel: every distance (4 bytes a pair), or, when the seed kernel
     # selects, a few 8-byte keys per query and seed segment
     seed_handover = pf["seed_run_keys"] * 8 if pf["seed_selected"] else pf["seed_pairs"] * 4
-    scan_kernel = ("scan_topk_kernel", "scan_topk16_kernel", "scan_valu_kernel")[pf["scan_kernel"]]
+    scan_kernel = SCAN_KERNELS[pf["scan_kernel"]]
+    # the filtering kernel streams the bfloat16 copy of the lists (half the bytes per component) and leaves
+    # k + margin candidates per query and list segment for the re-ranking kernel
+    scan_vec_bytes = vec_bytes // 2 if pf["scan_kernel"] == 3 else vec_bytes
     kernels = {
         "beam_kernel": {
             "ms": beam_avg_ms, "bound": "hbm",
@@ -391,7 +401,7 @@ def main():
             "flops": ({0: 3, 1: 2, 2: 4}[int(pf["seeds_on_matrix_cores"])]) * pf["seed_pairs"] * s.dim},
         scan_kernel: {
             "ms": scan_avg_ms, "bound": "hbm",
-            "bytes": pf["scan_list_entries"] * (vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),
+            "bytes": pf["scan_list_entries"] * (scan_vec_bytes + 4) + pf["n_scan_queries"] * (vec_bytes + k * 12),
             "flops": 2 * pf["scan_pairs"] * s.dim},
     }
     # the dominant kernel: the one with the longest average launch duration in the timed region
@@ -428,6 +438,7 @@ def main():
             + pf["beam_tested"] * 4 + n_gq * (vec_bytes + k * 12)),
         "dense_contraction": dense,
         "graph_queries_per_launch": int(n_gq), "scan_queries_per_launch": int(pf["n_scan_queries"]),
+        "scan_queries_rescanned_exactly": int(pf["scan_fallbacks"]),
         "distances_per_graph_query": round(pf["beam_scored"] / max(n_gq, 1), 1),
         "all_kernels": {n: {"avg_launch_ms": round(v["ms"], 4), "avg_launch_ms_alone": round(alone_ms[n], 4), "bound": v["bound"],
                             "algorithmic_bytes_per_launch": int(v["bytes"]), "flops_per_launch": int(v["flops"]),

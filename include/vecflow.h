@@ -309,12 +309,16 @@ int vf_index_export(const vf_index *index, int which, void *host_dst, size_t *by
  *   bytes_bitsets  membership bitsets of the graph labels (the AND predicate of Section 4.3.2 as this library
  *                  stores it): n_graph_labels ceil(N / 32) 4
  *   bytes_meta     per-label sizes and offsets ("label metadata" of Section 4.2.4): 24 bytes per label
- *   bytes_total    the sum of the five
+ *   bytes_x_ls_bf16  float32 data: the vectors of the LS partition once more, rounded to bfloat16 in the same
+ *                  interleaved layout (half of bytes_x_ls without its norms); the scan of large batches streams
+ *                  this copy and re-ranks what it keeps.  0 for uint8 data.  Not in the paper's model
+ *   bytes_total    the sum of the six
  */
 typedef struct vf_stats {
     int64_t n, n_HS, n_LS, n_groups_LS;
     int32_t dim, dtype, n_labels, T, graph_degree, n_graph_labels, n_scan_labels, chunks_per_vector;
     int64_t bytes_graph, bytes_maps, bytes_x_ls, bytes_bitsets, bytes_meta, bytes_total;
+    int64_t bytes_x_ls_bf16;
 } vf_stats;
 
 int vf_index_stats(const vf_index *index, vf_stats *out);
@@ -325,7 +329,7 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * defaults change, which indexes built afterwards start from (the build-time switches "build16",
  * "build_panel_kb" and "build_progress" only act that way); with an index, that index's own copy changes, and
  * no call on it may be in flight.  Names: "seg_groups", "seg_groups_heavy", "heavy_rows", "tile_rows",
- * "zero_copy_bytes", "scan_valu", "scan16", "overlap", "seed_exact", "seed_slack", "seed_margin",
+ * "zero_copy_bytes", "scan_valu", "scan16", "scan_bf16", "scan_bf16_margin", "scan_bf16_slots", "scan_bf16_seg_groups", "overlap", "seed_exact", "seed_slack", "seed_margin",
  * "seed_margin_bf16", "seed_cache", "seed_bf16", "seed_bf16_min_batch", "seed_fb_window", "seed_select",
  * "seed_seg_seeds", "build16",
  * "build_panel_kb", "build_progress".  Returns VF_EINVAL for an unknown name or a value out of range.
@@ -369,9 +373,15 @@ typedef struct vf_profile {
     int64_t seed_rescored;             /* ordered distances computed for that re-ranking                                 */
     int64_t seed_fallbacks;            /* queries whose proof failed and that scored every seed themselves               */
     int64_t beam_gathered;             /* distances whose vector the beam kernel fetched itself (children, re-ranked seeds, seeds when not scored densely) */
-    int64_t scan_kernel;               /* IVF-BFS kernel of the call: 0 = 32-row matrix-core tiles, 1 = 16-row matrix-core tiles, 2 = FMA */
+    int64_t scan_kernel;               /* IVF-BFS kernel of the call: 0 = 32-row matrix-core tiles, 1 = 16-row matrix-core tiles, 2 = FMA,
+                                          3 = filter from the bfloat16 copy of the lists + exact re-ranking (float32 data)         */
     int64_t seed_selected;             /* 1: the seed kernel also selected (a few keys per query and seed segment instead of every distance) */
     int64_t seed_run_keys;             /* 8-byte keys that kernel left for the beam kernel (sum over graph queries of segments x keys per run) */
+    int64_t scan_fallbacks;            /* scan queries since profiling was enabled whose filtered result (scan_kernel 3) could not
+                                          be proven complete and that the exact kernels scanned again                         */
+    double host_plan_ms_sum, host_blob_ms_sum, host_launch_ms_sum; /* host time inside the calls since profiling was enabled:
+                                          routing and work lists; assembling the routing blob; everything else (HIP calls)   */
+    double host_wait_ms_sum;           /* ... and time the host waited for a staging buffer (two calls ahead of the device) */
 } vf_profile;
 
 int vf_profile_enable(vf_index *index, int on);

@@ -37,7 +37,7 @@ class VfStats(C.Structure):
                [(n, C.c_int32) for n in ("dim", "dtype", "n_labels", "T", "graph_degree", "n_graph_labels",
                                          "n_scan_labels", "chunks_per_vector")] + \
                [(n, C.c_int64) for n in ("bytes_graph", "bytes_maps", "bytes_x_ls", "bytes_bitsets", "bytes_meta",
-                                         "bytes_total")]
+                                         "bytes_total", "bytes_x_ls_bf16")]
 
 
 class VfProfile(C.Structure):
@@ -47,7 +47,8 @@ class VfProfile(C.Structure):
                                          "scan_list_entries", "scan_pairs", "beam_scored", "beam_expanded",
                                          "beam_tested", "n_seed_tiles", "seed_pairs", "seed_tile_seeds",
                                          "seeds_on_matrix_cores", "seed_rescored", "seed_fallbacks", "beam_gathered",
-                                         "scan_kernel", "seed_selected", "seed_run_keys")]
+                                         "scan_kernel", "seed_selected", "seed_run_keys", "scan_fallbacks")] + \
+               [(n, C.c_double) for n in ("host_plan_ms_sum", "host_blob_ms_sum", "host_launch_ms_sum", "host_wait_ms_sum")]
 
 
 class VfSearchParams(C.Structure):

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvecflow.so")
-SOURCES = ["vf_api.hip", "vf_index_build.hip", "vf_search.hip", "vf_route.hip", "vf_noalloc.hip", "vf_serve.hip", "vf_scan.hip", "vf_beam.hip", "vf_seed.hip", "vf_build.hip", "vf_graphopt.hip"]
+SOURCES = ["vf_api.hip", "vf_index_build.hip", "vf_search.hip", "vf_route.hip", "vf_noalloc.hip", "vf_serve.hip", "vf_scan.hip", "vf_scan_bf16.hip", "vf_beam.hip", "vf_seed.hip", "vf_build.hip", "vf_graphopt.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
          "-Wno-pass-failed"]

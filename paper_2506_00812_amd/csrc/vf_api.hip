@@ -140,7 +140,9 @@ static int stats_impl(const vf_index *ix, vf_stats *out)
     out->bytes_x_ls = ix->n_groups_LS * (int64_t)ix->group_bytes() + ix->n_groups_LS * 32 * 4;
     out->bytes_bitsets = (int64_t)ix->graph_labels.size() * ix->bitset_words * 4;
     out->bytes_meta = (int64_t)ix->n_labels * (4 + 8 + 8 + 4);
-    out->bytes_total = out->bytes_graph + out->bytes_maps + out->bytes_x_ls + out->bytes_bitsets + out->bytes_meta;
+    out->bytes_x_ls_bf16 = ix->has_ls16 ? ix->n_groups_LS * (int64_t)ix->group_bytes() / 2 : 0;
+    out->bytes_total = out->bytes_graph + out->bytes_maps + out->bytes_x_ls + out->bytes_bitsets + out->bytes_meta +
+                       out->bytes_x_ls_bf16;
     return VF_OK;
 }
 
@@ -162,7 +164,12 @@ static int profile_enable_impl(vf_index *ix, int on)
     ix->prof_valid = false;
     ix->prof_next = 0; ix->prof_unfolded = 0;
     ix->prof_scan_sum = ix->prof_seed_sum = ix->prof_beam_sum = 0;
+    ix->prof_host_plan = ix->prof_host_blob = ix->prof_host_launch = ix->prof_host_wait = 0;
     ix->prof_calls = 0;
+    if (on && ix->has_ls16) {   // failed scan proofs are counted from here on
+        VF_HIP(hipDeviceSynchronize());
+        VF_HIP(hipMemcpy(&ix->scan_fb_seen, ix->d_scan_fb.p, 4, hipMemcpyDeviceToHost));
+    }
     return VF_OK;
 }
 
@@ -176,6 +183,7 @@ static int profile_read_impl(vf_index *ix, vf_profile *out, int32_t *per_query)
     vf_profile pf = ix->prof;
     pf.scan_ms_sum = ix->prof_scan_sum; pf.seed_ms_sum = ix->prof_seed_sum; pf.beam_ms_sum = ix->prof_beam_sum;
     pf.calls = ix->prof_calls;
+    pf.host_plan_ms_sum = ix->prof_host_plan; pf.host_blob_ms_sum = ix->prof_host_blob; pf.host_launch_ms_sum = ix->prof_host_launch; pf.host_wait_ms_sum = ix->prof_host_wait;
     {
         std::vector<int32_t> cn((size_t)pf.nq * 4);
         VF_HIP(hipMemcpy(cn.data(), ix->counters.p, cn.size() * 4, hipMemcpyDeviceToHost));
@@ -190,6 +198,11 @@ static int profile_read_impl(vf_index *ix, vf_profile *out, int32_t *per_query)
             pf.beam_gathered += gathered[(size_t)j];
             if (per_query) memcpy(per_query + (size_t)j * 4, row, 16);
         }
+    }
+    if (ix->has_ls16) {
+        uint32_t now = 0;
+        VF_HIP(hipMemcpy(&now, ix->d_scan_fb.p, 4, hipMemcpyDeviceToHost));
+        pf.scan_fallbacks = (int64_t)(uint32_t)(now - ix->scan_fb_seen);
     }
     *out = pf;
     return VF_OK;

@@ -176,7 +176,7 @@ struct BeamQuery {
 
 // The search of one query by one wave (a one-wave workgroup: __syncthreads orders the wave's LDS traffic).
 // smem: beam_lds_bytes of LDS.
-template <int DT, int E>
+template <int DT, int E, bool STREAM_SEEDS = false>
 __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const BeamQuery &bq, uint4 *smem)
 {
     const int lane = threadIdx.x, team = lane >> 3, tl = lane & 7;
@@ -281,6 +281,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     // every seed, at a fraction of the insertions.  as_index: the list stores the seed index j
     // instead of the local id floor(j * n / ns).  Returns the number of seeds dealt with (a chunk
     // whose bound lets more than 128 seeds through ends the selection early).
+    bool lazy_used = false;
     auto select_seeds = [&](TopM<1> &list, const uint32_t *drow, bool as_index) -> int {
         constexpr int NBLK = VF_SEED_BLOCKS;
         int done_to = 0;
@@ -292,7 +293,14 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 v[i] = j < ns ? drow[j] : 0xFFFFFFFFu;
             }
             int chunk_scored = (ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK), chunk_tested = 0;
-            if (o_cnt > 0) {
+            // AND with a full list: the predicate is only evaluated for the few seeds at or below the list's worst
+            // entry (below); a predicate test is a 4-byte read from a bitset of n / 8 bytes, a cache line each
+            const bool lazy = o_cnt > 0 && list.worst != KEY_MAX;
+            if (lazy) {
+                chunk_tested = chunk_scored;   // counted as the definition counts them: every seed is tested
+                lazy_used = true;
+            }
+            if (o_cnt > 0 && !lazy) {
                 // AND: a seed that fails the predicate is taken out before the selection.  Its local id
                 // floor(j n / ns) advances by (64 n) / ns per step of 64 seeds: one division per lane and
                 // chunk, then quotient / remainder increments.
@@ -355,9 +363,16 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             n_tested += chunk_tested;
             for (int i0 = 0; i0 < cnt; i0 += 64) {
                 const int i = i0 + lane;
-                const bool valid = i < cnt;
+                bool valid = i < cnt;
                 int c = valid ? cand_c[i] : 0;
-                if (!as_index) c = (int)(((uint64_t)c * (uint64_t)n) / (uint64_t)ns);
+                if (lazy || !as_index) {
+                    const int cl = (int)(((uint64_t)c * (uint64_t)n) / (uint64_t)ns);
+                    if (lazy && valid) {
+                        const int g = p.meta.M_HS[base + cl];
+                        for (int o = 0; o < o_cnt && valid; ++o) valid = has_label(p.meta, bq.others[o], g);
+                    }
+                    if (!as_index) c = cl;
+                }
                 offer_seeds_to(list, valid, valid ? cand_d[i] : 0u, c);
             }
             done_to = jc + 64 * NBLK < ns ? jc + 64 * NBLK : ns;
@@ -367,6 +382,11 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
 
     bool seeds_done = false;
     int n_rescored = 0, seed_fallback = 0;   // profiling only
+    // After a seed phase that skipped predicate tests the number of seeds that pass (the definition's count of
+    // distances computed) is not known to the wave; while profiling a small kernel has counted them beforehand.
+    auto fix_seed_count = [&]() {
+        if (lazy_used && bq.seed_pass >= 0) n_scored = bq.seed_pass;
+    };
     // The runs the selection kernel left for this query: one per seed segment, sorted, keys
     // (value bits << 32 | seed index).  as_index as in select_seeds.
     auto merge_runs = [&](TopM<1> &list, bool as_index) {
@@ -400,6 +420,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             if (bq.runs != nullptr) merge_runs(tmp, true);
             else got = select_seeds(tmp, bq.dseed_row, true);
             if (got == ns) {
+                fix_seed_count();
                 const uint64_t key = tmp.cur[0];
                 const bool valid = key != KEY_MAX;
                 const int c = valid ? seed_local_id((uint32_t)(key >> 1) & 0x7FFFFFFFu, (uint32_t)n, (uint32_t)ns) : 0;
@@ -456,7 +477,10 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             int c = 0;
             if (o_cnt > 0) {
                 n_tested += __popcll(__ballot(valid));
-                if (valid) {
+                // (a seed above the list's worst entry cannot enter it: its predicate is not evaluated)
+                const bool full = top.worst != KEY_MAX;
+                if (full) { lazy_used = true; pass = valid && bits <= (uint32_t)(top.worst >> 32); }
+                if (pass) {
                     c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
                     const int g = p.meta.M_HS[base + c];
                     for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, bq.others[o], g);
@@ -468,7 +492,8 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             }
             offer(pass, bits, c);
         }
-    } else if (p.sblk != nullptr) {
+        fix_seed_count();
+    } else if (STREAM_SEEDS && p.sblk != nullptr) {
         // The wave scores its seeds itself from the interleaved copy (a wave that serves one query at a time has
         // no tile of queries to share a dense kernel with): one seed per lane, 64 seeds a step, every load a
         // coalesced 16-byte chunk, the query a broadcast from LDS.  A lane walks its seed's chunks in the order

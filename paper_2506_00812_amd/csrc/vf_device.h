@@ -26,6 +26,13 @@ __device__ __forceinline__ bool has_label(const LabelMeta &m, int32_t l, int32_t
     return false;
 }
 
+// float -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_rn_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 // ---------------------------------------------------------------- 8-lane teams
 
 // Sum over the 8 lanes of a team in the fixed tree ((a0+a1)+(a2+a3)) + ((a4+a5)+(a6+a7));

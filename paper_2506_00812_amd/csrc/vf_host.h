@@ -92,6 +92,10 @@ struct Tuning {
     int zero_copy_bytes = 8192;   // a per-call routing blob up to this size is read in place from pinned host memory
     int scan_valu = 1;            // float32 FMA scan kernel: 0 never, 1 for batches of <= 256 scan queries, 2 always
     int scan16 = 1;               // 0: float32 search tiles keep the 32-row matrix-core kernel
+    int scan_bf16 = 1;            // float32 lists of large batches: filter from the bfloat16 copy, re-rank exactly (0: off)
+    int scan_bf16_margin = 22;    // approximations kept beyond k per query and segment by that filter
+    int scan_bf16_slots = 1;      // list groups a wave of that filter keeps in flight (1 or 2)
+    int scan_bf16_seg_groups = 24;   // 32-vector groups per list segment when that filter runs (half the bytes per group)
     int overlap = 1;              // 0: the scan path runs on the caller's stream, before the graph path
     int seed_exact = 0;           // 1: seeds are scored by the ordered-distance kernel, never on the matrix cores
     double seed_slack = 1.0;      // scales the rounding-error bound of the float32 seed proofs
@@ -155,6 +159,7 @@ struct ItemBuilder {
     int64_t part_rows = 0;
     int32_t max_nseg = 1;
     int32_t tile_rows = 16, seg_groups = 16, seg_groups_heavy = 16, heavy_rows = 9;
+    bool all_partial = false;   // every item writes partial rows and every query gets a merge item (one-segment lists too)
     explicit ItemBuilder(const Tuning &t)
         : tile_rows(t.tile_rows), seg_groups(t.seg_groups), seg_groups_heavy(t.seg_groups_heavy), heavy_rows(t.heavy_rows) {}
     // pairs[lo, hi) all carry the same label, whose list is (group0, map_off, n)
@@ -173,9 +178,8 @@ struct Workspace {
     std::vector<int32_t> multi_qids;
     // the scan path runs beside the graph path on a second stream of the same (default) priority
     hipStream_t side = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_copy = nullptr;
-    hipEvent_t ev_blob_done[2] = {nullptr, nullptr};   // recorded on the caller's stream when a call that read blob b ends
-    bool blob_used[2] = {false, false};
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool prev_forked = false;   // the previous call on this workspace ran its scan path on the side stream
     int blob_next = 0;   // the device blob alternates between two buffers
     Staging stage[2];
     int stage_next = 0;
@@ -223,6 +227,12 @@ struct vf_index {
     int32_t n_scan_labels = 0;
     // device
     vf::DevBuf d_S, d_O_HS, d_O_LS, d_hs_slot, d_M_HS, d_M_LS, d_G, d_X_LS, d_xnorm_LS, d_bitsets;
+    // float32 data: the scan lists once more in bfloat16 (16-byte chunks of 8 components, half the bytes), which the
+    // filtering scan kernel streams; ls_bf16_delta = max |x - bf16(x)| over the lists' vectors (its error bound)
+    vf::DevBuf d_X_LS16, d_scan_fb;
+    bool has_ls16 = false;
+    float ls_bf16_delta = 0.f, ls_xn_max = 0.f;   // ... and the largest squared norm of a list vector
+    uint32_t scan_fb_seen = 0;   // failed proofs already reported (d_scan_fb counts them on the device)
     vf::DevBuf d_Gg;   // [n_HS][R] the graph rows once more with global ids: saves the search one dependent load per expansion
     // indexes with graph labels: squared norm of every row of X and the largest of them, for the matrix-core
     // seed scoring (its error bound needs the largest norm)
@@ -263,13 +273,14 @@ struct vf_index {
     vf_profile prof{};
     std::vector<int32_t> prof_graph_queries;   // graph-routed queries of the last profiled call
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;
+    double prof_host_plan = 0, prof_host_blob = 0, prof_host_launch = 0, prof_host_wait = 0;   // host milliseconds inside profiled calls
     int64_t prof_calls = 0;
 
     vf_index();
     std::vector<vf::DevBuf *> bufs()
     {
         return {&d_S, &d_O_HS, &d_O_LS, &d_hs_slot, &d_M_HS, &d_M_LS, &d_G, &d_Gg, &d_X_LS, &d_xnorm_LS, &d_bitsets,
-                &d_xnorm_all, &tmp_blk, &tmp_norm, &counters, &d_fb_count};
+                &d_xnorm_all, &tmp_blk, &tmp_norm, &counters, &d_fb_count, &d_X_LS16, &d_scan_fb};
     }
     vf::LabelMeta meta() const
     {
@@ -322,7 +333,10 @@ struct CallPlan {
     int32_t sel_K = 0, seg_seeds = 0, max_segs = 0;
     BlobLayout L{};
     size_t dseed_words = 0;               // seed distance matrix + the dump area behind it
-    size_t part_words = 0;                // partial result rows x k
+    size_t part_words = 0;                // partial result rows x k (x scan_keep with the bfloat16 filter)
+    // float32 scan lists filtered from their bfloat16 copy and re-ranked
+    bool scan_bf16 = false;
+    int32_t scan_keep = 0;                // approximations kept per (query, segment)
     explicit CallPlan(const Tuning &t) : ib(t) {}
 };
 

@@ -104,9 +104,6 @@ void free_index(vf_index *ix)
         for (DevBuf *b : w.bufs()) b->release();
         if (w.ev_fork) (void)hipEventDestroy(w.ev_fork);
         if (w.ev_join) (void)hipEventDestroy(w.ev_join);
-        if (w.ev_copy) (void)hipEventDestroy(w.ev_copy);
-        for (hipEvent_t e : w.ev_blob_done)
-            if (e) (void)hipEventDestroy(e);
         if (w.side) (void)hipStreamDestroy(w.side);
         for (Staging &s : w.stage) {
             if (s.done) (void)hipEventDestroy(s.done);
@@ -341,6 +338,41 @@ int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, con
                               ix->n_LS, ix->n_groups_LS, ix->ncp, ix->d_X_LS.as<uint4>(), ix->d_xnorm_LS.p, s);
             VF_HIP(hipGetLastError());
             VF_HIP(hipStreamSynchronize(s));
+            // float32 lists once more in bfloat16, for the filtering scan kernel.  Its proofs need the largest
+            // rounding error |x - bf16(x)| and the largest squared norm of a list vector; a table with NaN or
+            // overflowing values, or norms outside [1e-24, 1e30] (the bound is relative to the norm and assumes
+            // that what the matrix cores flush is negligible beside it), keeps the exact kernels only.
+            if (dtype == VF_F32 && ix->tune.scan_bf16 && scan_bf16_supported(dtype, dim, 16, 32)) {
+                const size_t n_slots = (size_t)ix->n_groups_LS * 32;
+                DevBuf d_err2(&ix->alloc);
+                DevBufGuard r4{&d_err2};
+                if ((rc = ix->d_X_LS16.reserve((size_t)ix->n_groups_LS * ix->group_bytes() / 2)) != VF_OK) return rc;
+                if ((rc = d_err2.reserve(n_slots * 4)) != VF_OK) return rc;
+                launch_seed_pack_bf16(ix->d_X_LS.as<uint4>(), ix->n_groups_LS, ix->ncp, ix->d_X_LS16.as<uint4>(),
+                                      d_err2.as<float>(), s);
+                std::vector<float> e2(n_slots), nr(n_slots);
+                VF_HIP(hipMemcpyAsync(e2.data(), d_err2.p, n_slots * 4, hipMemcpyDeviceToHost, s));
+                VF_HIP(hipMemcpyAsync(nr.data(), ix->d_xnorm_LS.p, n_slots * 4, hipMemcpyDeviceToHost, s));
+                VF_HIP(hipStreamSynchronize(s));
+                double mx_e = 0.0;
+                float mx_n = 0.f;
+                bool finite = true;
+                for (size_t i = 0; i < n_slots; ++i) {
+                    finite = finite && e2[i] == e2[i] && e2[i] <= 3.0e38f && nr[i] == nr[i] && nr[i] <= 3.0e38f;
+                    mx_e = e2[i] > mx_e ? e2[i] : mx_e;
+                    mx_n = nr[i] > mx_n ? nr[i] : mx_n;
+                }
+                if (finite && mx_n >= 1e-24f && mx_n <= 1e30f) {
+                    if ((rc = ix->d_scan_fb.reserve(4)) != VF_OK) return rc;
+                    VF_HIP(hipMemsetAsync(ix->d_scan_fb.p, 0, 4, s));
+                    VF_HIP(hipStreamSynchronize(s));
+                    ix->has_ls16 = true;
+                    ix->ls_bf16_delta = (float)(std::sqrt(mx_e) * 1.001);
+                    ix->ls_xn_max = mx_n;
+                } else {
+                    ix->d_X_LS16.release();
+                }
+            }
         }
 
         // ---- graph partition: membership bitsets and one exact kNN graph per list

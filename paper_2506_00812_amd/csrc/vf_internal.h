@@ -50,6 +50,8 @@ struct MergeItem {
     int32_t part_row;  // partial row of segment 0
     int32_t stride;    // partial rows between consecutive segments
     int32_t nseg;
+    int32_t n;         // entries of the list
+    int32_t pad;
 };
 
 struct ScanParams {
@@ -86,6 +88,32 @@ void launch_scan_valu(const ScanParams &p, int n_items, hipStream_t s);
 void launch_scan_merge(int dtype, const MergeItem *items, int n_items, const int32_t *res_idx, const uint32_t *res_bits,
                        int32_t K, int32_t max_keys, const int32_t *map, int64_t *out_ids, float *out_dists,
                        hipStream_t s);
+
+// float32 lists filtered from their bfloat16 copy (scan_bf16_kernel: xblk holds chunks of 8 bfloat16 components,
+// xnorm the norms of the unrounded vectors, K = candidates kept per query and segment, every item writes partial
+// rows), then re-ranked: per query the Kc best approximations of all its segments are re-scored with the ordered
+// float32 distance from the vector table; the k best of them are the result if the proof holds that no dropped
+// candidate can be among them, else the query's wave scans the whole list with the ordered distance.
+struct RerankParams {
+    const MergeItem *items;
+    const int32_t *res_idx;     // partial rows [*][Kc]
+    const uint32_t *res_bits;
+    const int32_t *map;         // local -> global id of the scan partition
+    const void *X;              // vector table, row-major
+    const void *Q;
+    int32_t dim, Kc, K;
+    float err_bound, xn_max, err_q;   // |approximation - ordered distance| <= err_bound (|q|^2 + xn_max) + err_q |q|
+    uint32_t *fail_count;       // incremented once per query whose proof failed
+    const int32_t *others_off;  // AND partner labels per query; null when the batch has none
+    const int32_t *others;
+    LabelMeta meta;
+    int64_t *out_ids;
+    float *out_dists;
+};
+bool scan_bf16_supported(int dtype, int dim, int tile_rows, int keep);
+size_t scan_bf16_lds_bytes(int tile_rows, int keep);
+void launch_scan_bf16(const ScanParams &p, int n_items, int slots, hipStream_t s);
+void launch_scan_rerank(const RerankParams &p, int n_items, hipStream_t s);
 
 // ---------------------------------------------------------------- beam search kernel
 

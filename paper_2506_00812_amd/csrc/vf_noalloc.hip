@@ -7,7 +7,7 @@
 
 namespace vf {
 
-// Device-side temporaries of one call: routing blob | partial rows of segmented scan lists (index, distance
+// Device-side temporaries of one call: routing blob | partial rows of the scan lists' segments (index, distance
 // bits) | seed distance matrix.  One array per GPU the library runs on, held until the process ends; every call
 // on a GPU shares it and finds the last call's contents in it (no part of it needs to start at zero: every word
 // a kernel reads has been written earlier in the same call).

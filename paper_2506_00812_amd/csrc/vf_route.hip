@@ -43,6 +43,10 @@ bool Tuning::set(const char *name, double value)
         {"zero_copy_bytes", &Tuning::zero_copy_bytes, 0, 1 << 20},
         {"scan_valu", &Tuning::scan_valu, 0, 2},
         {"scan16", &Tuning::scan16, 0, 1},
+        {"scan_bf16", &Tuning::scan_bf16, 0, 1},
+        {"scan_bf16_margin", &Tuning::scan_bf16_margin, 0, 54},
+        {"scan_bf16_slots", &Tuning::scan_bf16_slots, 1, 2},
+        {"scan_bf16_seg_groups", &Tuning::scan_bf16_seg_groups, 1, 1024},
         {"overlap", &Tuning::overlap, 0, 1},
         {"seed_exact", &Tuning::seed_exact, 0, 1},
         {"seed_margin", &Tuning::seed_margin, 1, 32},
@@ -170,12 +174,12 @@ void ItemBuilder::add_label(const std::vector<uint64_t> &pairs, size_t lo, size_
             it.entry0 = sg * sg_len * 32;
             it.n = std::min(sg_len * 32, n - it.entry0);
             it.q_begin = q_begin; it.q_count = q_count; it.self_base = -1;
-            it.part_row = nseg == 1 ? -1 : (int32_t)(part_rows + (int64_t)sg * q_count);
+            it.part_row = (nseg == 1 && !all_partial) ? -1 : (int32_t)(part_rows + (int64_t)sg * q_count);
             items.push_back(it);
         }
-        if (nseg > 1) {
+        if (nseg > 1 || all_partial) {
             for (int32_t r = 0; r < q_count; ++r)
-                merges.push_back(MergeItem{map_off, qrow[(size_t)q_begin + r], (int32_t)(part_rows + r), q_count, nseg});
+                merges.push_back(MergeItem{map_off, qrow[(size_t)q_begin + r], (int32_t)(part_rows + r), q_count, nseg, n, 0});
             part_rows += (int64_t)nseg * q_count;
         }
     }

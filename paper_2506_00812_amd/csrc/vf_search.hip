@@ -1,5 +1,7 @@
 // Search calls (Alg. 2): per-stream workspaces, the interleaved seed copies, and the launch schedule of one
 // batch -- route on the host, IVF-BFS scan beside IVF-Graph seed scoring and beam search, finalise.
+#include <chrono>
+
 #include "vf_host.h"
 
 namespace vf {
@@ -51,14 +53,13 @@ static int workspace_for(vf_index *ix, hipStream_t s, Workspace **out)
             VF_HIP(hipStreamSynchronize(w->side));
         }
     }
+    if (!w->owned || w->owner != s) w->prev_forked = false;
     w->owned = true;
     w->owner = s;
     if (!w->ready) {
         VF_HIP(hipStreamCreateWithFlags(&w->side, hipStreamNonBlocking));
         VF_HIP(hipEventCreateWithFlags(&w->ev_fork, hipEventDisableTiming));
         VF_HIP(hipEventCreateWithFlags(&w->ev_join, hipEventDisableTiming));
-        VF_HIP(hipEventCreateWithFlags(&w->ev_copy, hipEventDisableTiming));
-        for (hipEvent_t &e : w->ev_blob_done) VF_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
         w->ready = true;
     }
     *out = w;
@@ -266,6 +267,21 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
     // scan items over the stored interleaved lists (scan labels); in exact mode graph labels follow
     ItemBuilder &ib = P.ib;
     size_t first_hs = r.scan_pairs.size();
+    // float32 lists of large batches are filtered from their bfloat16 copy and re-ranked (every item then leaves
+    // partial rows of scan_keep candidates and every scan query gets a merge item); small batches keep the FMA kernel
+    {
+        const Tuning &tn = ix->tune;
+        const int32_t keep = std::min(64, k + tn.scan_bf16_margin);
+        const bool small_batch = tn.scan_valu == 2 || (tn.scan_valu == 1 && r.scan_pairs.size() <= 256);
+        if (!exact && ix->has_ls16 && tn.scan_bf16 && tn.scan16 && !small_batch && keep > k &&
+            !r.scan_pairs.empty() && scan_bf16_supported(ix->dtype, ix->dim, ib.tile_rows, keep) &&
+            scan_bf16_lds_bytes(std::max(ib.tile_rows, 16), keep) <= 64 * 1024) {
+            P.scan_bf16 = true;
+            P.scan_keep = keep;
+            ib.all_partial = true;
+            ib.seg_groups = ib.seg_groups_heavy = tn.scan_bf16_seg_groups;
+        }
+    }
     if (exact) {
         // scan labels first, graph labels after them (both still ordered by label)
         std::stable_partition(r.scan_pairs.begin(), r.scan_pairs.end(), [&](uint64_t pr) {
@@ -294,7 +310,7 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
         i = e;
     }
     VF_REQUIRE(ib.part_rows < ((int64_t)1 << 31), "too many partial result rows in one call");
-    P.part_words = (size_t)ib.part_rows * k;
+    P.part_words = (size_t)ib.part_rows * (P.scan_bf16 ? P.scan_keep : k);
 
     // selectivity-aware routing: AND queries whose (smallest) graph list is short leave the graph path
     r.xq_query.clear(); r.xq_label.clear();
@@ -375,7 +391,7 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
     L.off_gq_label = o; o = align_up(o + P.n_gq * 4);
     L.off_xq_query = o; o = align_up(o + P.n_xq * 4);
     L.off_xq_label = o; o = align_up(o + P.n_xq * 4);
-    L.off_others_off = o; o = align_up(o + r.others_off.size() * 4);
+    L.off_others_off = o; o = align_up(o + (r.any_and ? r.others_off.size() : 1) * 4);   // (not sent when no query has partners)
     L.off_others = o; o = align_up(o + std::max<size_t>(r.others.size(), 1) * 4);
     L.off_qrow = o; o = align_up(o + std::max<size_t>(ib.qrow.size(), 1) * 4);
     L.off_items = o; o = align_up(o + std::max<size_t>(ib.items.size(), 1) * sizeof(ScanItem));
@@ -399,7 +415,7 @@ void fill_blob(const CallPlan &P, const Routed &r, char *hp)
         memcpy(hp + L.off_xq_query, r.xq_query.data(), P.n_xq * 4);
         memcpy(hp + L.off_xq_label, r.xq_label.data(), P.n_xq * 4);
     }
-    memcpy(hp + L.off_others_off, r.others_off.data(), r.others_off.size() * 4);
+    if (r.any_and) memcpy(hp + L.off_others_off, r.others_off.data(), r.others_off.size() * 4);
     if (!r.others.empty()) memcpy(hp + L.off_others, r.others.data(), r.others.size() * 4);
     if (!ib.qrow.empty()) memcpy(hp + L.off_qrow, ib.qrow.data(), ib.qrow.size() * 4);
     if (!ib.items.empty()) memcpy(hp + L.off_items, ib.items.data(), ib.items.size() * sizeof(ScanItem));
@@ -470,9 +486,10 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         bp.dseed = nullptr; bp.ns_stride = P.ns_stride;
     }
     auto run_seeds = [&]() -> int {
-        if (prof && n_gq && P.seed_select && r.any_and) {
+        if (prof && n_gq && (P.seed_select || P.dense_seeds) && r.any_and) {
             // profiling only, outside the timed interval: the counters report the seeds that pass the predicate as
-            // distances computed, and the selecting kernel only tests the seeds that reach a queue
+            // distances computed, and neither the selecting seed kernel nor the beam kernel's selection from a
+            // row of seed distances tests the seeds that cannot enter a full list
             launch_seed_pass_count(bp.gq_query, bp.gq_label, bp.meta, P.n_seeds, d_others_off, d_others,
                                    ix->counters.as<int32_t>() + (size_t)P.nq * 5, (int)n_gq, s);
         }
@@ -559,6 +576,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                 launch_seed_dist(ix->dtype, sd, (int)P.tiles.size(), s);
             }
             bp.dseed = sd.dseed;
+            if (prof && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
         }
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
         return VF_OK;
@@ -584,7 +602,24 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
             // small batches are latency-bound: the FMA kernel finishes a one-query tile three times sooner;
             // large batches keep the matrix-core kernel, which leaves the vector ALU to the beam search
             const bool small_batch = tune.scan_valu == 2 || (tune.scan_valu == 1 && ib.qrow.size() <= 256);
-            if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) {
+            if (P.scan_bf16) {
+                // filter from the bfloat16 copy, then re-rank (a query whose result is not proven complete is
+                // scanned exactly by its re-ranking wave)
+                ScanParams sb = sp;
+                sb.xblk = ix->d_X_LS16.as<uint4>(); sb.K = P.scan_keep;
+                launch_scan_bf16(sb, (int)P.n_ls_items, tune.scan_bf16_slots, ss);
+                if (prof) { ix->prof.scan_kernel = 3; VF_HIP(hipEventRecord(ix->prof_ev[1], ss)); }
+                RerankParams rp{};
+                rp.items = d_merges; rp.res_idx = sp.res_idx; rp.res_bits = sp.res_bits; rp.map = sp.map;
+                rp.X = ix->X; rp.Q = queries; rp.dim = ix->dim; rp.Kc = P.scan_keep; rp.K = k;
+                // the bound of the bfloat16 seed proofs (same arithmetic: two bfloat16 products per component into a
+                // float32 accumulator, norms of the unrounded vectors), with the lists' own largest norm and rounding error
+                rp.err_bound = ix->seed_err_bound() * 8.0f; rp.xn_max = ix->ls_xn_max; rp.err_q = 2.0f * ix->ls_bf16_delta;
+                rp.fail_count = ix->d_scan_fb.as<uint32_t>();
+                rp.others_off = sp.others_off; rp.others = sp.others; rp.meta = sp.meta;
+                rp.out_ids = out_ids; rp.out_dists = out_dists;
+                launch_scan_rerank(rp, (int)P.n_ls_merges, ss);
+            } else if (!exact && small_batch && scan_valu_supported(ix->dtype, ix->dim, sp.tile_rows)) {
                 launch_scan_valu(sp, (int)P.n_ls_items, ss);
                 if (prof) ix->prof.scan_kernel = 2;
             } else if (!exact && tune.scan16 && scan16_supported(ix->dtype, ix->dim, sp.tile_rows)) {
@@ -594,9 +629,11 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                 launch_scan(ix->dtype, sp, (int)P.n_ls_items, ss);
             }
             // a search times its scan kernel by itself (the merge of the segments' candidates follows it)
-            if (prof && P.hs_runs.empty()) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
-            launch_scan_merge(ix->dtype, d_merges, (int)P.n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
-                              ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
+            if (!P.scan_bf16) {
+                if (prof && P.hs_runs.empty()) VF_HIP(hipEventRecord(ix->prof_ev[1], ss));
+                launch_scan_merge(ix->dtype, d_merges, (int)P.n_ls_merges, sp.res_idx, sp.res_bits, k, ib.max_nseg * k,
+                                  ix->d_M_LS.as<int32_t>(), out_ids, out_dists, ss);
+            }
         }
         if (!P.hs_runs.empty()) {
             const int64_t max_groups = (P.max_hs_list + 31) / 32;
@@ -662,6 +699,7 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     int rc = check_search_args(ix, queries, nq, k, out_ids, out_dists);
     if (rc != VF_OK) return rc;
     std::lock_guard<std::recursive_mutex> lock(ix->mu);
+    const auto t_enter = std::chrono::steady_clock::now();
     if ((rc = check_search_params(ix, exact, k, itopk, width, iters, n_seeds)) != VF_OK) return rc;
     Workspace *W = nullptr;
     if ((rc = workspace_for(ix, s, &W)) != VF_OK) return rc;
@@ -669,7 +707,8 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     const Tuning &tune = ix->tune;
     // the seed distance matrix reuses what is allocated, or grows into at most half of the free memory
     uint64_t dseed_budget = W->dseed.cap / 4;
-    {
+    // (the driver is only asked when the buffer at hand may be too small for this call: the query is slow)
+    if ((uint64_t)nq * (uint64_t)((std::max(n_seeds, itopk) + 31) & ~31) + 64 * 1024 > dseed_budget) {
         size_t free_b = 0, total_b = 0;
         VF_HIP(hipMemGetInfo(&free_b, &total_b));
         dseed_budget = std::max<uint64_t>(dseed_budget, (uint64_t)((free_b + W->dseed.cap) / 2) / 5);   // / 4 bytes, / 1.25 growth
@@ -698,10 +737,13 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
                         dseed_budget, sc, P)) != VF_OK)
         return rc;
     const BlobLayout &L = P.L;
+    const auto t_planned = std::chrono::steady_clock::now();
     Staging *st = nullptr;
     if ((rc = get_staging(W, L.total, &st)) != VF_OK) return rc;
+    const auto t_staged = std::chrono::steady_clock::now();   // (waiting for the staging buffer is the GPU's time, not the host's)
     char *hp = (char *)st->p;
     fill_blob(P, r, hp);
+    const auto t_blob = std::chrono::steady_clock::now();
     if (P.dense_seeds && (rc = W->dseed.reserve(P.dseed_words * 4)) != VF_OK) return rc;
     if (P.part_words > 0) {
         if ((rc = W->part_idx.reserve(P.part_words * 4)) != VF_OK) return rc;
@@ -711,7 +753,9 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     const bool forked = tune.overlap && !ix->prof_serial && !exact && P.n_gq > 0 && !P.ib.items.empty();
     // Two device blobs alternate.  When the call forks, its blob is uploaded on the side stream: there it
     // follows the previous call's scan, not the previous call's beam search, so the upload is off the
-    // critical path.  The buffer was last read two calls ago; the upload waits for that call's end.
+    // critical path.  The buffer was last read two calls ago, by kernels on the side stream (which precede the
+    // upload there) and on the caller's stream: those precede the fork event of the previous call, which the
+    // side stream has waited for -- if that call forked; if not, the upload first waits for the caller's stream.
     // A small blob (small batches) is not copied at all: the kernels read the few hundred bytes they need
     // straight from the pinned staging buffer, which saves the copy's submission and its latency; the
     // staging buffer then stays untouched until the call's last kernel has ended.
@@ -728,15 +772,16 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
         if ((rc = blob.reserve(L.total)) != VF_OK) return rc;
         M.blob = blob.as<char>();
         hipStream_t cs = forked ? W->side : s;
-        if (forked && W->blob_used[bsel]) VF_HIP(hipStreamWaitEvent(cs, W->ev_blob_done[bsel], 0));
+        if (forked && !W->prev_forked) {
+            VF_HIP(hipEventRecord(W->ev_fork, s));
+            VF_HIP(hipStreamWaitEvent(cs, W->ev_fork, 0));
+        }
         VF_HIP(hipMemcpyAsync(M.blob, hp, L.total, hipMemcpyHostToDevice, cs));
         VF_HIP(hipEventRecord(st->done, cs));
         st->pending = true;
-        if (forked) {
-            VF_HIP(hipEventRecord(W->ev_copy, cs));
-            VF_HIP(hipStreamWaitEvent(s, W->ev_copy, 0));
-        }
+        if (forked) VF_HIP(hipStreamWaitEvent(s, st->done, 0));
     }
+    W->prev_forked = forked;
     M.dseed = W->dseed.as<uint32_t>();
     M.part_idx = W->part_idx.as<int32_t>();
     M.part_bits = W->part_bits.as<uint32_t>();
@@ -746,11 +791,16 @@ int search_impl(vf_index *ix, const void *queries, int64_t nq, const int64_t *qo
     if (zero_copy) {
         VF_HIP(hipEventRecord(st->done, s));
         st->pending = true;
-    } else {
-        VF_HIP(hipEventRecord(W->ev_blob_done[bsel], s));
-        W->blob_used[bsel] = true;
     }
     VF_HIP(hipGetLastError());
+    if (ix->profiling) {
+        const auto t_end = std::chrono::steady_clock::now();
+        auto ms = [](auto a, auto b) { return std::chrono::duration<double, std::milli>(b - a).count(); };
+        ix->prof_host_plan += ms(t_enter, t_planned);
+        ix->prof_host_wait += ms(t_planned, t_staged);
+        ix->prof_host_blob += ms(t_staged, t_blob);
+        ix->prof_host_launch += ms(t_blob, t_end);
+    }
     if (exact) {
         VF_HIP(hipStreamSynchronize(s));
         ix->tmp_blk.release();

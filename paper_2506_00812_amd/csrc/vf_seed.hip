@@ -116,13 +116,6 @@ typedef int v16i_seed __attribute__((ext_vector_type(16)));
 typedef int v4i_seed __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf_seed __attribute__((ext_vector_type(8)));
 
-// float -> bfloat16 bits, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_rn_bits(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // CACHED: the B operand comes from the interleaved copy of the seeds (coalesced 1-KiB loads, lane (v, h)
 // taking chunk 2 c + h of seed v of the group); otherwise every lane pair gathers its seed's row from X
 // (32 rows of 32 bytes per load instruction).  NG = 32-seed groups per wave (fully unrolled: a loop with a

@@ -198,7 +198,7 @@ __global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
             bq.q = qvec; bq.label = best; bq.others = own; bq.o_cnt = o_cnt;
             bq.out_ids = res->ids; bq.out_dists = res->dists;
             bq.counters = nullptr; bq.gathered = nullptr; bq.dseed_row = nullptr; bq.runs = nullptr; bq.seed_pass = -1;
-            beam_search_wave<DT, 1>(p.bp, bq, smem);
+            beam_search_wave<DT, 1, true>(p.bp, bq, smem);
         } else {
             ScanParams sp = p.sp;
             sp.qsrc = qvec; sp.qrow = own + 10;

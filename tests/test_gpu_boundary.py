@@ -46,7 +46,8 @@ def test_index_sizes_follow_the_memory_model(vf, tiny, tiny_oracle):
     assert st["bytes_x_ls"] == model_x_ls + padding + groups * 32 * 4
     assert st["bytes_bitsets"] == len(hs) * ((N + 31) // 32) * 4
     assert st["bytes_meta"] == s.n_labels * 24
-    assert st["bytes_total"] == sum(st[k] for k in ("bytes_graph", "bytes_maps", "bytes_x_ls", "bytes_bitsets", "bytes_meta"))
+    assert st["bytes_total"] == sum(st[k] for k in ("bytes_graph", "bytes_maps", "bytes_x_ls", "bytes_bitsets", "bytes_meta", "bytes_x_ls_bf16"))
+    assert st["bytes_x_ls_bf16"] == 0   # uint8 data have no bfloat16 copy
     # what the index really holds
     assert 2 * ix.export("G_HS").nbytes == st["bytes_graph"]
     assert ix.export("M_HS").nbytes + ix.export("M_LS").nbytes == st["bytes_maps"]

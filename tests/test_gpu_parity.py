@@ -386,6 +386,65 @@ def test_float_small_batches_use_fma_scan(vf, name):
     assert n_checked > 300
 
 
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_float_scan_filtered_from_the_bfloat16_copy(vf, name):
+    """Large float32 batches scan the bfloat16 copy of their lists, keep k + margin approximations per query and
+    segment, re-rank those with the ordered distance and accept the result only with a proof; queries without one
+    are scanned again by the exact kernels.  Every route -- proof holds (default), proof mostly fails (margin 1),
+    two list groups in flight instead of one, filter switched off -- must agree with the oracle within the stated
+    tolerance (ids up to ties), single-label (dim 128) and AND (dim 96), lists of one and of several segments."""
+    import torch
+    if name == "c2":
+        w = make_workload("c2", n=60_000, nq=3000, n_labels=150, n_clusters=64, T=3000, graph_degree=16)
+    else:
+        w = make_workload("c5", n=40_000, nq=2500, n_labels=80, n_clusters=32, T=2500, graph_degree=16)
+    s = w.spec
+    ix = _gpu_index(vf, w)
+    st = ix.stats()
+    assert st["bytes_x_ls_bf16"] == st["n_groups_LS"] * 32 * s.dim * 2
+    ixo = OracleIndex(w.vectors, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree, lazy_graph=True)
+    Q = torch.from_numpy(w.queries).cuda()
+    params = dict(itopk=32, width=1, iters=4, n_seeds=64)
+    io, do, info = ixo.search(w.queries, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+    sc = info["method"] == 1
+    assert sc.sum() > 400
+    searched = info["route_label"][sc]
+    assert (ixo.S[searched] > 1024).sum() > 50 and (ixo.S[searched] <= 512).sum() > 50   # several segments / one
+    results = {}
+    for label, knobs in (("default", {}), ("two groups in flight", {"scan_bf16_slots": 2}),
+                         ("proofs fail", {"scan_bf16_margin": 1}), ("off", {"scan_bf16": 0})):
+        ix.tune("scan_bf16", 1); ix.tune("scan_bf16_margin", 22); ix.tune("scan_bf16_slots", 1)
+        for key, value in knobs.items():
+            ix.tune(key, value)
+        ix.profile_enable(True)
+        ig, dg = _search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+        pf = ix.profile_read()
+        ix.profile_enable(False)
+        assert pf["scan_kernel"] == (1 if label == "off" else 3), (label, pf["scan_kernel"])
+        if label in ("default", "two groups in flight"):
+            assert pf["scan_fallbacks"] <= 0.05 * sc.sum(), (label, pf["scan_fallbacks"])
+        elif label == "proofs fail":
+            # (AND queries with fewer than k + 1 matches in a list keep every candidate: nothing to prove)
+            assert pf["scan_fallbacks"] > 0.1 * sc.sum(), (label, pf["scan_fallbacks"])
+        else:
+            assert pf["scan_fallbacks"] == 0
+        assert_close_with_ties(ig[sc], dg[sc], io[sc], do[sc], RTOL, f"{name} scan, {label}")
+        results[label] = (ig[sc].copy(), dg[sc].copy())
+    # the re-ranked results are the ordered float32 distances: the two filtered routes agree bit for bit
+    assert_exact(*results["default"], *results["two groups in flight"], f"{name}: one vs two groups in flight")
+    # small batches keep the FMA kernel
+    few = np.flatnonzero(sc)[:100]
+    qo = np.zeros(len(few) + 1, dtype=np.int64)
+    np.cumsum(np.diff(w.qlabel_offsets)[few], out=qo[1:])
+    ql = np.concatenate([w.qlabel_ids[w.qlabel_offsets[j]:w.qlabel_offsets[j + 1]] for j in few])
+    ix.tune("scan_bf16", 1); ix.tune("scan_bf16_margin", 22); ix.tune("scan_bf16_slots", 1)
+    ix.profile_enable(True)
+    ig, dg = _search(vf, ix, torch.from_numpy(np.ascontiguousarray(w.queries[few])).cuda(), qo, ql, 10, **params)
+    assert ix.profile_read()["scan_kernel"] == 2
+    ix.profile_enable(False)
+    assert_close_with_ties(ig, dg, io[few], do[few], RTOL, f"{name} small batch")
+
+
 def _multi_queries(nq, n_labels, seed, lo, hi, popular):
     rng = np.random.default_rng(seed)
     counts = rng.integers(lo, hi + 1, size=nq)
