@@ -349,6 +349,10 @@ int vf_tune(vf_index *index, const char *name, double value);
  * IVF-Graph, so the two intervals overlap and each kernel shares the chip); on = 2 also
  * puts every launch on the caller's stream, one after the other, so each interval is
  * that kernel's duration with the chip to itself; on = 0 switches both off.
+ * on | 4: batches with AND queries also run a small kernel before each call that counts, per graph query, the
+ * seeds that pass its predicate, so that "distances computed" is exact for them; without it that count
+ * includes, for such a query, the seeds whose predicate the search never had to evaluate (seeds that could not
+ * enter a full list).
  *   per_query   optional host buffer [nq][4] int32 of the last call:
  *               distances computed, rows expanded, predicate tests, and a mode word:
  *               0 = scan path (the first three are then 0); low byte 2 = graph path,
@@ -365,7 +369,8 @@ typedef struct vf_profile {
     int64_t scan_list_entries;         /* sum over scan items of the list length       */
     int64_t scan_pairs;                /* sum over scan items of queries x list length */
     int64_t beam_scored, beam_expanded, beam_tested;
-    int64_t n_seed_tiles;              /* tiles of <= 64 same-label graph queries scored densely (0: seeds were gathered) */
+    int64_t n_seed_tiles;              /* tiles of same-label graph queries scored densely (<= 32 queries on the matrix cores,
+                                          <= 64 with the ordered-distance kernel; 0: seeds were gathered)                  */
     int64_t seed_pairs;                /* sum over graph queries of the seeds scored for them                            */
     int64_t seed_tile_seeds;           /* sum over seed tiles of the seeds they read                                     */
     int64_t seeds_on_matrix_cores;     /* 1: the seeds were scored on MFMA (float32: approximations, re-ranked by the beam

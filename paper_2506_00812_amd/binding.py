@@ -218,9 +218,11 @@ class Index:
         _check(load_library().vf_index_stats(self._h, C.byref(st)))
         return {n: getattr(st, n) for n, _ in VfStats._fields_}
 
-    def profile_enable(self, on=True, serial: bool = False):
-        """serial=True also runs the IVF-BFS and IVF-Graph launches one after the other."""
-        _check(load_library().vf_profile_enable(self._h, 2 if (on and serial) else int(bool(on))))
+    def profile_enable(self, on=True, serial: bool = False, exact_counts: bool = False):
+        """serial=True also runs the IVF-BFS and IVF-Graph launches one after the other; exact_counts=True has a
+        small kernel count, before every call with AND queries, the seeds that pass each query's predicate."""
+        mode = (2 if serial else 1) if on else 0
+        _check(load_library().vf_profile_enable(self._h, mode | (4 if (on and exact_counts) else 0)))
 
     def profile_read(self, per_query: bool = False):
         """Durations and work counters of the last profiled search; waits for it."""

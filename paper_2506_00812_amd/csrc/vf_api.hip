@@ -159,8 +159,10 @@ static int profile_enable_impl(vf_index *ix, int on)
         for (auto &set : ix->prof_ring)
             for (hipEvent_t &e : set)
                 if (!e) VF_HIP(hipEventCreate(&e));
-    ix->profiling = on != 0;
-    ix->prof_serial = on == 2;
+    VF_REQUIRE(on >= 0 && on <= 7 && (on & 3) != 3, "on must be 0, 1 or 2, optionally | 4");
+    ix->profiling = (on & 3) != 0;
+    ix->prof_serial = (on & 3) == 2;
+    ix->prof_exact_counts = (on & 4) != 0;
     ix->prof_valid = false;
     ix->prof_next = 0; ix->prof_unfolded = 0;
     ix->prof_scan_sum = ix->prof_seed_sum = ix->prof_beam_sum = 0;

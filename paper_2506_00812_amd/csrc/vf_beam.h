@@ -176,7 +176,8 @@ struct BeamQuery {
 
 // The search of one query by one wave (a one-wave workgroup: __syncthreads orders the wave's LDS traffic).
 // smem: beam_lds_bytes of LDS.
-template <int DT, int E, bool STREAM_SEEDS = false>
+// AND = false: compiled for batches without predicate labels (none of the predicate's code and registers).
+template <int DT, int E, bool STREAM_SEEDS = false, bool AND = true>
 __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const BeamQuery &bq, uint4 *smem)
 {
     const int lane = threadIdx.x, team = lane >> 3, tl = lane & 7;
@@ -199,7 +200,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     for (int i = lane; i < (1 << p.hash_bits); i += 64) hash[i] = 0xFFFFFFFFu;
     __syncthreads();
 
-    const int o_cnt = bq.o_cnt;
+    const int o_cnt = AND ? bq.o_cnt : 0;
     const int qq_lane = DT == 0 ? lane_qq_u8(qv, nchunks, tl) : 0;
 
     TopM<E> top;
@@ -281,7 +282,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     // every seed, at a fraction of the insertions.  as_index: the list stores the seed index j
     // instead of the local id floor(j * n / ns).  Returns the number of seeds dealt with (a chunk
     // whose bound lets more than 128 seeds through ends the selection early).
-    bool lazy_used = false;
+    bool lazy_used = false, lazy_ok = true;
     auto select_seeds = [&](TopM<1> &list, const uint32_t *drow, bool as_index) -> int {
         constexpr int NBLK = VF_SEED_BLOCKS;
         int done_to = 0;
@@ -292,23 +293,16 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 const int j = jc + i * 64 + lane;
                 v[i] = j < ns ? drow[j] : 0xFFFFFFFFu;
             }
-            int chunk_scored = (ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK), chunk_tested = 0;
-            // AND with a full list: the predicate is only evaluated for the few seeds at or below the list's worst
-            // entry (below); a predicate test is a 4-byte read from a bitset of n / 8 bytes, a cache line each
-            const bool lazy = o_cnt > 0 && list.worst != KEY_MAX;
-            if (lazy) {
-                chunk_tested = chunk_scored;   // counted as the definition counts them: every seed is tested
-                lazy_used = true;
-            }
-            if (o_cnt > 0 && !lazy) {
-                // AND: a seed that fails the predicate is taken out before the selection.  Its local id
-                // floor(j n / ns) advances by (64 n) / ns per step of 64 seeds: one division per lane and
-                // chunk, then quotient / remainder increments.
+            const int chunk_n = ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK;
+            int chunk_scored = chunk_n, chunk_tested = o_cnt > 0 ? chunk_n : 0;   // every seed counts as tested
+            // AND: a seed that fails the predicate is taken out before the selection (its value becomes +inf).
+            // Its local id floor(j n / ns) advances by (64 n) / ns per step of 64 seeds: one division per lane and
+            // chunk, then quotient / remainder increments.
+            auto apply_predicate = [&]() {
                 const uint64_t t64 = 64ull * (uint64_t)n;
                 const uint32_t Q64 = (uint32_t)(t64 / (uint64_t)ns), R64 = (uint32_t)(t64 % (uint64_t)ns);
                 const uint64_t t0 = (uint64_t)(jc + lane) * (uint64_t)n;
                 uint32_t cq = (uint32_t)(t0 / (uint64_t)ns), cr = (uint32_t)(t0 % (uint64_t)ns);
-                chunk_tested = chunk_scored;
                 chunk_scored = 0;
 #pragma unroll
                 for (int i = 0; i < NBLK; ++i) {
@@ -323,41 +317,58 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                     cr += R64; cq += Q64;
                     if (cr >= (uint32_t)ns) { cr -= (uint32_t)ns; cq += 1; }
                 }
-            }
-            // the two smallest values of every lane; the M-th smallest of those 128 bounds the M-th
-            // smallest of the chunk: sort both sets across the wave, take the 64 smallest of their
-            // union (element-wise minimum against the reversed other set), sort those
-            // (a full list bounds the chunk as well as that, or better from the third chunk on: its worst
-            // entry is the M-th smallest of everything before)
-            uint32_t tau = (uint32_t)(list.worst >> 32);
-            if (list.worst == KEY_MAX) {
-                uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
+            };
+            // With a full list the predicate is only evaluated for the few seeds at or below the list's worst entry
+            // (a predicate test is a 4-byte read from a bitset of n / 8 bytes: a cache line each).  Not for queries
+            // whose predicate passes so few seeds that most values stay below that entry (lazy_ok, sticky).
+            bool lazy = lazy_ok && o_cnt > 0 && list.worst != KEY_MAX;
+            // seeds at or below the bound, compacted into cand[] (those beyond its 128 slots only counted)
+            auto compact = [&](uint32_t tau) -> int {
+                __syncthreads();
+                int cnt = 0;
 #pragma unroll
-                for (int i = 1; i < NBLK; ++i) {
-                    const uint32_t hi = v[i] > m1 ? v[i] : m1;
-                    m2 = hi < m2 ? hi : m2;
-                    m1 = v[i] < m1 ? v[i] : m1;
+                for (int i = 0; i < NBLK; ++i) {
+                    const int j = jc + i * 64 + lane;
+                    const bool pass = v[i] <= tau && v[i] != 0xFFFFFFFFu && j < ns;
+                    const uint64_t m = __ballot(pass);
+                    const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
+                    if (pass && at < 128) {
+                        cand_d[at] = v[i];
+                        cand_c[at] = j;
+                    }
+                    cnt += __popcll(m);
                 }
-                const uint32_t s1 = wave_sort_u32(m1, lane), s2 = wave_sort_u32(m2, lane);
-                const uint32_t s2r = (uint32_t)__shfl((int)s2, 63 - lane);
-                const uint32_t sorted = wave_merge_u32(s1 < s2r ? s1 : s2r, lane);
-                tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, list.itopk - 1);
-            }
-            __syncthreads();
-            int cnt = 0;   // seeds at or below the bound, compacted into cand[] (those beyond its 128 slots only counted)
+                __syncthreads();
+                return cnt;
+            };
+            int cnt;
+            for (;;) {
+                if (o_cnt > 0 && !lazy) apply_predicate();
+                // the two smallest values of every lane; the M-th smallest of those 128 bounds the M-th
+                // smallest of the chunk: sort both sets across the wave, take the 64 smallest of their
+                // union (element-wise minimum against the reversed other set), sort those
+                // (a full list bounds the chunk as well as that, or better from the third chunk on: its worst
+                // entry is the M-th smallest of everything before)
+                uint32_t tau = (uint32_t)(list.worst >> 32);
+                if (list.worst == KEY_MAX) {
+                    uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
 #pragma unroll
-            for (int i = 0; i < NBLK; ++i) {
-                const int j = jc + i * 64 + lane;
-                const bool pass = v[i] <= tau && v[i] != 0xFFFFFFFFu && j < ns;
-                const uint64_t m = __ballot(pass);
-                const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
-                if (pass && at < 128) {
-                    cand_d[at] = v[i];
-                    cand_c[at] = j;
+                    for (int i = 1; i < NBLK; ++i) {
+                        const uint32_t hi = v[i] > m1 ? v[i] : m1;
+                        m2 = hi < m2 ? hi : m2;
+                        m1 = v[i] < m1 ? v[i] : m1;
+                    }
+                    const uint32_t s1 = wave_sort_u32(m1, lane), s2 = wave_sort_u32(m2, lane);
+                    const uint32_t s2r = (uint32_t)__shfl((int)s2, 63 - lane);
+                    const uint32_t sorted = wave_merge_u32(s1 < s2r ? s1 : s2r, lane);
+                    tau = (uint32_t)__builtin_amdgcn_readlane((int)sorted, list.itopk - 1);
                 }
-                cnt += __popcll(m);
+                cnt = compact(tau);
+                if (!(lazy && cnt > 128)) break;
+                lazy = false;      // too many for the candidate area: the predicate first after all
+                lazy_ok = false;
             }
-            __syncthreads();
+            if (lazy) lazy_used = true;
             if (cnt > 128) break;
             n_scored += chunk_scored;
             n_tested += chunk_tested;

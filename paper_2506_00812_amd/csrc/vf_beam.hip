@@ -3,7 +3,7 @@
 
 namespace vf {
 
-template <int DT, int E>
+template <int DT, int E, bool AND>
 __global__ __launch_bounds__(64, (DT == 1 && E == 1) ? 7 : 8) void beam_kernel(BeamParams p)
 {
     extern __shared__ uint4 smem[];
@@ -14,7 +14,7 @@ __global__ __launch_bounds__(64, (DT == 1 && E == 1) ? 7 : 8) void beam_kernel(B
     bq.q = (const char *)p.Q + (int64_t)qi * row_bytes;
     bq.label = p.gq_label[gq];
     bq.others = nullptr; bq.o_cnt = 0;
-    if (p.others_off != nullptr) {
+    if (AND && p.others_off != nullptr) {
         const int o_begin = p.others_off[qi];
         bq.others = p.others + o_begin;
         bq.o_cnt = p.others_off[qi + 1] - o_begin;
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(64, (DT == 1 && E == 1) ? 7 : 8) void beam_kernel(B
     bq.dseed_row = p.dseed != nullptr ? p.dseed + (int64_t)gq * p.ns_stride : nullptr;
     bq.runs = p.seed_runs != nullptr ? p.seed_runs + (int64_t)gq * p.run_segs * p.run_K : nullptr;
     bq.seed_pass = p.seed_pass != nullptr ? p.seed_pass[gq] : -1;
-    beam_search_wave<DT, E>(p, bq, smem);
+    beam_search_wave<DT, E, false, AND>(p, bq, smem);
 }
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype)
@@ -35,20 +35,22 @@ size_t beam_lds_bytes(const BeamParams &p, int dtype)
     return row_bytes + 128 * 4 * 3 + 8 * 4 + ((size_t)4 << p.hash_bits);
 }
 
-template <int DT> static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s)
+template <int DT, bool AND> static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s)
 {
     const dim3 grid(n_gq), block(64);
-    if (p.itopk <= 64) hipLaunchKernelGGL((beam_kernel<DT, 1>), grid, block, lds, s, p);
-    else if (p.itopk <= 128) hipLaunchKernelGGL((beam_kernel<DT, 2>), grid, block, lds, s, p);
-    else hipLaunchKernelGGL((beam_kernel<DT, 4>), grid, block, lds, s, p);
+    if (p.itopk <= 64) hipLaunchKernelGGL((beam_kernel<DT, 1, AND>), grid, block, lds, s, p);
+    else if (p.itopk <= 128) hipLaunchKernelGGL((beam_kernel<DT, 2, AND>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((beam_kernel<DT, 4, AND>), grid, block, lds, s, p);
 }
 
 void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s)
 {
     if (n_gq <= 0) return;
     const size_t lds = beam_lds_bytes(p, dtype);
-    if (dtype == 0) launch_beam_dt<0>(p, n_gq, lds, s);
-    else launch_beam_dt<1>(p, n_gq, lds, s);
+    // batches without predicate labels run an instantiation without the predicate's code
+    const bool with_and = p.others_off != nullptr;
+    if (dtype == 0) { if (with_and) launch_beam_dt<0, true>(p, n_gq, lds, s); else launch_beam_dt<0, false>(p, n_gq, lds, s); }
+    else { if (with_and) launch_beam_dt<1, true>(p, n_gq, lds, s); else launch_beam_dt<1, false>(p, n_gq, lds, s); }
 }
 
 }  // namespace vf

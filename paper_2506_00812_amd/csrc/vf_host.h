@@ -270,6 +270,7 @@ struct vf_index {
     hipEvent_t *prof_ev = prof_ring[0];   // the set of the call being issued
     int prof_next = 0, prof_unfolded = 0; // next ring slot; recorded sets whose durations are not in the sums yet
     bool prof_serial = false;  // vf_profile_enable(index, 2): every launch on the caller's stream
+    bool prof_exact_counts = false;   // ... | 4: count the seeds that pass each AND query's predicate before every call
     vf_profile prof{};
     std::vector<int32_t> prof_graph_queries;   // graph-routed queries of the last profiled call
     double prof_scan_sum = 0, prof_seed_sum = 0, prof_beam_sum = 0;

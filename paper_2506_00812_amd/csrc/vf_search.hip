@@ -485,15 +485,18 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         bp.gathered = prof ? ix->counters.as<int32_t>() + (size_t)P.nq * 4 : nullptr;
         bp.dseed = nullptr; bp.ns_stride = P.ns_stride;
     }
-    auto run_seeds = [&]() -> int {
-        if (prof && n_gq && (P.seed_select || P.dense_seeds) && r.any_and) {
+    auto count_passing_seeds = [&]() {
+        if (prof && ix->prof_exact_counts && n_gq && (P.seed_select || P.dense_seeds) && r.any_and) {
             // profiling only, outside the timed interval: the counters report the seeds that pass the predicate as
             // distances computed, and neither the selecting seed kernel nor the beam kernel's selection from a
             // row of seed distances tests the seeds that cannot enter a full list
             launch_seed_pass_count(bp.gq_query, bp.gq_label, bp.meta, P.n_seeds, d_others_off, d_others,
                                    ix->counters.as<int32_t>() + (size_t)P.nq * 5, (int)n_gq, s);
         }
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
+    };
+    auto run_seeds = [&]() -> int {
+        // (a profiled call that forks has recorded this event already: it is its fork event)
+        if (prof && !forked) VF_HIP(hipEventRecord(ix->prof_ev[2], s));
         if (n_gq && P.seed_select) {
             // scoring and selection in one kernel: runs of sel_K keys per (query, seed segment)
             SeedSelParams sl{};
@@ -515,7 +518,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                     const int64_t ns_l = std::min<int64_t>(P.n_seeds, ix->S[(size_t)t.label]);
                     ix->prof.seed_run_keys += (int64_t)t.q_count * ((ns_l + P.seg_seeds - 1) / P.seg_seeds) * P.sel_K;
                 }
-                if (r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
+                if (ix->prof_exact_counts && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
             }
             if (ix->dtype == VF_F32) {
                 // two bfloat16 products per component (<= 256 terms, <= 2 u each: 512 u), the query's split
@@ -576,15 +579,18 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                 launch_seed_dist(ix->dtype, sd, (int)P.tiles.size(), s);
             }
             bp.dseed = sd.dseed;
-            if (prof && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
+            if (prof && ix->prof_exact_counts && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
         }
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
         return VF_OK;
     };
     auto run_scan = [&]() -> int {
         if (forked) {
-            VF_HIP(hipEventRecord(ev_fork, s));
-            VF_HIP(hipStreamWaitEvent(side, ev_fork, 0));
+            // (while profiling the event that marks the start of the graph path serves as the fork event: every
+            // event recorded on the caller's stream delays the kernel behind it by a few microseconds)
+            hipEvent_t fork = prof ? ix->prof_ev[2] : ev_fork;
+            VF_HIP(hipEventRecord(fork, s));
+            VF_HIP(hipStreamWaitEvent(side, fork, 0));
             ss = side;
         }
         if (prof) VF_HIP(hipEventRecord(ix->prof_ev[0], ss));
@@ -656,6 +662,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
     };
     // the scan goes first: its longest work items decide when it ends (measured: forking it
     // after the seed kernel costs 6 to 20 % of the step)
+    count_passing_seeds();
     if ((rc = run_scan()) != VF_OK) return rc;
     if ((rc = run_seeds()) != VF_OK) return rc;
     if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);

@@ -3,17 +3,26 @@
 // label, computed densely.
 //
 // The seeds of a label -- local ids floor(j * n / ns) -- do not depend on the query,
-// so all queries of a label score the same vectors.  Instead of every query gathering
-// its seeds from HBM, one wave takes up to 64 queries of one label (one query per lane,
-// the query vector held in registers) and a chunk of kSeedChunk seeds; a seed vector is the
-// same for all lanes, so it is fetched with scalar loads and used as a scalar operand: the
-// seed vectors are fetched once per 64 queries and the inner loop is pure VALU work with
-// no LDS or cross-lane traffic.  A lane evaluates the
-// distance in exactly the order the 8-lane teams of the beam kernel use (partial sum t
-// takes the 16-byte chunks 8s + t, fused multiply-add, fixed tree), so the bits are
-// identical to a gathered evaluation and to the CPU evaluation.
+// so all queries of a label score the same vectors: a dense queries x seeds block per label
+// instead of every query gathering its seeds from HBM.  Three kernels fill that block:
 //
-// Output: dseed[gq][j] = distance bits of graph query gq to seed j, consumed by the
+//   seed_mfma_kernel    the default wherever it has an instantiation.  The block is a contraction,
+//                       |q|^2 + |x|^2 - 2 q.x on the matrix cores: exact for uint8, an approximation
+//                       for float32 that the beam kernel re-ranks under a proof (see below).
+//   seed_select_kernel  the same scoring with the selection fused in: per (query, seed segment) only a
+//                       run of the K smallest keys leaves the kernel (off by default: slower than the
+//                       unfused pair except on long uint8 seed lists).
+//   seed_dist_kernel    the ordered distance itself on the vector ALU, for dimensions and list sizes the
+//                       matrix-core kernels do not cover and as the reference route of the tests: one wave
+//                       takes up to 64 queries of one label (one query per lane, the query vector held in
+//                       registers) and a chunk of kSeedChunk seeds; a seed vector is the same for all lanes,
+//                       so it is fetched with scalar loads and used as a scalar operand -- no LDS or
+//                       cross-lane traffic in the inner loop.  A lane evaluates the distance in exactly the
+//                       order the 8-lane teams of the beam kernel use (partial sum t takes the 16-byte
+//                       chunks 8s + t, fused multiply-add, fixed tree), so the bits are identical to a
+//                       gathered evaluation and to the CPU evaluation.
+//
+// Output of the unfused kernels: dseed[gq][j] = distance bits of graph query gq to seed j, consumed by the
 // beam kernel, which keeps the best itopk.
 #include "vf_select.h"
 
@@ -103,9 +112,9 @@ __global__ __launch_bounds__(64) void seed_dist_kernel(SeedParams p)
 // float32, matrix cores.  queries x seeds of one label is a dense contraction, so the bulk of the
 // work can run on MFMA as |q|^2 + |x|^2 - 2 q.x.  That value is rounded differently from the
 // ordered distance the search is defined with, so it is used as a filter only: the beam kernel
-// keeps the 64 best approximations per query, re-scores those with the ordered distance, and
-// checks that the gap to the 65th exceeds the rounding-error bound (else it scores every seed
-// itself).  One wave: a tile of <= 32 queries (A operand, staged in LDS) against kSeedMfmaChunk
+// keeps the itopk + margin best approximations per query (at most 64), re-scores those with the
+// ordered distance, and accepts the list only if its worst entry lies below the last kept approximation
+// by more than the rounding-error bound (else it scores every seed itself).  One wave: a tile of <= 32 queries (A operand, staged in LDS) against kSeedMfmaChunk
 // seeds in groups of 32 (B operand gathered row-wise from X: lane (v, h) reads the 16-byte
 // chunks 2c + h of seed v, the operand layout of v_mfma_f32_32x32x2_f32).
 // uint8 data go through the same kernel with v_mfma_i32_32x32x32_i8 on the vectors shifted by -128
@@ -124,8 +133,8 @@ typedef __bf16 v8bf_seed __attribute__((ext_vector_type(8)));
 // DT = 2: float32 data whose interleaved seed copy holds bfloat16 (16-byte chunks of 8 components, NCH of
 // them per seed, CACHED only).  The queries are split into a bfloat16 high part and the bfloat16 rounding
 // of the rest (|q - hi - lo| <= 2^-16 |q| per component), both multiplied with the seeds by
-// v_mfma_f32_32x32x16_bf16 into one float32 accumulator: half the operand bytes and an eighth of the
-// matrix-core time of the float32 form.  The norms stay those of the unrounded vectors, so the only new
+// v_mfma_f32_32x32x16_bf16 into one float32 accumulator: half the operand bytes and a quarter of the
+// matrix-core time of the float32 form (two products per component at sixteen times the rate).  The norms stay those of the unrounded vectors, so the only new
 // error is 2 q.(x - bf16(x)), which the beam kernel's bound carries as err_q * |q|.
 template <int DT, int NCP, bool CACHED, int NG>
 __global__ __launch_bounds__(64) void seed_mfma_kernel(SeedParams p)

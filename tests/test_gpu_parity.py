@@ -252,7 +252,7 @@ def test_work_counters_equal_oracle_counts(vf, tiny, tiny_oracle, tiny_gpu):
     ix, Q = tiny_gpu
     nq = 600
     qoff, qids = _and_queries(nq, tiny.spec.n_labels, 23)
-    ix.profile_enable(True)
+    ix.profile_enable(True, exact_counts=True)   # (AND: the seeds that pass a predicate are counted by a kernel of their own)
     try:
         for (qo, qi, n) in ((tiny.qlabel_offsets, tiny.qlabel_ids, tiny.spec.nq), (qoff, qids, nq)):
             for params, fused in ((dict(itopk=32, width=1, iters=20, n_seeds=0), 0), (dict(itopk=64, width=2, iters=24, n_seeds=700), 0),
