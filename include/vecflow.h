@@ -87,7 +87,9 @@ typedef struct vf_allocator {
  * separately for the graph ("HS") and scan ("LS") partitions, both compacted in
  * ascending label id.  Posting lists are in ascending global id.  A graph list's
  * rows are the exact R nearest other members of the list, as local ids, ordered by
- * (distance, local id).
+ * (distance, local id); for float32 data, distance is the ordered float32 distance the search uses (a row taken
+ * from the matrix-core self-join's candidates is kept only with a proof that no other member can belong to it,
+ * and is otherwise computed from every member of the list).
  */
 int vf_build_index(const void *vectors, int dtype, int64_t n, int32_t dim, const int64_t *label_offsets,
                    const int32_t *label_ids, int32_t n_labels, int32_t T, int32_t graph_degree,

@@ -1,7 +1,7 @@
 // Build-time kernels for Alg. 1: the interleaved list layout of Section 4.2.2
 // (StoreInterleaved), per-label membership bitsets for the AND predicate of
 // Section 4.3.2, and the final ordering of graph rows.
-#include "vf_device.h"
+#include "vf_beam.h"
 
 namespace vf {
 
@@ -104,11 +104,16 @@ __global__ void graph_rows_copy_kernel(const int32_t *cand_idx, int64_t n, int32
 
 // float32: the contraction's |q|^2+|x|^2-2q.x distances are rounded differently from
 // the ordered fp32 distance the search uses, so the K > R best candidates are scored
-// again with that distance and the R best by (distance, local id) become the row.
+// again with that distance and the R best by (distance, local id) become the row -- if that is provably the
+// exact row: every list member the self-join dropped has an approximation >= T (the largest one kept), hence an
+// ordered distance >= T - B with B = err_bound (|x_v|^2 + max |x|^2); the row stands when its R-th distance is
+// below T - B or nothing was dropped.  Otherwise (near-ties at rank R beyond the K - R spare candidates, data far
+// from the origin) the wave scores every member of the list itself.  err_bound < 0: no check (no norms).
 // One wave per vertex.
 __global__ __launch_bounds__(64) void graph_rows_rerank_kernel(const char *X, int32_t row_bytes, const int32_t *map,
-                                                               int64_t n, const int32_t *cand_idx, int32_t K, int32_t R,
-                                                               int32_t *G_rows)
+                                                               int64_t n, const int32_t *cand_idx, const uint32_t *cand_bits,
+                                                               int32_t K, int32_t R, int32_t *G_rows, float err_bound,
+                                                               float xn_max, uint32_t *rescanned)
 {
     extern __shared__ uint4 smem[];
     const int lane = threadIdx.x, team = lane >> 3, tl = lane & 7;
@@ -129,14 +134,46 @@ __global__ __launch_bounds__(64) void graph_rows_rerank_kernel(const char *X, in
     }
     __syncthreads();
     wave_bitonic_sort(keys, 64, lane);
-    if (lane < R) {
-        const uint64_t key = keys[lane];
-        G_rows[j * R + lane] = key == KEY_MAX ? -1 : (int32_t)(uint32_t)key;
+    uint64_t key = keys[lane];
+    if (err_bound >= 0.f && n - 1 > K) {   // members were dropped: can one of them belong to the row?
+        float vn = 0.f;
+        for (int i = lane; i < nchunks; i += 64) {
+            const uint4 v = qv[i];
+            const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+            vn += f[0] * f[0] + f[1] * f[1] + f[2] * f[2] + f[3] * f[3];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) vn += __shfl_xor(vn, o);
+        const float B = err_bound * (vn + xn_max);
+        const float T = __uint_as_float(cand_bits[j * K + K - 1]);
+        const uint64_t rth = readlane64(key, R - 1);
+        const bool proven = rth != KEY_MAX && __uint_as_float((uint32_t)(rth >> 32)) < T - B;
+        if (!proven) {   // (wave-uniform) the definition itself
+            if (lane == 0 && rescanned != nullptr) atomicAdd(rescanned, 1u);
+            uint32_t *dist = (uint32_t *)keys;   // [64]
+            TopM<1> ex;
+            ex.init(R);
+            for (int64_t e0 = 0; e0 < n; e0 += 64) {
+                __syncthreads();
+                for (int r0 = 0; r0 < 64; r0 += 8) {
+                    const int64_t e = e0 + r0 + team;
+                    const char *xrow = X + (int64_t)map[e < n ? e : 0] * row_bytes;
+                    const uint32_t bits = team_dist_bits_f32(qv, xrow, nchunks, tl);
+                    if (tl == 0) dist[r0 + team] = bits;
+                }
+                __syncthreads();
+                const int64_t e = e0 + lane;
+                merge_batch(ex, (e < n && e != j) ? ((uint64_t)dist[lane] << 32) | (uint32_t)e : KEY_MAX, lane);
+            }
+            key = ex.cur[0];
+        }
     }
+    if (lane < R) G_rows[j * R + lane] = key == KEY_MAX ? -1 : (int32_t)(uint32_t)key;
 }
 
 void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map, int64_t n, const int32_t *cand_idx,
-                       int32_t K, int32_t R, int32_t *G_rows, hipStream_t s)
+                       const uint32_t *cand_bits, int32_t K, int32_t R, int32_t *G_rows, float err_bound, float xn_max,
+                       uint32_t *rescanned, hipStream_t s)
 {
     if (n <= 0) return;
     if (dtype == 0) {
@@ -145,7 +182,8 @@ void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map
     } else {
         const int32_t row_bytes = dim * 4;
         hipLaunchKernelGGL(graph_rows_rerank_kernel, dim3((unsigned)n), dim3(64), (size_t)row_bytes + 64 * 8, s,
-                           (const char *)X, row_bytes, map, n, cand_idx, K, R, G_rows);
+                           (const char *)X, row_bytes, map, n, cand_idx, cand_bits, K, R, G_rows, err_bound, xn_max,
+                           rescanned);
     }
 }
 

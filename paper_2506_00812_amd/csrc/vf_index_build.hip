@@ -164,7 +164,11 @@ static int build_graph_for_label(vf_index *ix, int32_t l, int32_t K, int32_t deg
     } else {
         launch_scan(ix->dtype, p, (int)n_tiles, s);
     }
-    launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), K, deg, rows_out, s);
+    // float32 rows are accepted only with a proof that the self-join's K candidates contain them (the bound of the
+    // float32 matrix-core approximations, relative to the largest squared norm of the table)
+    const bool checked = ix->dtype == VF_F32 && ix->xn_max > 0.f;
+    launch_graph_rows(ix->dtype, ix->X, ix->dim, map, nl, cand_idx.as<int32_t>(), cand_dist.as<uint32_t>(), K, deg, rows_out,
+                      checked ? ix->seed_err_bound() : -1.f, ix->xn_max, nullptr, s);
     if (global_ids)
         launch_graph_global_ids(rows_out, map, (int64_t)nl * deg, ix->d_Gg.as<int32_t>() + base * ix->R, s);
     VF_HIP(hipGetLastError());
@@ -398,6 +402,32 @@ int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, con
             if ((rc = ix->tmp_norm.reserve((size_t)max_groups * 32 * 4)) != VF_OK) return rc;
             if ((rc = cand_idx.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
             if ((rc = cand_dist.reserve((size_t)max_groups * 32 * K * 4)) != VF_OK) return rc;
+            // squared norm of every row of X and the largest of them: the matrix-core seed scoring reads the norms,
+            // its proofs and those of the float32 graph rows need the largest
+            if (ix->dtype == VF_F32 || seed_mfma_supported(ix->dtype, ix->dim)) {
+                if ((rc = ix->d_xnorm_all.reserve((size_t)n * 4)) != VF_OK) return rc;
+                launch_row_norms(ix->dtype, ix->X, ix->dim, n, ix->d_xnorm_all.as<uint32_t>(), s);
+                float mx = 0.f;
+                bool finite = true;
+                if (ix->dtype == VF_F32) {
+                    std::vector<float> hn((size_t)n);
+                    VF_HIP(hipMemcpyAsync(hn.data(), ix->d_xnorm_all.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+                    VF_HIP(hipStreamSynchronize(s));
+                    for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
+                }
+                // a table with NaN or overflowing norms keeps the exact kernel, and so does one whose largest
+                // squared norm is outside [1e-24, 1e30]: the proofs' bound is relative to that norm and assumes
+                // that what the matrix cores flush (products under 1.2e-38) is negligible beside it.
+                // The bound itself: |approximation - ordered distance| <= 300 u (|q|^2 + |x|^2), u = 2^-24 (dot
+                // product of <= 512 terms in any order, two norms, the final additions, the ordered sum's own
+                // error); 512 u = 2^-15 is used (vf_index::seed_err_bound).
+                if (ix->dtype == VF_F32 && !(mx >= 1e-24f && mx <= 1e30f)) finite = false;
+                if (finite) {
+                    ix->xn_max = mx;
+                    ix->seed_mfma_ok = seed_mfma_supported(ix->dtype, ix->dim);
+                }
+                if (!finite || !ix->seed_mfma_ok) ix->d_xnorm_all.release();
+            }
             // optionally a line on stderr every few seconds (index builds of 10^7 vectors take minutes)
             const bool progress = ix->tune.build_progress != 0;
             time_t last_print = time(nullptr);
@@ -425,31 +455,6 @@ int build_index_impl(const void *vectors, int dtype, int64_t n, int32_t dim, con
             ix->graph_kind = graph_kind; ix->knn_degree = pruned ? D : 0;
             ix->tmp_blk.release();
             ix->tmp_norm.release();
-            if (seed_mfma_supported(ix->dtype, ix->dim)) {
-                if ((rc = ix->d_xnorm_all.reserve((size_t)n * 4)) != VF_OK) return rc;
-                launch_row_norms(ix->dtype, ix->X, ix->dim, n, ix->d_xnorm_all.as<uint32_t>(), s);
-                float mx = 0.f;
-                bool finite = true;
-                if (ix->dtype == VF_F32) {
-                    std::vector<float> hn((size_t)n);
-                    VF_HIP(hipMemcpyAsync(hn.data(), ix->d_xnorm_all.p, (size_t)n * 4, hipMemcpyDeviceToHost, s));
-                    VF_HIP(hipStreamSynchronize(s));
-                    for (float v : hn) { finite = finite && v == v && v <= 3.0e38f; mx = v > mx ? v : mx; }
-                }
-                // a table with NaN or overflowing norms keeps the exact kernel, and so does one whose largest
-                // squared norm is outside [1e-24, 1e30]: the proofs' bound is relative to that norm and assumes
-                // that what the matrix cores flush (products under 1.2e-38) is negligible beside it.
-                // The bound itself: |approximation - ordered distance| <= 300 u (|q|^2 + |x|^2), u = 2^-24 (dot
-                // product of <= 512 terms in any order, two norms, the final additions, the ordered sum's own
-                // error); 512 u = 2^-15 is used (vf_index::seed_err_bound).
-                if (ix->dtype == VF_F32 && !(mx >= 1e-24f && mx <= 1e30f)) finite = false;
-                if (finite) {
-                    ix->xn_max = mx;
-                    ix->seed_mfma_ok = true;
-                } else {
-                    ix->d_xnorm_all.release();
-                }
-            }
         }
         VF_HIP(hipGetLastError());
     }

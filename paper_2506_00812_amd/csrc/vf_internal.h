@@ -240,9 +240,13 @@ void launch_interleave(int dtype, const void *X, int32_t dim, const int32_t *map
 void launch_bitset_fill(const int32_t *map, int64_t n, uint32_t *bits, hipStream_t s);
 
 // Graph rows from candidate lists: u8 copies the first R candidates (already exact);
-// f32 re-scores K candidates with the ordered fp32 distance and keeps the best R.
+// f32 re-scores K candidates with the ordered fp32 distance and keeps the best R, provided that no member the
+// self-join dropped can belong to the row (cand_bits: the candidates' approximate distances; err_bound, xn_max:
+// |approximation - ordered distance| <= err_bound (|x_v|^2 + xn_max); err_bound < 0: unchecked); a row without
+// that proof is computed from every member of the list and counted in *rescanned (optional).
 void launch_graph_rows(int dtype, const void *X, int32_t dim, const int32_t *map, int64_t n, const int32_t *cand_idx,
-                       int32_t K, int32_t R, int32_t *G_rows, hipStream_t s);
+                       const uint32_t *cand_bits, int32_t K, int32_t R, int32_t *G_rows, float err_bound, float xn_max,
+                       uint32_t *rescanned, hipStream_t s);
 
 // out[i] = map[rows[i]] (rows[i] >= 0), -1 otherwise: graph rows as global ids
 void launch_graph_global_ids(const int32_t *rows, const int32_t *map, int64_t count, int32_t *out, hipStream_t s);

@@ -207,6 +207,35 @@ def test_float_graph_rows_and_search(vf):
     assert_close_with_ties(to_np(ie), to_np(de), io, do, RTOL, "float exact")
 
 
+def test_float_graph_rows_far_from_origin(vf):
+    """Data far from the origin: |x|^2 is 10^5 times the distances between neighbours, so the matrix-core
+    approximations |q|^2 + |x|^2 - 2 q.x order a vertex's neighbours almost at random and the candidates the
+    self-join keeps need not contain the exact row.  The build must notice (its proof fails) and compute such
+    rows from the whole list; graph searches must notice too (their seed proofs fail) and still return the
+    oracle's bits."""
+    import torch
+    w = make_workload("c2", n=8_000, nq=600, n_labels=12, n_clusters=16, T=1200, graph_degree=16)
+    s = w.spec
+    vec = np.ascontiguousarray(w.vectors + np.float32(300.0))
+    qs = np.ascontiguousarray(w.queries + np.float32(300.0))
+    X = torch.from_numpy(vec).cuda()
+    ix = vf.build_index(X, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    ixo = OracleIndex(vec, w.label_offsets, w.label_ids, s.n_labels, s.T, s.graph_degree)
+    G = ix.export("G_HS").reshape(-1, s.graph_degree)
+    assert len(G) > 3000
+    bad = np.flatnonzero((G != ixo.G_HS).any(axis=1))
+    assert len(bad) == 0, f"{len(bad)} of {len(G)} graph rows differ, first {bad[:3]}"
+    Q = torch.from_numpy(qs).cuda()
+    params = dict(itopk=32, width=1, iters=6, n_seeds=256)
+    ig, dg = _search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, 10, **params)
+    io, do, info = ixo.search(qs, w.qlabel_offsets, w.qlabel_ids, 10, with_info=True, **params)
+    g = info["method"] == 2
+    assert g.sum() > 100
+    assert_exact(ig[g], dg[g], io[g], do[g], "far from the origin, graph path")
+    # (the scan kernels evaluate |q|^2 + |x|^2 - 2 q.x in float32: their 1e-4 tolerance is stated for data whose
+    # norms are comparable to the distances, which this table is not -- the scan path is not compared here)
+
+
 def test_float_and_dim96(vf):
     import torch
     w = make_workload("c5", n=20_000, nq=800, n_labels=80, n_clusters=32, T=600, graph_degree=16)
