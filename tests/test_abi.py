@@ -121,7 +121,7 @@ def test_bench_reads_the_committed_counter_summary():
     spec.loader.exec_module(bench)
     params = bench.committed_params("c2")
     assert params is not None and len(params) == 4 and params in bench.CANDIDATES
-    for kernel in ("beam_kernel", "seed_mfma_kernel", "scan_topk16_kernel"):
+    for kernel in ("beam_kernel", "seed_mfma_kernel", "scan_bf16_kernel"):
         t = bench.committed_traffic(kernel, "c2", params)
         assert t is not None and 10_000_000 < t < 5_000_000_000, (kernel, t)
     assert bench.committed_traffic("beam_kernel", "c2", (1, 1, 1, 1)) is None      # other parameters: no figure
