@@ -209,8 +209,9 @@ int vf_search_noalloc(vf_index *index, const void *queries, int64_t nq, const in
  * (uint8 and graph-searched float32 queries bit for bit).
  *
  *   k, itopk, width, iters, n_seeds   as in vf_search, fixed for the session; itopk <= 64.  A worker scores its
- *                  query's seeds itself, one wave for all of them: sessions are meant for moderate seed counts
- *   n_workers      worker waves, 0 = 240 (every workgroup of the kernel must fit on the chip at once)
+ *                  query's seeds itself (no batch to share a dense seed kernel with), its waves each a share
+ *   n_workers      worker workgroups, 0 = 240 (every workgroup of the kernel must fit on the chip at once)
+ *   waves_per_worker  waves of a worker, 1, 4 or 8; 0 = 8.  All of them score seeds, the first one searches
  *   ring_slots     jobs that may be in flight or unread, 0 = 1024
  *   max_jobs       the kernel ends after this many jobs, 0 = no limit
  *   idle_polls     the kernel ends after this many consecutive polls of the job ring without a new job
@@ -232,7 +233,7 @@ typedef struct vf_server vf_server;
 typedef struct vf_serve_params {
     int32_t k, itopk, width, iters, n_seeds;
     int32_t n_workers, ring_slots;
-    int32_t reserved;
+    int32_t waves_per_worker;
     int64_t max_jobs, idle_polls;
 } vf_serve_params;
 int vf_serve_begin(vf_index *index, const vf_serve_params *params, vf_server **out);

@@ -57,7 +57,7 @@ class VfSearchParams(C.Structure):
 
 
 class VfServeParams(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("k", "itopk", "width", "iters", "n_seeds", "n_workers", "ring_slots", "reserved")] + \
+    _fields_ = [(n, C.c_int32) for n in ("k", "itopk", "width", "iters", "n_seeds", "n_workers", "ring_slots", "waves_per_worker")] + \
                [(n, C.c_int64) for n in ("max_jobs", "idle_polls")]
 
 
@@ -371,10 +371,10 @@ class Server:
     """A serving session (vf_serve_*): a resident kernel that answers single queries from a job ring."""
 
     def __init__(self, index: Index, k, itopk=32, width=1, iters=8, n_seeds=0, n_workers=0, ring_slots=0, max_jobs=0,
-                 idle_polls=0):
+                 idle_polls=0, waves_per_worker=0):
         self.index, self.k = index, int(k)
-        prm = VfServeParams(int(k), int(itopk), int(width), int(iters), int(n_seeds), int(n_workers), int(ring_slots), 0,
-                            int(max_jobs), int(idle_polls))
+        prm = VfServeParams(int(k), int(itopk), int(width), int(iters), int(n_seeds), int(n_workers), int(ring_slots),
+                            int(waves_per_worker), int(max_jobs), int(idle_polls))
         h = C.c_void_p()
         index._enter()
         _check(load_library().vf_serve_begin(index._h, C.byref(prm), C.byref(h)))

@@ -159,6 +159,108 @@ __device__ __forceinline__ void merge_sorted_run(TopM<1> &list, uint64_t key, in
     list.worst = readlane64(m, list.itopk - 1);
 }
 
+// Offers the keys held one per lane (distance bits, id; distinct and none of them in the list yet) to a
+// one-register list: many at once through a sort and merge, a few one by one.
+__device__ __forceinline__ void offer_distinct(TopM<1> &list, bool valid, uint32_t bits, int id, int lane)
+{
+    const bool in = valid && bits <= (uint32_t)(list.worst >> 32);
+    uint64_t m = __ballot(in);
+    if (__popcll(m) >= 10) {
+        merge_batch(list, in ? ((uint64_t)bits << 32) | ((uint64_t)(uint32_t)id << 1) | 1ull : KEY_MAX, lane);
+        return;
+    }
+    while (m) {
+        const int b = __builtin_ctzll(m);
+        m &= m - 1;
+        const uint32_t kb = __builtin_amdgcn_readlane(bits, b);
+        const uint32_t kc = (uint32_t)__builtin_amdgcn_readlane(id, b);
+        list.insert(((uint64_t)kb << 32) | ((uint64_t)kc << 1) | 1ull, lane);
+    }
+}
+
+// A wave scores seeds [j_lo, j_hi) of a list itself from the interleaved copy of the seeds (p.sblk; a wave that
+// serves one query at a time has no tile of queries to share a dense kernel with) and offers them to `list`: one
+// seed per lane, 64 seeds a step, every load a coalesced 16-byte chunk, the query (qv, LDS) a broadcast.  A lane
+// walks its seed's chunks in the order of the 8-lane teams (partial sum t takes chunks t, t + 8, ...; fused
+// multiply-add; the fixed tree), so the bits are those of a gathered evaluation.  Seeds that fail the predicate
+// (others / o_cnt) are left out.  as_index: the list stores the seed index j instead of the local id.
+template <int DT>
+__device__ __forceinline__ void stream_seed_segment(const BeamParams &p, int label, const int32_t *others, int o_cnt,
+                                                    const uint4 *qv, int nchunks, int j_lo, int j_hi, bool as_index,
+                                                    TopM<1> &list, int lane)
+{
+    const int n = p.meta.S[label];
+    const int ns = p.n_seeds < n ? p.n_seeds : n;
+    const int64_t base = p.meta.O_HS[label];
+    const int64_t g0 = p.sgoff[p.meta.hs_slot[label]];
+    int qq_all = 0;
+    if (DT == 0) {
+        for (int ci = 0; ci < nchunks; ++ci) {
+            const uint4 q = qv[ci];
+            qq_all = (int)__builtin_amdgcn_udot4(q.x, q.x, (uint32_t)qq_all, false);
+            qq_all = (int)__builtin_amdgcn_udot4(q.y, q.y, (uint32_t)qq_all, false);
+            qq_all = (int)__builtin_amdgcn_udot4(q.z, q.z, (uint32_t)qq_all, false);
+            qq_all = (int)__builtin_amdgcn_udot4(q.w, q.w, (uint32_t)qq_all, false);
+        }
+    }
+    for (int j0 = j_lo; j0 < j_hi; j0 += 64) {
+        const int j = j0 + lane;
+        const bool valid = j < j_hi;
+        const int je = valid ? j : j_hi - 1;   // lanes past the end re-read the last seed (in bounds), masked below
+        const uint4 *col = p.sblk + (g0 + (je >> 5)) * (int64_t)(p.sblk_chunks * 32) + (je & 31);
+        uint32_t bits;
+        if (DT == 0) {
+            uint32_t xx = 0, qx = 0;
+            for (int c0 = 0; c0 < nchunks; c0 += 8) {
+                uint4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (c0 + u < nchunks) {
+                        const uint4 q = qv[c0 + u];
+                        xx = __builtin_amdgcn_udot4(x[u].x, x[u].x, xx, false); qx = __builtin_amdgcn_udot4(q.x, x[u].x, qx, false);
+                        xx = __builtin_amdgcn_udot4(x[u].y, x[u].y, xx, false); qx = __builtin_amdgcn_udot4(q.y, x[u].y, qx, false);
+                        xx = __builtin_amdgcn_udot4(x[u].z, x[u].z, xx, false); qx = __builtin_amdgcn_udot4(q.z, x[u].z, qx, false);
+                        xx = __builtin_amdgcn_udot4(x[u].w, x[u].w, xx, false); qx = __builtin_amdgcn_udot4(q.w, x[u].w, qx, false);
+                    }
+                }
+            }
+            bits = (uint32_t)(qq_all + (int)xx - 2 * (int)qx);
+        } else {
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = 0.0f;
+            for (int c0 = 0; c0 < nchunks; c0 += 8) {   // chunk c0 + u belongs to partial sum u
+                uint4 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (c0 + u < nchunks) {
+                        const uint4 q = qv[c0 + u];
+                        float d;
+                        d = __uint_as_float(q.x) - __uint_as_float(x[u].x); a[u] = __builtin_fmaf(d, d, a[u]);
+                        d = __uint_as_float(q.y) - __uint_as_float(x[u].y); a[u] = __builtin_fmaf(d, d, a[u]);
+                        d = __uint_as_float(q.z) - __uint_as_float(x[u].z); a[u] = __builtin_fmaf(d, d, a[u]);
+                        d = __uint_as_float(q.w) - __uint_as_float(x[u].w); a[u] = __builtin_fmaf(d, d, a[u]);
+                    }
+                }
+            }
+            const float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];
+            const float c0s = b0 + b1, c1s = b2 + b3;
+            bits = __float_as_uint(c0s + c1s);
+        }
+        const int c = valid ? seed_local_id((uint32_t)j, (uint32_t)n, (uint32_t)ns) : 0;
+        bool pass = valid;
+        if (o_cnt > 0 && valid) {
+            const int g = p.meta.M_HS[base + c];
+            for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, others[o], g);
+        }
+        offer_distinct(list, pass, bits, as_index ? j : c, lane);
+    }
+}
+
 // One query of a beam search launch: where its inputs and outputs are.
 struct BeamQuery {
     const void *q;             // the query vector (16-byte aligned)
@@ -174,13 +276,14 @@ struct BeamQuery {
     int32_t seed_pass;         // seeds that pass the predicate (profiling, AND), -1: not counted
 };
 
-// The search of one query by one wave (a one-wave workgroup: __syncthreads orders the wave's LDS traffic).
+// The search of one query by one wave: a one-wave workgroup, or (STREAM_SEEDS, the serving kernel) one wave of a
+// larger workgroup working by itself (wave_sync orders the wave's LDS traffic either way).
 // smem: beam_lds_bytes of LDS.
 // AND = false: compiled for batches without predicate labels (none of the predicate's code and registers).
 template <int DT, int E, bool STREAM_SEEDS = false, bool AND = true>
 __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const BeamQuery &bq, uint4 *smem)
 {
-    const int lane = threadIdx.x, team = lane >> 3, tl = lane & 7;
+    const int lane = wave_lane<STREAM_SEEDS>(), team = lane >> 3, tl = lane & 7;
     const int label = bq.label;
     const int n = p.meta.S[label];
     const int64_t base = p.meta.O_HS[label];
@@ -198,7 +301,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     for (int i = lane; i < nchunks; i += 64)
         qv[i] = *(const uint4 *)((const char *)bq.q + i * kChunkBytes);
     for (int i = lane; i < (1 << p.hash_bits); i += 64) hash[i] = 0xFFFFFFFFu;
-    __syncthreads();
+    wave_sync<STREAM_SEEDS>();
 
     const int o_cnt = AND ? bq.o_cnt : 0;
     const int qq_lane = DT == 0 ? lane_qq_u8(qv, nchunks, tl) : 0;
@@ -241,7 +344,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             else bits = team_dist_bits_f32(qv, xrow, nchunks, tl);
             if (tl == 0 && my < cnt) cand_d[my] = bits;
         }
-        __syncthreads();
+        wave_sync<STREAM_SEEDS>();
         for (int i0 = 0; i0 < cnt; i0 += 64) {
             const int i = i0 + lane;
             const bool valid = i < cnt;
@@ -324,7 +427,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             bool lazy = lazy_ok && o_cnt > 0 && list.worst != KEY_MAX;
             // seeds at or below the bound, compacted into cand[] (those beyond its 128 slots only counted)
             auto compact = [&](uint32_t tau) -> int {
-                __syncthreads();
+                wave_sync<STREAM_SEEDS>();
                 int cnt = 0;
 #pragma unroll
                 for (int i = 0; i < NBLK; ++i) {
@@ -338,7 +441,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                     }
                     cnt += __popcll(m);
                 }
-                __syncthreads();
+                wave_sync<STREAM_SEEDS>();
                 return cnt;
             };
             int cnt;
@@ -436,10 +539,10 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 const bool valid = key != KEY_MAX;
                 const int c = valid ? seed_local_id((uint32_t)(key >> 1) & 0x7FFFFFFFu, (uint32_t)n, (uint32_t)ns) : 0;
                 // the kept seeds sit in lanes 0 .. cnt - 1 (sorted list) and have passed the predicate already
-                __syncthreads();
+                wave_sync<STREAM_SEEDS>();
                 const int cnt = __popcll(__ballot(valid));
                 if (valid) { cand_c[lane] = c; cand_g[lane] = p.meta.M_HS[base + c]; }
-                __syncthreads();
+                wave_sync<STREAM_SEEDS>();
                 score(cnt, true);
                 float qn = 0.f;
                 for (int i = lane; i < nchunks; i += 64) {
@@ -504,92 +607,16 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             offer(pass, bits, c);
         }
         fix_seed_count();
-    } else if (STREAM_SEEDS && p.sblk != nullptr) {
-        // The wave scores its seeds itself from the interleaved copy (a wave that serves one query at a time has
-        // no tile of queries to share a dense kernel with): one seed per lane, 64 seeds a step, every load a
-        // coalesced 16-byte chunk, the query a broadcast from LDS.  A lane walks its seed's chunks in the order
-        // of the 8-lane teams (partial sum t takes chunks t, t + 8, ...; fused multiply-add; the fixed tree), so
-        // the bits are those of a gathered evaluation.
-        const int64_t g0 = p.sgoff[p.meta.hs_slot[label]];
-        int qq_all = 0;
-        if (DT == 0) {
-            for (int ci = 0; ci < nchunks; ++ci) {
-                const uint4 q = qv[ci];
-                qq_all = (int)__builtin_amdgcn_udot4(q.x, q.x, (uint32_t)qq_all, false);
-                qq_all = (int)__builtin_amdgcn_udot4(q.y, q.y, (uint32_t)qq_all, false);
-                qq_all = (int)__builtin_amdgcn_udot4(q.z, q.z, (uint32_t)qq_all, false);
-                qq_all = (int)__builtin_amdgcn_udot4(q.w, q.w, (uint32_t)qq_all, false);
-            }
-        }
-        for (int j0 = 0; j0 < ns; j0 += 64) {
-            const int j = j0 + lane;
-            const bool valid = j < ns;
-            const int je = valid ? j : ns - 1;   // lanes past the end re-read the last seed (in bounds), masked below
-            const uint4 *col = p.sblk + (g0 + (je >> 5)) * (int64_t)(p.sblk_chunks * 32) + (je & 31);
-            uint32_t bits;
-            if (DT == 0) {
-                uint32_t xx = 0, qx = 0;
-                for (int c0 = 0; c0 < nchunks; c0 += 8) {
-                    uint4 x[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        if (c0 + u < nchunks) {
-                            const uint4 q = qv[c0 + u];
-                            xx = __builtin_amdgcn_udot4(x[u].x, x[u].x, xx, false); qx = __builtin_amdgcn_udot4(q.x, x[u].x, qx, false);
-                            xx = __builtin_amdgcn_udot4(x[u].y, x[u].y, xx, false); qx = __builtin_amdgcn_udot4(q.y, x[u].y, qx, false);
-                            xx = __builtin_amdgcn_udot4(x[u].z, x[u].z, xx, false); qx = __builtin_amdgcn_udot4(q.z, x[u].z, qx, false);
-                            xx = __builtin_amdgcn_udot4(x[u].w, x[u].w, xx, false); qx = __builtin_amdgcn_udot4(q.w, x[u].w, qx, false);
-                        }
-                    }
-                }
-                bits = (uint32_t)(qq_all + (int)xx - 2 * (int)qx);
-            } else {
-                float a[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) a[u] = 0.0f;
-                for (int c0 = 0; c0 < nchunks; c0 += 8) {   // chunk c0 + u belongs to partial sum u
-                    uint4 x[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) x[u] = col[(int64_t)((c0 + u < nchunks) ? c0 + u : nchunks - 1) * 32];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        if (c0 + u < nchunks) {
-                            const uint4 q = qv[c0 + u];
-                            float d;
-                            d = __uint_as_float(q.x) - __uint_as_float(x[u].x); a[u] = __builtin_fmaf(d, d, a[u]);
-                            d = __uint_as_float(q.y) - __uint_as_float(x[u].y); a[u] = __builtin_fmaf(d, d, a[u]);
-                            d = __uint_as_float(q.z) - __uint_as_float(x[u].z); a[u] = __builtin_fmaf(d, d, a[u]);
-                            d = __uint_as_float(q.w) - __uint_as_float(x[u].w); a[u] = __builtin_fmaf(d, d, a[u]);
-                        }
-                    }
-                }
-                const float b0 = a[0] + a[1], b1 = a[2] + a[3], b2 = a[4] + a[5], b3 = a[6] + a[7];
-                const float c0s = b0 + b1, c1s = b2 + b3;
-                bits = __float_as_uint(c0s + c1s);
-            }
-            const int c = valid ? seed_local_id((uint32_t)j, (uint32_t)n, (uint32_t)ns) : 0;
-            bool pass = valid;
-            if (o_cnt > 0) {
-                n_tested += __popcll(__ballot(valid));
-                if (valid) {
-                    const int g = p.meta.M_HS[base + c];
-                    for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, bq.others[o], g);
-                }
-            }
-            n_scored += __popcll(__ballot(pass));
-            if constexpr (E == 1) offer_seeds_to(top, pass, bits, c);
-            else offer(pass, bits, c);
-        }
+    } else if (STREAM_SEEDS && E == 1 && p.sblk != nullptr) {
+        if constexpr (E == 1) stream_seed_segment<DT>(p, label, bq.others, o_cnt, qv, nchunks, 0, ns, false, top, lane);
     } else {
         for (int j0 = 0; j0 < ns; j0 += 64) {
             const int j = j0 + lane;
             const bool valid = j < ns;
             const int c = valid ? (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns) : 0;
-            __syncthreads();
+            wave_sync<STREAM_SEEDS>();
             const int cnt = filter_and_compact(valid, c, 0);
-            __syncthreads();
+            wave_sync<STREAM_SEEDS>();
             score(cnt);
         }
     }
@@ -619,7 +646,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             for (int r = 0; r < E; ++r)
                 if (r == wr) top.worst = readlane64(top.cur[r], wl);
         }
-        __syncthreads();
+        wave_sync<STREAM_SEEDS>();
         if (np == 0) break;
         n_expanded += np;
         int cnt = 0;
@@ -639,7 +666,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             }
             cnt = filter_and_compact(valid, c, cnt, g);
         }
-        __syncthreads();
+        wave_sync<STREAM_SEEDS>();
         score(cnt);
     }
 

@@ -26,6 +26,20 @@ __device__ __forceinline__ bool has_label(const LabelMeta &m, int32_t l, int32_t
     return false;
 }
 
+// The barrier of a one-wave workgroup; or (WAVE_ONLY), for a wave that works by itself inside a larger workgroup
+// (the serving kernel's workers), only what a one-wave barrier is needed for: the ordering of the wave's own LDS
+// traffic -- without the workgroup barrier the other waves would have to join.
+template <bool WAVE_ONLY> __device__ __forceinline__ void wave_sync()
+{
+    if constexpr (WAVE_ONLY) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
+    }
+}
+template <bool WAVE_ONLY> __device__ __forceinline__ int wave_lane() { return WAVE_ONLY ? (int)(threadIdx.x & 63u) : (int)threadIdx.x; }
+
 // float -> bfloat16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t bf16_rn_bits(float f)
 {

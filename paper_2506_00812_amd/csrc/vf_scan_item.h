@@ -17,10 +17,11 @@ template <> struct Acc<1> { using type = v16f; };
 
 constexpr int kDrainRows = 4;   // rows merged at a time by the 64-lane networks
 
-template <int DT, int NCP>
+// WAVE_ONLY: the wave works by itself inside a larger workgroup (the serving kernel), see wave_sync
+template <int DT, int NCP, bool WAVE_ONLY = false>
 __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanItem &it, uint4 *smem)
 {
-    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int lane = wave_lane<WAVE_ONLY>(), n32 = lane & 31, h = lane >> 5;
     const int ncp = NCP > 0 ? NCP : p.ncp;
     const int nchunks = 2 * ncp, K = p.K;
     const int row_bytes = p.dim * (DT == 0 ? 1 : 4);
@@ -38,7 +39,7 @@ __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanIt
 
     if (lane < 32) { qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1; pcnt[lane] = 0; }
     for (int i = lane; i < p.tile_rows * KS; i += 64) best[i] = KEY_MAX;
-    __syncthreads();
+    wave_sync<WAVE_ONLY>();
 
     // ---- stage the query tile, chunk-major, and its norms
     {
@@ -67,7 +68,7 @@ __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanIt
             }
         }
     }
-    __syncthreads();
+    wave_sync<WAVE_ONLY>();
     {
         // row n32, chunks h, h+2, ...
         if (DT == 0) {
@@ -97,7 +98,7 @@ __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanIt
             if (h == 0) qnorm_s[n32] = __float_as_uint(acc);
         }
     }
-    __syncthreads();
+    wave_sync<WAVE_ONLY>();
 
     // per-lane constants for its 16 accumulator rows: row(j) = 8*(j/4) + 4*h + (j%4)
     uint32_t qn[16], thr[16];
@@ -248,7 +249,7 @@ __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanIt
         }
         if (__any(pcv > PC - 32) || (grp + 1 == n_groups && __any(pcv != 0))) drain();
     }
-    __syncthreads();
+    wave_sync<WAVE_ONLY>();
 
     // ---- results: every row's K best are already in ascending order
     for (int r = 0; r < it.q_count; ++r) {
@@ -275,7 +276,7 @@ __device__ __forceinline__ void scan_topk_item(const ScanParams &p, const ScanIt
 template <int NCH, bool QLDS = false>
 __device__ __forceinline__ void scan_valu_item(const ScanParams &p, const ScanItem &it, uint4 *smem, const float *q_lds = nullptr)
 {
-    const int lane = threadIdx.x, n32 = lane & 31, h = lane >> 5;
+    const int lane = wave_lane<QLDS>(), n32 = lane & 31, h = lane >> 5;
     const int K = p.K, KS = K | 1, TR = p.tile_rows;
     constexpr int PC = 96;   // a step adds <= 64 keys to a row and rows above 32 are drained after every step
     constexpr int row_bytes = NCH * kChunkBytes;
@@ -286,7 +287,7 @@ __device__ __forceinline__ void scan_valu_item(const ScanParams &p, const ScanIt
 
     if (lane < 32) qrow_s[lane] = lane < it.q_count ? p.qrow[it.q_begin + lane] : -1;
     for (int i = lane; i < TR * KS; i += 64) best[i] = KEY_MAX;
-    __syncthreads();
+    wave_sync<QLDS>();
     for (int r = 0; r < it.q_count; ++r) {
         float acc = 0.f;
         if (lane < NCH) {
@@ -298,7 +299,7 @@ __device__ __forceinline__ void scan_valu_item(const ScanParams &p, const ScanIt
         for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
         if (lane == 0) qnorm_s[r] = acc;
     }
-    __syncthreads();
+    wave_sync<QLDS>();
 
     // state of tile row r, held by lane r
     int pcv = 0;
@@ -379,7 +380,7 @@ __device__ __forceinline__ void scan_valu_item(const ScanParams &p, const ScanIt
             wave_lds_sync();
         }
     }
-    __syncthreads();
+    wave_sync<QLDS>();
 
     for (int r = 0; r < it.q_count; ++r) {
         if (lane >= K) continue;

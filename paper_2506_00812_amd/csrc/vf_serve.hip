@@ -4,8 +4,9 @@
 // Shape on this machine.  The host writes a job (query vector + labels) into a ring in pinned host memory and
 // bumps a counter.  Workgroup 0 of the resident kernel is the DISPATCHER: it alone polls that counter across
 // PCIe, copies new jobs into a ring in device memory and publishes them by advancing a device-side tail.  The
-// other workgroups are WORKERS (one wave each, one query at a time, as in the paper's one block per query):
-// a worker claims the next job with a compare-and-swap on the device-side head -- the atomic ring buffer of
+// other workgroups are WORKERS (one query at a time, as in the paper's one block per query; NW waves each: all of
+// them score a share of the query's seeds, then the first wave searches while the others wait at the workgroup's
+// barrier): a worker claims the next job with a compare-and-swap on the device-side head -- the atomic ring buffer of
 // the paper's figure; "which worker is free" needs no queue of its own, a free worker is one that is polling --
 // routes it (smallest list, graph or scan by T, Section 4.1.2 / 4.3.2), runs the same beam search or list
 // scan the batched kernels run (the device functions are shared), writes the k results straight into the
@@ -70,7 +71,8 @@ struct ServeParams {
     ServeHostCtrl *hctrl;       // device view
     ServeDevCtrl *dctrl;
     int64_t max_jobs, idle_polls;
-    int32_t lds_kernels;        // bytes of LDS the search functions use; the worker's own words follow
+    int32_t lds_kernels;        // bytes of LDS the search functions use; the worker's own words follow (lds_own bytes)
+    int32_t lds_own;
 };
 
 template <class T> __device__ __forceinline__ T load_sys(const T *p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM); }
@@ -78,14 +80,15 @@ template <class T> __device__ __forceinline__ T load_dev(const T *p) { return __
 
 // DT: 0 uint8, 1 float32.  NC: compile-time chunk count of the scan function (chunk pairs for scan_topk_item,
 // chunks for scan_valu_item), 0 = generic.
-template <int DT, int NC>
-__global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
+template <int DT, int NC, int NW>
+__global__ __launch_bounds__(64 * NW) void serve_kernel(ServeParams p)
 {
     extern __shared__ uint4 smem[];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 
     if (blockIdx.x == 0) {
-        // ---------------- dispatcher
+        // ---------------- dispatcher (the first wave; it never meets a workgroup barrier)
+        if (wv != 0) return;
         uint64_t published = 0;
         int64_t idle = 0;
         uint32_t reason = 0;
@@ -128,11 +131,17 @@ __global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
     }
 
     // ---------------- worker
-    // [0..7] others, [8..9] others_off, [10] qrow, [11..12] job, [16..] the query (FMA scan only)
+    // Every wave of the workgroup passes the same four barriers per job.  LDS: the search functions' area (first
+    // wave), then [0..7] others, [8..9] others_off, [10] qrow, [11..12] job, [16..] the query (FMA scan only), then
+    // per wave a copy of the query and a run of 64 seed keys.
     int32_t *own = (int32_t *)((char *)smem + p.lds_kernels);
+    char *share = (char *)smem + p.lds_kernels + p.lds_own;
+    const int q_bytes = (p.row_bytes + 15) & ~15;
+    uint4 *hq = (uint4 *)(share + (size_t)wv * q_bytes);                         // this wave's copy of the query
+    uint64_t *runs = (uint64_t *)(share + (size_t)NW * q_bytes);                 // [NW][64]
     int64_t idle = 0;
     while (true) {
-        if (lane == 0) {
+        if (wv == 0 && lane == 0) {
             int64_t job = -1;
             while (true) {
                 const uint64_t h = load_dev(&p.dctrl->head), t = load_dev(&p.dctrl->tail);
@@ -146,13 +155,13 @@ __global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
                 if (++idle > 16 * p.idle_polls) break;          // nothing for very long: the dispatcher must be gone
                 __builtin_amdgcn_s_sleep(32);
             }
+            idle = 0;
             own[11] = (int32_t)(job & 0xFFFFFFFFll);
             own[12] = (int32_t)(job >> 32);
         }
         __syncthreads();
         const int64_t job = ((int64_t)own[12] << 32) | (uint32_t)own[11];
-        if (job < 0) return;
-        idle = 0;
+        if (job < 0) return;   // (the whole workgroup: every wave reads the same word)
         // an acquire by every lane: the job's slot may sit in this CU's cache from an earlier trip round the ring
         (void)load_dev(&p.dctrl->tail);
         const size_t soff = (size_t)((uint64_t)job % (uint64_t)p.ring_slots);
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
             if (sl < sb || (sl == sb && labs[i] < best)) best = labs[i];
         }
         int o_cnt = 0;
-        if (lane == 0) {
+        if (wv == 0 && lane == 0) {
             for (int i = 0; i < nl; ++i)
                 if (labs[i] != best) own[o_cnt++] = labs[i];
             own[8] = 0; own[9] = o_cnt; own[10] = 0;
@@ -191,37 +200,65 @@ __global__ __launch_bounds__(64) void serve_kernel(ServeParams p)
         __syncthreads();
 
         const int k = p.bp.k;
-        if (empty) {
-            if (lane < k) { res->ids[lane] = -1; res->dists[lane] = __builtin_inff(); }
-        } else if (p.bp.meta.S[best] >= p.T) {
-            BeamQuery bq;
-            bq.q = qvec; bq.label = best; bq.others = own; bq.o_cnt = o_cnt;
-            bq.out_ids = res->ids; bq.out_dists = res->dists;
-            bq.counters = nullptr; bq.gathered = nullptr; bq.dseed_row = nullptr; bq.runs = nullptr; bq.seed_pass = -1;
-            beam_search_wave<DT, 1, true>(p.bp, bq, smem);
-        } else {
-            ScanParams sp = p.sp;
-            sp.qsrc = qvec; sp.qrow = own + 10;
-            sp.others_off = o_cnt > 0 ? own + 8 : nullptr; sp.others = own;
-            sp.out_ids = res->ids; sp.out_dists = res->dists;
-            ScanItem it;
-            it.group0 = p.GO_LS[best]; it.map_off = p.bp.meta.O_LS[best]; it.entry0 = 0; it.n = p.bp.meta.S[best];
-            it.q_begin = 0; it.q_count = 1; it.self_base = -1; it.part_row = -1;
-            if constexpr (DT == 1 && (NC == 24 || NC == 32)) {
-                // the FMA scan takes its query as a wave-uniform operand: from LDS here (see scan_valu_item)
-                float *q_lds = (float *)(own + 16);
-                for (int i = lane; i < NC; i += 64) ((uint4 *)q_lds)[i] = ((const uint4 *)qvec)[i];
-                __syncthreads();
-                scan_valu_item<NC, true>(sp, it, smem, q_lds);
-            } else {
-                scan_topk_item<DT, NC>(sp, it, smem);
-            }
+        const bool graph = !empty && p.bp.meta.S[best] >= p.T;
+        // the seeds of a graph job are shared out over the workgroup's waves: each scores its share from the
+        // interleaved seed copy into a list of its own and leaves that list as a sorted run of keys
+        const bool shared_seeds = graph && p.bp.sblk != nullptr;
+        int seg = 64;
+        if (shared_seeds) {
+            const int n = p.bp.meta.S[best];
+            const int ns = p.bp.n_seeds < n ? p.bp.n_seeds : n;
+            const int nchunks = p.row_bytes / kChunkBytes;
+            seg = (((ns + NW - 1) / NW) + 63) & ~63;
+            const int j_lo = wv * seg, j_hi = j_lo + seg < ns ? j_lo + seg : ns;
+            for (int i = lane; i < nchunks; i += 64) hq[i] = ((const uint4 *)qvec)[i];
+            wave_sync<true>();
+            TopM<1> part;
+            part.init(p.bp.itopk);
+            if (j_lo < j_hi) stream_seed_segment<DT>(p.bp, best, own, o_cnt, hq, nchunks, j_lo, j_hi, true, part, lane);
+            const uint64_t key = part.cur[0];   // (distance bits << 32 | seed index << 1 | 1), ascending
+            runs[wv * 64 + lane] = key == KEY_MAX ? KEY_MAX : (key & 0xFFFFFFFF00000000ull) | ((key >> 1) & 0x7FFFFFFFull);
         }
         __syncthreads();
-        __threadfence_system();
-        if (lane == 0) {
-            __hip_atomic_store(&res->done, (uint64_t)job + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-            __hip_atomic_fetch_add(&p.dctrl->jobs_done, (uint64_t)1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+
+        if (wv == 0) {
+            if (empty) {
+                if (lane < k) { res->ids[lane] = -1; res->dists[lane] = __builtin_inff(); }
+            } else if (graph) {
+                BeamQuery bq;
+                bq.q = qvec; bq.label = best; bq.others = own; bq.o_cnt = o_cnt;
+                bq.out_ids = res->ids; bq.out_dists = res->dists;
+                bq.counters = nullptr; bq.gathered = nullptr; bq.dseed_row = nullptr; bq.runs = nullptr; bq.seed_pass = -1;
+                BeamParams bp = p.bp;
+                if (shared_seeds) {   // the waves' runs, merged by the search as the runs of a selecting seed kernel would be
+                    bq.runs = runs;
+                    bp.run_K = 64; bp.run_segs = NW; bp.seg_seeds = seg; bp.seed_approx = 0;
+                }
+                beam_search_wave<DT, 1, true>(bp, bq, smem);
+            } else {
+                ScanParams sp = p.sp;
+                sp.qsrc = qvec; sp.qrow = own + 10;
+                sp.others_off = o_cnt > 0 ? own + 8 : nullptr; sp.others = own;
+                sp.out_ids = res->ids; sp.out_dists = res->dists;
+                ScanItem it;
+                it.group0 = p.GO_LS[best]; it.map_off = p.bp.meta.O_LS[best]; it.entry0 = 0; it.n = p.bp.meta.S[best];
+                it.q_begin = 0; it.q_count = 1; it.self_base = -1; it.part_row = -1;
+                if constexpr (DT == 1 && (NC == 24 || NC == 32)) {
+                    // the FMA scan takes its query as a wave-uniform operand: from LDS here (see scan_valu_item)
+                    float *q_lds = (float *)(own + 16);
+                    for (int i = lane; i < NC; i += 64) ((uint4 *)q_lds)[i] = ((const uint4 *)qvec)[i];
+                    wave_sync<true>();
+                    scan_valu_item<NC, true>(sp, it, smem, q_lds);
+                } else {
+                    scan_topk_item<DT, NC, true>(sp, it, smem);
+                }
+            }
+            wave_sync<true>();
+            __threadfence_system();
+            if (lane == 0) {
+                __hip_atomic_store(&res->done, (uint64_t)job + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_fetch_add(&p.dctrl->jobs_done, (uint64_t)1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         __syncthreads();
     }
@@ -258,9 +295,12 @@ static void free_server(vf_server *sv)
     delete sv;
 }
 
-template <int DT, int NC> static void launch_serve(const ServeParams &p, int n_workers, size_t lds, hipStream_t s)
+template <int DT, int NC> static void launch_serve(const ServeParams &p, int n_workers, int waves, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL((serve_kernel<DT, NC>), dim3(1 + n_workers), dim3(64), lds, s, p);
+    const dim3 grid(1 + n_workers);
+    if (waves == 1) hipLaunchKernelGGL((serve_kernel<DT, NC, 1>), grid, dim3(64), lds, s, p);
+    else if (waves == 4) hipLaunchKernelGGL((serve_kernel<DT, NC, 4>), grid, dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((serve_kernel<DT, NC, 8>), grid, dim3(512), lds, s, p);
 }
 
 static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server **out)
@@ -274,8 +314,10 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     if (rc != VF_OK) return rc;
     VF_REQUIRE(itopk <= 64, "vf_serve_begin: itopk must be at most 64");
     const int32_t n_workers = prm->n_workers > 0 ? prm->n_workers : 240;
+    const int32_t waves = prm->waves_per_worker > 0 ? prm->waves_per_worker : 8;
+    VF_REQUIRE(waves == 1 || waves == 4 || waves == 8, "waves_per_worker must be 1, 4 or 8 (0 = 8)");
     const int32_t ring_slots = prm->ring_slots > 0 ? prm->ring_slots : 1024;
-    // every workgroup must be resident at once (one wave each: a CU takes several)
+    // every workgroup must be resident at once (a CU takes several)
     VF_REQUIRE(n_workers >= 1 && n_workers <= 1023, "n_workers must be in [1, 1023]");
     VF_REQUIRE(ring_slots >= 1 && ring_slots <= (1 << 20), "ring_slots must be in [1, 2^20]");
     const int64_t max_jobs = prm->max_jobs > 0 ? prm->max_jobs : ((int64_t)1 << 62);
@@ -328,8 +370,10 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     const bool valu = scan_valu_supported(ix->dtype, ix->dim, 16);
     const size_t scan_lds = valu ? (size_t)16 * (96 + (k | 1)) * 8 + 2 * 32 * 4 : scan_lds_bytes(ix->ncp, 16, k);
     const size_t lds_kernels = (std::max(beam_lds, scan_lds) + 63) & ~(size_t)63;
-    const size_t lds_own = 64 + (valu ? (size_t)sv->row_bytes : 0);
-    VF_REQUIRE(lds_kernels + lds_own <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
+    const size_t lds_own = (64 + (valu ? (size_t)sv->row_bytes : 0) + 63) & ~(size_t)63;
+    // per wave a copy of the query and a run of 64 seed keys
+    const size_t lds_share = (size_t)waves * ((((size_t)sv->row_bytes + 15) & ~(size_t)15) + 64 * 8);
+    VF_REQUIRE(lds_kernels + lds_own + lds_share <= 64 * 1024, "search parameters need more than 64 KiB of LDS");
     p.GO_LS = sv->d_GO_LS.as<int64_t>(); p.T = ix->T; p.n_labels = ix->n_labels;
     p.ring_slots = ring_slots; p.slot_stride = sv->slot_stride; p.row_bytes = sv->row_bytes;
     void *dv = nullptr;
@@ -337,16 +381,16 @@ static int serve_begin_impl(vf_index *ix, const vf_serve_params *prm, vf_server 
     VF_HIP(hipHostGetDevicePointer(&dv, sv->h_results, 0)); p.results = (ServeResult *)dv;
     VF_HIP(hipHostGetDevicePointer(&dv, sv->h_ctrl, 0)); p.hctrl = (ServeHostCtrl *)dv;
     p.dev_ring = sv->d_ring.as<char>(); p.dctrl = sv->d_ctrl.as<ServeDevCtrl>();
-    p.max_jobs = max_jobs; p.idle_polls = idle_polls; p.lds_kernels = (int32_t)lds_kernels;
-    const size_t lds = lds_kernels + lds_own;
+    p.max_jobs = max_jobs; p.idle_polls = idle_polls; p.lds_kernels = (int32_t)lds_kernels; p.lds_own = (int32_t)lds_own;
+    const size_t lds = lds_kernels + lds_own + lds_share;
     if (ix->dtype == VF_U8) {
-        if (ix->dim == 128) launch_serve<0, 4>(p, n_workers, lds, sv->stream);
-        else if (ix->dim == 192) launch_serve<0, 6>(p, n_workers, lds, sv->stream);
-        else launch_serve<0, 0>(p, n_workers, lds, sv->stream);
+        if (ix->dim == 128) launch_serve<0, 4>(p, n_workers, waves, lds, sv->stream);
+        else if (ix->dim == 192) launch_serve<0, 6>(p, n_workers, waves, lds, sv->stream);
+        else launch_serve<0, 0>(p, n_workers, waves, lds, sv->stream);
     } else {
-        if (ix->dim == 128) launch_serve<1, 32>(p, n_workers, lds, sv->stream);
-        else if (ix->dim == 96) launch_serve<1, 24>(p, n_workers, lds, sv->stream);
-        else launch_serve<1, 0>(p, n_workers, lds, sv->stream);
+        if (ix->dim == 128) launch_serve<1, 32>(p, n_workers, waves, lds, sv->stream);
+        else if (ix->dim == 96) launch_serve<1, 24>(p, n_workers, waves, lds, sv->stream);
+        else launch_serve<1, 0>(p, n_workers, waves, lds, sv->stream);
     }
     VF_HIP(hipGetLastError());
     sv->launched = true;

@@ -97,6 +97,15 @@ def test_served_queries_equal_batched_search(vf, name):
     finally:
         done, why = srv.end()
     assert done == 2 * nq and why == 1
+    # workers of one and of four waves (the default is eight): the seeds are shared out differently, the bits are the same
+    for waves in (1, 4):
+        srv = vf.Server(ix, 10, n_workers=32, ring_slots=256, waves_per_worker=waves, **params)
+        try:
+            wi, wd, _ = srv.run(w.queries[:nq], off, ids, in_flight=32)
+        finally:
+            done, why = srv.end()
+        assert done == nq and why == 1
+        assert np.array_equal(wi, ri) and np.array_equal(wd.view(np.uint32), rd.view(np.uint32)), f"{waves} waves per worker"
     gi = np.stack([got[j][0] for j in range(nq)])
     gd = np.stack([got[j][1] for j in range(nq)])
     assert np.array_equal(gi[graph], ref_i[graph]), "graph-searched jobs"
