@@ -257,7 +257,7 @@ def main():
     for params in cands:
         if params[1] * s.graph_degree > 128:
             continue
-        ms = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, params, 3, 1, out_ids, out_dists)
+        ms = time_search(vf, ix, Q, w.qlabel_offsets, w.qlabel_ids, k, params, 10 if s.nq <= 20000 else 3, 2, out_ids, out_dists)
         found = out_ids.cpu().numpy()
         rec = recall_of(found)
         table.append((params, rec, s.nq / ms * 1e3))
@@ -275,7 +275,7 @@ def main():
     # queries, whose answers are exact)
     ok_all = [t for t in table if worst_stratum[t[0]] >= 0.90]
     p90_all = max(ok_all, key=lambda t: t[2]) if ok_all else None
-    # several settings are within measurement noise of one another (three timed steps each); among those
+    # several settings are within measurement noise of one another (ten timed steps each); among those
     # within 10 % of the fastest, the one the committed rocprofv3 counters were taken at is preferred, so
     # that the `traffic` figure applies to the run
     pref = committed_params(s.name)

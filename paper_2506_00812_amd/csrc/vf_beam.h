@@ -434,6 +434,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                     const int j = jc + i * 64 + lane;
                     const bool pass = v[i] <= tau && v[i] != 0xFFFFFFFFu && j < ns;
                     const uint64_t m = __ballot(pass);
+                    if (m == 0) continue;   // (wave-uniform; with a full list most blocks of 64 hold no candidate)
                     const int at = cnt + __popcll(m & ((1ull << lane) - 1ull));
                     if (pass && at < 128) {
                         cand_d[at] = v[i];
@@ -453,7 +454,12 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 // (a full list bounds the chunk as well as that, or better from the third chunk on: its worst
                 // entry is the M-th smallest of everything before)
                 uint32_t tau = (uint32_t)(list.worst >> 32);
-                if (list.worst == KEY_MAX) {
+                // (a chunk whose passing seeds all fit into the list's free entries needs no bound: AND queries
+                // whose predicate passes few seeds spend most of their chunks in this state)
+                const bool all_fit = list.worst == KEY_MAX && o_cnt > 0 &&
+                                     __popcll(__ballot(list.cur[0] != KEY_MAX)) + chunk_scored <= list.itopk;
+                if (all_fit) tau = 0xFFFFFFFEu;
+                if (list.worst == KEY_MAX && !all_fit) {
                     uint32_t m1 = v[0], m2 = 0xFFFFFFFFu;
 #pragma unroll
                     for (int i = 1; i < NBLK; ++i) {

@@ -4,7 +4,7 @@
 namespace vf {
 
 template <int DT, int E, bool AND>
-__global__ __launch_bounds__(64, (DT == 1 && E == 1) ? 7 : 8) void beam_kernel(BeamParams p)
+__global__ __launch_bounds__(64, (DT == 1 && E == 1) ? (AND ? 6 : 7) : 8) void beam_kernel(BeamParams p)
 {
     extern __shared__ uint4 smem[];
     const int gq = blockIdx.x;
