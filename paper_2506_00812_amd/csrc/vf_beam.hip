@@ -1,4 +1,6 @@
 // Launch of the IVF-Graph beam search (Section 4.2.1, Alg. 2): one wave64 per graph query of the batch.
+#include <hip/hip_ext.h>
+
 #include "vf_beam.h"
 
 namespace vf {
@@ -35,22 +37,31 @@ size_t beam_lds_bytes(const BeamParams &p, int dtype)
     return row_bytes + 128 * 4 * 3 + 8 * 4 + ((size_t)4 << p.hash_bits);
 }
 
-template <int DT, bool AND> static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s)
+template <int DT, bool AND>
+static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 grid(n_gq), block(64);
-    if (p.itopk <= 64) hipLaunchKernelGGL((beam_kernel<DT, 1, AND>), grid, block, lds, s, p);
-    else if (p.itopk <= 128) hipLaunchKernelGGL((beam_kernel<DT, 2, AND>), grid, block, lds, s, p);
-    else hipLaunchKernelGGL((beam_kernel<DT, 4, AND>), grid, block, lds, s, p);
+    if (p.itopk <= 64) hipExtLaunchKernelGGL((beam_kernel<DT, 1, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
+    else if (p.itopk <= 128) hipExtLaunchKernelGGL((beam_kernel<DT, 2, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
+    else hipExtLaunchKernelGGL((beam_kernel<DT, 4, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
 }
 
-void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s)
+// start / stop (optional): events that take the kernel's own begin and end times.  Recording events around the
+// launch instead puts a barrier packet of their own before and behind the kernel, each of which delays the next
+// kernel on the stream by a few microseconds.
+void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s, hipEvent_t start, hipEvent_t stop)
 {
     if (n_gq <= 0) return;
     const size_t lds = beam_lds_bytes(p, dtype);
     // batches without predicate labels run an instantiation without the predicate's code
     const bool with_and = p.others_off != nullptr;
-    if (dtype == 0) { if (with_and) launch_beam_dt<0, true>(p, n_gq, lds, s); else launch_beam_dt<0, false>(p, n_gq, lds, s); }
-    else { if (with_and) launch_beam_dt<1, true>(p, n_gq, lds, s); else launch_beam_dt<1, false>(p, n_gq, lds, s); }
+    if (dtype == 0) {
+        if (with_and) launch_beam_dt<0, true>(p, n_gq, lds, s, start, stop);
+        else launch_beam_dt<0, false>(p, n_gq, lds, s, start, stop);
+    } else {
+        if (with_and) launch_beam_dt<1, true>(p, n_gq, lds, s, start, stop);
+        else launch_beam_dt<1, false>(p, n_gq, lds, s, start, stop);
+    }
 }
 
 }  // namespace vf

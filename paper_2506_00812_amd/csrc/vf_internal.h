@@ -225,7 +225,7 @@ void launch_seed_mfma(int dtype, const SeedParams &p, int n_tiles, hipStream_t s
 void launch_row_norms(int dtype, const void *X, int32_t dim, int64_t n, uint32_t *out, hipStream_t s);
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype);
-void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s);
+void launch_beam(int dtype, const BeamParams &p, int n_gq, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 // ---------------------------------------------------------------- build-time kernels
 

@@ -485,6 +485,10 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         bp.gathered = prof ? ix->counters.as<int32_t>() + (size_t)P.nq * 4 : nullptr;
         bp.dseed = nullptr; bp.ns_stride = P.ns_stride;
     }
+    // While profiling, the beam kernel's launch takes the two events that bracket it (end of seed scoring = its begin,
+    // and its end) as the kernel's own begin and end times: events recorded around it would each put a barrier packet
+    // on the stream, and the timed kernels a few microseconds apart.
+    const bool attach = prof && n_gq > 0 && P.n_xq == 0;
     auto count_passing_seeds = [&]() {
         if (prof && ix->prof_exact_counts && n_gq && (P.seed_select || P.dense_seeds) && r.any_and) {
             // profiling only, outside the timed interval: the counters report the seeds that pass the predicate as
@@ -581,7 +585,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
             bp.dseed = sd.dseed;
             if (prof && ix->prof_exact_counts && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
         }
-        if (prof) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
+        if (prof && !attach) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
         return VF_OK;
     };
     auto run_scan = [&]() -> int {
@@ -665,7 +669,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
     count_passing_seeds();
     if ((rc = run_scan()) != VF_OK) return rc;
     if ((rc = run_seeds()) != VF_OK) return rc;
-    if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s);
+    if (n_gq) launch_beam(ix->dtype, bp, (int)n_gq, s, attach ? ix->prof_ev[3] : nullptr, attach ? ix->prof_ev[4] : nullptr);
     if (P.n_xq) {
         // the exact route of short AND queries: the beam kernel with every member of the list as a seed, no
         // iteration and a list of k entries -- each member is tested with the predicate, the members that pass
@@ -688,7 +692,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         }
     }
     if (prof) {
-        VF_HIP(hipEventRecord(ix->prof_ev[4], s));
+        if (!attach) VF_HIP(hipEventRecord(ix->prof_ev[4], s));
         ix->prof_valid = true;
         ix->prof_next = (ix->prof_next + 1) % vf_index::kProfRing;
         ++ix->prof_unfolded;
