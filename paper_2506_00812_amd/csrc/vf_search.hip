@@ -290,6 +290,9 @@ int plan_call(const vf_index *ix, Routed &r, int64_t nq, const int64_t *qoff, co
         first_hs = 0;
         while (first_hs < r.scan_pairs.size() && ix->O_LS[(size_t)(r.scan_pairs[first_hs] >> 32)] >= 0) ++first_hs;
     }
+    ib.qrow.reserve(r.scan_pairs.size());     // (no regrowth while the work lists are built)
+    ib.items.reserve(r.scan_pairs.size());
+    ib.merges.reserve(r.scan_pairs.size());
     for (size_t i = 0; i < first_hs;) {
         const int32_t l = (int32_t)(r.scan_pairs[i] >> 32);
         size_t e = i;
