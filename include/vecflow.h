@@ -137,7 +137,12 @@ int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, c
  *                   floor(j * |C_l| / n_seeds); 0 means itopk
  *   out_ids         device [nq][k] global vector ids, ascending by (distance, id);
  *                   -1 where fewer than k vectors qualify
- *   out_dists       device [nq][k] squared distances; +inf where out_ids is -1
+ *   out_dists       device [nq][k] squared distances; +inf where out_ids is -1.  uint8: exact integers.
+ *                   float32: graph-searched queries, and scan-routed queries of batches with more than 256
+ *                   of them, carry the ordered float32 distance (eight partial sums over 16-byte chunks,
+ *                   fused multiply-add, a fixed tree); other scan-routed queries |q|^2 + |x|^2 - 2 q.x in
+ *                   float32, within 1e-4 relative of the exact value on data whose norms are comparable
+ *                   to the distances
  *   hip_stream      the search is enqueued on this stream and the call returns
  *                   without waiting; outputs are valid once the stream has been
  *                   synchronised.  Calls on one stream run in order.  Calls on
@@ -148,8 +153,8 @@ int vf_build_index_opt(const void *vectors, int dtype, int64_t n, int32_t dim, c
  *                   takes over the workspace of a stream that is idle, else it waits on
  *                   the host until one has drained.  This is how
  *                   small batches that arrive faster than one call completes are
- *                   served (the case of the paper's persistent kernel, Section 4.2.3,
- *                   which is not built).  vf_search_multi follows the same rule; profiled calls
+ *                   served by plain calls (the paper's own answer to that case, a resident
+ *                   kernel, Section 4.2.3, is vf_serve_begin below).  vf_search_multi follows the same rule; profiled calls
  *                   and vf_search_exact must not overlap with other calls on the index.
  *
  * A query whose label (any of its labels) has an empty posting list, or whose
