@@ -331,11 +331,12 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     };
 
     // Distances of cand[0..cnt) (eight at a time, one per team) into cand_d.
-    auto score = [&](int cnt, bool distinct_new = false) {   // distinct_new: seeds (see offer_seeds_to)
-        n_scored += cnt;
-        n_gathered += cnt;
+    // (lo: a multiple of 8, the entries before it have been dealt with)
+    auto score = [&](int cnt, bool distinct_new = false, int lo = 0) {   // distinct_new: seeds (see offer_seeds_to)
+        n_scored += cnt - lo;
+        n_gathered += cnt - lo;
 #pragma unroll 2
-        for (int r0 = 0; r0 < cnt; r0 += 8) {
+        for (int r0 = lo; r0 < cnt; r0 += 8) {
             const int my = r0 + team;
             const int g = cand_g[my < cnt ? my : 0];
             const char *xrow = (const char *)p.X + (int64_t)g * row_bytes;
@@ -347,7 +348,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
         wave_sync<STREAM_SEEDS>();
         for (int i0 = 0; i0 < cnt; i0 += 64) {
             const int i = i0 + lane;
-            const bool valid = i < cnt;
+            const bool valid = i < cnt && i >= lo;
             if constexpr (E == 1) {
                 if (distinct_new) { offer_seeds_to(top, valid, valid ? cand_d[i] : 0u, valid ? cand_c[i] : 0); continue; }
             }
@@ -549,7 +550,6 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 const int cnt = __popcll(__ballot(valid));
                 if (valid) { cand_c[lane] = c; cand_g[lane] = p.meta.M_HS[base + c]; }
                 wave_sync<STREAM_SEEDS>();
-                score(cnt, true);
                 float qn = 0.f;
                 for (int i = lane; i < nchunks; i += 64) {
                     const uint4 v = qv[i];
@@ -560,12 +560,28 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 for (int o = 32; o > 0; o >>= 1) qn += __shfl_xor(qn, o);
                 const float B = p.err_bound * (qn + p.xn_max) + p.err_q * sqrtf(qn);
                 const bool all_kept = tmp.worst == KEY_MAX;
-                const bool proven = top.worst != KEY_MAX &&
-                                    __uint_as_float((uint32_t)(top.worst >> 32)) < __uint_as_float((uint32_t)(tmp.worst >> 32)) - B;
-                if (all_kept || proven) {
+                // The kept seeds are re-scored in the order of their approximations, first enough to fill the list and
+                // eight to spare, then eight at a time, until everything not re-scored yet is provably worse than the
+                // list's worst entry: those seeds have approximations >= T, the approximation of the first one not
+                // re-scored (the last one kept, once all are), hence ordered distances >= T - B.  Most queries stop
+                // after the first step; the spare candidates beyond it are for the few that need them.
+                int done_to = (itopk + 8 + 7) & ~7;
+                done_to = done_to < cnt ? done_to : cnt;
+                score(done_to, true);
+                bool proven = false;
+                while (true) {
+                    const uint64_t next = done_to < cnt ? readlane64(key, done_to) : tmp.worst;
+                    proven = top.worst != KEY_MAX && next != KEY_MAX &&
+                             __uint_as_float((uint32_t)(top.worst >> 32)) < __uint_as_float((uint32_t)(next >> 32)) - B;
+                    if (proven || done_to == cnt) break;
+                    const int upto = done_to + 8 < cnt ? done_to + 8 : cnt;
+                    score(upto, true, done_to);
+                    done_to = upto;
+                }
+                if (proven || (all_kept && done_to == cnt)) {
                     seeds_done = true;
-                    n_scored -= cnt;       // the re-scored seeds were counted when they were selected
-                    n_rescored = cnt;
+                    n_scored -= done_to;   // the re-scored seeds were counted when they were selected
+                    n_rescored = done_to;
                 }
             }
             if (!seeds_done) {   // start over; the gather path below scores every seed
