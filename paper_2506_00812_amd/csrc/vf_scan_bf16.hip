@@ -250,21 +250,16 @@ __global__ __launch_bounds__(64) void scan_rerank_kernel(RerankParams p)
     const int cnt = __popcll(__ballot(valid));   // the kept candidates sit in lanes 0 .. cnt - 1
     if (valid) cand_g[lane] = p.map[it.map_off + idx];
     __syncthreads();
-    // ordered distances of cand_g[0 .. n) into cand_d, eight at a time (one per 8-lane team)
-    auto score = [&](int n) {
+    // ordered distances of cand_g[lo .. n) into cand_d, eight at a time (one per 8-lane team); lo a multiple of 8
+    auto score = [&](int n, int lo = 0) {
 #pragma unroll 2
-        for (int r0 = 0; r0 < n; r0 += 8) {
+        for (int r0 = lo; r0 < n; r0 += 8) {
             const int my = r0 + team;
             const int g = cand_g[my < n ? my : 0];
             const uint32_t bits = team_dist_bits_f32(qv, (const char *)p.X + (int64_t)g * row_bytes, nchunks, tl);
             if (tl == 0 && my < n) cand_d[my] = bits;
         }
     };
-    score(cnt);
-    __syncthreads();
-    uint64_t key = valid ? ((uint64_t)cand_d[lane] << 32) | idx : KEY_MAX;
-    key = wave_sort64(key, lane);
-
     float qn = 0.f;
     for (int i = lane; i < nchunks; i += 64) {
         const uint4 v = qv[i];
@@ -275,9 +270,29 @@ __global__ __launch_bounds__(64) void scan_rerank_kernel(RerankParams p)
     for (int o = 32; o > 0; o >>= 1) qn += __shfl_xor(qn, o);
     const float B = p.err_bound * (qn + p.xn_max) + p.err_q * sqrtf(qn);
     const bool all_kept = list.worst == KEY_MAX;   // fewer than Kc candidates in all: no segment dropped one
-    const uint64_t kth = readlane64(key, p.K - 1);
-    const bool proven = all_kept || (kth != KEY_MAX && __uint_as_float((uint32_t)(kth >> 32)) <
-                                                           __uint_as_float((uint32_t)(list.worst >> 32)) - B);
+    // The kept candidates are re-scored in the order of their approximations, first k and a few to spare, then eight
+    // at a time, until everything not re-scored is provably worse than the k-th result: those candidates have
+    // approximations >= T, the approximation of the first one not re-scored (the last one kept, once all are),
+    // hence ordered distances >= T - B.  Most queries stop after the first step.
+    int done_to = (p.K + 6 + 7) & ~7;
+    done_to = done_to < cnt ? done_to : cnt;
+    int scored_to = 0;
+    uint64_t key = KEY_MAX;
+    bool proven = false;
+    while (true) {
+        score(done_to, scored_to);
+        scored_to = done_to;
+        __syncthreads();
+        key = (valid && lane < done_to) ? ((uint64_t)cand_d[lane] << 32) | idx : KEY_MAX;
+        key = wave_sort64(key, lane);
+        const uint64_t rest = done_to < cnt ? readlane64(kept, done_to) : list.worst;
+        const uint64_t kth = readlane64(key, p.K - 1);
+        proven = (all_kept && done_to == cnt) ||
+                 (kth != KEY_MAX && rest != KEY_MAX &&
+                  __uint_as_float((uint32_t)(kth >> 32)) < __uint_as_float((uint32_t)(rest >> 32)) - B);
+        if (proven || done_to == cnt) break;
+        done_to = done_to + 8 < cnt ? done_to + 8 : cnt;
+    }
     if (!proven) {   // (wave-uniform) the definition itself: every entry of the list that passes the predicate
         if (lane == 0) atomicAdd(p.fail_count, 1u);
         int o_begin = 0, o_end = 0;
