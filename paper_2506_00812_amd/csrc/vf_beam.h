@@ -306,6 +306,28 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     const int o_cnt = AND ? bq.o_cnt : 0;
     const int qq_lane = DT == 0 ? lane_qq_u8(qv, nchunks, tl) : 0;
 
+    // The AND predicate of global id g.  One partner label with a bitset -- every two-label query whose searched
+    // list is its smallest: the partner's list is at least as long, so it is a graph list too -- is one word of
+    // that bitset; the general form walks the partner labels (bitset or binary search each).
+    const uint32_t *bits0 = nullptr;
+    if (AND && o_cnt == 1) {
+        const int32_t slot = p.meta.hs_slot[bq.others[0]];
+        if (slot >= 0) bits0 = p.meta.bitsets + (int64_t)slot * p.meta.bitset_words;
+    }
+    auto passes = [&](int g) -> bool {
+        if (bits0 != nullptr) return (bits0[g >> 5] >> (g & 31)) & 1u;
+        bool ok = true;
+        for (int o = 0; o < o_cnt && ok; ++o) ok = has_label(p.meta, bq.others[o], g);
+        return ok;
+    };
+    // global ids of this list's seeds in seed order, when the call has them (else M_HS[base + floor(j n / ns)])
+    const int32_t *smap = nullptr;
+    if (AND && o_cnt > 0 && p.seed_map != nullptr) smap = p.seed_map + p.seed_goff[p.meta.hs_slot[label]] * 32;
+    auto seed_gid = [&](int j) -> int {   // (ns as below: the number of seeds of this list)
+        const int ns_ = p.n_seeds < n ? p.n_seeds : n;
+        return smap != nullptr ? smap[j] : p.meta.M_HS[base + (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns_)];
+    };
+
     TopM<E> top;
     top.init(itopk);
     int n_scored = 0, n_expanded = 0, n_tested = 0;  // work counters (uniform across the wave)
@@ -363,7 +385,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
         if (o_cnt > 0) n_tested += __popcll(__ballot(valid));
         if (valid) {
             if (g < 0) g = p.meta.M_HS[base + c];
-            for (int o = 0; o < o_cnt && valid; ++o) valid = has_label(p.meta, bq.others[o], g);
+            valid = passes(g);
         }
         const uint64_t m = __ballot(valid);
         if (valid) {
@@ -400,22 +422,30 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
             const int chunk_n = ns - jc < 64 * NBLK ? ns - jc : 64 * NBLK;
             int chunk_scored = chunk_n, chunk_tested = o_cnt > 0 ? chunk_n : 0;   // every seed counts as tested
             // AND: a seed that fails the predicate is taken out before the selection (its value becomes +inf).
-            // Its local id floor(j n / ns) advances by (64 n) / ns per step of 64 seeds: one division per lane and
-            // chunk, then quotient / remainder increments.
+            // Without the seeds' own id map the local id floor(j n / ns) advances by (64 n) / ns per step of 64 seeds:
+            // one division per lane and chunk, then quotient / remainder increments.
             auto apply_predicate = [&]() {
+                chunk_scored = 0;
+                if (smap != nullptr) {
+#pragma unroll
+                    for (int i = 0; i < NBLK; ++i) {
+                        const int j = jc + i * 64 + lane;
+                        bool pass = j < ns;
+                        if (pass) pass = passes(smap[j]);
+                        if (!pass) v[i] = 0xFFFFFFFFu;
+                        chunk_scored += __popcll(__ballot(pass));
+                    }
+                    return;
+                }
                 const uint64_t t64 = 64ull * (uint64_t)n;
                 const uint32_t Q64 = (uint32_t)(t64 / (uint64_t)ns), R64 = (uint32_t)(t64 % (uint64_t)ns);
                 const uint64_t t0 = (uint64_t)(jc + lane) * (uint64_t)n;
                 uint32_t cq = (uint32_t)(t0 / (uint64_t)ns), cr = (uint32_t)(t0 % (uint64_t)ns);
-                chunk_scored = 0;
 #pragma unroll
                 for (int i = 0; i < NBLK; ++i) {
                     const int j = jc + i * 64 + lane;
                     bool pass = j < ns;
-                    if (pass) {
-                        const int g = p.meta.M_HS[base + cq];
-                        for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, bq.others[o], g);
-                    }
+                    if (pass) pass = passes(p.meta.M_HS[base + cq]);
                     if (!pass) v[i] = 0xFFFFFFFFu;
                     chunk_scored += __popcll(__ballot(pass));
                     cr += R64; cq += Q64;
@@ -488,10 +518,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 int c = valid ? cand_c[i] : 0;
                 if (lazy || !as_index) {
                     const int cl = (int)(((uint64_t)c * (uint64_t)n) / (uint64_t)ns);
-                    if (lazy && valid) {
-                        const int g = p.meta.M_HS[base + cl];
-                        for (int o = 0; o < o_cnt && valid; ++o) valid = has_label(p.meta, bq.others[o], g);
-                    }
+                    if (lazy && valid) valid = passes(seed_gid(c));
                     if (!as_index) c = cl;
                 }
                 offer_seeds_to(list, valid, valid ? cand_d[i] : 0u, c);
@@ -618,8 +645,7 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
                 if (full) { lazy_used = true; pass = valid && bits <= (uint32_t)(top.worst >> 32); }
                 if (pass) {
                     c = (int)(((uint64_t)j * (uint64_t)n) / (uint64_t)ns);
-                    const int g = p.meta.M_HS[base + c];
-                    for (int o = 0; o < o_cnt && pass; ++o) pass = has_label(p.meta, bq.others[o], g);
+                    pass = passes(seed_gid(j));
                 }
                 n_scored += __popcll(__ballot(pass));
             } else {

@@ -5,8 +5,11 @@
 
 namespace vf {
 
+// Waves per SIMD the register budget is set for: the one-register-list kernels (E = 1) are the ones whose every
+// wave should be resident at once.  float32 without predicate 7 (<= 72 VGPRs), with predicate 6 (80, a few values
+// spilled: measured faster on 100,000 two-label queries than 5 waves without spills); uint8 with predicate 7.
 template <int DT, int E, bool AND>
-__global__ __launch_bounds__(64, (DT == 1 && E == 1) ? (AND ? 6 : 7) : 8) void beam_kernel(BeamParams p)
+__global__ __launch_bounds__(64, (DT == 1 && E == 1) ? (AND ? 6 : 7) : (E == 1 && AND) ? 7 : 8) void beam_kernel(BeamParams p)
 {
     extern __shared__ uint4 smem[];
     const int gq = blockIdx.x;

@@ -149,6 +149,11 @@ struct BeamParams {
     const uint64_t *seed_runs;
     int32_t run_K, run_segs, seg_seeds;
     const int32_t *seed_pass;  // optional (profiling, AND batches): seeds of the query that pass its predicate
+    // optional (AND batches with a dense seed distance matrix): global ids of the seeds of every graph list in seed
+    // order, 32-seed groups, first group of a list at seed_goff[rank of the list among graph lists] -- consecutive
+    // seeds at consecutive addresses, where M_HS holds them floor(n / n_seeds) entries apart
+    const int32_t *seed_map;
+    const int64_t *seed_goff;
     // optional: an interleaved copy of the seeds (uint8 or float32, never bfloat16) from which a wave scores its
     // seeds itself when no dense seed kernel ran (the serving kernel); sgoff: first group of each graph list
     const uint4 *sblk;

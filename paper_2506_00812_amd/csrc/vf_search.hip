@@ -586,6 +586,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
                 launch_seed_dist(ix->dtype, sd, (int)P.tiles.size(), s);
             }
             bp.dseed = sd.dseed;
+            if (r.any_and && sc != nullptr && sc->ok) { bp.seed_map = sc->map.as<int32_t>(); bp.seed_goff = sc->goff.as<int64_t>(); }
             if (prof && ix->prof_exact_counts && r.any_and) bp.seed_pass = ix->counters.as<int32_t>() + (size_t)P.nq * 5;   // filled before the timed interval
         }
         if (prof && !attach) VF_HIP(hipEventRecord(ix->prof_ev[3], s));
