@@ -337,7 +337,7 @@ int vf_index_stats(const vf_index *index, vf_stats *out);
  * defaults change, which indexes built afterwards start from (the build-time switches "build16",
  * "build_panel_kb" and "build_progress" only act that way); with an index, that index's own copy changes, and
  * no call on it may be in flight.  Names: "seg_groups", "seg_groups_heavy", "heavy_rows", "tile_rows",
- * "zero_copy_bytes", "scan_valu", "scan16", "scan_bf16", "scan_bf16_margin", "scan_bf16_slots", "scan_bf16_seg_groups", "overlap", "seed_exact", "seed_slack", "seed_margin",
+ * "zero_copy_bytes", "scan_valu", "scan16", "scan_bf16", "scan_bf16_margin", "scan_bf16_slots", "scan_bf16_seg_groups", "beam_lat_waves", "overlap", "seed_exact", "seed_slack", "seed_margin",
  * "seed_margin_bf16", "seed_cache", "seed_bf16", "seed_bf16_min_batch", "seed_fb_window", "seed_select",
  * "seed_seg_seeds", "build16",
  * "build_panel_kb", "build_progress".  Returns VF_EINVAL for an unknown name or a value out of range.

@@ -280,7 +280,10 @@ struct BeamQuery {
 // larger workgroup working by itself (wave_sync orders the wave's LDS traffic either way).
 // smem: beam_lds_bytes of LDS.
 // AND = false: compiled for batches without predicate labels (none of the predicate's code and registers).
-template <int DT, int E, bool STREAM_SEEDS = false, bool AND = true>
+// LAT: for launches of so few waves that each has a SIMD to itself (small batches, serving workers): the vectors of up
+// to 64 candidates are requested before the first distance is computed (128 registers of loads in flight), so a
+// batch of children costs one memory latency instead of one per 16 candidates.
+template <int DT, int E, bool STREAM_SEEDS = false, bool AND = true, bool LAT = false>
 __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const BeamQuery &bq, uint4 *smem)
 {
     const int lane = wave_lane<STREAM_SEEDS>(), team = lane >> 3, tl = lane & 7;
@@ -357,8 +360,65 @@ __device__ __forceinline__ void beam_search_wave(const BeamParams &p, const Beam
     auto score = [&](int cnt, bool distinct_new = false, int lo = 0) {   // distinct_new: seeds (see offer_seeds_to)
         n_scored += cnt - lo;
         n_gathered += cnt - lo;
+        int lo_rest = lo;
+        if constexpr (LAT) {
+            if (nchunks <= 32) {   // at most four 16-byte chunks per lane of a team
+                constexpr int NR = 8;
+                for (int r0 = lo; r0 < cnt; r0 += 8 * NR) {
+                    uint4 x[NR][4];
+#pragma unroll
+                    for (int u = 0; u < NR; ++u) {
+                        const int my = r0 + 8 * u + team;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) x[u][w] = make_uint4(0, 0, 0, 0);
+                        if (r0 + 8 * u < cnt) {   // (wave-uniform)
+                            const char *xrow = (const char *)p.X + (int64_t)cand_g[my < cnt ? my : 0] * row_bytes;
+#pragma unroll
+                            for (int w = 0; w < 4; ++w)
+                                if (w * 8 + tl < nchunks) x[u][w] = *(const uint4 *)(xrow + (w * 8 + tl) * kChunkBytes);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < NR; ++u) {
+                        const int my = r0 + 8 * u + team;
+                        if (r0 + 8 * u >= cnt) break;   // (wave-uniform)
+                        uint32_t bits;
+                        if constexpr (DT == 0) {
+                            uint32_t xx = 0, qx = 0;
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+                                if (w * 8 + tl < nchunks) {
+                                    const uint4 q = qv[w * 8 + tl], xv = x[u][w];
+                                    xx = __builtin_amdgcn_udot4(xv.x, xv.x, xx, false); qx = __builtin_amdgcn_udot4(q.x, xv.x, qx, false);
+                                    xx = __builtin_amdgcn_udot4(xv.y, xv.y, xx, false); qx = __builtin_amdgcn_udot4(q.y, xv.y, qx, false);
+                                    xx = __builtin_amdgcn_udot4(xv.z, xv.z, xx, false); qx = __builtin_amdgcn_udot4(q.z, xv.z, qx, false);
+                                    xx = __builtin_amdgcn_udot4(xv.w, xv.w, xx, false); qx = __builtin_amdgcn_udot4(q.w, xv.w, qx, false);
+                                }
+                            }
+                            bits = (uint32_t)team_sum_i(qq_lane + (int)xx - 2 * (int)qx);
+                        } else {   // the order of team_dist_bits_f32
+                            float acc = 0.0f;
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+                                if (w * 8 + tl < nchunks) {
+                                    const uint4 q = qv[w * 8 + tl], xv = x[u][w];
+                                    float d;
+                                    d = __uint_as_float(q.x) - __uint_as_float(xv.x); acc = __builtin_fmaf(d, d, acc);
+                                    d = __uint_as_float(q.y) - __uint_as_float(xv.y); acc = __builtin_fmaf(d, d, acc);
+                                    d = __uint_as_float(q.z) - __uint_as_float(xv.z); acc = __builtin_fmaf(d, d, acc);
+                                    d = __uint_as_float(q.w) - __uint_as_float(xv.w); acc = __builtin_fmaf(d, d, acc);
+                                }
+                            }
+                            bits = __float_as_uint(team_sum_f(acc));
+                        }
+                        if (tl == 0 && my < cnt) cand_d[my] = bits;
+                    }
+                }
+                lo_rest = cnt;
+            }
+        }
 #pragma unroll 2
-        for (int r0 = lo; r0 < cnt; r0 += 8) {
+        for (int r0 = lo_rest; r0 < cnt; r0 += 8) {
             const int my = r0 + team;
             const int g = cand_g[my < cnt ? my : 0];
             const char *xrow = (const char *)p.X + (int64_t)g * row_bytes;

@@ -8,8 +8,10 @@ namespace vf {
 // Waves per SIMD the register budget is set for: the one-register-list kernels (E = 1) are the ones whose every
 // wave should be resident at once.  float32 without predicate 7 (<= 72 VGPRs), with predicate 6 (80, a few values
 // spilled: measured faster on 100,000 two-label queries than 5 waves without spills); uint8 with predicate 7.
-template <int DT, int E, bool AND>
-__global__ __launch_bounds__(64, (DT == 1 && E == 1) ? (AND ? 6 : 7) : (E == 1 && AND) ? 7 : 8) void beam_kernel(BeamParams p)
+// LAT: the instantiation for launches of at most BeamParams::lat_waves queries (every wave on a SIMD of its own): two waves per
+// SIMD's worth of registers, the candidates' vectors requested 64 at a time.
+template <int DT, int E, bool AND, bool LAT = false>
+__global__ __launch_bounds__(64, LAT ? 2 : (DT == 1 && E == 1) ? (AND ? 6 : 7) : (E == 1 && AND) ? 7 : 8) void beam_kernel(BeamParams p)
 {
     extern __shared__ uint4 smem[];
     const int gq = blockIdx.x;
@@ -31,7 +33,7 @@ __global__ __launch_bounds__(64, (DT == 1 && E == 1) ? (AND ? 6 : 7) : (E == 1 &
     bq.dseed_row = p.dseed != nullptr ? p.dseed + (int64_t)gq * p.ns_stride : nullptr;
     bq.runs = p.seed_runs != nullptr ? p.seed_runs + (int64_t)gq * p.run_segs * p.run_K : nullptr;
     bq.seed_pass = p.seed_pass != nullptr ? p.seed_pass[gq] : -1;
-    beam_search_wave<DT, E, false, AND>(p, bq, smem);
+    beam_search_wave<DT, E, false, AND, LAT>(p, bq, smem);
 }
 
 size_t beam_lds_bytes(const BeamParams &p, int dtype)
@@ -44,7 +46,8 @@ template <int DT, bool AND>
 static void launch_beam_dt(const BeamParams &p, int n_gq, size_t lds, hipStream_t s, hipEvent_t start, hipEvent_t stop)
 {
     const dim3 grid(n_gq), block(64);
-    if (p.itopk <= 64) hipExtLaunchKernelGGL((beam_kernel<DT, 1, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
+    if (p.itopk <= 64 && n_gq <= p.lat_waves) hipExtLaunchKernelGGL((beam_kernel<DT, 1, AND, true>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
+    else if (p.itopk <= 64) hipExtLaunchKernelGGL((beam_kernel<DT, 1, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
     else if (p.itopk <= 128) hipExtLaunchKernelGGL((beam_kernel<DT, 2, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
     else hipExtLaunchKernelGGL((beam_kernel<DT, 4, AND>), grid, block, (uint32_t)lds, s, start, stop, 0, p);
 }

@@ -96,6 +96,7 @@ struct Tuning {
     int scan_bf16_margin = 22;    // approximations kept beyond k per query and segment by that filter
     int scan_bf16_slots = 1;      // list groups a wave of that filter keeps in flight (1 or 2)
     int scan_bf16_seg_groups = 24;   // 32-vector groups per list segment when that filter runs (half the bytes per group)
+    int beam_lat_waves = 1024;    // beam launches of up to this many graph queries use the latency instantiation (a wave per SIMD); 0: never
     int overlap = 1;              // 0: the scan path runs on the caller's stream, before the graph path
     int seed_exact = 0;           // 1: seeds are scored by the ordered-distance kernel, never on the matrix cores
     double seed_slack = 1.0;      // scales the rounding-error bound of the float32 seed proofs

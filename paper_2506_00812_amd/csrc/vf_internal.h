@@ -154,6 +154,7 @@ struct BeamParams {
     // seeds at consecutive addresses, where M_HS holds them floor(n / n_seeds) entries apart
     const int32_t *seed_map;
     const int64_t *seed_goff;
+    int32_t lat_waves;         // launches of at most this many graph queries (itopk <= 64) run the latency instantiation
     // optional: an interleaved copy of the seeds (uint8 or float32, never bfloat16) from which a wave scores its
     // seeds itself when no dense seed kernel ran (the serving kernel); sgoff: first group of each graph list
     const uint4 *sblk;

@@ -47,6 +47,7 @@ bool Tuning::set(const char *name, double value)
         {"scan_bf16_margin", &Tuning::scan_bf16_margin, 0, 54},
         {"scan_bf16_slots", &Tuning::scan_bf16_slots, 1, 2},
         {"scan_bf16_seg_groups", &Tuning::scan_bf16_seg_groups, 1, 1024},
+        {"beam_lat_waves", &Tuning::beam_lat_waves, 0, 1 << 20},
         {"overlap", &Tuning::overlap, 0, 1},
         {"seed_exact", &Tuning::seed_exact, 0, 1},
         {"seed_margin", &Tuning::seed_margin, 1, 32},

@@ -481,6 +481,7 @@ int launch_call(vf_index *ix, const CallPlan &P, const Routed &r, const CallMem 
         bp.others_off = d_others_off; bp.others = d_others; bp.meta = ix->meta();
         bp.dim = ix->dim; bp.R = ix->R; bp.k = k; bp.itopk = P.itopk; bp.width = P.width; bp.iters = P.iters;
         bp.n_seeds = P.n_seeds;
+        bp.lat_waves = ix->tune.beam_lat_waves;
         bp.LP = P.beam_LP;
         bp.hash_bits = P.beam_hb;
         bp.out_ids = out_ids; bp.out_dists = out_dists;

@@ -86,9 +86,9 @@ def test_tuning_names_and_ranges_without_gpu(lib):
     hdr = open(os.path.join(ROOT, "include", "vecflow.h")).read()
     doc = re.search(r"Names: (.*?)\.  Returns VF_EINVAL", hdr, re.S).group(1)
     names = re.findall(r'"([a-z_0-9]+)"', doc)
-    assert len(names) == 25
+    assert len(names) == 26
     defaults = dict(seg_groups=16, seg_groups_heavy=16, heavy_rows=9, tile_rows=16, zero_copy_bytes=8192, scan_valu=1,
-                    scan16=1, scan_bf16=1, scan_bf16_margin=22, scan_bf16_slots=1, scan_bf16_seg_groups=24, overlap=1, seed_exact=0, seed_slack=1.0, seed_margin=8, seed_margin_bf16=24, seed_cache=1,
+                    scan16=1, scan_bf16=1, scan_bf16_margin=22, scan_bf16_slots=1, scan_bf16_seg_groups=24, beam_lat_waves=1024, overlap=1, seed_exact=0, seed_slack=1.0, seed_margin=8, seed_margin_bf16=24, seed_cache=1,
                     seed_bf16=1, seed_bf16_min_batch=512, seed_fb_window=131072, seed_select=0, seed_seg_seeds=0, build16=1, build_panel_kb=4096,
                     build_progress=0)
     assert sorted(names) == sorted(defaults)

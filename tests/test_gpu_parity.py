@@ -90,9 +90,14 @@ def test_tiny_interleaved_lists_and_bitsets(vf, tiny, tiny_oracle, tiny_gpu):
 def test_tiny_search_bit_exact(vf, tiny, tiny_oracle, tiny_gpu, params):
     ix, Q = tiny_gpu
     k = tiny.spec.k
-    ig, dg = _search(vf, ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k, **params)
     io, do = tiny_oracle.search(tiny.queries, tiny.qlabel_offsets, tiny.qlabel_ids, k, **params)
-    assert_exact(ig, dg, io, do, f"tiny {params}")
+    # small launches run the beam kernel's latency instantiation (candidates' vectors requested 64 at a time),
+    # large ones the throughput instantiation: both on the same batch
+    for lat_waves in (1024, 0):
+        ix.tune("beam_lat_waves", lat_waves)
+        ig, dg = _search(vf, ix, Q, tiny.qlabel_offsets, tiny.qlabel_ids, k, **params)
+        assert_exact(ig, dg, io, do, f"tiny {params} lat_waves={lat_waves}")
+    ix.tune("beam_lat_waves", 1024)
 
 
 def _and_queries(nq, n_labels, seed, hi_a=12, hi_b=40):
@@ -116,11 +121,14 @@ def test_tiny_and_queries_bit_exact(vf, tiny, tiny_oracle, tiny_gpu):
     nq, k = 600, 10
     qoff, qids = _and_queries(nq, tiny.spec.n_labels, 21)
     for params in (dict(itopk=64, width=1, iters=40, n_seeds=256), dict(itopk=32, width=2, iters=10, n_seeds=0)):
-        ig, dg = _search(vf, ix, Q[:nq], qoff, qids, k, **params)
         io, do, info = tiny_oracle.search(tiny.queries[:nq], qoff, qids, k, with_info=True, **params)
         assert (info["method"] == 2).sum() > 50 and (info["method"] == 1).sum() > 50
         assert (io[:, -1] == -1).any()         # short and empty rows are exercised
-        assert_exact(ig, dg, io, do, f"tiny AND {params}")
+        for lat_waves in (1024, 0):            # both instantiations of the beam kernel
+            ix.tune("beam_lat_waves", lat_waves)
+            ig, dg = _search(vf, ix, Q[:nq], qoff, qids, k, **params)
+            assert_exact(ig, dg, io, do, f"tiny AND {params} lat_waves={lat_waves}")
+        ix.tune("beam_lat_waves", 1024)
 
 
 def test_tiny_exact_search_matches_oracle_scan(vf, tiny, tiny_oracle, tiny_gpu):
