@@ -231,6 +231,26 @@ __device__ __forceinline__ void stream_seed_segment(const BeamParams &p, int lab
             float a[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) a[u] = 0.0f;
+            if (nchunks <= 32) {
+                // every chunk of the lane's seed is requested before the first is used (128 registers of loads in
+                // flight): a step of 64 seeds then costs one memory latency, not one per eight chunks -- the wave has
+                // a SIMD to itself and nothing else hides that latency.  Same order of operations as below.
+                uint4 x[32];
+#pragma unroll
+                for (int c = 0; c < 32; ++c)
+                    if (c < nchunks) x[c] = col[(int64_t)c * 32];   // (wave-uniform)
+#pragma unroll
+                for (int c = 0; c < 32; ++c) {
+                    if (c < nchunks) {
+                        const uint4 q = qv[c];
+                        float d;
+                        d = __uint_as_float(q.x) - __uint_as_float(x[c].x); a[c & 7] = __builtin_fmaf(d, d, a[c & 7]);
+                        d = __uint_as_float(q.y) - __uint_as_float(x[c].y); a[c & 7] = __builtin_fmaf(d, d, a[c & 7]);
+                        d = __uint_as_float(q.z) - __uint_as_float(x[c].z); a[c & 7] = __builtin_fmaf(d, d, a[c & 7]);
+                        d = __uint_as_float(q.w) - __uint_as_float(x[c].w); a[c & 7] = __builtin_fmaf(d, d, a[c & 7]);
+                    }
+                }
+            } else
             for (int c0 = 0; c0 < nchunks; c0 += 8) {   // chunk c0 + u belongs to partial sum u
                 uint4 x[8];
 #pragma unroll
